@@ -1,0 +1,244 @@
+"""fp64 numpy oracle of the GSA forward path.  TEST INFRASTRUCTURE, not product code.
+
+Each function restates one passage of the paper, in the paper's order and
+notation, with no blocking, fusion or reordering.  All arithmetic is float64.
+Inputs are the values the GPU sees (already rounded to bf16 / fp32 by the
+caller and then widened), so input quantisation is not counted as error.
+
+Shapes (paper symbol -> axis):
+  qI [B, Lq, HI, dI]   indexer queries q^I_{t,j}
+  kI [B, Lk, dI]       one indexer key k^I_s per token
+  w  [B, Lq, HI]       head weights sigma(h_t W^{Iw}_j), i.e. already in (0,1)
+  bI [HI] or None      per-head bias b^I_j
+  Q  [B, Lq, H, dh]; K, V [B, Lk, Hkv, dh]
+  g2 [B, Lk, Hkv, dh]  value-gate logits h_s W^g_V      (None: V is already gated)
+  g1 [B, Lq, H, dh]    output-gate logits h_t W^g_{O,h} (None: no output gate)
+Query row i has absolute position p = q_offset + i and sees keys s <= min(p, Lk-1)
+(self included).
+
+Readings taken where the paper is silent are listed in the design notes of the
+repository; the ones that show up here: no 1/sqrt(d^I) factor on the indexer
+logit (Eq. "indexer" prints none); population variance over the visible
+prefix; floor before clamp; n_sel = min(k_t, #visible); ties go to the lowest
+index; one index set per query shared by all heads; kv head of query head h is
+h // (H // Hkv).
+
+Parity unpinned: ema_update (Sec. 3.4 names an exponential moving average but
+gives no decay, initial value or update order).
+"""
+import math
+
+import numpy as np
+
+
+# --------------------------------------------------------------------------- helpers
+def sigmoid(z):
+    """Logistic function, evaluated without overflow on either side."""
+    z = np.asarray(z, dtype=np.float64)
+    out = np.empty_like(z)
+    pos = z >= 0
+    out[pos] = 1.0 / (1.0 + np.exp(-z[pos]))
+    ez = np.exp(z[~pos])
+    out[~pos] = ez / (1.0 + ez)
+    return out
+
+
+def n_visible(i, q_offset, Lk):
+    """Number of keys query row i may look at: s = 0 .. min(q_offset+i, Lk-1)."""
+    return min(q_offset + i, Lk - 1) + 1
+
+
+# --------------------------------------------------------------------------- Sec. 3.3
+def indexer_scores_row(qI_t, kI_vis, w_t, bI=None):
+    """Eq. "indexer" (Sec. 3.3) for one query: I_{t,s} = sum_j w_{t,j} sigma(q^I_{t,j}.k^I_s + b^I_j).
+
+    qI_t [HI, dI], kI_vis [n, dI] (the visible keys only), w_t [HI] -> I [n].
+    """
+    qI_t = np.asarray(qI_t, np.float64)
+    kI_vis = np.asarray(kI_vis, np.float64)
+    w_t = np.asarray(w_t, np.float64)
+    HI = qI_t.shape[0]
+    I = np.zeros(kI_vis.shape[0], np.float64)
+    for j in range(HI):
+        z = kI_vis @ qI_t[j]
+        if bI is not None:
+            z = z + float(bI[j])
+        I += w_t[j] * sigmoid(z)
+    return I
+
+
+def row_stats(I_vis):
+    """Mean and population variance of the visible scores (Var(I_{t,:}) of Eq. "adaptive_k"), two-pass."""
+    I_vis = np.asarray(I_vis, np.float64)
+    n = I_vis.shape[0]
+    mean = float(np.sum(I_vis) / n)
+    var = float(np.sum((I_vis - mean) ** 2) / n)
+    return mean, var
+
+
+def indexer_scores(qI, kI, w, bI=None, q_offset=0):
+    """All rows of Sec. 3.3.  Returns scores [B, Lq, Lk] (NaN where the key is not
+    visible), row_mean [B, Lq], row_var [B, Lq]."""
+    B, Lq, HI, dI = qI.shape
+    Lk = kI.shape[1]
+    scores = np.full((B, Lq, Lk), np.nan, np.float64)
+    mean = np.zeros((B, Lq), np.float64)
+    var = np.zeros((B, Lq), np.float64)
+    for b in range(B):
+        for i in range(Lq):
+            n = n_visible(i, q_offset, Lk)
+            I = indexer_scores_row(qI[b, i], kI[b, :n], w[b, i], bI)
+            scores[b, i, :n] = I
+            mean[b, i], var[b, i] = row_stats(I)
+    return scores, mean, var
+
+
+# --------------------------------------------------------------------------- Sec. 3.4
+def adaptive_k(var, vbar, k_base, k_min, k_max, k_fixed=0, mode=0):
+    """Eq. "adaptive_k" (Sec. 3.4): k_t = clamp(floor(k_base * Var / Vbar), k_min, k_max).
+
+    mode 0 is the equation as printed (k_t grows with the variance).  mode 1 is
+    the inverse ratio k_base * Vbar / Var, which follows the prose of Sec. 3.4
+    (a confident, high-variance query gets a smaller budget); Var = 0 then maps
+    to k_max.  k_fixed > 0 switches the controller off.  Returns int64 array.
+    """
+    var = np.asarray(var, np.float64)
+    if k_fixed > 0:
+        return np.full(var.shape, int(k_fixed), np.int64)
+    if not (vbar > 0 and math.isfinite(vbar)):
+        raise ValueError("vbar must be positive and finite")
+    if mode == 0:
+        r = float(k_base) * var / float(vbar)
+    else:
+        with np.errstate(divide="ignore"):
+            r = np.where(var > 0, float(k_base) * float(vbar) / np.where(var > 0, var, 1.0), np.inf)
+    r = np.floor(r)
+    r = np.minimum(np.maximum(r, float(k_min)), float(k_max))  # clamp while still floating
+    return r.astype(np.int64)
+
+
+def ema_update(vbar, row_var, beta=0.99):
+    """One step of a moving average of the batch-mean score variance.  PARITY UNPINNED:
+    Sec. 3.4 only names the average; beta and the update order are this file's choice."""
+    return beta * float(vbar) + (1.0 - beta) * float(np.mean(row_var))
+
+
+# --------------------------------------------------------------------------- Eq. 4 (Sec. 2.2)
+def topk_select_row(I_vis, n_sel):
+    """S_t of Eq. 4: indices of the n_sel largest visible scores; equal scores are
+    taken lowest index first.  Returned ascending."""
+    I_vis = np.asarray(I_vis, np.float64)
+    n = I_vis.shape[0]
+    n_sel = int(min(n_sel, n))
+    # lexsort: last key is primary.  Primary = score descending, secondary = index ascending.
+    order = np.lexsort((np.arange(n), -I_vis))
+    return np.sort(order[:n_sel]).astype(np.int64)
+
+
+# --------------------------------------------------------------------------- Sec. 3.5 / 3.6
+def sparse_gated_attn_row(Q_t, K, V, g2, g1_t, idx, scale=None):
+    """Sec. 3.6 over S_t = idx with the value gate G2 applied to V before aggregation and
+    the output gate G1 after it (Sec. 3.5).
+
+    Q_t [H, dh], K/V [Lk, Hkv, dh], g2 [Lk, Hkv, dh] or None, g1_t [H, dh] or None,
+    idx ascending int array.  Returns out [H, dh] and A [H, |S|] (the attention weights).
+    """
+    Q_t = np.asarray(Q_t, np.float64)
+    H, dh = Q_t.shape
+    Hkv = K.shape[1]
+    group = H // Hkv
+    if scale is None:
+        scale = 1.0 / math.sqrt(dh)
+    idx = np.asarray(idx, np.int64)
+    out = np.zeros((H, dh), np.float64)
+    A_all = np.zeros((H, idx.shape[0]), np.float64)
+    if idx.shape[0] == 0:
+        return out, A_all
+    for h in range(H):
+        g = h // group
+        Ks = np.asarray(K[idx, g], np.float64)             # [|S|, dh]
+        Vs = np.asarray(V[idx, g], np.float64)
+        if g2 is not None:
+            Vs = Vs * sigmoid(np.asarray(g2[idx, g], np.float64))   # V'_s = V_s * sigma(h_s W^g_V)
+        logit = (Ks @ Q_t[h]) * scale
+        logit = logit - np.max(logit)
+        e = np.exp(logit)
+        A = e / np.sum(e)                                   # softmax over S_t only
+        O = A @ Vs
+        if g1_t is not None:
+            O = O * sigmoid(np.asarray(g1_t[h], np.float64))    # O_gated = O_sparse * sigma(h_t W^g_{O,h})
+        out[h] = O
+        A_all[h] = A
+    return out, A_all
+
+
+# --------------------------------------------------------------------------- whole path
+def gsa_forward_row(b, i, Q, K, V, g1, g2, qI, kI, w, bI, q_offset, ctl, scale=None):
+    """The four stages for one query row (b, i).  ctl: dict(vbar, k_base, k_min, k_max,
+    k_fixed, mode).  Returns dict with I, mean, var, k, n_sel, idx, out."""
+    Lk = kI.shape[1]
+    n = n_visible(i, q_offset, Lk)
+    I = indexer_scores_row(qI[b, i], kI[b, :n], w[b, i], bI)
+    mean, var = row_stats(I)
+    k = int(adaptive_k(np.array(var), ctl["vbar"], ctl["k_base"], ctl["k_min"], ctl["k_max"],
+                       ctl.get("k_fixed", 0), ctl.get("mode", 0)))
+    n_sel = min(k, n)
+    idx = topk_select_row(I, n_sel)
+    out, _ = sparse_gated_attn_row(Q[b, i], K[b], V[b], None if g2 is None else g2[b],
+                                   None if g1 is None else g1[b, i], idx, scale)
+    return dict(I=I, mean=mean, var=var, k=k, n_sel=n_sel, idx=idx, out=out)
+
+
+def gsa_forward(Q, K, V, g1, g2, qI, kI, w, bI, q_offset, ctl, scale=None, k_cap=None):
+    """All rows.  Returns out [B,Lq,H,dh], idx [B,Lq,k_cap] (ascending, padded -1),
+    n_sel, k, var, mean."""
+    B, Lq, H, dh = Q.shape
+    if k_cap is None:
+        k_cap = int(ctl["k_fixed"]) if ctl.get("k_fixed", 0) > 0 else int(ctl["k_max"])
+    out = np.zeros((B, Lq, H, dh), np.float64)
+    idx = np.full((B, Lq, k_cap), -1, np.int64)
+    n_sel = np.zeros((B, Lq), np.int64)
+    k = np.zeros((B, Lq), np.int64)
+    var = np.zeros((B, Lq), np.float64)
+    mean = np.zeros((B, Lq), np.float64)
+    for b in range(B):
+        for i in range(Lq):
+            r = gsa_forward_row(b, i, Q, K, V, g1, g2, qI, kI, w, bI, q_offset, ctl, scale)
+            out[b, i] = r["out"]
+            idx[b, i, :r["n_sel"]] = r["idx"]
+            n_sel[b, i], k[b, i], var[b, i], mean[b, i] = r["n_sel"], r["k"], r["var"], r["mean"]
+    return dict(out=out, idx=idx, n_sel=n_sel, k=k, var=var, mean=mean)
+
+
+# --------------------------------------------------------------------------- Eq. 2 brute force
+def dense_causal_gated_attn(Q, K, V, g1, g2, q_offset=0, scale=None):
+    """Eq. 2 (Sec. 2.1) over every visible key, with V replaced by V' (G2) and the G1
+    factor on the result: what the sparse path must equal when k_t >= #visible."""
+    B, Lq, H, dh = Q.shape
+    Lk, Hkv = K.shape[1], K.shape[2]
+    group = H // Hkv
+    if scale is None:
+        scale = 1.0 / math.sqrt(dh)
+    out = np.zeros((B, Lq, H, dh), np.float64)
+    for b in range(B):
+        Vp = np.asarray(V[b], np.float64)
+        if g2 is not None:
+            Vp = Vp * sigmoid(np.asarray(g2[b], np.float64))
+        for i in range(Lq):
+            n = n_visible(i, q_offset, Lk)
+            for h in range(H):
+                g = h // group
+                num = np.zeros(dh, np.float64)
+                den = 0.0
+                logits = [float(np.dot(np.asarray(Q[b, i, h], np.float64), np.asarray(K[b, s, g], np.float64))) * scale
+                          for s in range(n)]
+                m = max(logits)
+                for s in range(n):
+                    e = math.exp(logits[s] - m)
+                    den += e
+                    num += e * Vp[s, g]
+                o = num / den
+                if g1 is not None:
+                    o = o * sigmoid(np.asarray(g1[b, i, h], np.float64))
+                out[b, i, h] = o
+    return out

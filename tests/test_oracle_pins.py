@@ -1,0 +1,303 @@
+"""Pins for the CPU oracle: what the paper and the mathematics fix, checked without the oracle
+grading itself.  Each test names the passage it comes from.  CPU only."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import gsa_oracle as O
+from oracle import naive as N
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+rng = np.random.default_rng
+
+
+def _tiny(seed=0, B=2, Lq=7, Lk=7, q_offset=0, H=4, Hkv=2, dh=8, HI=3, dI=5):
+    r = rng(seed)
+    return dict(
+        Q=r.standard_normal((B, Lq, H, dh)), K=r.standard_normal((B, Lk, Hkv, dh)),
+        V=r.standard_normal((B, Lk, Hkv, dh)), g1=r.standard_normal((B, Lq, H, dh)),
+        g2=r.standard_normal((B, Lk, Hkv, dh)), qI=r.standard_normal((B, Lq, HI, dI)),
+        kI=r.standard_normal((B, Lk, dI)), w=r.uniform(0.05, 0.95, (B, Lq, HI)),
+        bI=r.standard_normal(HI), q_offset=q_offset)
+
+
+# ---------------------------------------------------------------- Sec. 3.3 indexer
+def test_indexer_range_open_interval():
+    """Sec. 3.3: every sigmoid factor is in (0,1) so I in (0, H^I); more sharply I < sum_j w_j."""
+    t = _tiny(1, Lq=12, Lk=12, HI=4, dI=16)
+    t["qI"] *= 3.0
+    S, _, _ = O.indexer_scores(t["qI"], t["kI"], t["w"], t["bI"], 0)
+    vis = ~np.isnan(S)
+    assert vis.sum() == 2 * 12 * 13 // 2
+    assert np.all(S[vis] > 0.0) and np.all(S[vis] < 4.0)
+    bound = t["w"].sum(-1)[..., None] * np.ones_like(S)
+    assert np.all(S[vis] < bound[vis])
+    # causality: strictly upper triangle is not visible
+    for i in range(12):
+        assert np.all(np.isnan(S[:, i, i + 1:])) and not np.any(np.isnan(S[:, i, :i + 1]))
+
+
+def test_indexer_zero_query_closed_form():
+    """q^I = 0, b = 0 makes every logit 0, so I_{t,s} = (1/2) sum_j w_{t,j} for all s and Var = 0."""
+    t = _tiny(2)
+    t["qI"][:] = 0.0
+    S, mean, var = O.indexer_scores(t["qI"], t["kI"], t["w"], None, 0)
+    want = 0.5 * t["w"].sum(-1)
+    for i in range(S.shape[1]):
+        assert np.allclose(S[:, i, :i + 1], want[:, i, None], rtol=0, atol=1e-15)
+    assert np.allclose(mean, want, atol=1e-15) and np.allclose(var, 0.0, atol=1e-28)
+
+
+def test_indexer_bias_closed_form_via_tanh():
+    """q^I = 0 leaves sigma(b_j); sigma(x) = (1 + tanh(x/2))/2 gives the value by another route."""
+    t = _tiny(3)
+    t["qI"][:] = 0.0
+    S, _, _ = O.indexer_scores(t["qI"], t["kI"], t["w"], t["bI"], 0)
+    sig_b = np.array([0.5 * (1.0 + math.tanh(0.5 * b)) for b in t["bI"]])
+    want = (t["w"] * sig_b).sum(-1)
+    assert np.allclose(S[:, 3, :4], want[:, 3, None], rtol=1e-14)
+
+
+def test_indexer_alternating_keys_variance():
+    """H^I = 1, w = 1, q = e_1, k_s = +-c e_1 alternating: scores alternate sigma(c), sigma(-c);
+    for an even count Var = (sigma(c) - sigma(-c))^2 / 4 = tanh(c/2)^2 / 4 and mean = 1/2."""
+    c, L, dI = 1.7, 8, 4
+    qI = np.zeros((1, L, 1, dI)); qI[..., 0] = 1.0
+    kI = np.zeros((1, L, dI)); kI[0, :, 0] = c * np.where(np.arange(L) % 2 == 0, 1.0, -1.0)
+    kI[0, :, 1:] = 5.0        # orthogonal to q: must not matter
+    w = np.ones((1, L, 1))
+    S, mean, var = O.indexer_scores(qI, kI, w, None, 0)
+    hi = 0.5 * (1 + math.tanh(c / 2)); lo = 0.5 * (1 - math.tanh(c / 2))
+    assert np.allclose(S[0, L - 1, 0::2], hi, rtol=1e-14) and np.allclose(S[0, L - 1, 1::2], lo, rtol=1e-14)
+    for i in (1, 3, 5, 7):   # even number of visible keys
+        assert abs(var[0, i] - math.tanh(c / 2) ** 2 / 4) < 1e-15 and abs(mean[0, i] - 0.5) < 1e-15
+    assert var[0, 0] == 0.0  # a single visible key has no spread
+
+
+def test_indexer_index_roles_not_transposed():
+    """q^I_{t,j} = a_t e_j picks component j of k^I_s: logit_{j,s} = a_t k^I_s[j].  A swapped head/feature
+    axis, a swapped query/key role or a wrong weight index changes the result."""
+    HI = dI = 3
+    L = 4
+    a = np.array([1.0, 2.0, -1.0, 0.5])
+    qI = np.zeros((1, L, HI, dI))
+    for t in range(L):
+        for j in range(HI):
+            qI[0, t, j, j] = a[t]
+    kI = rng(5).standard_normal((1, L, dI))
+    w = rng(6).uniform(0.1, 0.9, (1, L, HI))
+    S, _, _ = O.indexer_scores(qI, kI, w, None, 0)
+    for t in range(L):
+        for s in range(t + 1):
+            want = sum(w[0, t, j] * 0.5 * (1 + math.tanh(0.5 * a[t] * kI[0, s, j])) for j in range(HI))
+            assert abs(S[0, t, s] - want) < 1e-14
+
+
+def test_indexer_matches_naive_loops():
+    t = _tiny(7, B=2, Lq=5, Lk=9, q_offset=4)
+    S, mean, var = O.indexer_scores(t["qI"], t["kI"], t["w"], t["bI"], 4)
+    Sn = N.indexer_scores(t["qI"], t["kI"], t["w"], t["bI"], 4, 2, 5, 9, 3, 5)
+    for b in range(2):
+        for i in range(5):
+            n = O.n_visible(i, 4, 9)
+            assert n == len(Sn[b][i]) == 5 + i
+            assert np.allclose(S[b, i, :n], Sn[b][i], rtol=1e-13)
+            assert abs(var[b, i] - N.variance(Sn[b][i])) < 1e-14
+            assert abs(var[b, i] - np.var(S[b, i, :n])) < 1e-14     # library routine: population variance
+
+
+# ---------------------------------------------------------------- Sec. 3.4 controller
+def test_adaptive_k_paper_defaults_and_hand_values():
+    """Sec. 3.4: k = clamp(floor(k_base Var / Vbar), k_min, k_max) with the printed defaults."""
+    kb, kmin, kmax = (int(x) for x in open(os.path.join(GOLD, "adaptive_k_defaults.txt")).read().split("\n")[1].split())
+    assert (kb, kmin, kmax) == (2048, 256, 4096)
+    vbar = 0.5
+    # hand-computed: 2048*0.3/0.5 = 1228.8 -> 1228 ; 2048*0.05/0.5 = 204.8 -> 204 -> 256 ; 2048*1.2/0.5 = 4915.2 -> 4096
+    k = O.adaptive_k(np.array([0.3, 0.05, 1.2, 0.5, 0.0, 0.25, 0.2499999]), vbar, kb, kmin, kmax)
+    assert k.tolist() == [1228, 256, 4096, 2048, 256, 1024, 1023]
+
+
+def test_adaptive_k_bounds_and_monotone():
+    r = rng(11)
+    var = np.sort(r.uniform(0, 3, 4000))
+    for mode in (0, 1):
+        k = O.adaptive_k(var, 0.7, 100, 16, 333, mode=mode)
+        assert k.min() >= 16 and k.max() <= 333
+        d = np.diff(k)
+        assert np.all(d >= 0) if mode == 0 else np.all(d <= 0)
+        assert len(np.unique(k)) > 50            # not a constant
+        for v in var[::97]:
+            assert int(O.adaptive_k(np.array(v), 0.7, 100, 16, 333, mode=mode)) == N.adaptive_k(float(v), 0.7, 100, 16, 333, mode)
+    assert int(O.adaptive_k(np.array(0.0), 0.7, 100, 16, 333, mode=1)) == 333      # zero spread: largest budget
+    assert int(O.adaptive_k(np.array(0.7), 0.7, 100, 16, 333, mode=1)) == 100
+    assert O.adaptive_k(var, 0.7, 100, 16, 333, k_fixed=64).tolist() == [64] * 4000
+    with pytest.raises(ValueError):
+        O.adaptive_k(var, 0.0, 100, 16, 333)
+
+
+# ---------------------------------------------------------------- Eq. 4 selection
+def test_topk_ties_take_lowest_index():
+    assert O.topk_select_row(np.full(10, 0.75), 4).tolist() == [0, 1, 2, 3]
+    row = np.array([0.5, 0.9, 0.5, 0.9, 0.5, 0.9])
+    assert O.topk_select_row(row, 2).tolist() == [1, 3]
+    assert O.topk_select_row(row, 4).tolist() == [0, 1, 3, 5]
+    assert O.topk_select_row(row, 99).tolist() == [0, 1, 2, 3, 4, 5]
+
+
+def test_topk_monotone_scores():
+    n, m = 50, 7
+    inc = np.linspace(0.1, 0.9, n)
+    assert O.topk_select_row(inc, m).tolist() == list(range(n - m, n))
+    assert O.topk_select_row(inc[::-1].copy(), m).tolist() == list(range(m))
+
+
+def test_topk_vs_full_sort_and_naive():
+    r = rng(13)
+    for trial in range(40):
+        n = int(r.integers(1, 40))
+        row = np.round(r.uniform(0, 4, n), 1)          # coarse grid: many exact ties
+        m = int(r.integers(1, n + 1))
+        want = sorted(sorted(range(n), key=lambda s: (-row[s], s))[:m])
+        assert O.topk_select_row(row, m).tolist() == want
+        assert N.topk(list(row), m) == want
+
+
+def test_indexer_through_selection_increasing():
+    """k^I_s = (s/L) e_1, q = e_1 gives scores strictly increasing in s, so S_t is the last n_sel visible keys."""
+    L, dI = 16, 4
+    qI = np.zeros((1, L, 2, dI)); qI[..., 0] = 1.0
+    kI = np.zeros((1, L, dI)); kI[0, :, 0] = np.arange(L) / L
+    w = np.full((1, L, 2), 0.5)
+    S, _, _ = O.indexer_scores(qI, kI, w, None, 0)
+    for t in range(L):
+        n_sel = min(5, t + 1)
+        assert O.topk_select_row(S[0, t, :t + 1], 5).tolist() == list(range(t - n_sel + 1, t + 1))
+
+
+# ---------------------------------------------------------------- Sec. 3.5 / 3.6 attention
+def _all_visible_idx(i, q_offset, Lk):
+    return np.arange(O.n_visible(i, q_offset, Lk))
+
+
+def test_sparse_equals_dense_when_budget_covers_everything():
+    """With S_t = all visible keys, Sec. 3.6 is Eq. 2 with V -> V' and the G1 factor."""
+    t = _tiny(17, B=2, Lq=6, Lk=9, q_offset=3)
+    dense = O.dense_causal_gated_attn(t["Q"], t["K"], t["V"], t["g1"], t["g2"], 3)
+    ctl = dict(vbar=1.0, k_base=1, k_min=1, k_max=64, k_fixed=64)
+    full = O.gsa_forward(t["Q"], t["K"], t["V"], t["g1"], t["g2"], t["qI"], t["kI"], t["w"], t["bI"], 3, ctl)
+    assert np.allclose(full["out"], dense, rtol=1e-12, atol=1e-14)
+    assert full["n_sel"][0].tolist() == [4, 5, 6, 7, 8, 9]
+
+
+def test_gates_open_reduce_to_library_sdpa():
+    """Gate logits -> +inf make both sigmoids exactly 1 (Sec. 2.3): dense causal GQA attention,
+    which torch's scaled_dot_product_attention computes independently (fp64, CPU)."""
+    B, L, H, Hkv, dh = 2, 10, 4, 2, 8
+    t = _tiny(19, B=B, Lq=L, Lk=L, H=H, Hkv=Hkv, dh=dh)
+    big = np.full_like(t["g1"], np.inf), np.full_like(t["g2"], 1.0e4)
+    got = O.dense_causal_gated_attn(t["Q"], t["K"], t["V"], big[0], big[1], 0)
+    q = torch.from_numpy(t["Q"]).permute(0, 2, 1, 3)
+    k = torch.from_numpy(t["K"]).permute(0, 2, 1, 3).repeat_interleave(H // Hkv, dim=1)
+    v = torch.from_numpy(t["V"]).permute(0, 2, 1, 3).repeat_interleave(H // Hkv, dim=1)
+    ref = torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=True).permute(0, 2, 1, 3).numpy()
+    assert np.allclose(got, ref, rtol=1e-12, atol=1e-14)
+    # the sparse routine on an arbitrary subset equals SDPA restricted to that subset
+    idx = np.array([0, 2, 3, 7])
+    out, A = O.sparse_gated_attn_row(t["Q"][1, 9], t["K"][1], t["V"][1], None, None, idx)
+    ks = k[1][:, idx]; vs = v[1][:, idx]
+    ref2 = torch.nn.functional.scaled_dot_product_attention(q[1][:, 9:10], ks, vs)[:, 0].numpy()
+    assert np.allclose(out, ref2, rtol=1e-12, atol=1e-14)
+    assert np.allclose(A.sum(-1), 1.0, atol=1e-15)          # Sec. 3.6: weights normalised over S_t only
+
+
+def test_gate_algebra():
+    """Zero logits halve V and halve the output (factor 1/4); -inf logits kill the output (Sec. 5.3);
+    a gate only shrinks magnitudes (Sec. 5.4); Q = 0 gives the plain mean of V' over S_t."""
+    t = _tiny(23, B=1, Lq=8, Lk=8)
+    idx = np.array([1, 4, 6])
+    Qt, K, V = t["Q"][0, 7], t["K"][0], t["V"][0]
+    plain, _ = O.sparse_gated_attn_row(Qt, K, V, None, None, idx)
+    z1, z2 = np.zeros_like(t["g1"][0, 7]), np.zeros_like(t["g2"][0])
+    quarter, _ = O.sparse_gated_attn_row(Qt, K, V, z2, z1, idx)
+    assert np.allclose(quarter, 0.25 * plain, rtol=1e-14)
+    dead, _ = O.sparse_gated_attn_row(Qt, K, V, None, np.full_like(z1, -np.inf), idx)
+    assert np.all(dead == 0.0)
+    dead2, _ = O.sparse_gated_attn_row(Qt, K, V, np.full_like(z2, -np.inf), None, idx)
+    assert np.all(dead2 == 0.0)
+    nog1, _ = O.sparse_gated_attn_row(Qt, K, V, t["g2"][0], None, idx)
+    both, _ = O.sparse_gated_attn_row(Qt, K, V, t["g2"][0], t["g1"][0, 7], idx)
+    assert np.all(np.abs(both) <= np.abs(nog1)) and np.all(np.abs(both) > 0)
+    # Q = 0: uniform weights
+    o0, A0 = O.sparse_gated_attn_row(np.zeros_like(Qt), K, V, t["g2"][0], None, idx)
+    assert np.allclose(A0, 1.0 / 3.0)
+    Vp = V * (0.5 * (1 + np.tanh(0.5 * t["g2"][0])))
+    H, Hkv = 4, 2
+    for h in range(H):
+        assert np.allclose(o0[h], Vp[idx, h // (H // Hkv)].mean(0), rtol=1e-13)
+
+
+def test_attention_matches_naive_loops_and_scale():
+    t = _tiny(29, B=1, Lq=6, Lk=6, H=4, Hkv=1, dh=6)
+    idx = np.array([0, 2, 5])
+    out, _ = O.sparse_gated_attn_row(t["Q"][0, 5], t["K"][0], t["V"][0], t["g2"][0], t["g1"][0, 5], idx)
+    outn = N.sparse_gated_attn(t["Q"][0, 5], t["K"][0], t["V"][0], t["g2"][0], t["g1"][0, 5], list(idx), 4, 1, 6)
+    assert np.allclose(out, np.array(outn), rtol=1e-13)
+    out2, _ = O.sparse_gated_attn_row(t["Q"][0, 5], t["K"][0], t["V"][0], None, None, idx, scale=0.3)
+    outn2 = N.sparse_gated_attn(t["Q"][0, 5], t["K"][0], t["V"][0], None, None, list(idx), 4, 1, 6, scale=0.3)
+    assert np.allclose(out2, np.array(outn2), rtol=1e-13)
+    assert not np.allclose(out2, O.sparse_gated_attn_row(t["Q"][0, 5], t["K"][0], t["V"][0], None, None, idx)[0])
+
+
+# ---------------------------------------------------------------- whole path
+def test_forward_tiny_vs_naive_pipeline():
+    """Tiny case against the loop version stage by stage (Sec. 4 'Processing stages')."""
+    B, Lq, Lk, H, Hkv, dh, HI, dI = 1, 9, 9, 2, 1, 4, 2, 3
+    t = _tiny(31, B=B, Lq=Lq, Lk=Lk, H=H, Hkv=Hkv, dh=dh, HI=HI, dI=dI)
+    ctl = dict(vbar=0.02, k_base=4, k_min=2, k_max=6, k_fixed=0, mode=0)
+    full = O.gsa_forward(t["Q"], t["K"], t["V"], t["g1"], t["g2"], t["qI"], t["kI"], t["w"], t["bI"], 0, ctl)
+    Sn = N.indexer_scores(t["qI"], t["kI"], t["w"], t["bI"], 0, B, Lq, Lk, HI, dI)
+    ks = set()
+    for i in range(Lq):
+        k = N.adaptive_k(N.variance(Sn[0][i]), 0.02, 4, 2, 6)
+        ks.add(k)
+        idx = N.topk(Sn[0][i], k)
+        assert full["k"][0, i] == k and full["n_sel"][0, i] == len(idx) == min(k, i + 1)
+        assert full["idx"][0, i, :len(idx)].tolist() == idx and np.all(full["idx"][0, i, len(idx):] == -1)
+        on = N.sparse_gated_attn(t["Q"][0][i], t["K"][0], t["V"][0], t["g2"][0], t["g1"][0][i], idx, H, Hkv, dh)
+        assert np.allclose(full["out"][0, i], np.array(on), rtol=1e-12)
+    assert len(ks) >= 3          # the controller really varied
+
+
+def test_decode_row_equals_last_prefill_row_and_batches_are_independent():
+    t = _tiny(37, B=2, Lq=8, Lk=8)
+    ctl = dict(vbar=0.03, k_base=4, k_min=2, k_max=5, k_fixed=0, mode=0)
+    full = O.gsa_forward(t["Q"], t["K"], t["V"], t["g1"], t["g2"], t["qI"], t["kI"], t["w"], t["bI"], 0, ctl)
+    dec = O.gsa_forward(t["Q"][:, 7:], t["K"], t["V"], t["g1"][:, 7:], t["g2"], t["qI"][:, 7:], t["kI"], t["w"][:, 7:],
+                        t["bI"], 7, ctl)
+    assert np.array_equal(dec["idx"][:, 0], full["idx"][:, 7]) and np.allclose(dec["out"][:, 0], full["out"][:, 7], rtol=1e-14)
+    for b in range(2):
+        one = O.gsa_forward(*(t[k][b:b + 1] for k in ("Q", "K", "V", "g1", "g2", "qI", "kI", "w")), t["bI"], 0, ctl)
+        assert np.array_equal(one["idx"][0], full["idx"][b]) and np.array_equal(one["out"][0], full["out"][b])
+
+
+# ---------------------------------------------------------------- cost model (host bookkeeping)
+def test_cost_model_reproduces_printed_speedup():
+    """Cor. 2 / App. A print 16 * 1/1.25 = 12.8x for d=4096, d^I=64, H^I=4, k=2048, L=128000, and 0.002."""
+    from paper_2601_15305_amd import cost_model as C
+    gold = dict(l.split() for l in open(os.path.join(GOLD, "cost_model.txt")) if l.strip() and not l.startswith("#"))
+    d, dI, HI, k, L, n_h = 4096, 64, 4, 2048, 128000, 32
+    assert d / (dI * HI) == float(gold["leading_factor"])
+    bracket = 1.0 + k * d / (L * dI * HI)
+    assert abs(bracket - 1.256) < 1e-12 and round(bracket - 0.005, 2) == float(gold["bracket_as_printed"])
+    s = C.speedup_vs_dense(d, dI, HI, k, L)
+    assert abs(s - 16.0 / 1.256) < 1e-12 and abs(s - float(gold["speedup_as_printed"])) < 0.1
+    assert round(C.indexer_cost_ratio(dI, HI, d, n_h), 3) == float(gold["indexer_ratio_as_printed"])
+    # exact pair counts against brute force
+    for (B, Lq, Lk, off) in [(1, 5, 5, 0), (2, 3, 9, 6), (1, 1, 7, 6), (3, 4, 6, 1)]:
+        brute = B * sum(min(off + i, Lk - 1) + 1 for i in range(Lq))
+        assert C.causal_pairs(B, Lq, Lk, off) == brute
+    assert C.indexer_flops(10, 4, 64) == 5120 and C.attention_flops(3, 16, 128) == 3 * 8192
+    assert C.gathered_bytes(5, 4, 128, 2) == 5 * 2048 and C.gathered_bytes(5, 4, 128, 2, True) == 5 * 3072
