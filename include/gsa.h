@@ -1,0 +1,171 @@
+/*
+ * libgsa -- forward path of Gated Sparse Attention (GSA) on AMD MI355X (gfx950).
+ *
+ * C ABI.  Every pointer named "device" is GPU memory owned by the caller; the
+ * library never allocates, never frees and never synchronises: each call
+ * validates its arguments on the host, enqueues kernels on the caller's HIP
+ * stream (`stream` is a hipStream_t passed as void*, NULL = default stream)
+ * and returns.  Scratch memory is a caller-supplied workspace whose size is
+ * queried with the *_workspace_bytes helpers.  The library keeps no state
+ * between calls apart from the text of the last HIP error of the calling
+ * thread.
+ *
+ * Notation follows the paper: L (Lq query rows, Lk keys), H = n_h query
+ * heads, H_kv = n_kv key-value heads, d_h = d_k head dimension, HI = H^I
+ * indexer heads, dI = d^I indexer dimension, k_min/k_max/k_base the budget
+ * bounds of the adaptive controller.
+ *
+ * Layouts (row-major, token-major, innermost index last):
+ *   qI [B, Lq, HI, dI]   kI [B, Lk, dI]          w [B, Lq, HI] fp32   bI [HI] fp32
+ *   Q, g1, out [B, Lq, H, d_h]                   K, V, g2 [B, Lk, H_kv, d_h]
+ *   idx [B, Lq, k_cap] int32                     n_sel, k [B, Lq] int32
+ *   row_mean, row_var [B, Lq] fp32
+ * qI, kI, Q, K, V, g1, g2, out have the element type named by gsa_shape.dtype;
+ * all base pointers must be 16-byte aligned.
+ *
+ * Causality: query row i has absolute position p = q_offset + i and sees keys
+ * s = 0 .. min(p, Lk-1), itself included.  Prefill: Lq = Lk, q_offset = 0.
+ * Decode: Lq = 1, q_offset = Lk - 1.
+ *
+ * Return value of every call: GSA_OK or a negative gsa_status.  All argument
+ * errors are detected before anything is launched.
+ */
+#ifndef GSA_H
+#define GSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum gsa_dtype { GSA_F32 = 0, GSA_BF16 = 1 };
+
+enum gsa_status {
+    GSA_OK = 0,
+    GSA_ERR_NULL = -1,        /* a required pointer is NULL */
+    GSA_ERR_SHAPE = -2,       /* non-positive or inconsistent dimensions / row range / k bounds */
+    GSA_ERR_UNSUPPORTED = -3, /* d_h, dI, HI, H/H_kv or dtype outside what the kernels are built for */
+    GSA_ERR_VBAR = -4,        /* controller on and vbar not a positive finite number */
+    GSA_ERR_WORKSPACE = -5,   /* workspace NULL, misaligned (256 B) or too small */
+    GSA_ERR_HIP = -6          /* a launch failed; see gsa_last_error() */
+};
+
+/* Problem shape.  Supported: d_h in {64,128}; dI in {32,64,128}; HI in {1,2,4,8};
+ * H % H_kv == 0 and H/H_kv <= 16; Lk <= 2^20; q_offset + Lq <= Lk. */
+typedef struct gsa_shape {
+    int32_t B, Lq, Lk, q_offset;
+    int32_t H, H_kv, d_h;
+    int32_t HI, dI;
+    int32_t dtype; /* gsa_dtype */
+} gsa_shape;
+
+/* Adaptive sparsity controller, Sec. 3.4, Eq. "adaptive_k":
+ *   k_t = clamp(floor(k_base * Var(I_t,:) / vbar), k_min, k_max).
+ * mode 0 is that equation as printed; mode 1 uses the inverse ratio
+ * k_base * vbar / Var (Var = 0 gives k_max), which is what the prose of the
+ * same section describes.  k_fixed > 0 turns the controller off: k_t = k_fixed.
+ * vbar is the moving average of the score variance, a frozen input here. */
+typedef struct gsa_adaptive {
+    float vbar;
+    int32_t k_base, k_min, k_max;
+    int32_t k_fixed;
+    int32_t mode;
+} gsa_adaptive;
+
+/* ---- stage 1: gated lightning indexer, Sec. 3.3, Eq. "indexer" ----------------------
+ *   I[t,s] = sum_j w[t,j] * sigmoid(qI[t,j,:] . kI[s,:] + bI[j])   for every visible s,
+ * with no 1/sqrt(dI) factor, plus the mean and the population variance of each
+ * row's visible scores (the Var(I_t,:) that Sec. 3.4 consumes).
+ * Rows [row_begin, row_end) of every batch element are computed.
+ *   qI, kI   device, in   dtype elements
+ *   w        device, in   fp32, the head weights sigma(h_t W^Iw_j), already in (0,1)
+ *   bI       device, in   fp32 [HI], or NULL for zero bias
+ *   scores   device, out  fp32, or NULL to compute only the statistics.  Element
+ *            (b, t, s) is written at scores[(b*(row_end-row_begin) + (t-row_begin))*ld_scores + s];
+ *            positions of invisible keys are left untouched.  ld_scores >= Lk, multiple of 4.
+ *   row_mean device, out  fp32 [B, Lq] (only rows in range written), may be NULL
+ *   row_var  device, out  fp32 [B, Lq] (only rows in range written)
+ *   workspace device scratch of gsa_indexer_workspace_bytes(shape, row_begin, row_end) bytes.
+ */
+int32_t gsa_indexer_scores(const gsa_shape* shape, const void* qI, const void* kI, const float* w,
+                           const float* bI, int32_t row_begin, int32_t row_end, float* scores,
+                           int64_t ld_scores, float* row_mean, float* row_var, void* workspace,
+                           size_t workspace_bytes, void* stream);
+size_t gsa_indexer_workspace_bytes(const gsa_shape* shape, int32_t row_begin, int32_t row_end);
+
+/* ---- stage 2: adaptive sparsity controller, Sec. 3.4 --------------------------------
+ *   k[b,t]     = the budget of Eq. "adaptive_k" (always within [k_min, k_max], or k_fixed)
+ *   n_sel[b,t] = min(k[b,t], number of visible keys of row t)
+ *   row_var device, in, fp32 [B, Lq];  k_out (may be NULL), n_sel_out device, out, int32 [B, Lq].
+ * The ratio is evaluated in double precision from the fp32 variance; floor comes
+ * before the clamp.  Errors: GSA_ERR_VBAR, GSA_ERR_SHAPE (k_min < 1, k_min > k_max, k_base < 1). */
+int32_t gsa_adaptive_k(const gsa_shape* shape, const gsa_adaptive* ctl, const float* row_var,
+                       int32_t* k_out, int32_t* n_sel_out, void* stream);
+
+/* ---- stage 3: top-k_t selection, Sec. 2.2 Eq. 4 (used with k_t in Sec. 3.2) ---------
+ * For each row in [row_begin,row_end): the n_sel[b,t] visible keys with the largest score;
+ * equal scores are taken lowest index first.  idx_out[b,t,0:n_sel] holds them in ascending
+ * order, the rest of the k_cap entries is -1.  One set per query, shared by all heads.
+ *   scores  device, in, fp32, laid out as written by gsa_indexer_scores for the same row range;
+ *           must be >= 0 and finite (the paper's scores lie in (0, HI)); negative values
+ *           are ranked as 0.
+ *   n_sel   device, in, int32 [B, Lq]; values above min(k_cap, visible) are clamped.
+ *   idx_out device, out, int32 [B, Lq, k_cap] (only rows in range written); 1 <= k_cap <= 8192.
+ * No workspace. */
+int32_t gsa_topk_select(const gsa_shape* shape, int32_t row_begin, int32_t row_end, const float* scores,
+                        int64_t ld_scores, const int32_t* n_sel, int32_t k_cap, int32_t* idx_out,
+                        void* stream);
+
+/* ---- stage 4: sparse attention with value gate G2 and output gate G1, Sec. 3.5-3.6 --
+ * For query head h (kv head g = h / (H/H_kv)) over S_t = idx[b,t,0:n_sel[b,t]]:
+ *   A[s]  = softmax_{s in S_t}(softmax_scale * Q[t,h,:] . K[s,g,:])
+ *   O     = sum_s A[s] * (V[s,g,:] * sigmoid(g2[s,g,:]))          (G2, before aggregation)
+ *   out[t,h,:] = O * sigmoid(g1[t,h,:])                            (G1, after SDPA)
+ * Rows [row_begin,row_end) are computed.  g2 == NULL: V is taken as already gated.
+ * g1 == NULL: no output gate.  softmax_scale == 0 selects 1/sqrt(d_h).  A row with
+ * n_sel == 0 produces zeros.  Indices are clamped into [0, Lk-1] before use.
+ * bf16: products on the matrix cores with fp32 accumulation, probabilities and gated
+ * values rounded to bf16 before the PV product, result rounded to bf16.  f32: fp32 throughout.
+ *   workspace: gsa_attn_workspace_bytes(...) bytes (0 unless the kernel splits a row's
+ *   selected set over several workgroups, which it does when B*(row_end-row_begin) is small). */
+int32_t gsa_sparse_gated_attn(const gsa_shape* shape, int32_t row_begin, int32_t row_end, const void* Q,
+                              const void* K, const void* V, const void* g2_logits, const void* g1_logits,
+                              const int32_t* idx, const int32_t* n_sel, int32_t k_cap, float softmax_scale,
+                              void* out, void* workspace, size_t workspace_bytes, void* stream);
+size_t gsa_attn_workspace_bytes(const gsa_shape* shape, int32_t row_begin, int32_t row_end, int32_t k_cap);
+
+/* ---- the value gate as a dense pre-pass, Sec. 3.5 / stage (2) of Sec. 4 -------------
+ * Vg = V * sigmoid(g2), element-wise over [B, Lk, H_kv, d_h], rounded to dtype.  Vg may alias V. */
+int32_t gsa_value_gate(const gsa_shape* shape, const void* V, const void* g2_logits, void* Vg, void* stream);
+
+/* ---- fused forward: stages 1-4 in the order of Sec. 3.2 / Sec. 4 --------------------
+ * G2 (dense pre-pass into the workspace when g2 != NULL) -> indexer -> controller ->
+ * top-k_t -> sparse SDPA -> G1, processed in slabs of query rows so that the score
+ * matrix never exists as a whole.
+ *   out          device, out [B, Lq, H, d_h]
+ *   idx_out      device, out [B, Lq, k_cap] or NULL (then kept per slab in the workspace)
+ *   n_sel_out, k_out   device, out [B, Lq] or NULL
+ *   row_var_out  device, out [B, Lq] or NULL
+ *   k_cap        >= k_max (or >= k_fixed), <= 8192
+ *   workspace    at least gsa_forward_workspace_bytes(shape, k_cap, g2 != NULL, 0) bytes;
+ *                a larger workspace lets the call use larger slabs (fewer launches).
+ * gsa_forward_workspace_bytes(.., slab_rows): bytes needed to run with slabs of that many
+ * query rows (rounded up to a multiple of 32); slab_rows = 0 gives the minimum. */
+int32_t gsa_forward(const gsa_shape* shape, const gsa_adaptive* ctl, const void* Q, const void* K,
+                    const void* V, const void* g1_logits, const void* g2_logits, const void* qI,
+                    const void* kI, const float* w, const float* bI, float softmax_scale, void* out,
+                    int32_t* idx_out, int32_t* n_sel_out, int32_t* k_out, float* row_var_out,
+                    int32_t k_cap, void* workspace, size_t workspace_bytes, void* stream);
+size_t gsa_forward_workspace_bytes(const gsa_shape* shape, int32_t k_cap, int32_t has_g2, int32_t slab_rows);
+
+/* ---- misc ---------------------------------------------------------------------------- */
+const char* gsa_status_string(int32_t status); /* static string */
+const char* gsa_last_error(void);              /* text of the calling thread's last HIP error, "" if none */
+int32_t gsa_version(void);                     /* major*10000 + minor*100 + patch */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GSA_H */

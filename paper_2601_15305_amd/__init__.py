@@ -1,0 +1,193 @@
+"""libgsa: forward path of Gated Sparse Attention on MI355X.
+
+Thin ctypes binding over the C ABI declared in include/gsa.h.  The functions
+have the same names as the C entry points and only marshal arguments: torch
+tensors supply device memory and the current stream, every step of the path
+runs in the HIP kernels of libgsa.so.  There is no fallback: if the library
+has not been built, loading it raises.
+"""
+import ctypes
+import os
+
+import torch
+
+from . import synthetic  # noqa: F401  (input generators, no arithmetic of the method)
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgsa.so")
+
+GSA_F32, GSA_BF16 = 0, 1
+GSA_OK = 0
+GSA_ERR_NULL, GSA_ERR_SHAPE, GSA_ERR_UNSUPPORTED, GSA_ERR_VBAR, GSA_ERR_WORKSPACE, GSA_ERR_HIP = -1, -2, -3, -4, -5, -6
+
+ENTRY_POINTS = (
+    "gsa_indexer_scores", "gsa_indexer_workspace_bytes", "gsa_adaptive_k", "gsa_topk_select",
+    "gsa_sparse_gated_attn", "gsa_attn_workspace_bytes", "gsa_value_gate", "gsa_forward",
+    "gsa_forward_workspace_bytes", "gsa_status_string", "gsa_last_error", "gsa_version",
+)
+
+
+class GsaShape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("B", "Lq", "Lk", "q_offset", "H", "H_kv", "d_h", "HI", "dI", "dtype")]
+
+
+class GsaAdaptive(ctypes.Structure):
+    _fields_ = [("vbar", ctypes.c_float)] + [(n, ctypes.c_int32) for n in ("k_base", "k_min", "k_max", "k_fixed", "mode")]
+
+
+class GsaError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        lib = load()
+        msg = lib.gsa_status_string(status).decode()
+        extra = lib.gsa_last_error().decode() if status == GSA_ERR_HIP else ""
+        super().__init__("%s: %s (%d) %s" % (where, msg, status, extra))
+
+
+_lib = None
+
+
+def load():
+    """Load libgsa.so (built in-tree by paper_2601_15305_amd.build).  Raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libgsa.so is not built: run `python -m paper_2601_15305_amd.build` (no fallback path exists)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, sz, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t, ctypes.c_float
+    shp, ctl = ctypes.POINTER(GsaShape), ctypes.POINTER(GsaAdaptive)
+    lib.gsa_indexer_scores.argtypes = [shp, vp, vp, vp, vp, i32, i32, vp, i64, vp, vp, vp, sz, vp]
+    lib.gsa_indexer_scores.restype = i32
+    lib.gsa_indexer_workspace_bytes.argtypes = [shp, i32, i32]
+    lib.gsa_indexer_workspace_bytes.restype = sz
+    lib.gsa_adaptive_k.argtypes = [shp, ctl, vp, vp, vp, vp]
+    lib.gsa_adaptive_k.restype = i32
+    lib.gsa_topk_select.argtypes = [shp, i32, i32, vp, i64, vp, i32, vp, vp]
+    lib.gsa_topk_select.restype = i32
+    lib.gsa_sparse_gated_attn.argtypes = [shp, i32, i32, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
+    lib.gsa_sparse_gated_attn.restype = i32
+    lib.gsa_attn_workspace_bytes.argtypes = [shp, i32, i32, i32]
+    lib.gsa_attn_workspace_bytes.restype = sz
+    lib.gsa_value_gate.argtypes = [shp, vp, vp, vp, vp]
+    lib.gsa_value_gate.restype = i32
+    lib.gsa_forward.argtypes = [shp, ctl, vp, vp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, i32, vp, sz, vp]
+    lib.gsa_forward.restype = i32
+    lib.gsa_forward_workspace_bytes.argtypes = [shp, i32, i32, i32]
+    lib.gsa_forward_workspace_bytes.restype = sz
+    lib.gsa_status_string.argtypes = [i32]
+    lib.gsa_status_string.restype = ctypes.c_char_p
+    lib.gsa_last_error.argtypes = []
+    lib.gsa_last_error.restype = ctypes.c_char_p
+    lib.gsa_version.argtypes = []
+    lib.gsa_version.restype = i32
+    _lib = lib
+    return lib
+
+
+# ------------------------------------------------------------------------------- marshalling
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    assert t.is_contiguous(), "libgsa takes dense row-major tensors"
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is not None:
+        return stream
+    if torch.cuda.is_available():
+        return torch.cuda.current_stream().cuda_stream
+    return None
+
+
+def make_shape(B, Lq, Lk, q_offset, H, H_kv, d_h, HI, dI, dtype):
+    code = {"f32": GSA_F32, "bf16": GSA_BF16, torch.float32: GSA_F32, torch.bfloat16: GSA_BF16}.get(dtype, dtype)
+    return GsaShape(B, Lq, Lk, q_offset, H, H_kv, d_h, HI, dI, code)
+
+
+def shape_of(wl):
+    """gsa_shape of a synthetic.Workload."""
+    return make_shape(wl.B, wl.Lq, wl.Lk, wl.q_offset, wl.H, wl.H_kv, wl.d_h, wl.HI, wl.dI, wl.dtype)
+
+
+def make_adaptive(vbar, k_base, k_min, k_max, k_fixed=0, mode=0):
+    return GsaAdaptive(float(vbar), k_base, k_min, k_max, k_fixed, mode)
+
+
+def _check(rc, where):
+    if rc != GSA_OK:
+        raise GsaError(rc, where)
+
+
+# ------------------------------------------------------------------------------- entry points
+def gsa_version():
+    return load().gsa_version()
+
+
+def gsa_indexer_workspace_bytes(shape, row_begin, row_end):
+    return load().gsa_indexer_workspace_bytes(ctypes.byref(shape), row_begin, row_end)
+
+
+def gsa_indexer_scores(shape, qI, kI, w, bI, row_begin, row_end, scores, ld_scores, row_mean, row_var, workspace,
+                       workspace_bytes=None, stream=None):
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load().gsa_indexer_scores(ctypes.byref(shape), _ptr(qI), _ptr(kI), _ptr(w), _ptr(bI), row_begin, row_end,
+                                   _ptr(scores), ld_scores, _ptr(row_mean), _ptr(row_var), _ptr(workspace),
+                                   workspace_bytes, _stream(stream))
+    _check(rc, "gsa_indexer_scores")
+
+
+def gsa_adaptive_k(shape, ctl, row_var, k_out, n_sel_out, stream=None):
+    rc = load().gsa_adaptive_k(ctypes.byref(shape), ctypes.byref(ctl) if ctl is not None else None, _ptr(row_var),
+                               _ptr(k_out), _ptr(n_sel_out), _stream(stream))
+    _check(rc, "gsa_adaptive_k")
+
+
+def gsa_topk_select(shape, row_begin, row_end, scores, ld_scores, n_sel, k_cap, idx_out, stream=None):
+    rc = load().gsa_topk_select(ctypes.byref(shape), row_begin, row_end, _ptr(scores), ld_scores, _ptr(n_sel), k_cap,
+                                _ptr(idx_out), _stream(stream))
+    _check(rc, "gsa_topk_select")
+
+
+def gsa_attn_workspace_bytes(shape, row_begin, row_end, k_cap):
+    return load().gsa_attn_workspace_bytes(ctypes.byref(shape), row_begin, row_end, k_cap)
+
+
+def gsa_sparse_gated_attn(shape, row_begin, row_end, Q, K, V, g2_logits, g1_logits, idx, n_sel, k_cap, softmax_scale,
+                          out, workspace=None, workspace_bytes=None, stream=None):
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load().gsa_sparse_gated_attn(ctypes.byref(shape), row_begin, row_end, _ptr(Q), _ptr(K), _ptr(V),
+                                      _ptr(g2_logits), _ptr(g1_logits), _ptr(idx), _ptr(n_sel), k_cap,
+                                      float(softmax_scale), _ptr(out), _ptr(workspace), workspace_bytes, _stream(stream))
+    _check(rc, "gsa_sparse_gated_attn")
+
+
+def gsa_value_gate(shape, V, g2_logits, Vg, stream=None):
+    rc = load().gsa_value_gate(ctypes.byref(shape), _ptr(V), _ptr(g2_logits), _ptr(Vg), _stream(stream))
+    _check(rc, "gsa_value_gate")
+
+
+def gsa_forward_workspace_bytes(shape, k_cap, has_g2, slab_rows=0):
+    return load().gsa_forward_workspace_bytes(ctypes.byref(shape), k_cap, int(bool(has_g2)), slab_rows)
+
+
+def gsa_forward(shape, ctl, Q, K, V, g1_logits, g2_logits, qI, kI, w, bI, softmax_scale, out, idx_out, n_sel_out, k_out,
+                row_var_out, k_cap, workspace, workspace_bytes=None, stream=None):
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load().gsa_forward(ctypes.byref(shape) if shape is not None else None,
+                            ctypes.byref(ctl) if ctl is not None else None, _ptr(Q), _ptr(K), _ptr(V),
+                            _ptr(g1_logits), _ptr(g2_logits), _ptr(qI), _ptr(kI), _ptr(w), _ptr(bI), float(softmax_scale),
+                            _ptr(out), _ptr(idx_out), _ptr(n_sel_out), _ptr(k_out), _ptr(row_var_out), k_cap,
+                            _ptr(workspace), workspace_bytes, _stream(stream))
+    _check(rc, "gsa_forward")
+
+
+def workspace(nbytes, device="cuda"):
+    """Device scratch of at least nbytes, 256-byte aligned (torch's allocator aligns to 512)."""
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)

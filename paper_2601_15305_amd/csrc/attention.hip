@@ -1,0 +1,379 @@
+// Sparse attention over the selected keys with the value gate G2 and the output gate G1
+// (Sec. 3.5 and Sec. 3.6):
+//   A[s] = softmax_{s in S_t}(scale * Q[t,h,:] . K[s,g,:]),  O = sum_s A[s] (V[s,g,:] * sigmoid(g2[s,g,:])),
+//   out[t,h,:] = O * sigmoid(g1[t,h,:]),   g = h / (H / H_kv).
+//
+// bf16 kernel.  One workgroup per query; wave w handles kv heads w, w+4, ...  For one kv head the
+// G = H/H_kv query heads that share it form the N dimension of the MFMAs (padded to 16), the
+// gathered tokens form M for the score product and K for the value product:
+//   S^T[token, head] = K[token, :] . Q[head, :]       A operand = gathered K rows, read from global
+//                                                     memory straight into the MFMA register layout
+//                                                     (a lane owns 16 consecutive bytes of a row);
+//   O^T[d, head]    += V'^T[d, token] . P^T[token, head]
+// The accumulator layout of S^T (a lane holds four tokens of one head) is exactly the B-operand
+// layout the second product needs, so probabilities never move between lanes.  V' rows go through
+// a wave-private LDS tile and come back transposed with the LDS transpose read of gfx950
+// (ds_read_b64_tr_b16), which turns 4 tokens x 16 features into the "feature row, token
+// contraction" A operand.  Softmax is the usual online form in base 2; G2 is applied to the V
+// rows in registers on their way to LDS, G1 to the accumulators before the store.
+#include "common.hpp"
+
+namespace gsa {
+
+struct AttnArgs {
+    const void* Q;
+    const void* K;
+    const void* V;
+    const void* g2;
+    const void* g1;
+    const int32_t* idx;
+    const int32_t* n_sel;
+    void* out;
+    int32_t B, Lq, Lk, H, H_kv, row_begin, row_end, k_cap;
+    int32_t idx_rows, idx_row0;  // idx holds rows [idx_row0, idx_row0+idx_rows) of every batch element
+    float scale;  // softmax scale
+};
+
+constexpr float kNegBig = -1.0e30f;
+
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+template <int DH, bool HAS_G2>
+__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
+    constexpr int KK = DH / 32;        // MFMA k-steps of the score product
+    constexpr int MB = DH / 16;        // 16-feature blocks of the value product
+    constexpr int ROWB = DH * 2;       // bytes of one head row
+    constexpr int VROW = ROWB + 32;    // padded LDS row
+    constexpr int VCH = ROWB / 16;     // 16-byte chunks per row
+    constexpr int TPI = 64 / VCH;      // tokens covered by one V load instruction
+    constexpr int NVL = 32 / TPI;      // V load instructions per 32-token tile
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wv = tid >> 6;
+    const int n = lane & 15;   // head within the group / token within a 16-token sub-tile
+    const int q = lane >> 4;   // k-chunk selector
+    unsigned char* vlds = smem + wv * (32 * VROW);
+
+    const int R = a.row_end - a.row_begin;
+    const int64_t rid = blockIdx.x;
+    const int b = (int)(rid / R);
+    const int t = a.row_begin + (int)(rid % R);
+    const int64_t qrow = (int64_t)b * a.Lq + t;
+    const int nsel = max(0, min(a.n_sel[qrow], a.k_cap));
+    const int32_t* idxrow = a.idx + ((int64_t)b * a.idx_rows + (t - a.idx_row0)) * a.k_cap;
+    const int G = a.H / a.H_kv;
+    const float sl2 = a.scale * kLog2e;
+    const int64_t tokstride = (int64_t)a.H_kv * ROWB;  // bytes between consecutive tokens
+    const int ntile = (nsel + 31) >> 5;
+
+    for (int g = wv; g < a.H_kv; g += 4) {
+        const int head = g * G + n;
+        const bool head_ok = n < G;
+        // ---- Q fragments (B operand): lane (head n, chunk q) holds features (4*kk+q)*8 .. +8 --------
+        bf16x8 qf[KK];
+        {
+            const u32x4* src = reinterpret_cast<const u32x4*>(static_cast<const __bf16*>(a.Q) + (qrow * a.H + (head_ok ? head : 0)) * DH);
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) {
+                u32x4 v = head_ok ? src[kk * 4 + q] : u32x4{0, 0, 0, 0};
+                qf[kk] = __builtin_bit_cast(bf16x8, v);
+            }
+        }
+        f32x4 o[MB];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) o[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        float mrun = kNegBig, lrun = 0.f;
+
+        const unsigned char* Kb = static_cast<const unsigned char*>(a.K) + ((int64_t)b * a.Lk * a.H_kv + g) * ROWB;
+        const unsigned char* Vb = static_cast<const unsigned char*>(a.V) + ((int64_t)b * a.Lk * a.H_kv + g) * ROWB;
+        const unsigned char* Gb = HAS_G2 ? static_cast<const unsigned char*>(a.g2) + ((int64_t)b * a.Lk * a.H_kv + g) * ROWB : nullptr;
+
+        u32x4 kf[2][KK];
+        u32x4 vf[NVL];
+        u32x4 gf[HAS_G2 ? NVL : 1];
+        auto load_tile = [&](int j0) {
+            int tok = idxrow[min(j0 + (lane & 31), nsel - 1)];
+            tok = max(0, min(tok, a.Lk - 1));
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) {
+                const int tk = __shfl(tok, sub * 16 + n, 64);
+                const unsigned char* p = Kb + (int64_t)tk * tokstride + q * 16;
+#pragma unroll
+                for (int kk = 0; kk < KK; ++kk) kf[sub][kk] = *reinterpret_cast<const u32x4*>(p + kk * 64);
+            }
+#pragma unroll
+            for (int r = 0; r < NVL; ++r) {
+                const int tk = __shfl(tok, r * TPI + lane / VCH, 64);
+                const int64_t off = (int64_t)tk * tokstride + (lane % VCH) * 16;
+                vf[r] = *reinterpret_cast<const u32x4*>(Vb + off);
+                if constexpr (HAS_G2) gf[r] = *reinterpret_cast<const u32x4*>(Gb + off);
+            }
+        };
+
+        if (ntile > 0) load_tile(0);
+        for (int it = 0; it < ntile; ++it) {
+            const int j0 = it * 32;
+            // ---- V' rows -> LDS (natural layout: row = token slot, 16 B per lane) -----------------
+#pragma unroll
+            for (int r = 0; r < NVL; ++r) {
+                u32x4 v = vf[r];
+                if constexpr (HAS_G2) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float v0 = bf16_bits_to_f32(v[e] & 0xffffu) * sigmoid_f32(bf16_bits_to_f32(gf[r][e] & 0xffffu));
+                        const float v1 = bf16_bits_to_f32(v[e] >> 16) * sigmoid_f32(bf16_bits_to_f32(gf[r][e] >> 16));
+                        v[e] = pack_bf16x2(v0, v1);
+                    }
+                }
+                *reinterpret_cast<u32x4*>(vlds + (r * TPI + lane / VCH) * VROW + (lane % VCH) * 16) = v;
+            }
+            u32x4 kc[2][KK];
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                for (int kk = 0; kk < KK; ++kk) kc[sub][kk] = kf[sub][kk];
+            if (it + 1 < ntile) load_tile(j0 + 32);
+
+            // ---- S^T = K . Q^T for two 16-token sub-tiles ------------------------------------------
+            f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) {
+                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kc[0][kk]), qf[kk], s0, 0, 0, 0);
+                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kc[1][kk]), qf[kk], s1, 0, 0, 0);
+            }
+            // lane (head n, q): s0[i] is token j0 + 4q + i, s1[i] is token j0 + 16 + 4q + i
+            float x[8];
+            float tmax = kNegBig;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                x[i] = (j0 + 4 * q + i < nsel) ? s0[i] * sl2 : kNegBig;
+                x[4 + i] = (j0 + 16 + 4 * q + i < nsel) ? s1[i] * sl2 : kNegBig;
+                tmax = fmaxf(tmax, fmaxf(x[i], x[4 + i]));
+            }
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+            const float mnew = fmaxf(mrun, tmax);
+            const float alpha = fast_exp2(mrun - mnew);
+            float psum = 0.f;
+            float p[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                p[i] = fast_exp2(x[i] - mnew);
+                psum += p[i];
+            }
+            lrun = lrun * alpha + psum;
+            mrun = mnew;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) o[mb] *= alpha;
+            u32x4 pw = {pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]), pack_bf16x2(p[4], p[5]), pack_bf16x2(p[6], p[7])};
+            const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
+
+            // ---- O^T += V'^T . P^T --------------------------------------------------------------------
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave's LDS writes have landed
+            {
+                const int r4 = (lane & 15) >> 2, c4 = lane & 3;
+                const unsigned char* p0 = vlds + (4 * q + r4) * VROW + c4 * 8;
+                const unsigned char* p1 = p0 + 16 * VROW;
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    s16x4 a0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p0 + mb * 32));
+                    s16x4 a1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p1 + mb * 32));
+                    typedef __attribute__((ext_vector_type(8))) short s16x8;
+                    s16x8 av = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+                    o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av), pf, o[mb], 0, 0, 0);
+                }
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // transpose reads done before the tile is overwritten
+        }
+
+        // ---- normalise, G1, store ---------------------------------------------------------------------
+        float ltot = lrun + __shfl_xor(lrun, 16, 64);
+        ltot += __shfl_xor(ltot, 32, 64);
+        if (head_ok) {
+            const float inv = ltot > 0.f ? 1.0f / ltot : 0.f;
+            const int64_t obase = (qrow * a.H + head) * DH;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                const int d0 = mb * 16 + 4 * q;
+                float y[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) y[i] = o[mb][i] * inv;
+                if (a.g1) {
+                    const u32x2 gw = *reinterpret_cast<const u32x2*>(static_cast<const __bf16*>(a.g1) + obase + d0);
+                    y[0] *= sigmoid_f32(bf16_bits_to_f32(gw[0] & 0xffffu));
+                    y[1] *= sigmoid_f32(bf16_bits_to_f32(gw[0] >> 16));
+                    y[2] *= sigmoid_f32(bf16_bits_to_f32(gw[1] & 0xffffu));
+                    y[3] *= sigmoid_f32(bf16_bits_to_f32(gw[1] >> 16));
+                }
+                u32x2 ow = {pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
+                *reinterpret_cast<u32x2*>(static_cast<__bf16*>(a.out) + obase + d0) = ow;
+            }
+        }
+    }
+}
+
+// fp32 kernel: plain vector arithmetic, one wave per query head, online softmax over chunks of 64
+// selected tokens (a lane computes one token's logit; then every lane owns DH/64 output features).
+template <int DH>
+__global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a) {
+    constexpr int DPL = DH / 64;  // features per lane (1 or 2)
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int R = a.row_end - a.row_begin;
+    const int64_t rid = blockIdx.x;
+    const int b = (int)(rid / R);
+    const int t = a.row_begin + (int)(rid % R);
+    const int64_t qrow = (int64_t)b * a.Lq + t;
+    const int nsel = max(0, min(a.n_sel[qrow], a.k_cap));
+    const int32_t* idxrow = a.idx + ((int64_t)b * a.idx_rows + (t - a.idx_row0)) * a.k_cap;
+    const int G = a.H / a.H_kv;
+    const float* Q = static_cast<const float*>(a.Q);
+    const float* K = static_cast<const float*>(a.K);
+    const float* V = static_cast<const float*>(a.V);
+    const float* G2 = static_cast<const float*>(a.g2);
+    const float* G1 = static_cast<const float*>(a.g1);
+    float* out = static_cast<float*>(a.out);
+
+    for (int h = wv; h < a.H; h += 4) {
+        const int g = h / G;
+        const float* qp = Q + (qrow * a.H + h) * DH;
+        float mrun = kNegBig, lrun = 0.f;
+        float o[DPL];
+#pragma unroll
+        for (int e = 0; e < DPL; ++e) o[e] = 0.f;
+        for (int j0 = 0; j0 < nsel; j0 += 64) {
+            const int j = j0 + lane;
+            int tok = idxrow[min(j, nsel - 1)];
+            tok = max(0, min(tok, a.Lk - 1));
+            const int64_t krow = (((int64_t)b * a.Lk + tok) * a.H_kv + g) * DH;
+            float acc = 0.f;
+            for (int c = 0; c < DH; c += 4) {
+                const float4 kv = *reinterpret_cast<const float4*>(K + krow + c);
+                const float4 qv = *reinterpret_cast<const float4*>(qp + c);
+                acc = fmaf(qv.x, kv.x, acc);
+                acc = fmaf(qv.y, kv.y, acc);
+                acc = fmaf(qv.z, kv.z, acc);
+                acc = fmaf(qv.w, kv.w, acc);
+            }
+            const float x = j < nsel ? acc * a.scale : kNegBig;
+            float cmax = x;
+#pragma unroll
+            for (int s = 32; s > 0; s >>= 1) cmax = fmaxf(cmax, __shfl_xor(cmax, s, 64));
+            const float mnew = fmaxf(mrun, cmax);
+            const float alpha = expf(mrun - mnew);
+            const float p = j < nsel ? expf(x - mnew) : 0.f;
+            lrun = lrun * alpha + wave_sum(p);
+            mrun = mnew;
+#pragma unroll
+            for (int e = 0; e < DPL; ++e) o[e] *= alpha;
+            const int cnt = min(64, nsel - j0);
+            for (int u = 0; u < cnt; ++u) {
+                const float pu = __shfl(p, u, 64);
+                const int tu = __shfl(tok, u, 64);
+                const int64_t vrow = (((int64_t)b * a.Lk + tu) * a.H_kv + g) * DH;
+#pragma unroll
+                for (int e = 0; e < DPL; ++e) {
+                    float v = V[vrow + lane + 64 * e];
+                    if (G2) v *= 1.0f / (1.0f + expf(-G2[vrow + lane + 64 * e]));
+                    o[e] = fmaf(pu, v, o[e]);
+                }
+            }
+        }
+        const float inv = lrun > 0.f ? 1.0f / lrun : 0.f;
+#pragma unroll
+        for (int e = 0; e < DPL; ++e) {
+            const int64_t oi = (qrow * a.H + h) * DH + lane + 64 * e;
+            float y = o[e] * inv;
+            if (G1) y *= 1.0f / (1.0f + expf(-G1[oi]));
+            out[oi] = y;
+        }
+    }
+}
+
+// Value gate as a dense pre-pass: Vg = V * sigmoid(g2), 8 elements (bf16) or 4 (f32) per thread.
+__global__ void value_gate_bf16_kernel(const u32x4* V, const u32x4* g2, u32x4* Vg, int64_t nchunks) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= nchunks) return;
+    u32x4 v = V[i];
+    const u32x4 g = g2[i];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float v0 = bf16_bits_to_f32(v[e] & 0xffffu) * sigmoid_f32(bf16_bits_to_f32(g[e] & 0xffffu));
+        const float v1 = bf16_bits_to_f32(v[e] >> 16) * sigmoid_f32(bf16_bits_to_f32(g[e] >> 16));
+        v[e] = pack_bf16x2(v0, v1);
+    }
+    Vg[i] = v;
+}
+__global__ void value_gate_f32_kernel(const float4* V, const float4* g2, float4* Vg, int64_t nchunks) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= nchunks) return;
+    float4 v = V[i];
+    const float4 g = g2[i];
+    v.x *= 1.0f / (1.0f + expf(-g.x));
+    v.y *= 1.0f / (1.0f + expf(-g.y));
+    v.z *= 1.0f / (1.0f + expf(-g.z));
+    v.w *= 1.0f / (1.0f + expf(-g.w));
+    Vg[i] = v;
+}
+
+hipError_t launch_value_gate(const gsa_shape& sh, const void* V, const void* g2, void* Vg, hipStream_t st) {
+    const int64_t elems = (int64_t)sh.B * sh.Lk * sh.H_kv * sh.d_h;
+    if (sh.dtype == GSA_BF16) {
+        const int64_t nch = elems / 8;
+        hipLaunchKernelGGL(value_gate_bf16_kernel, dim3((unsigned)cdiv(nch, 256)), dim3(256), 0, st,
+                           static_cast<const u32x4*>(V), static_cast<const u32x4*>(g2), static_cast<u32x4*>(Vg), nch);
+    } else {
+        const int64_t nch = elems / 4;
+        hipLaunchKernelGGL(value_gate_f32_kernel, dim3((unsigned)cdiv(nch, 256)), dim3(256), 0, st,
+                           static_cast<const float4*>(V), static_cast<const float4*>(g2), static_cast<float4*>(Vg), nch);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_attention(const gsa_shape& sh, int row_begin, int row_end, const void* Q, const void* K, const void* V,
+                            const void* g2, const void* g1, const int32_t* idx, int idx_rows, int idx_row0,
+                            const int32_t* n_sel, int k_cap, float scale, void* out, hipStream_t st) {
+    AttnArgs a;
+    a.Q = Q;
+    a.K = K;
+    a.V = V;
+    a.g2 = g2;
+    a.g1 = g1;
+    a.idx = idx;
+    a.n_sel = n_sel;
+    a.out = out;
+    a.B = sh.B;
+    a.Lq = sh.Lq;
+    a.Lk = sh.Lk;
+    a.H = sh.H;
+    a.H_kv = sh.H_kv;
+    a.row_begin = row_begin;
+    a.row_end = row_end;
+    a.k_cap = k_cap;
+    a.idx_rows = idx_rows;
+    a.idx_row0 = idx_row0;
+    a.scale = scale;
+    const int64_t rows = (int64_t)sh.B * (row_end - row_begin);
+    if (sh.dtype == GSA_BF16) {
+        const size_t smem = 4 * 32 * (sh.d_h * 2 + 32);
+        if (sh.d_h == 128) {
+            if (g2)
+                hipLaunchKernelGGL((attn_bf16_kernel<128, true>), dim3((unsigned)rows), dim3(256), smem, st, a);
+            else
+                hipLaunchKernelGGL((attn_bf16_kernel<128, false>), dim3((unsigned)rows), dim3(256), smem, st, a);
+        } else {
+            if (g2)
+                hipLaunchKernelGGL((attn_bf16_kernel<64, true>), dim3((unsigned)rows), dim3(256), smem, st, a);
+            else
+                hipLaunchKernelGGL((attn_bf16_kernel<64, false>), dim3((unsigned)rows), dim3(256), smem, st, a);
+        }
+    } else {
+        if (sh.d_h == 128)
+            hipLaunchKernelGGL(attn_f32_kernel<128>, dim3((unsigned)rows), dim3(256), 0, st, a);
+        else
+            hipLaunchKernelGGL(attn_f32_kernel<64>, dim3((unsigned)rows), dim3(256), 0, st, a);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace gsa

@@ -1,0 +1,392 @@
+// Gated lightning indexer (Sec. 3.3, Eq. "indexer") with the row statistics that the adaptive
+// controller of Sec. 3.4 consumes.
+//
+//   I[t,s] = sum_j w[t,j] * sigmoid(qI[t,j,:] . kI[s,:] + bI[j]),   s <= min(q_offset + t, Lk-1)
+//
+// Mapping to the matrix cores.  The logits of all heads of a block of queries form one GEMM
+// C[(t,j), s] = A[(t,j), :] . B[s, :] with M = queries x heads (head fastest), N = keys, K = dI.
+// A 32x32 MFMA accumulator leaves, in every lane, sixteen rows of one key column; with the head
+// index fastest in M those sixteen rows are whole groups of heads of a few queries, so the
+// sigmoid, the head weighting and the head sum all happen inside one lane, with no cross-lane
+// traffic, and a lane's column index runs over consecutive keys so score rows are written in
+// 128-byte pieces.
+//
+// A workgroup is four waves; each wave owns 32 M-rows (32/HI queries) and keeps its A fragments
+// in registers for the whole key loop.  Key tiles of 128 tokens are staged through LDS (double
+// buffered, one barrier per tile) and shared by the four waves.  Tiles above the causal diagonal
+// are skipped, tiles crossing it take a masked epilogue.
+//
+// Row statistics: every lane accumulates sum(d) and sum(d^2) of d = I - c_t, c_t = (1/2) sum_j w[t,j]
+// (the row mean when logits are symmetric), which removes the cancellation of the one-pass
+// variance formula.  The key range of a row may be split over several workgroups (grid.y); each
+// writes its partial sums to the workspace and a second small kernel merges them in double
+// precision into row_mean / row_var.
+#include "common.hpp"
+
+namespace gsa {
+
+struct IndexerArgs {
+    const void* qI;
+    const void* kI;
+    const float* w;
+    const float* bI;
+    float* scores;
+    int64_t ld;
+    float2* partial;  // [B][R][nsplit]
+    int32_t B, Lq, Lk, q_offset, row_begin, row_end;
+    int32_t kc;      // keys per split (multiple of 128)
+    int32_t nsplit;
+    int32_t ntiles;  // query tiles in the slab
+};
+
+constexpr int kBN = 128;  // keys per LDS tile
+
+template <typename T>
+struct ElemTraits;
+template <>
+struct ElemTraits<__bf16> {
+    static constexpr int kBytes = 2;
+};
+template <>
+struct ElemTraits<float> {
+    static constexpr int kBytes = 4;
+};
+
+// Row (t,j) index m of accumulator register i in lane half h (l/32) of a 32x32 MFMA result.
+__device__ __forceinline__ constexpr int acc_row(int i, int h) { return 8 * (i / 4) + 4 * h + (i % 4); }
+
+template <typename T, int DI, int HI>
+__global__ __launch_bounds__(256) void indexer_kernel(IndexerArgs a) {
+    constexpr int EB = ElemTraits<T>::kBytes;
+    constexpr int ROWB = DI * EB;            // bytes of one key row
+    constexpr int LDSROW = ROWB + 16;        // padded LDS row stride
+    constexpr int NCH = kBN * ROWB / 16 / 256;  // 16-byte chunks staged per thread per tile
+    constexpr int CHPR = ROWB / 16;          // chunks per key row
+    constexpr int QW = 32 / HI;              // queries per wave
+    constexpr int QT = 4 * QW;               // queries per workgroup
+    constexpr int HL = HI < 4 ? HI : 4;      // heads of one query held by a lane
+    constexpr int NSLOT = 16 / HL;           // (query) slots per lane
+    constexpr bool kIsBf16 = (EB == 2);
+    constexpr int KSTEPS = kIsBf16 ? DI / 16 : DI / 2;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // 2 * kBN * LDSROW
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wv = tid >> 6;
+    const int h = lane >> 5;   // lane half
+    const int n = lane & 31;   // column (key) within an N-block / row within A
+    const int b = blockIdx.z;
+    const int split = blockIdx.y;
+    const int tile = a.ntiles - 1 - (int)blockIdx.x;  // longest rows first
+    const int R = a.row_end - a.row_begin;
+
+    const int t_wg0 = a.row_begin + tile * QT;
+    const int t_w0 = t_wg0 + wv * QW;
+    const int t_wg_last = min(t_wg0 + QT, a.row_end) - 1;
+    const int kmax_wg = min(a.q_offset + t_wg_last, a.Lk - 1);  // last key any row of the workgroup sees
+    const int key_lo = split * a.kc;
+    const int key_hi = min(key_lo + a.kc, kmax_wg + 1);         // exclusive
+
+    // ---- per-lane slot bookkeeping -------------------------------------------------------
+    int lim[NSLOT];        // last visible key of the slot's query, -1 if the query is outside the range
+    int64_t rowoff[NSLOT]; // offset of the slot's score row
+    float wreg[16];        // head weight of accumulator register i
+    float nbias[16];       // -log2(e) * bias of accumulator register i
+    float center[NSLOT];
+    float s1[NSLOT], s2[NSLOT];
+#pragma unroll
+    for (int s = 0; s < NSLOT; ++s) {
+        const int m0 = acc_row(s * HL, h);
+        const int t = t_w0 + m0 / HI;
+        const bool ok = t < a.row_end;
+        lim[s] = ok ? min(a.q_offset + t, a.Lk - 1) : -1;
+        rowoff[s] = ((int64_t)b * R + (t - a.row_begin)) * a.ld;
+        float c = 0.f;
+#pragma unroll
+        for (int r = 0; r < HL; ++r) {
+            const int i = s * HL + r;
+            const int j = acc_row(i, h) % HI;
+            const float wv_ = ok ? a.w[((int64_t)b * a.Lq + t) * HI + j] : 0.f;
+            wreg[i] = wv_;
+            nbias[i] = a.bI ? -kLog2e * a.bI[j] : 0.f;
+            c += 0.5f * wv_;
+        }
+        if (HI == 8) c += __shfl_xor(c, 32, 64);
+        center[s] = c;
+        s1[s] = 0.f;
+        s2[s] = 0.f;
+    }
+
+    if (key_lo < key_hi) {
+        // ---- A fragments: rows (t,j) of this wave, kept for the whole key loop ------------
+        // bf16: register kk holds k = 16*kk + 8*h .. +8.   f32: register kk holds k = h*DI/2 + kk.
+        bf16x8 afrag_b[kIsBf16 ? KSTEPS : 1];
+        float afrag_f[kIsBf16 ? 1 : KSTEPS];
+        {
+            const int t = t_w0 + n / HI;
+            const bool ok = t < a.row_end;
+            const int64_t row = ((int64_t)b * a.Lq + (ok ? t : a.row_begin)) * HI + (n % HI);
+            if constexpr (kIsBf16) {
+                const u32x4* src = reinterpret_cast<const u32x4*>(static_cast<const __bf16*>(a.qI) + row * DI);
+#pragma unroll
+                for (int kk = 0; kk < KSTEPS; ++kk) {
+                    u32x4 v = ok ? src[kk * 2 + h] : u32x4{0, 0, 0, 0};
+                    afrag_b[kk] = __builtin_bit_cast(bf16x8, v);
+                }
+            } else {
+                const float4* src = reinterpret_cast<const float4*>(static_cast<const float*>(a.qI) + row * DI + h * (DI / 2));
+#pragma unroll
+                for (int c4 = 0; c4 < DI / 8; ++c4) {
+                    float4 v = ok ? src[c4] : float4{0.f, 0.f, 0.f, 0.f};
+                    afrag_f[c4 * 4 + 0] = v.x;
+                    afrag_f[c4 * 4 + 1] = v.y;
+                    afrag_f[c4 * 4 + 2] = v.z;
+                    afrag_f[c4 * 4 + 3] = v.w;
+                }
+            }
+        }
+
+        // limits of this wave (uniform): first/last visible key over its valid rows
+        const int t_w_last = min(t_w0 + QW, a.row_end) - 1;
+        const bool wave_has_rows = t_w0 < a.row_end;
+        const bool wave_rows_full = (t_w0 + QW) <= a.row_end;
+        const int lim_first = min(a.q_offset + t_w0, a.Lk - 1);
+        const int lim_last = wave_has_rows ? min(a.q_offset + t_w_last, a.Lk - 1) : -1;
+
+        const unsigned char* kbase = static_cast<const unsigned char*>(a.kI) + (int64_t)b * a.Lk * ROWB;
+        u32x4 stage[NCH];
+        auto load_tile = [&](int s0) {
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                const int ch = tid + c * 256;
+                const int r = ch / CHPR;
+                const int col = ch % CHPR;
+                const int s = s0 + r;
+                stage[c] = (s < a.Lk) ? *reinterpret_cast<const u32x4*>(kbase + (int64_t)s * ROWB + col * 16)
+                                      : u32x4{0, 0, 0, 0};
+            }
+        };
+        auto store_tile = [&](int buf) {
+            unsigned char* dst = smem + buf * (kBN * LDSROW);
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                const int ch = tid + c * 256;
+                const int r = ch / CHPR;
+                const int col = ch % CHPR;
+                *reinterpret_cast<u32x4*>(dst + r * LDSROW + col * 16) = stage[c];
+            }
+        };
+        auto mfma_block = [&](const unsigned char* tileptr, int nb) -> f32x16 {
+            f32x16 c = {0};
+            const unsigned char* rowp = tileptr + (nb * 32 + n) * LDSROW;
+            if constexpr (kIsBf16) {
+#pragma unroll
+                for (int kk = 0; kk < KSTEPS; ++kk) {
+                    u32x4 v = *reinterpret_cast<const u32x4*>(rowp + kk * 32 + h * 16);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag_b[kk], __builtin_bit_cast(bf16x8, v), c, 0, 0, 0);
+                }
+            } else {
+#pragma unroll
+                for (int c4 = 0; c4 < DI / 8; ++c4) {
+                    float4 v = *reinterpret_cast<const float4*>(rowp + h * (DI * 2) + c4 * 16);
+                    c = __builtin_amdgcn_mfma_f32_32x32x2f32(afrag_f[c4 * 4 + 0], v.x, c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x2f32(afrag_f[c4 * 4 + 1], v.y, c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x2f32(afrag_f[c4 * 4 + 2], v.z, c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x2f32(afrag_f[c4 * 4 + 3], v.w, c, 0, 0, 0);
+                }
+            }
+            return c;
+        };
+        auto epilogue = [&](const f32x16& c, int scol, bool masked) {
+#pragma unroll
+            for (int s = 0; s < NSLOT; ++s) {
+                float sc = 0.f;
+#pragma unroll
+                for (int r = 0; r < HL; ++r) {
+                    const int i = s * HL + r;
+                    const float e = fast_exp2(fmaf(c[i], -kLog2e, nbias[i]));
+                    sc = fmaf(wreg[i], fast_rcp(1.0f + e), sc);
+                }
+                if (HI == 8) sc += __shfl_xor(sc, 32, 64);
+                bool valid = (HI == 8) ? (h == 0) : true;
+                if (masked) valid = valid && (scol <= lim[s]);
+                if (valid) {
+                    const float d = sc - center[s];
+                    s1[s] += d;
+                    s2[s] = fmaf(d, d, s2[s]);
+                    if (a.scores) a.scores[rowoff[s] + scol] = sc;
+                }
+            }
+        };
+
+        // ---- key loop ---------------------------------------------------------------------
+        const int ntile = (int)cdiv(key_hi - key_lo, kBN);
+        load_tile(key_lo);
+        store_tile(0);
+        __syncthreads();
+        for (int it = 0; it < ntile; ++it) {
+            const int s0 = key_lo + it * kBN;
+            const bool more = (it + 1) < ntile;
+            if (more) load_tile(s0 + kBN);
+            const unsigned char* tileptr = smem + (it & 1) * (kBN * LDSROW);
+            if (wave_has_rows && s0 <= lim_last) {
+                const bool full = wave_rows_full && (s0 + kBN - 1 <= lim_first);
+                if (full) {
+                    f32x16 c = mfma_block(tileptr, 0);
+#pragma unroll
+                    for (int nb = 0; nb < 4; ++nb) {
+                        f32x16 cn;
+                        if (nb < 3) cn = mfma_block(tileptr, nb + 1);
+                        epilogue(c, s0 + nb * 32 + n, false);
+                        if (nb < 3) c = cn;
+                    }
+                } else {
+                    for (int nb = 0; nb < 4; ++nb) {
+                        if (s0 + nb * 32 > lim_last) break;
+                        f32x16 c = mfma_block(tileptr, nb);
+                        epilogue(c, s0 + nb * 32 + n, true);
+                    }
+                }
+            }
+            if (more) store_tile((it + 1) & 1);
+            __syncthreads();
+        }
+    }
+
+    // ---- reduce the statistics over the 32 lanes that share a lane half, write partials -------
+#pragma unroll
+    for (int s = 0; s < NSLOT; ++s) {
+        float x1 = s1[s], x2 = s2[s];
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) {
+            x1 += __shfl_xor(x1, o, 64);
+            x2 += __shfl_xor(x2, o, 64);
+        }
+        if (n == 0 && lim[s] >= 0 && !(HI == 8 && h == 1)) {
+            const int t = t_w0 + acc_row(s * HL, h) / HI;
+            a.partial[((int64_t)b * R + (t - a.row_begin)) * a.nsplit + split] = float2{x1, x2};
+        }
+    }
+}
+
+// Merge the per-split partial sums of a row in double precision:
+//   mean = c + S1/n,  var = S2/n - (S1/n)^2   with d = I - c.
+__global__ void indexer_finalize_kernel(const float2* partial, const float* w, float* row_mean, float* row_var,
+                                        int B, int Lq, int Lk, int q_offset, int row_begin, int row_end, int nsplit,
+                                        int HI) {
+    const int R = row_end - row_begin;
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= (int64_t)B * R) return;
+    const int b = (int)(gid / R);
+    const int t = row_begin + (int)(gid % R);
+    double S1 = 0.0, S2 = 0.0;
+    for (int s = 0; s < nsplit; ++s) {
+        const float2 p = partial[gid * nsplit + s];
+        S1 += (double)p.x;
+        S2 += (double)p.y;
+    }
+    float c = 0.f;  // same association as in the kernel above so that the centre is bit-identical
+    if (HI == 8) {
+        float c0 = 0.f, c1 = 0.f;
+        for (int j = 0; j < 4; ++j) c0 += 0.5f * w[((int64_t)b * Lq + t) * HI + j];
+        for (int j = 4; j < 8; ++j) c1 += 0.5f * w[((int64_t)b * Lq + t) * HI + j];
+        c = c0 + c1;
+    } else {
+        for (int j = 0; j < HI; ++j) c += 0.5f * w[((int64_t)b * Lq + t) * HI + j];
+    }
+    const double nvis = (double)(min(q_offset + t, Lk - 1) + 1);
+    const double m = S1 / nvis;
+    double var = S2 / nvis - m * m;
+    if (var < 0.0) var = 0.0;
+    if (row_mean) row_mean[(int64_t)b * Lq + t] = (float)((double)c + m);
+    row_var[(int64_t)b * Lq + t] = (float)var;
+}
+
+// ---- host side -----------------------------------------------------------------------------
+static int queries_per_wg(int HI) { return 4 * (32 / HI); }
+
+// Keys per split: enough splits that the launch fills the chip, never less than four key tiles.
+void indexer_plan(const gsa_shape& sh, int row_begin, int row_end, int* kc_out, int* nsplit_out, int* ntiles_out) {
+    const int QT = queries_per_wg(sh.HI);
+    const int ntiles = (int)cdiv(row_end - row_begin, QT);
+    const int maxvis = (sh.q_offset + row_end - 1 < sh.Lk - 1 ? sh.q_offset + row_end - 1 : sh.Lk - 1) + 1;
+    const int64_t want_wgs = 2048;
+    int64_t nsplit = cdiv(want_wgs, (int64_t)ntiles * sh.B);
+    if (nsplit < 1) nsplit = 1;
+    int64_t kc = cdiv(cdiv(maxvis, nsplit), kBN) * kBN;
+    if (kc < 4 * kBN) kc = 4 * kBN;
+    nsplit = cdiv(maxvis, kc);
+    *kc_out = (int)kc;
+    *nsplit_out = (int)nsplit;
+    *ntiles_out = ntiles;
+}
+
+size_t indexer_workspace_bytes(const gsa_shape& sh, int row_begin, int row_end) {
+    int kc, nsplit, ntiles;
+    indexer_plan(sh, row_begin, row_end, &kc, &nsplit, &ntiles);
+    return (size_t)sh.B * (size_t)(row_end - row_begin) * (size_t)nsplit * sizeof(float2);
+}
+
+template <typename T, int DI, int HI>
+static hipError_t launch_one(const IndexerArgs& a, hipStream_t st) {
+    constexpr int LDSROW = DI * ElemTraits<T>::kBytes + 16;
+    const size_t smem = 2 * kBN * LDSROW;
+    auto kern = indexer_kernel<T, DI, HI>;
+    if (smem > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+    }
+    dim3 grid(a.ntiles, a.nsplit, a.B);
+    hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, a);
+    return hipGetLastError();
+}
+
+template <typename T, int DI>
+static hipError_t launch_hi(const IndexerArgs& a, int HI, hipStream_t st) {
+    switch (HI) {
+        case 1: return launch_one<T, DI, 1>(a, st);
+        case 2: return launch_one<T, DI, 2>(a, st);
+        case 4: return launch_one<T, DI, 4>(a, st);
+        case 8: return launch_one<T, DI, 8>(a, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+template <typename T>
+static hipError_t launch_di(const IndexerArgs& a, int DI, int HI, hipStream_t st) {
+    switch (DI) {
+        case 32: return launch_hi<T, 32>(a, HI, st);
+        case 64: return launch_hi<T, 64>(a, HI, st);
+        case 128: return launch_hi<T, 128>(a, HI, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_indexer(const gsa_shape& sh, const void* qI, const void* kI, const float* w, const float* bI,
+                          int row_begin, int row_end, float* scores, int64_t ld, float* row_mean, float* row_var,
+                          void* workspace, hipStream_t st) {
+    IndexerArgs a;
+    a.qI = qI;
+    a.kI = kI;
+    a.w = w;
+    a.bI = bI;
+    a.scores = scores;
+    a.ld = ld;
+    a.partial = static_cast<float2*>(workspace);
+    a.B = sh.B;
+    a.Lq = sh.Lq;
+    a.Lk = sh.Lk;
+    a.q_offset = sh.q_offset;
+    a.row_begin = row_begin;
+    a.row_end = row_end;
+    indexer_plan(sh, row_begin, row_end, &a.kc, &a.nsplit, &a.ntiles);
+    hipError_t e = (sh.dtype == GSA_BF16) ? launch_di<__bf16>(a, sh.dI, sh.HI, st) : launch_di<float>(a, sh.dI, sh.HI, st);
+    if (e != hipSuccess) return e;
+    const int64_t rows = (int64_t)sh.B * (row_end - row_begin);
+    hipLaunchKernelGGL(indexer_finalize_kernel, dim3((unsigned)cdiv(rows, 256)), dim3(256), 0, st, a.partial, w, row_mean,
+                       row_var, sh.B, sh.Lq, sh.Lk, sh.q_offset, row_begin, row_end, a.nsplit, sh.HI);
+    return hipGetLastError();
+}
+
+}  // namespace gsa

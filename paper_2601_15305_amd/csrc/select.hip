@@ -1,0 +1,336 @@
+// Top-k_t selection (Sec. 2.2 Eq. 4 with the per-query budget of Sec. 3.4) and the adaptive
+// controller itself (Eq. "adaptive_k").
+//
+// Selection is an exact radix select on the fp32 bit pattern of the non-negative scores (which
+// orders like the value), one workgroup of four wavefronts per query row:
+//   A. histogram the next 13 key bits of every element that still matches the resolved prefix
+//      (LDS atomics), locate the bin holding the n_sel-th largest; repeat only while that bin
+//      holds more candidates than fit in LDS (at most three passes: 13 + 13 + 5 bits);
+//   B. stream the row once more: elements above the bin set a bit in an LDS bitmap of the row,
+//      elements inside it go to an LDS candidate list (or, if the prefix is already a whole
+//      key, to a second "tie" bitmap);
+//   C. finish the radix descent on the candidate list in LDS, giving the exact threshold key T
+//      and the number m_eq of elements equal to T that still have to be taken; candidates
+//      above T set selection bits, candidates equal to T set tie bits;
+//   D. walk the two bitmaps in index order: all selection bits and the first m_eq tie bits
+//      are emitted, which yields ascending indices and the lowest-index tie-break for free.
+// The result is deterministic and independent of the order in which atomics land.
+#include "common.hpp"
+
+namespace gsa {
+
+struct SelectArgs {
+    const float* scores;
+    int64_t ld;
+    const int32_t* n_sel;
+    int32_t* idx_out;
+    int32_t B, Lq, Lk, q_offset, row_begin, row_end, k_cap;
+    int32_t nw;  // bitmap words reserved per bitmap
+    int32_t idx_rows, idx_row0;  // idx_out holds rows [idx_row0, idx_row0+idx_rows) of every batch element
+};
+
+constexpr int kSelThreads = 256;
+constexpr int kBinsA = 8192;  // 13 bits per global pass
+constexpr int kBitsA = 13;
+constexpr int kCandCap = 2048;
+constexpr int kBinsC = 2048;  // 11 bits per LDS pass (size of hist_c)
+constexpr int kBitsC = 11;
+static_assert(2 * kCandCap + kBinsC <= kBinsA && (1 << kBitsC) == kBinsC, "LDS aliasing");
+
+__device__ __forceinline__ uint32_t score_key(float x) {
+    const uint32_t u = __float_as_uint(x);
+    return (u & 0x80000000u) ? 0u : u;  // negative values (and -0) rank as 0
+}
+
+// Block-wide: largest bin b with sum_{b' >= b} hist[b'] >= need; above = sum_{b' > b} hist[b'].
+// Requires sum(hist) >= need >= 1.  scratch: >= 8 words.  All threads return the same result.
+__device__ void find_threshold_bin(const uint32_t* hist, int nbins, uint32_t need, uint32_t* scratch, int* bin_out,
+                                   uint32_t* above_out) {
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wv = tid >> 6;
+    const int per = nbins >= kSelThreads ? nbins / kSelThreads : 1;
+    const int lo = tid * per;
+    uint32_t local = 0;
+    if (lo < nbins)
+        for (int i = 0; i < per; ++i) local += hist[lo + i];
+    // inclusive suffix sum inside the wave (towards higher lanes)
+    uint32_t incl = local;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t v = __shfl_down(incl, o, 64);
+        if (lane + o < 64) incl += v;
+    }
+    if (lane == 0) scratch[wv] = incl;  // wave total
+    __syncthreads();
+    uint32_t higher = 0;
+    for (int x = wv + 1; x < kSelThreads / 64; ++x) higher += scratch[x];
+    const uint32_t suf_incl = incl + higher;
+    const uint32_t suf_excl = suf_incl - local;
+    if (lo < nbins && suf_excl < need && need <= suf_incl) {
+        uint32_t acc = suf_excl;
+        for (int i = per - 1; i >= 0; --i) {
+            const uint32_t c = hist[lo + i];
+            if (acc + c >= need) {
+                scratch[4] = (uint32_t)(lo + i);
+                scratch[5] = acc;
+                break;
+            }
+            acc += c;
+        }
+    }
+    __syncthreads();
+    *bin_out = (int)scratch[4];
+    *above_out = scratch[5];
+    __syncthreads();  // scratch may be reused right away
+}
+
+__global__ __launch_bounds__(kSelThreads) void topk_select_kernel(SelectArgs a) {
+    extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+    uint32_t* hist = lds;                       // kBinsA words; later reused as below
+    uint32_t* cand_key = lds;                   // kCandCap
+    uint32_t* cand_idx = lds + kCandCap;        // kCandCap
+    uint32_t* hist_c = lds + 2 * kCandCap;      // kBinsC
+    uint32_t* bm_sel = lds + kBinsA;            // nw
+    uint32_t* bm_tie = bm_sel + a.nw;           // nw
+    uint32_t* scratch = bm_tie + a.nw;          // 16 words
+    unsigned long long* scan64 = reinterpret_cast<unsigned long long*>(scratch + 8);  // 4 entries
+
+    const int tid = threadIdx.x;
+    const int R = a.row_end - a.row_begin;
+    const int64_t rid = (int64_t)gridDim.x - 1 - blockIdx.x;  // longest rows of the slab first
+    const int b = (int)(rid / R);
+    const int t = a.row_begin + (int)(rid % R);
+    const int n = min(a.q_offset + t, a.Lk - 1) + 1;
+    int m = a.n_sel[(int64_t)b * a.Lq + t];
+    m = max(0, min(m, min(n, a.k_cap)));
+    int32_t* out = a.idx_out + ((int64_t)b * a.idx_rows + (t - a.idx_row0)) * a.k_cap;
+
+    if (m == n || m == 0) {  // everything visible is selected (or nothing is)
+        for (int j = tid; j < a.k_cap; j += kSelThreads) out[j] = j < m ? j : -1;
+        return;
+    }
+    const float* row = a.scores + ((int64_t)b * R + (t - a.row_begin)) * a.ld;
+
+    // ---- A: radix descent over the row in global memory -------------------------------------
+    uint32_t prefix = 0;
+    int pbits = 0;  // resolved leading bits of the 31-bit key
+    uint32_t need = (uint32_t)m;
+    uint32_t cand = 0;
+    while (true) {
+        const int nb = min(kBitsA, 31 - pbits);
+        const int shift = 31 - pbits - nb;
+        const uint32_t mask = (1u << nb) - 1u;
+        for (int i = tid; i < (1 << nb); i += kSelThreads) hist[i] = 0;
+        __syncthreads();
+        for (int base = tid * 4; base < n; base += kSelThreads * 4 * 2) {
+            float4 v0 = *reinterpret_cast<const float4*>(row + base);
+            const int base1 = base + kSelThreads * 4;
+            float4 v1 = base1 < n ? *reinterpret_cast<const float4*>(row + base1) : float4{0.f, 0.f, 0.f, 0.f};
+            const float x[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int s = (e < 4 ? base : base1) + (e & 3);
+                if (s < n) {
+                    const uint32_t key = score_key(x[e]);
+                    if (pbits == 0 || (key >> (31 - pbits)) == prefix) atomicAdd(&hist[(key >> shift) & mask], 1u);
+                }
+            }
+        }
+        __syncthreads();
+        int bin;
+        uint32_t above;
+        find_threshold_bin(hist, 1 << nb, need, scratch, &bin, &above);
+        cand = hist[bin];
+        need -= above;
+        prefix = (prefix << nb) | (uint32_t)bin;
+        pbits += nb;
+        __syncthreads();  // everyone has read hist[bin] before it is cleared or reused
+        if (cand <= (uint32_t)kCandCap || pbits == 31) break;
+    }
+    const bool exact = (pbits == 31);  // the prefix is a whole key: candidates are exact ties
+    const int rb0 = 31 - pbits;
+
+    // ---- B: mark the sure winners, gather the candidates --------------------------------------
+    const int nw_row = (n + 31) >> 5;
+    for (int i = tid; i < nw_row; i += kSelThreads) {
+        bm_sel[i] = 0;
+        bm_tie[i] = 0;
+    }
+    if (tid == 0) scratch[6] = 0;  // candidate counter
+    __syncthreads();
+    for (int base = tid * 4; base < n; base += kSelThreads * 4 * 2) {
+        float4 v0 = *reinterpret_cast<const float4*>(row + base);
+        const int base1 = base + kSelThreads * 4;
+        float4 v1 = base1 < n ? *reinterpret_cast<const float4*>(row + base1) : float4{0.f, 0.f, 0.f, 0.f};
+        const float x[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int s = (e < 4 ? base : base1) + (e & 3);
+            if (s < n) {
+                const uint32_t key = score_key(x[e]);
+                const uint32_t kp = key >> rb0;
+                if (kp > prefix) {
+                    atomicOr(&bm_sel[s >> 5], 1u << (s & 31));
+                } else if (kp == prefix) {
+                    if (exact) {
+                        atomicOr(&bm_tie[s >> 5], 1u << (s & 31));
+                    } else {
+                        const uint32_t pos = atomicAdd(&scratch[6], 1u);
+                        if (pos < (uint32_t)kCandCap) {
+                            cand_key[pos] = key;
+                            cand_idx[pos] = (uint32_t)s;
+                        }
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- C: finish the descent on the candidate list -------------------------------------------
+    if (!exact) {
+        const int nc = (int)min(cand, (uint32_t)kCandCap);
+        int rb = rb0;
+        while (rb > 0) {
+            const int nb = min(kBitsC, rb);
+            const uint32_t mask = (1u << nb) - 1u;
+            for (int i = tid; i < (1 << nb); i += kSelThreads) hist_c[i] = 0;
+            __syncthreads();
+            for (int c = tid; c < nc; c += kSelThreads) {
+                const uint32_t key = cand_key[c];
+                if ((key >> rb) == prefix) atomicAdd(&hist_c[(key >> (rb - nb)) & mask], 1u);
+            }
+            __syncthreads();
+            int bin;
+            uint32_t above;
+            find_threshold_bin(hist_c, 1 << nb, need, scratch, &bin, &above);
+            need -= above;
+            prefix = (prefix << nb) | (uint32_t)bin;
+            rb -= nb;
+        }
+        // prefix is now the threshold key T; `need` elements equal to T remain to be taken
+        for (int c = tid; c < nc; c += kSelThreads) {
+            const uint32_t key = cand_key[c];
+            const uint32_t s = cand_idx[c];
+            if (key > prefix)
+                atomicOr(&bm_sel[s >> 5], 1u << (s & 31));
+            else if (key == prefix)
+                atomicOr(&bm_tie[s >> 5], 1u << (s & 31));
+        }
+        __syncthreads();
+    }
+    const uint32_t m_eq = need;
+
+    // ---- D: ordered emission from the bitmaps ----------------------------------------------------
+    const int wpt = (nw_row + kSelThreads - 1) / kSelThreads;
+    const int w_lo = min(tid * wpt, nw_row), w_hi = min(w_lo + wpt, nw_row);
+    uint32_t cs = 0, ct = 0;
+    for (int wi = w_lo; wi < w_hi; ++wi) {
+        cs += __popc(bm_sel[wi]);
+        ct += __popc(bm_tie[wi]);
+    }
+    unsigned long long packed = ((unsigned long long)ct << 32) | cs;
+    unsigned long long incl = packed;
+    const int lane = tid & 63, wv = tid >> 6;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const unsigned long long v = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += v;
+    }
+    if (lane == 63) scan64[wv] = incl;
+    __syncthreads();
+    unsigned long long lower = 0;
+    for (int x = 0; x < wv; ++x) lower += scan64[x];
+    const unsigned long long excl = incl - packed + lower;
+    uint32_t ties_before = (uint32_t)(excl >> 32);
+    uint32_t pos = (uint32_t)(excl & 0xffffffffu) + min(ties_before, m_eq);
+    for (int wi = w_lo; wi < w_hi; ++wi) {
+        uint32_t wt = bm_tie[wi];
+        const uint32_t ntie = __popc(wt);
+        const uint32_t allow = m_eq - min(ties_before, m_eq);
+        while ((uint32_t)__popc(wt) > allow) wt &= ~(0x80000000u >> __clz(wt));  // drop the highest tie bits
+        uint32_t comb = bm_sel[wi] | wt;
+        while (comb) {
+            const int bit = __ffs(comb) - 1;
+            if (pos < (uint32_t)a.k_cap) out[pos] = wi * 32 + bit;
+            ++pos;
+            comb &= comb - 1u;
+        }
+        ties_before += ntie;
+    }
+    for (int j = m + tid; j < a.k_cap; j += kSelThreads) out[j] = -1;
+}
+
+size_t select_lds_bytes(int Lk) {
+    const int nw = (Lk + 31) / 32;
+    return (size_t)(kBinsA + 2 * nw + 16) * sizeof(uint32_t);
+}
+
+hipError_t launch_select(const gsa_shape& sh, int row_begin, int row_end, const float* scores, int64_t ld,
+                         const int32_t* n_sel, int k_cap, int32_t* idx_out, int idx_rows, int idx_row0, hipStream_t st) {
+    SelectArgs a;
+    a.scores = scores;
+    a.ld = ld;
+    a.n_sel = n_sel;
+    a.idx_out = idx_out;
+    a.B = sh.B;
+    a.Lq = sh.Lq;
+    a.Lk = sh.Lk;
+    a.q_offset = sh.q_offset;
+    a.row_begin = row_begin;
+    a.row_end = row_end;
+    a.k_cap = k_cap;
+    a.nw = (sh.Lk + 31) / 32;
+    a.idx_rows = idx_rows;
+    a.idx_row0 = idx_row0;
+    const size_t smem = select_lds_bytes(sh.Lk);
+    if (smem > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(topk_select_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+    }
+    const int64_t rows = (int64_t)sh.B * (row_end - row_begin);
+    hipLaunchKernelGGL(topk_select_kernel, dim3((unsigned)rows), dim3(kSelThreads), smem, st, a);
+    return hipGetLastError();
+}
+
+// ---- adaptive controller ------------------------------------------------------------------------
+// k_t = clamp(floor(k_base * Var / vbar), k_min, k_max)   (mode 1: k_base * vbar / Var), evaluated in
+// double precision from the fp32 variance; floor before clamp, clamp before the integer conversion.
+__global__ void adaptive_k_kernel(const float* row_var, int32_t* k_out, int32_t* n_sel_out, int B, int Lq, int Lk,
+                                  int q_offset, int row_begin, int row_end, double vbar, int k_base, int k_min,
+                                  int k_max, int k_fixed, int mode) {
+    const int R = row_end - row_begin;
+    const int64_t lid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (lid >= (int64_t)B * R) return;
+    const int t = row_begin + (int)(lid % R);
+    const int64_t gid = (lid / R) * Lq + t;
+    int k;
+    if (k_fixed > 0) {
+        k = k_fixed;
+    } else {
+        const double var = (double)row_var[gid];
+        double r;
+        if (mode == 0)
+            r = (double)k_base * var / vbar;
+        else
+            r = var > 0.0 ? (double)k_base * vbar / var : (double)k_max;
+        r = floor(r);
+        if (!(r >= (double)k_min)) r = (double)k_min;  // also catches NaN
+        if (r > (double)k_max) r = (double)k_max;
+        k = (int)r;
+    }
+    const int nvis = min(q_offset + t, Lk - 1) + 1;
+    if (k_out) k_out[gid] = k;
+    n_sel_out[gid] = min(k, nvis);
+}
+
+hipError_t launch_adaptive_k(const gsa_shape& sh, const gsa_adaptive& c, int row_begin, int row_end,
+                             const float* row_var, int32_t* k_out, int32_t* n_sel_out, hipStream_t st) {
+    const int64_t rows = (int64_t)sh.B * (row_end - row_begin);
+    hipLaunchKernelGGL(adaptive_k_kernel, dim3((unsigned)cdiv(rows, 256)), dim3(256), 0, st, row_var, k_out, n_sel_out,
+                       sh.B, sh.Lq, sh.Lk, sh.q_offset, row_begin, row_end, (double)c.vbar, c.k_base, c.k_min, c.k_max, c.k_fixed, c.mode);
+    return hipGetLastError();
+}
+
+}  // namespace gsa

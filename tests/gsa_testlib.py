@@ -1,0 +1,140 @@
+"""Helpers shared by the GPU parity tests: tensor conversion, calls through the C ABI, and the
+comparison rules (selection sets exact outside a 1e-6 relative band at the threshold; outputs
+within 2e-2 max-abs for bf16 and 1e-4 relative for fp32)."""
+import numpy as np
+import torch
+
+import paper_2601_15305_amd as G
+from oracle import gsa_oracle as O
+
+BF16_ATOL = 2e-2     # max-abs bound on bf16 outputs
+F32_RTOL = 1e-4      # relative (to the largest reference magnitude) bound on fp32 outputs
+SEL_BAND = 1e-6      # relative band around the n_sel-th largest fp64 score in which sets may differ
+
+
+def to64(t):
+    return None if t is None else t.detach().to("cpu", torch.float64).numpy()
+
+
+def oracle_inputs(t):
+    return {k: to64(v) for k, v in t.items()}
+
+
+def to_device(t, device="cuda"):
+    return {k: (None if v is None else v.to(device)) for k, v in t.items()}
+
+
+def gpu_indexer(wl, t, row_begin=0, row_end=None, want_scores=True, want_mean=True):
+    """gsa_indexer_scores on device tensors t.  Returns scores [B,R,ld] (or None), mean, var [B,Lq]."""
+    sh = G.shape_of(wl)
+    row_end = wl.Lq if row_end is None else row_end
+    R = row_end - row_begin
+    ld = (wl.Lk + 31) // 32 * 32
+    dev = t["qI"].device
+    scores = torch.full((wl.B, R, ld), float("nan"), dtype=torch.float32, device=dev) if want_scores else None
+    mean = torch.full((wl.B, wl.Lq), float("nan"), dtype=torch.float32, device=dev) if want_mean else None
+    var = torch.full((wl.B, wl.Lq), float("nan"), dtype=torch.float32, device=dev)
+    ws = G.workspace(G.gsa_indexer_workspace_bytes(sh, row_begin, row_end), dev)
+    G.gsa_indexer_scores(sh, t["qI"], t["kI"], t["w"], t["bI"], row_begin, row_end, scores, ld, mean, var, ws)
+    torch.cuda.synchronize()
+    return scores, mean, var
+
+
+def gpu_adaptive_k(wl, ctl, var):
+    sh = G.shape_of(wl)
+    k = torch.empty((wl.B, wl.Lq), dtype=torch.int32, device=var.device)
+    n_sel = torch.empty_like(k)
+    G.gsa_adaptive_k(sh, ctl, var, k, n_sel)
+    torch.cuda.synchronize()
+    return k, n_sel
+
+
+def gpu_select(wl, scores, n_sel, k_cap, row_begin=0, row_end=None):
+    sh = G.shape_of(wl)
+    row_end = wl.Lq if row_end is None else row_end
+    idx = torch.full((wl.B, wl.Lq, k_cap), -7, dtype=torch.int32, device=scores.device)
+    G.gsa_topk_select(sh, row_begin, row_end, scores, scores.shape[-1], n_sel, k_cap, idx)
+    torch.cuda.synchronize()
+    return idx
+
+
+def gpu_attention(wl, t, idx, n_sel, k_cap, use_g2=True, use_g1=True, scale=0.0, row_begin=0, row_end=None, V=None):
+    sh = G.shape_of(wl)
+    row_end = wl.Lq if row_end is None else row_end
+    out = torch.full_like(t["Q"], float("nan"))
+    G.gsa_sparse_gated_attn(sh, row_begin, row_end, t["Q"], t["K"], t["V"] if V is None else V,
+                            t["g2"] if use_g2 else None, t["g1"] if use_g1 else None, idx, n_sel, k_cap, scale, out)
+    torch.cuda.synchronize()
+    return out
+
+
+def gpu_forward(wl, t, ctl, k_cap=None, slab_rows=None, want_idx=True, scale=0.0, use_g2=True, use_g1=True):
+    sh = G.shape_of(wl)
+    k_cap = wl.k_cap if k_cap is None else k_cap
+    dev = t["Q"].device
+    out = torch.full_like(t["Q"], float("nan"))
+    idx = torch.full((wl.B, wl.Lq, k_cap), -7, dtype=torch.int32, device=dev) if want_idx else None
+    n_sel = torch.empty((wl.B, wl.Lq), dtype=torch.int32, device=dev)
+    k = torch.empty_like(n_sel)
+    var = torch.empty((wl.B, wl.Lq), dtype=torch.float32, device=dev)
+    nbytes = G.gsa_forward_workspace_bytes(sh, k_cap, use_g2, wl.Lq if slab_rows is None else slab_rows)
+    ws = G.workspace(nbytes, dev)
+    G.gsa_forward(sh, ctl, t["Q"], t["K"], t["V"], t["g1"] if use_g1 else None, t["g2"] if use_g2 else None, t["qI"],
+                  t["kI"], t["w"], t["bI"], scale, out, idx, n_sel, k, var, k_cap, ws)
+    torch.cuda.synchronize()
+    return dict(out=out, idx=idx, n_sel=n_sel, k=k, var=var)
+
+
+# ------------------------------------------------------------------------------------ comparison rules
+def check_index_row_wellformed(idx_row, n_sel, n_vis, k_cap):
+    idx_row = np.asarray(idx_row)
+    assert idx_row.shape[0] == k_cap
+    sel = idx_row[:n_sel]
+    assert np.all(idx_row[n_sel:] == -1), "padding must be -1"
+    assert np.all(sel >= 0) and np.all(sel < n_vis), "selected keys must be visible"
+    assert np.all(np.diff(sel) > 0), "indices must be strictly ascending (unique)"
+
+
+def check_selection_vs_fp64(idx_row, n_sel, I64, band=SEL_BAND):
+    """Set equality with the fp64 oracle except for elements whose fp64 score lies within `band`
+    (relative) of the n_sel-th largest fp64 score.  Returns the number of excused elements."""
+    n = I64.shape[0]
+    want = O.topk_select_row(I64, n_sel)
+    got = np.asarray(idx_row[:n_sel], np.int64)
+    if np.array_equal(want, got):
+        return 0
+    thr = np.sort(I64)[n - n_sel]          # n_sel-th largest
+    diff = np.setxor1d(want, got)
+    dev = np.abs(I64[diff] - thr)
+    assert np.all(dev <= band * abs(thr)), "selection differs outside the threshold band: max rel dev %.3g" % (dev.max() / abs(thr))
+    return int(diff.shape[0])
+
+
+def check_out(got, ref64, dtype):
+    got = to64(got) if isinstance(got, torch.Tensor) else np.asarray(got, np.float64)
+    err = np.abs(got - ref64)
+    assert not np.any(np.isnan(got)), "NaN in output"
+    if dtype == "bf16":
+        assert err.max() <= BF16_ATOL, "bf16 max-abs error %.4g > %.4g" % (err.max(), BF16_ATOL)
+    else:
+        scale = max(np.abs(ref64).max(), 1e-30)
+        assert err.max() <= F32_RTOL * scale, "fp32 relative error %.4g > %.4g" % (err.max() / scale, F32_RTOL)
+    return float(err.max())
+
+
+def k_band_ok(k_gpu, var64, ctl_kwargs, n_vis=None, rel=1e-5):
+    """k_t from the GPU variance may differ from the fp64 one by +-1 only where the fp64 ratio lies
+    within `rel` (relative) of an integer boundary.  Returns the number of rows that used the band."""
+    k_ref = O.adaptive_k(var64, **ctl_kwargs)
+    k_gpu = np.asarray(k_gpu, np.int64)
+    bad = k_ref != k_gpu
+    if not bad.any():
+        return 0
+    assert ctl_kwargs.get("k_fixed", 0) == 0
+    vbar, kb = ctl_kwargs["vbar"], ctl_kwargs["k_base"]
+    with np.errstate(divide="ignore", invalid="ignore"):
+        r = kb * var64 / vbar if ctl_kwargs.get("mode", 0) == 0 else kb * vbar / var64
+    near = np.abs(r - np.round(r)) <= rel * np.maximum(np.abs(r), 1.0)
+    assert np.all(np.abs(k_ref - k_gpu)[bad] <= 1), "k_t off by more than one"
+    assert np.all(near[bad]), "k_t differs away from an integer boundary of the ratio"
+    return int(bad.sum())

@@ -1,0 +1,340 @@
+"""GPU parity: every stage of the HIP path, called through the C ABI, against the fp64 oracle on the
+same seeded inputs.  Sizes span several tiles and ragged tails; index work is compared bit-exactly,
+floating point within the stated tolerances (see gsa_testlib)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2601_15305_amd as G
+from paper_2601_15305_amd import synthetic as S
+from oracle import gsa_oracle as O
+
+import gsa_testlib as T
+
+pytestmark = pytest.mark.gpu
+
+
+def wl_(name, B, Lq, Lk, off, H, Hkv, dh, HI, dI, dtype, kmin=8, kmax=64, kbase=None, **kw):
+    return S.Workload(name, B, Lq, Lk, off, H, Hkv, dh, HI, dI, dtype, kbase or int(math.sqrt(kmin * kmax)), kmin, kmax, **kw)
+
+
+# ------------------------------------------------------------------------------------ stage 1
+INDEXER_CASES = [
+    # dtype, HI, dI, B, Lq, Lk, q_offset, bias
+    ("f32", 4, 32, 1, 512, 512, 0, False),
+    ("bf16", 4, 64, 2, 700, 700, 0, True),
+    ("bf16", 4, 64, 1, 100, 1000, 900, False),
+    ("bf16", 1, 32, 1, 300, 300, 0, True),
+    ("bf16", 2, 128, 1, 260, 260, 0, False),
+    ("bf16", 8, 64, 2, 150, 333, 183, True),
+    ("f32", 8, 64, 1, 130, 130, 0, True),
+    ("f32", 2, 128, 1, 200, 200, 0, False),
+    ("f32", 1, 64, 1, 257, 257, 0, False),
+]
+
+
+@pytest.mark.parametrize("dtype,HI,dI,B,Lq,Lk,off,bias", INDEXER_CASES)
+def test_indexer_scores_and_stats(dtype, HI, dI, B, Lq, Lk, off, bias):
+    wl = wl_("idx", B, Lq, Lk, off, 4, 2, 64, HI, dI, dtype, seed=11 + HI + dI)
+    t = S.make_inputs(wl, "cpu", with_bias=bias)
+    ref, rmean, rvar = O.indexer_scores(*(T.to64(t[k]) for k in ("qI", "kI", "w")), T.to64(t["bI"]), off)
+    d = T.to_device(t)
+    scores, mean, var = T.gpu_indexer(wl, d)
+    got = T.to64(scores)[:, :, :Lk]
+    vis = ~np.isnan(ref)
+    assert np.all(np.isnan(got[~vis])), "invisible positions must be left untouched"
+    err = np.abs(got[vis] - ref[vis]).max()
+    atol = 3e-6 if dtype == "bf16" else 1e-5
+    assert err <= atol, "score error %.3g" % err
+    wsum = T.to64(t["w"]).sum(-1)[..., None]
+    assert np.all(got[vis] >= 0) and np.all((got <= wsum * (1 + 1e-6))[vis])      # Sec. 3.3: I in (0, sum w) up to rounding
+    assert np.abs(T.to64(mean) - rmean).max() <= 3e-6
+    assert np.all(np.abs(T.to64(var) - rvar) <= 2e-5 * rvar + 5e-8)
+    # statistics-only mode gives the same statistics; a slab of rows gives the same scores
+    _, mean2, var2 = T.gpu_indexer(wl, d, want_scores=False)
+    assert torch.equal(mean2, mean) and torch.equal(var2, var)
+    r0, r1 = Lq // 5, Lq - Lq // 7
+    s3, _, var3 = T.gpu_indexer(wl, d, r0, r1)
+    g3 = T.to64(s3)[:, :, :Lk]
+    assert np.array_equal(np.nan_to_num(g3, nan=-1.0), np.nan_to_num(got[:, r0:r1], nan=-1.0))
+    assert np.all(np.abs(T.to64(var3)[:, r0:r1] - rvar[:, r0:r1]) <= 2e-5 * rvar[:, r0:r1] + 5e-8)
+
+
+def test_indexer_closed_forms_on_gpu():
+    """q^I = 0: every score is (1/2) sum_j w_j and the variance is 0; saturated logits give exact ties."""
+    wl = wl_("idx0", 1, 200, 200, 0, 4, 2, 64, 4, 64, "bf16", seed=5)
+    t = S.make_inputs(wl, "cpu")
+    t["qI"].zero_()
+    d = T.to_device(t)
+    scores, mean, var = T.gpu_indexer(wl, d)
+    want = 0.5 * T.to64(t["w"]).sum(-1)
+    got = T.to64(scores)
+    for i in (0, 57, 199):
+        assert np.abs(got[0, i, :i + 1] - want[0, i]).max() <= 3e-7
+    assert T.to64(var).max() <= 1e-12 and np.abs(T.to64(mean) - want).max() <= 3e-7
+
+
+# ------------------------------------------------------------------------------------ stage 2
+@pytest.mark.parametrize("mode", [0, 1])
+def test_adaptive_k_bit_exact(mode):
+    wl = wl_("ctl", 3, 1000, 1000, 0, 4, 2, 64, 4, 64, "bf16")
+    g = torch.Generator().manual_seed(3)
+    var = (torch.rand((3, 1000), generator=g) ** 2 * 2.0).float()
+    var[0, :5] = torch.tensor([0.0, 1e-30, 0.35, 0.35 * (1 + 2 ** -20), 1e30])
+    vbar = float(np.float32(0.35))
+    ctl = G.make_adaptive(vbar, 300, 40, 700, 0, mode)
+    k, n_sel = T.gpu_adaptive_k(wl, ctl, var.cuda())
+    ref = O.adaptive_k(var.double().numpy(), vbar, 300, 40, 700, 0, mode)
+    assert np.array_equal(k.cpu().numpy().astype(np.int64), ref)
+    nvis = np.arange(1, 1001)[None, :]
+    assert np.array_equal(n_sel.cpu().numpy().astype(np.int64), np.minimum(ref, nvis))
+    assert ref.min() == 40 and ref.max() == 700 and len(np.unique(ref)) > 100
+    k2, n2 = T.gpu_adaptive_k(wl, G.make_adaptive(0.0, 1, 1, 1, k_fixed=77), var.cuda())
+    assert torch.all(k2 == 77) and np.array_equal(n2.cpu().numpy(), np.minimum(77, nvis).repeat(3, 0))
+
+
+# ------------------------------------------------------------------------------------ stage 3
+def _select_case(scores_np, n_sel_np, k_cap, q_offset):
+    """scores_np [B, Lq, Lk] float32 (full rows; only the visible prefix matters)."""
+    B, Lq, Lk = scores_np.shape
+    wl = wl_("sel", B, Lq, Lk, q_offset, 4, 2, 64, 4, 64, "bf16")
+    ld = (Lk + 31) // 32 * 32
+    sc = torch.full((B, Lq, ld), float("nan"))
+    sc[:, :, :Lk] = torch.from_numpy(scores_np)
+    for i in range(Lq):                       # poison what is not visible: it must never be read as data
+        sc[:, i, O.n_visible(i, q_offset, Lk):] = float("inf")
+    idx = T.gpu_select(wl, sc.cuda(), torch.from_numpy(n_sel_np.astype(np.int32)).cuda(), k_cap).cpu().numpy()
+    for b in range(B):
+        for i in range(Lq):
+            n = O.n_visible(i, q_offset, Lk)
+            m = int(min(n_sel_np[b, i], n, k_cap))
+            T.check_index_row_wellformed(idx[b, i], m, n, k_cap)
+            want = O.topk_select_row(scores_np[b, i, :n].astype(np.float64), m)
+            assert np.array_equal(idx[b, i, :m], want), "row (%d,%d) n=%d m=%d" % (b, i, n, m)
+
+
+def test_select_small_rows_all_distributions():
+    r = np.random.default_rng(21)
+    B, L, k_cap = 2, 600, 128
+    base = r.uniform(0, 4, (B, L, L)).astype(np.float32)
+    n_sel = r.integers(1, k_cap + 1, (B, L))
+    n_sel[0, :8] = [1, 1, 2, 3, 128, 128, 5, 8]
+    _select_case(base, n_sel, k_cap, 0)
+    ties = np.round(base * 4) / 4            # 17 distinct values: exact ties everywhere
+    _select_case(ties, n_sel, k_cap, 0)
+    const = np.full_like(base, 1.25)
+    _select_case(const, n_sel, k_cap, 0)
+    inc = np.broadcast_to(np.linspace(0.01, 3.9, L, dtype=np.float32), (B, L, L)).copy()
+    _select_case(inc, n_sel, k_cap, 0)
+    _select_case(inc[:, :, ::-1].copy(), n_sel, k_cap, 0)
+    tiny = (base * 1e-30).astype(np.float32)  # denormal-adjacent magnitudes and zeros
+    tiny[:, :, ::7] = 0.0
+    _select_case(tiny, n_sel, k_cap, 0)
+
+
+@pytest.mark.parametrize("kind", ["uniform", "saturated", "constant", "narrow"])
+def test_select_long_rows(kind):
+    """Rows of 131072 scores (the 128K configuration): several histogram passes, candidate overflow, ties."""
+    r = np.random.default_rng(33)
+    B, Lq, Lk, k_cap = 1, 6, 131072, 4096
+    if kind == "uniform":
+        sc = r.uniform(0, 4, (B, Lq, Lk)).astype(np.float32)
+    elif kind == "saturated":             # sums of a few fixed weights: at most 16 distinct values
+        wts = np.array([0.31, 0.77, 0.52, 0.93], np.float32)
+        bits = r.integers(0, 16, (B, Lq, Lk))
+        sc = sum(((bits >> j) & 1).astype(np.float32) * wts[j] for j in range(4)).astype(np.float32)
+    elif kind == "constant":
+        sc = np.full((B, Lq, Lk), 2.5, np.float32)
+    else:                                  # everything inside one 13-bit bin, distinct low bits
+        sc = (2.0 + r.uniform(0, 1e-3, (B, Lq, Lk))).astype(np.float32)
+    n_sel = np.array([[1, 1000, 2048, 4096, 4095, 3]])
+    _select_case(sc, n_sel, k_cap, Lk - Lq)
+
+
+# ------------------------------------------------------------------------------------ stage 4
+def _random_sets(r, wl, k_cap):
+    idx = np.full((wl.B, wl.Lq, k_cap), -1, np.int32)
+    n_sel = np.zeros((wl.B, wl.Lq), np.int32)
+    for b in range(wl.B):
+        for i in range(wl.Lq):
+            n = O.n_visible(i, wl.q_offset, wl.Lk)
+            m = int(r.integers(1, min(k_cap, n) + 1))
+            n_sel[b, i] = m
+            idx[b, i, :m] = np.sort(r.choice(n, m, replace=False))
+    return idx, n_sel
+
+
+ATTN_CASES = [
+    # dtype, H, Hkv, dh, B, Lq, Lk, off, k_cap
+    ("bf16", 16, 4, 128, 2, 150, 150, 0, 100),
+    ("bf16", 16, 16, 128, 1, 90, 90, 0, 70),
+    ("bf16", 16, 1, 128, 1, 70, 70, 0, 70),
+    ("bf16", 8, 2, 64, 1, 130, 130, 0, 96),
+    ("bf16", 16, 4, 128, 3, 1, 400, 399, 333),
+    ("f32", 4, 4, 64, 1, 200, 200, 0, 64),
+    ("f32", 4, 1, 128, 2, 100, 100, 0, 100),
+]
+
+
+@pytest.mark.parametrize("dtype,H,Hkv,dh,B,Lq,Lk,off,k_cap", ATTN_CASES)
+def test_sparse_gated_attention(dtype, H, Hkv, dh, B, Lq, Lk, off, k_cap):
+    wl = wl_("att", B, Lq, Lk, off, H, Hkv, dh, 4, 32, dtype, seed=40 + H + Hkv, gate_std=1.5)
+    t = S.make_inputs(wl, "cpu")
+    r = np.random.default_rng(7)
+    idx, n_sel = _random_sets(r, wl, k_cap)
+    if Lq > 3:
+        n_sel[0, -1] = min(k_cap, O.n_visible(Lq - 1, off, Lk))       # a full row
+        idx[0, -1, :n_sel[0, -1]] = np.sort(r.choice(O.n_visible(Lq - 1, off, Lk), n_sel[0, -1], replace=False))
+        n_sel[0, 2] = 0                                                # an empty row -> zeros
+        idx[0, 2] = -1
+    d = T.to_device(t)
+    di, dn = torch.from_numpy(idx).cuda(), torch.from_numpy(n_sel).cuda()
+    o = T.oracle_inputs(t)
+
+    def ref(use_g2, use_g1, scale=None):
+        out = np.zeros((B, Lq, H, dh))
+        for b in range(B):
+            for i in range(Lq):
+                out[b, i], _ = O.sparse_gated_attn_row(o["Q"][b, i], o["K"][b], o["V"][b], o["g2"][b] if use_g2 else None,
+                                                       o["g1"][b, i] if use_g1 else None, idx[b, i, :n_sel[b, i]], scale)
+        return out
+
+    full = ref(True, True)
+    T.check_out(T.gpu_attention(wl, d, di, dn, k_cap), full, dtype)
+    T.check_out(T.gpu_attention(wl, d, di, dn, k_cap, use_g1=False), ref(True, False), dtype)
+    T.check_out(T.gpu_attention(wl, d, di, dn, k_cap, use_g2=False, use_g1=False, scale=0.2), ref(False, False, 0.2), dtype)
+    # G2 as a dense pre-pass followed by the ungated-V kernel is the same computation
+    Vg = torch.empty_like(d["V"])
+    G.gsa_value_gate(G.shape_of(wl), d["V"], d["g2"], Vg)
+    T.check_out(T.gpu_attention(wl, d, di, dn, k_cap, use_g2=False, V=Vg), full, dtype)
+    # a row range leaves the other rows alone
+    if Lq > 8:
+        part = T.gpu_attention(wl, d, di, dn, k_cap, row_begin=3, row_end=Lq - 2)
+        assert torch.isnan(part[:, :3]).all() and torch.isnan(part[:, Lq - 2:]).all()
+        T.check_out(part[:, 3:Lq - 2], full[:, 3:Lq - 2], dtype)
+
+
+def test_attention_gate_limits_on_gpu():
+    """Saturated gate logits: +40 makes both sigmoids 1 in fp32 (plain SDPA on the set), -40 kills the output."""
+    wl = wl_("attlim", 1, 64, 64, 0, 8, 2, 128, 4, 32, "bf16", seed=9)
+    t = S.make_inputs(wl, "cpu")
+    r = np.random.default_rng(1)
+    idx, n_sel = _random_sets(r, wl, 48)
+    d = T.to_device(t)
+    di, dn = torch.from_numpy(idx).cuda(), torch.from_numpy(n_sel).cuda()
+    plain = T.gpu_attention(wl, d, di, dn, 48, use_g2=False, use_g1=False)
+    d["g1"].fill_(40.0)
+    d["g2"].fill_(40.0)
+    assert torch.equal(T.gpu_attention(wl, d, di, dn, 48), plain)
+    d["g1"].fill_(-40.0)
+    assert T.gpu_attention(wl, d, di, dn, 48).abs().max().item() <= 1e-15
+    d["g1"].fill_(0.0)
+    d["g2"].fill_(0.0)
+    quarter = T.gpu_attention(wl, d, di, dn, 48).float()
+    assert (quarter - 0.25 * plain.float()).abs().max().item() <= 2e-2
+
+
+# ------------------------------------------------------------------------------------ whole path
+def _check_forward(wl, t, res, ctl_kw, rows=None, k_cap=None):
+    """Stage-wise validation of a forward result against the fp64 oracle on rows (b, i)."""
+    o = T.oracle_inputs(t)
+    k_cap = wl.k_cap if k_cap is None else k_cap
+    idx = res["idx"].cpu().numpy()
+    n_sel = res["n_sel"].cpu().numpy()
+    kk = res["k"].cpu().numpy()
+    var = res["var"].cpu().numpy()
+    out = T.to64(res["out"])
+    rows = [(b, i) for b in range(wl.B) for i in range(wl.Lq)] if rows is None else rows
+    excused = kband = 0
+    worst = 0.0
+    for (b, i) in rows:
+        n = O.n_visible(i, wl.q_offset, wl.Lk)
+        I = O.indexer_scores_row(o["qI"][b, i], o["kI"][b, :n], o["w"][b, i], o["bI"])
+        _, v64 = O.row_stats(I)
+        assert abs(var[b, i] - v64) <= 2e-5 * v64 + 5e-8
+        kband += T.k_band_ok(kk[b, i:i + 1], np.array([v64]), ctl_kw)
+        assert n_sel[b, i] == min(kk[b, i], n)
+        T.check_index_row_wellformed(idx[b, i], n_sel[b, i], n, k_cap)
+        excused += T.check_selection_vs_fp64(idx[b, i], int(n_sel[b, i]), I)
+        ref, _ = O.sparse_gated_attn_row(o["Q"][b, i], o["K"][b], o["V"][b], o["g2"][b], o["g1"][b, i], idx[b, i, :n_sel[b, i]])
+        worst = max(worst, T.check_out(out[b, i], ref, wl.dtype))
+    return excused, kband, worst
+
+
+def _ctl_for(wl, vbar):
+    kw = dict(vbar=float(np.float32(vbar)), k_base=wl.k_base, k_min=wl.k_min, k_max=wl.k_max, k_fixed=wl.k_fixed, mode=0)
+    return G.make_adaptive(kw["vbar"], wl.k_base, wl.k_min, wl.k_max, wl.k_fixed, 0), kw
+
+
+def _vbar_from_gpu(wl, d):
+    _, _, var = T.gpu_indexer(wl, d, want_scores=False, want_mean=False)
+    return float(var.double().mean().item())
+
+
+@pytest.mark.parametrize("wl", [S.C1_FIXED, S.C1], ids=lambda w: w.name)
+def test_forward_tiny_fp32_configs(wl):
+    t = S.make_inputs(wl, "cpu")
+    d = T.to_device(t)
+    ctl, kw = _ctl_for(wl, _vbar_from_gpu(wl, d))
+    res = T.gpu_forward(wl, d, ctl)
+    excused, kband, worst = _check_forward(wl, t, res, kw)
+    assert excused <= 4 and kband <= 8
+    if wl.k_fixed == 0:
+        kk = res["k"].cpu().numpy()
+        assert kk.min() >= wl.k_min and kk.max() <= wl.k_max and len(np.unique(kk)) > 10
+    # end to end against the oracle's own selection wherever the sets agree (they do except inside the band)
+    o = T.oracle_inputs(t)
+    full = O.gsa_forward(o["Q"], o["K"], o["V"], o["g1"], o["g2"], o["qI"], o["kI"], o["w"], None, 0, kw, k_cap=wl.k_cap)
+    same = np.all(full["idx"] == res["idx"].cpu().numpy(), axis=-1)
+    assert same.mean() > 0.97
+    T.check_out(T.to64(res["out"])[same], full["out"][same], wl.dtype)
+
+
+@pytest.mark.parametrize("heavy", [False, True])
+def test_forward_bf16_mid_size(heavy):
+    wl = wl_("mid", 2, 1536, 1536, 0, 16, 4, 128, 4, 64, "bf16", kmin=64, kmax=256, seed=77, gate_std=2.0,
+             heavy_frac=0.05 if heavy else 0.0, heavy_scale=4.0 if heavy else 1.0)
+    t = S.make_inputs(wl, "cpu")
+    d = T.to_device(t)
+    ctl, kw = _ctl_for(wl, _vbar_from_gpu(wl, d))
+    res = T.gpu_forward(wl, d, ctl)
+    r = np.random.default_rng(2)
+    rows = [(int(b), int(i)) for b, i in zip(r.integers(0, 2, 60), r.integers(0, 1536, 60))] + [(0, 0), (1, 1535), (0, 63), (1, 64)]
+    excused, kband, worst = _check_forward(wl, t, res, kw, rows)
+    assert excused <= 6 and kband <= 3
+    kk = res["k"].cpu().numpy()
+    assert len(np.unique(kk)) > 20
+    # slabbed execution (several slabs, split key ranges) selects the same sets wherever k_t agrees
+    res2 = T.gpu_forward(wl, d, ctl, slab_rows=128)
+    same_k = (res2["k"] == res["k"])
+    assert same_k.float().mean().item() > 0.995
+    assert torch.equal(res2["idx"][same_k], res["idx"][same_k])
+    assert torch.equal(res2["out"][same_k], res["out"][same_k])
+    # no index output requested: same result
+    res3 = T.gpu_forward(wl, d, ctl, want_idx=False)
+    assert torch.equal(res3["out"], res["out"]) and torch.equal(res3["n_sel"], res["n_sel"])
+    # determinism
+    res4 = T.gpu_forward(wl, d, ctl)
+    assert torch.equal(res4["out"], res["out"]) and torch.equal(res4["idx"], res["idx"]) and torch.equal(res4["var"], res["var"])
+
+
+def test_forward_decode_shape_equals_prefill_last_row():
+    """Lq = 1 with q_offset = Lk-1 is the last row of the prefill (same kernels, different launch shape)."""
+    wl = wl_("pre", 3, 640, 640, 0, 16, 4, 128, 4, 64, "bf16", kmin=32, kmax=128, seed=5)
+    t = S.make_inputs(wl, "cpu")
+    d = T.to_device(t)
+    ctl, kw = _ctl_for(wl, 0.3)
+    pre = T.gpu_forward(wl, d, ctl)
+    wd = wl.with_(Lq=1, q_offset=639)
+    dd = dict(d)
+    for name in ("Q", "g1", "qI", "w"):
+        dd[name] = d[name][:, 639:].contiguous()
+    dec = T.gpu_forward(wd, dd, ctl)
+    same_k = dec["k"][:, 0] == pre["k"][:, 639]          # the two launches sum the variance in different orders
+    assert same_k.sum().item() >= 2
+    assert torch.equal(dec["idx"][:, 0][same_k], pre["idx"][:, 639][same_k])
+    assert torch.equal(dec["out"][:, 0][same_k], pre["out"][:, 639][same_k])
+    td = {k: (v[:, 639:] if k in ("Q", "g1", "qI", "w") else v) for k, v in t.items()}
+    _check_forward(wd, td, dec, kw)
