@@ -1,0 +1,219 @@
+#!/usr/bin/env python3
+"""Benchmark of the GSA forward hot path on one MI355X.
+
+One step = one gsa_forward call (value gate -> indexer -> adaptive k_t -> top-k_t -> sparse gated
+attention) over one batch of synthetic input shaped like the paper's 1.7B model at 128K context
+(Sec. 7.1; indexer defaults of Sec. 4.1).  Inputs are resident in HBM before the timed region.
+Prints one JSON line: whole-path queries/s, the roofline of the dominant kernel (the gathered
+sparse attention, HBM-bound), per-stage figures, and the CPU oracle timed on a bounded sample of
+the same workload on this machine's host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import paper_2601_15305_amd as G  # noqa: E402
+from paper_2601_15305_amd import cost_model as CM  # noqa: E402
+from paper_2601_15305_amd import synthetic as S  # noqa: E402
+
+PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
+PEAK_MFMA_BF16_TFLOPS = 2500.0
+# measured on this chip with a dependent-free mul/exp2/add/rcp/fma chain: sigmoids per second the
+# vector ALUs can retire (3 full-rate + 2 half-rate instructions each, 256 CUs x 64 lanes x 2.4 GHz)
+PEAK_SIGMOID_PER_S = 256 * 64 * 2.4e9 / 7.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="C4-128k-prefill", choices=sorted(S.CONFIGS))
+    ap.add_argument("--h-kv", type=int, default=0, help="override the number of key-value heads")
+    ap.add_argument("--slab-rows", type=int, default=0, help="query rows per slab (0 = whole problem)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget for the CPU oracle leg (0 = skip)")
+    ap.add_argument("--stage-steps", type=int, default=0, help="steps of the per-stage timing loop (0 = same as --steps)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (reads 1 GiB, writes 1 GiB): the reference dispatch for HBM byte counters")
+    return ap.parse_args()
+
+
+def ev():
+    return torch.cuda.Event(enable_timing=True)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    G.load()
+    wl = S.CONFIGS[args.workload]
+    if args.h_kv:
+        wl = wl.with_(H_kv=args.h_kv)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    t = S.make_inputs(wl, dev)
+    sh = G.shape_of(wl)
+    k_cap = wl.k_cap
+    elt = 2 if wl.dtype == "bf16" else 4
+
+    # moving-average variance: the batch mean of the row variances of this same data (a frozen input)
+    var = torch.empty((wl.B, wl.Lq), dtype=torch.float32, device=dev)
+    ws_i = G.workspace(G.gsa_indexer_workspace_bytes(sh, 0, wl.Lq), dev)
+    G.gsa_indexer_scores(sh, t["qI"], t["kI"], t["w"], None, 0, wl.Lq, None, 0, None, var, ws_i)
+    torch.cuda.synchronize()
+    vbar = float(np.float32(var.double().mean().item()))
+    ctl_kw = dict(vbar=vbar, k_base=wl.k_base, k_min=wl.k_min, k_max=wl.k_max, k_fixed=wl.k_fixed, mode=0)
+    ctl = G.make_adaptive(vbar, wl.k_base, wl.k_min, wl.k_max, wl.k_fixed, 0)
+
+    slab = args.slab_rows if args.slab_rows > 0 else wl.Lq
+    ws = G.workspace(G.gsa_forward_workspace_bytes(sh, k_cap, True, slab), dev)
+    out = torch.empty_like(t["Q"])
+    idx = torch.empty((wl.B, wl.Lq, k_cap), dtype=torch.int32, device=dev)
+    n_sel = torch.empty((wl.B, wl.Lq), dtype=torch.int32, device=dev)
+    kbuf = torch.empty_like(n_sel)
+
+    def step():
+        G.gsa_forward(sh, ctl, t["Q"], t["K"], t["V"], t["g1"], t["g2"], t["qI"], t["kI"], t["w"], None, 0.0, out, idx,
+                      n_sel, kbuf, var, k_cap, ws)
+
+    if args.copy_calibration:
+        src = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0, e1 = ev(), ev()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    queries = wl.B * wl.Lq
+    sum_nsel = int(n_sel.sum().item())
+
+    # ---- per-stage timing: the same launches gsa_forward makes for one slab, events between them ----
+    R = wl.Lq
+    ld = (wl.Lk + 31) // 32 * 32
+    del ws
+    torch.cuda.empty_cache()
+    scores = torch.empty((wl.B, R, ld), dtype=torch.float32, device=dev)
+    Vg = torch.empty_like(t["V"])
+    names = ("value_gate", "indexer", "adaptive_k", "select", "attention")
+    acc = {n: 0.0 for n in names}
+    ssteps = args.stage_steps or args.steps
+    for it in range(ssteps + 1):
+        evs = [ev() for _ in range(len(names) + 1)]
+        evs[0].record()
+        G.gsa_value_gate(sh, t["V"], t["g2"], Vg)
+        evs[1].record()
+        G.gsa_indexer_scores(sh, t["qI"], t["kI"], t["w"], None, 0, R, scores, ld, None, var, ws_i)
+        evs[2].record()
+        G.gsa_adaptive_k(sh, ctl, var, kbuf, n_sel)
+        evs[3].record()
+        G.gsa_topk_select(sh, 0, R, scores, ld, n_sel, k_cap, idx)
+        evs[4].record()
+        G.gsa_sparse_gated_attn(sh, 0, R, t["Q"], t["K"], Vg, None, t["g1"], idx, n_sel, k_cap, 0.0, out)
+        evs[5].record()
+        torch.cuda.synchronize()
+        if it > 0:  # first pass is a warm-up
+            for j, n in enumerate(names):
+                acc[n] += evs[j].elapsed_time(evs[j + 1])
+    stage_ms = {n: acc[n] / ssteps for n in names}
+
+    pairs = CM.causal_pairs(wl.B, wl.Lq, wl.Lk, wl.q_offset)
+    fl_idx = CM.indexer_flops(pairs, wl.HI, wl.dI)
+    fl_att = CM.attention_flops(sum_nsel, wl.H, wl.d_h)
+    gbytes = CM.gathered_bytes(sum_nsel, wl.H_kv, wl.d_h, elt, gate_in_kernel=False)
+    att_s = stage_ms["attention"] * 1e-3
+    idx_s = stage_ms["indexer"] * 1e-3
+    sel_s = stage_ms["select"] * 1e-3
+    att_gbs = gbytes / att_s / 1e9
+    stages = {
+        "ms": {n: round(v, 4) for n, v in stage_ms.items()},
+        "indexer": {"tflops": round(fl_idx / idx_s / 1e12, 2), "frac_mfma_bf16_peak": round(fl_idx / idx_s / 1e12 / PEAK_MFMA_BF16_TFLOPS, 4),
+                    "sigmoids_per_s": round(pairs * wl.HI / idx_s, 0), "frac_valu_sigmoid_ceiling": round(pairs * wl.HI / idx_s / PEAK_SIGMOID_PER_S, 4),
+                    "score_write_gbs": round(pairs * 4 / idx_s / 1e9, 1)},
+        "select": {"algorithmic_read_gbs": round(pairs * 4 / sel_s / 1e9, 1), "frac_hbm_peak": round(pairs * 4 / sel_s / 1e9 / PEAK_HBM_GBS, 4)},
+        "attention": {"gathered_gbs": round(att_gbs, 1), "tflops": round(fl_att / att_s / 1e12, 2)},
+        "sum_n_sel": sum_nsel, "mean_k": round(sum_nsel / queries, 1), "pairs": pairs,
+    }
+
+    result = {
+        "metric": "GSA fwd queries/s at 128K ctx" if wl.Lk == 131072 else "GSA fwd queries/s",
+        "value": round(queries / (ms_per_step * 1e-3), 1),
+        "unit": "queries/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3), "wall_ms_per_step": round(wall_ms, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "B": wl.B, "Lq": wl.Lq, "Lk": wl.Lk, "H": wl.H, "H_kv": wl.H_kv, "d_h": wl.d_h,
+                   "HI": wl.HI, "dI": wl.dI, "k_min": wl.k_min, "k_max": wl.k_max, "k_base": wl.k_base, "vbar": vbar,
+                   "slab_rows": slab},
+        "tflops": round((fl_idx + fl_att) / (ms_per_step * 1e-3) / 1e12, 2),
+        "roofline": {"kernel": "attn_bf16_kernel (gathered sparse gated attention)", "bound": "hbm",
+                     "achieved": round(att_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": round(att_gbs / PEAK_HBM_GBS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": gbytes, "avg_launch_ms": round(stage_ms["attention"], 4)},
+        "stages": stages,
+    }
+
+    if args.cpu_seconds > 0:
+        result["cpu_baseline"] = cpu_baseline(wl, t, ctl_kw, idx, n_sel, out, args.cpu_seconds)
+    print(json.dumps(result))
+
+
+def cpu_baseline(wl, t, ctl_kw, idx_gpu, n_sel_gpu, out_gpu, budget_s):
+    """The fp64 oracle, as it stands, on a seeded uniform sample of query rows of the same tensors.
+    Rows are independent given vbar, so rows/second over a uniform sample is the oracle's throughput
+    on the whole job.  The sampled rows are compared with the GPU result on the way."""
+    from oracle import gsa_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    o = {k: (None if v is None else v.to("cpu", torch.float64).numpy()) for k, v in t.items()}
+    idx_h = idx_gpu.cpu().numpy()
+    n_h = n_sel_gpu.cpu().numpy()
+    out_h = out_gpu.to("cpu", torch.float64).numpy()
+    r = np.random.default_rng(12345)
+    order = [(int(b), int(i)) for b, i in zip(r.integers(0, wl.B, 4096), r.integers(0, wl.Lq, 4096))]
+    done = 0
+    same = 0
+    worst = 0.0
+    t0 = time.perf_counter()
+    for (b, i) in order:
+        res = O.gsa_forward_row(b, i, o["Q"], o["K"], o["V"], o["g1"], o["g2"], o["qI"], o["kI"], o["w"], None, wl.q_offset, ctl_kw)
+        done += 1
+        if res["n_sel"] == n_h[b, i] and np.array_equal(res["idx"], idx_h[b, i, :n_h[b, i]]):
+            same += 1
+            worst = max(worst, float(np.abs(out_h[b, i] - res["out"]).max()))
+        if time.perf_counter() - t0 > budget_s and done >= 8:
+            break
+    dt = time.perf_counter() - t0
+    return {"value": round(done / dt, 3), "unit": "queries/s", "cores": threads, "kind": "oracle",
+            "sample": "%d uniformly drawn query rows (seed 12345) of the same tensors, %.1f s" % (done, dt),
+            "rows_with_identical_selection": same, "max_abs_err_on_those": worst}
+
+
+if __name__ == "__main__":
+    main()
