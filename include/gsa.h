@@ -141,9 +141,12 @@ size_t gsa_attn_workspace_bytes(const gsa_shape* shape, int32_t row_begin, int32
 int32_t gsa_value_gate(const gsa_shape* shape, const void* V, const void* g2_logits, void* Vg, void* stream);
 
 /* ---- fused forward: stages 1-4 in the order of Sec. 3.2 / Sec. 4 --------------------
- * G2 (dense pre-pass into the workspace when g2 != NULL) -> indexer -> controller ->
- * top-k_t -> sparse SDPA -> G1, processed in slabs of query rows so that the score
- * matrix never exists as a whole.
+ * G2 -> indexer -> controller -> top-k_t -> sparse SDPA -> G1, processed in slabs of query
+ * rows so that the score matrix need not exist as a whole.  When g2 != NULL the value gate
+ * runs as a dense pre-pass into the workspace if the queries together gather at least four
+ * times more rows than there are key tokens (Lq * min(k_cap, Lk) >= 4 * Lk, prefill);
+ * otherwise (decode) it is applied in registers to the gathered rows.  Both give the same
+ * bits: V * sigmoid(g2) rounded to dtype.
  *   out          device, out [B, Lq, H, d_h]
  *   idx_out      device, out [B, Lq, k_cap] or NULL (then kept per slab in the workspace)
  *   n_sel_out, k_out   device, out [B, Lq] or NULL

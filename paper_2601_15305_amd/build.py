@@ -13,6 +13,9 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc", "-Wall", "-Wno-unused-function",
     # packed fp32 VALU forms are kept out of the generated code on purpose
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # MFMA accumulators live in ordinary VGPRs: the epilogues consume them with vector ALU
+    # instructions right away, so the AGPR form would only add a copy per element
+    "-mllvm", "-amdgpu-mfma-vgpr-form",
 ]
 
 

@@ -79,8 +79,17 @@ static int round_slab(const gsa_shape& s, int64_t rows) {
     return (int)(r < s.Lq ? r : s.Lq);
 }
 
+// The value gate runs as a dense pre-pass (once per key token) when the queries together gather
+// clearly more rows than there are tokens; otherwise (decode: one query against a long cache) it
+// is applied in registers to the gathered rows only.
+static bool gate_as_prepass(const gsa_shape& s, int k_cap) {
+    const int64_t k_eff = k_cap < s.Lk ? k_cap : s.Lk;
+    return (int64_t)s.Lq * k_eff >= 4 * (int64_t)s.Lk;
+}
+
 static ForwardPlan plan_forward(const gsa_shape& s, int k_cap, bool has_g2, bool own_idx, int slab_rows) {
     ForwardPlan p;
+    has_g2 = has_g2 && gate_as_prepass(s, k_cap);
     const int Rs = round_slab(s, slab_rows);
     p.slab_rows = Rs;
     size_t off = 0;
@@ -242,6 +251,7 @@ int32_t gsa_forward(const gsa_shape* shape, const gsa_adaptive* ctl, const void*
     if (!workspace || !aligned(workspace, 256)) return GSA_ERR_WORKSPACE;
     const gsa_shape& s = *shape;
     const bool has_g2 = g2_logits != nullptr;
+    const bool prepass = has_g2 && gate_as_prepass(*shape, k_cap);
     const bool own_idx = idx_out == nullptr;
     // largest slab that fits the workspace: whole problem first, then halve
     ForwardPlan plan;
@@ -256,11 +266,13 @@ int32_t gsa_forward(const gsa_shape* shape, const gsa_adaptive* ctl, const void*
     unsigned char* ws = static_cast<unsigned char*>(workspace);
     const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt((float)s.d_h);
     const void* Vuse = V;
+    const void* g2use = has_g2 ? g2_logits : nullptr;
     hipError_t e;
-    if (has_g2) {  // stage (2) of Sec. 4: the value gate, once per token
+    if (prepass) {  // stage (2) of Sec. 4: the value gate, once per token
         e = launch_value_gate(s, V, g2_logits, ws + plan.off_vg, st);
         if (e != hipSuccess) return hip_fail(e, "gsa_forward/value_gate");
         Vuse = ws + plan.off_vg;
+        g2use = nullptr;
     }
     float* var = row_var_out ? row_var_out : reinterpret_cast<float*>(ws + plan.off_var);
     int32_t* kbuf = k_out ? k_out : reinterpret_cast<int32_t*>(ws + plan.off_k);
@@ -279,7 +291,7 @@ int32_t gsa_forward(const gsa_shape* shape, const gsa_adaptive* ctl, const void*
         const int idx_row0 = own_idx ? r0 : 0;
         e = launch_select(s, r0, r1, scores, ld, nsel, k_cap, idx, idx_rows, idx_row0, st);
         if (e != hipSuccess) return hip_fail(e, "gsa_forward/select");
-        e = launch_attention(s, r0, r1, Q, K, Vuse, nullptr, g1_logits, idx, idx_rows, idx_row0, nsel, k_cap, scale, out, st);
+        e = launch_attention(s, r0, r1, Q, K, Vuse, g2use, g1_logits, idx, idx_rows, idx_row0, nsel, k_cap, scale, out, st);
         if (e != hipSuccess) return hip_fail(e, "gsa_forward/attention");
     }
     return GSA_OK;

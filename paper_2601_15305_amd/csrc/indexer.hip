@@ -55,7 +55,7 @@ struct ElemTraits<float> {
 // Row (t,j) index m of accumulator register i in lane half h (l/32) of a 32x32 MFMA result.
 __device__ __forceinline__ constexpr int acc_row(int i, int h) { return 8 * (i / 4) + 4 * h + (i % 4); }
 
-template <typename T, int DI, int HI>
+template <typename T, int DI, int HI, bool STORE>
 __global__ __launch_bounds__(256) void indexer_kernel(IndexerArgs a) {
     constexpr int EB = ElemTraits<T>::kBytes;
     constexpr int ROWB = DI * EB;            // bytes of one key row
@@ -89,27 +89,32 @@ __global__ __launch_bounds__(256) void indexer_kernel(IndexerArgs a) {
     const int key_hi = min(key_lo + a.kc, kmax_wg + 1);         // exclusive
 
     // ---- per-lane slot bookkeeping -------------------------------------------------------
-    int lim[NSLOT];        // last visible key of the slot's query, -1 if the query is outside the range
-    int64_t rowoff[NSLOT]; // offset of the slot's score row
-    float wreg[16];        // head weight of accumulator register i
-    float nbias[16];       // -log2(e) * bias of accumulator register i
+    // Score rows of this wave start at a wave-uniform base; a lane adds a 32-bit element offset.
+    float* const wave_scores = STORE ? a.scores + ((int64_t)b * R + (t_w0 - a.row_begin)) * a.ld : nullptr;
+    int lim[NSLOT];         // last visible key of the slot's query, -1 if the query is outside the range
+    uint32_t rowoff[NSLOT]; // element offset of the slot's score row from wave_scores
+    float wreg[16];         // head weight of accumulator register i
+    float nbias[HL];        // -log2(e) * bias of the lane's r-th head
     float center[NSLOT];
     float s1[NSLOT], s2[NSLOT];
 #pragma unroll
+    for (int r = 0; r < HL; ++r) {
+        const int j = (HI == 8) ? 4 * h + r : r;  // head of accumulator register s*HL + r
+        nbias[r] = a.bI ? -kLog2e * a.bI[j] : 0.f;
+    }
+#pragma unroll
     for (int s = 0; s < NSLOT; ++s) {
-        const int m0 = acc_row(s * HL, h);
-        const int t = t_w0 + m0 / HI;
+        const int tl = acc_row(s * HL, h) / HI;  // query of the slot, relative to the wave
+        const int t = t_w0 + tl;
         const bool ok = t < a.row_end;
         lim[s] = ok ? min(a.q_offset + t, a.Lk - 1) : -1;
-        rowoff[s] = ((int64_t)b * R + (t - a.row_begin)) * a.ld;
+        rowoff[s] = (uint32_t)tl * (uint32_t)a.ld;
         float c = 0.f;
 #pragma unroll
         for (int r = 0; r < HL; ++r) {
-            const int i = s * HL + r;
-            const int j = acc_row(i, h) % HI;
+            const int j = (HI == 8) ? 4 * h + r : r;
             const float wv_ = ok ? a.w[((int64_t)b * a.Lq + t) * HI + j] : 0.f;
-            wreg[i] = wv_;
-            nbias[i] = a.bI ? -kLog2e * a.bI[j] : 0.f;
+            wreg[s * HL + r] = wv_;
             c += 0.5f * wv_;
         }
         if (HI == 8) c += __shfl_xor(c, 32, 64);
@@ -205,7 +210,7 @@ __global__ __launch_bounds__(256) void indexer_kernel(IndexerArgs a) {
 #pragma unroll
                 for (int r = 0; r < HL; ++r) {
                     const int i = s * HL + r;
-                    const float e = fast_exp2(fmaf(c[i], -kLog2e, nbias[i]));
+                    const float e = fast_exp2(fmaf(c[i], -kLog2e, nbias[r]));
                     sc = fmaf(wreg[i], fast_rcp(1.0f + e), sc);
                 }
                 if (HI == 8) sc += __shfl_xor(sc, 32, 64);
@@ -215,7 +220,7 @@ __global__ __launch_bounds__(256) void indexer_kernel(IndexerArgs a) {
                     const float d = sc - center[s];
                     s1[s] += d;
                     s2[s] = fmaf(d, d, s2[s]);
-                    if (a.scores) a.scores[rowoff[s] + scol] = sc;
+                    if constexpr (STORE) wave_scores[rowoff[s] + (uint32_t)scol] = sc;
                 }
             }
         };
@@ -332,7 +337,7 @@ template <typename T, int DI, int HI>
 static hipError_t launch_one(const IndexerArgs& a, hipStream_t st) {
     constexpr int LDSROW = DI * ElemTraits<T>::kBytes + 16;
     const size_t smem = 2 * kBN * LDSROW;
-    auto kern = indexer_kernel<T, DI, HI>;
+    auto kern = a.scores ? indexer_kernel<T, DI, HI, true> : indexer_kernel<T, DI, HI, false>;
     if (smem > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;

@@ -29,7 +29,10 @@ struct SelectArgs {
     int32_t idx_rows, idx_row0;  // idx_out holds rows [idx_row0, idx_row0+idx_rows) of every batch element
 };
 
-constexpr int kSelThreads = 256;
+constexpr int kSelThreads = 512;
+constexpr int kSelWaves = kSelThreads / 64;
+constexpr int kVecPerBatch = 4;  // float4 loads a thread keeps in flight per batch (two batches are in flight)
+constexpr int kBatch = kSelThreads * 4 * kVecPerBatch;
 constexpr int kBinsA = 8192;  // 13 bits per global pass
 constexpr int kBitsA = 13;
 constexpr int kCandCap = 2048;
@@ -43,7 +46,7 @@ __device__ __forceinline__ uint32_t score_key(float x) {
 }
 
 // Block-wide: largest bin b with sum_{b' >= b} hist[b'] >= need; above = sum_{b' > b} hist[b'].
-// Requires sum(hist) >= need >= 1.  scratch: >= 8 words.  All threads return the same result.
+// Requires sum(hist) >= need >= 1.  scratch: kSelWaves + 2 words.  All threads return the same result.
 __device__ void find_threshold_bin(const uint32_t* hist, int nbins, uint32_t need, uint32_t* scratch, int* bin_out,
                                    uint32_t* above_out) {
     const int tid = threadIdx.x;
@@ -71,17 +74,50 @@ __device__ void find_threshold_bin(const uint32_t* hist, int nbins, uint32_t nee
         for (int i = per - 1; i >= 0; --i) {
             const uint32_t c = hist[lo + i];
             if (acc + c >= need) {
-                scratch[4] = (uint32_t)(lo + i);
-                scratch[5] = acc;
+                scratch[kSelWaves] = (uint32_t)(lo + i);
+                scratch[kSelWaves + 1] = acc;
                 break;
             }
             acc += c;
         }
     }
     __syncthreads();
-    *bin_out = (int)scratch[4];
-    *above_out = scratch[5];
+    *bin_out = (int)scratch[kSelWaves];
+    *above_out = scratch[kSelWaves + 1];
     __syncthreads();  // scratch may be reused right away
+}
+
+// Stream the n visible scores of a row through f(index, value).  Every thread keeps two batches of
+// kVecPerBatch 16-byte loads in flight (the next batch is requested before the current one is
+// consumed), which is what lets a workgroup cover the HBM latency.
+template <class F>
+__device__ __forceinline__ void stream_row(const float* __restrict__ row, int n, F&& f) {
+    const int tid = threadIdx.x;
+    float4 cur[kVecPerBatch], nxt[kVecPerBatch];
+    auto load = [&](int b0, float4* v) {
+#pragma unroll
+        for (int u = 0; u < kVecPerBatch; ++u) {
+            const int base = b0 + (u * kSelThreads + tid) * 4;
+            v[u] = base < n ? *reinterpret_cast<const float4*>(row + base) : float4{0.f, 0.f, 0.f, 0.f};
+        }
+    };
+    load(0, cur);
+    for (int b0 = 0; b0 < n; b0 += kBatch) {
+        const bool more = b0 + kBatch < n;
+        if (more) load(b0 + kBatch, nxt);
+#pragma unroll
+        for (int u = 0; u < kVecPerBatch; ++u) {
+            const int base = b0 + (u * kSelThreads + tid) * 4;
+            const float x[4] = {cur[u].x, cur[u].y, cur[u].z, cur[u].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (base + e < n) f(base + e, x[e]);
+        }
+        if (more) {
+#pragma unroll
+            for (int u = 0; u < kVecPerBatch; ++u) cur[u] = nxt[u];
+        }
+    }
 }
 
 __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(SelectArgs a) {
@@ -92,8 +128,8 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(SelectArgs a) 
     uint32_t* hist_c = lds + 2 * kCandCap;      // kBinsC
     uint32_t* bm_sel = lds + kBinsA;            // nw
     uint32_t* bm_tie = bm_sel + a.nw;           // nw
-    uint32_t* scratch = bm_tie + a.nw;          // 16 words
-    unsigned long long* scan64 = reinterpret_cast<unsigned long long*>(scratch + 8);  // 4 entries
+    uint32_t* scratch = bm_tie + a.nw;          // 32 words: [0,kSelWaves+2) threshold search, [kSelWaves+2] counter
+    unsigned long long* scan64 = reinterpret_cast<unsigned long long*>(scratch + 12);  // kSelWaves entries
 
     const int tid = threadIdx.x;
     const int R = a.row_end - a.row_begin;
@@ -122,19 +158,13 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(SelectArgs a) 
         const uint32_t mask = (1u << nb) - 1u;
         for (int i = tid; i < (1 << nb); i += kSelThreads) hist[i] = 0;
         __syncthreads();
-        for (int base = tid * 4; base < n; base += kSelThreads * 4 * 2) {
-            float4 v0 = *reinterpret_cast<const float4*>(row + base);
-            const int base1 = base + kSelThreads * 4;
-            float4 v1 = base1 < n ? *reinterpret_cast<const float4*>(row + base1) : float4{0.f, 0.f, 0.f, 0.f};
-            const float x[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int s = (e < 4 ? base : base1) + (e & 3);
-                if (s < n) {
-                    const uint32_t key = score_key(x[e]);
-                    if (pbits == 0 || (key >> (31 - pbits)) == prefix) atomicAdd(&hist[(key >> shift) & mask], 1u);
-                }
-            }
+        {
+            const int pshift = 31 - pbits;
+            const bool all = pbits == 0;
+            stream_row(row, n, [&](int, float xv) {
+                const uint32_t key = score_key(xv);
+                if (all || (key >> pshift) == prefix) atomicAdd(&hist[(key >> shift) & mask], 1u);
+            });
         }
         __syncthreads();
         int bin;
@@ -156,35 +186,25 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(SelectArgs a) 
         bm_sel[i] = 0;
         bm_tie[i] = 0;
     }
-    if (tid == 0) scratch[6] = 0;  // candidate counter
+    if (tid == 0) scratch[kSelWaves + 2] = 0;  // candidate counter
     __syncthreads();
-    for (int base = tid * 4; base < n; base += kSelThreads * 4 * 2) {
-        float4 v0 = *reinterpret_cast<const float4*>(row + base);
-        const int base1 = base + kSelThreads * 4;
-        float4 v1 = base1 < n ? *reinterpret_cast<const float4*>(row + base1) : float4{0.f, 0.f, 0.f, 0.f};
-        const float x[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int s = (e < 4 ? base : base1) + (e & 3);
-            if (s < n) {
-                const uint32_t key = score_key(x[e]);
-                const uint32_t kp = key >> rb0;
-                if (kp > prefix) {
-                    atomicOr(&bm_sel[s >> 5], 1u << (s & 31));
-                } else if (kp == prefix) {
-                    if (exact) {
-                        atomicOr(&bm_tie[s >> 5], 1u << (s & 31));
-                    } else {
-                        const uint32_t pos = atomicAdd(&scratch[6], 1u);
-                        if (pos < (uint32_t)kCandCap) {
-                            cand_key[pos] = key;
-                            cand_idx[pos] = (uint32_t)s;
-                        }
-                    }
+    stream_row(row, n, [&](int si, float xv) {
+        const uint32_t key = score_key(xv);
+        const uint32_t kp = key >> rb0;
+        if (kp > prefix) {
+            atomicOr(&bm_sel[si >> 5], 1u << (si & 31));
+        } else if (kp == prefix) {
+            if (exact) {
+                atomicOr(&bm_tie[si >> 5], 1u << (si & 31));
+            } else {
+                const uint32_t pos = atomicAdd(&scratch[kSelWaves + 2], 1u);
+                if (pos < (uint32_t)kCandCap) {
+                    cand_key[pos] = key;
+                    cand_idx[pos] = (uint32_t)si;
                 }
             }
         }
-    }
+    });
     __syncthreads();
 
     // ---- C: finish the descent on the candidate list -------------------------------------------
@@ -263,7 +283,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(SelectArgs a) 
 
 size_t select_lds_bytes(int Lk) {
     const int nw = (Lk + 31) / 32;
-    return (size_t)(kBinsA + 2 * nw + 16) * sizeof(uint32_t);
+    return (size_t)(kBinsA + 2 * nw + 32) * sizeof(uint32_t);
 }
 
 hipError_t launch_select(const gsa_shape& sh, int row_begin, int row_end, const float* scores, int64_t ld,
