@@ -138,6 +138,15 @@ def main():
             for j, n in enumerate(names):
                 acc[n] += evs[j].elapsed_time(evs[j + 1])
     stage_ms = {n: acc[n] / ssteps for n in names}
+    # the indexer in statistics-only mode (no score matrix written): isolates the arithmetic from the stores
+    es0, es1 = ev(), ev()
+    G.gsa_indexer_scores(sh, t["qI"], t["kI"], t["w"], None, 0, R, None, 0, None, var, ws_i)
+    es0.record()
+    for _ in range(ssteps):
+        G.gsa_indexer_scores(sh, t["qI"], t["kI"], t["w"], None, 0, R, None, 0, None, var, ws_i)
+    es1.record()
+    torch.cuda.synchronize()
+    stats_only_ms = es0.elapsed_time(es1) / ssteps
 
     pairs = CM.causal_pairs(wl.B, wl.Lq, wl.Lk, wl.q_offset)
     fl_idx = CM.indexer_flops(pairs, wl.HI, wl.dI)
@@ -151,7 +160,11 @@ def main():
         "ms": {n: round(v, 4) for n, v in stage_ms.items()},
         "indexer": {"tflops": round(fl_idx / idx_s / 1e12, 2), "frac_mfma_bf16_peak": round(fl_idx / idx_s / 1e12 / PEAK_MFMA_BF16_TFLOPS, 4),
                     "sigmoids_per_s": round(pairs * wl.HI / idx_s, 0), "frac_valu_sigmoid_ceiling": round(pairs * wl.HI / idx_s / PEAK_SIGMOID_PER_S, 4),
-                    "score_write_gbs": round(pairs * 4 / idx_s / 1e9, 1)},
+                    "score_write_gbs": round(pairs * 4 / idx_s / 1e9, 1),
+                    "stats_only_ms": round(stats_only_ms, 4),
+                    "stats_only_tflops": round(fl_idx / (stats_only_ms * 1e-3) / 1e12, 2),
+                    "stats_only_frac_mfma_bf16_peak": round(fl_idx / (stats_only_ms * 1e-3) / 1e12 / PEAK_MFMA_BF16_TFLOPS, 4),
+                    "stats_only_frac_valu_sigmoid_ceiling": round(pairs * wl.HI / (stats_only_ms * 1e-3) / PEAK_SIGMOID_PER_S, 4)},
         "select": {"algorithmic_read_gbs": round(pairs * 4 / sel_s / 1e9, 1), "frac_hbm_peak": round(pairs * 4 / sel_s / 1e9 / PEAK_HBM_GBS, 4)},
         "attention": {"gathered_gbs": round(att_gbs, 1), "tflops": round(fl_att / att_s / 1e12, 2)},
         "sum_n_sel": sum_nsel, "mean_k": round(sum_nsel / queries, 1), "pairs": pairs,

@@ -16,6 +16,8 @@
 // (ds_read_b64_tr_b16), which turns 4 tokens x 16 features into the "feature row, token
 // contraction" A operand.  Softmax is the usual online form in base 2; G2 is applied to the V
 // rows in registers on their way to LDS, G1 to the accumulators before the store.
+#include <cstdlib>
+
 #include "common.hpp"
 
 namespace gsa {
@@ -67,7 +69,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     const int64_t tokstride = (int64_t)a.H_kv * ROWB;  // bytes between consecutive tokens
     const int ntile = (nsel + 31) >> 5;
 
-    for (int g = wv; g < a.H_kv; g += 4) {
+    // blockDim.x / 64 kv heads per workgroup; blockIdx.y selects which ones.  Blocks are dispatched
+    // x-fastest, so all queries work on one slice of kv heads before the next slice starts: the K/V'
+    // columns in use at any time then fit the on-die memory-side cache even when the whole K/V' does not.
+    for (int g = blockIdx.y * (blockDim.x >> 6) + wv; g < a.H_kv; g += a.H_kv) {
         const int head = g * G + n;
         const bool head_ok = n < G;
         // ---- Q fragments (B operand): lane (head n, chunk q) holds features (4*kk+q)*8 .. +8 --------
@@ -330,6 +335,22 @@ hipError_t launch_value_gate(const gsa_shape& sh, const void* V, const void* g2,
     return hipGetLastError();
 }
 
+// kv heads handled by one workgroup (one wave each).  With many query rows the kv heads are cut
+// into slices that are processed one after the other by the whole chip (see the kernel), sized so
+// that a slice of K and V' stays near 64 MiB; with few rows (decode) one workgroup takes up to four.
+static int attn_groups_per_block(const gsa_shape& sh, int64_t rows) {
+    int gpb = sh.H_kv < 4 ? sh.H_kv : 4;
+    while (sh.H_kv % gpb != 0) --gpb;
+    if (const char* e = getenv("GSA_ATTN_GPB")) {  // tuning override
+        const int v = atoi(e);
+        if (v >= 1 && v <= 4 && sh.H_kv % v == 0) return v;
+    }
+    if (rows < 4096) return gpb;
+    const double slice_target = 64.0 * 1024 * 1024;
+    while (gpb > 1 && (double)sh.B * sh.Lk * gpb * sh.d_h * 2 * 2 > slice_target && sh.H_kv % (gpb / 2) == 0) gpb /= 2;
+    return gpb;
+}
+
 hipError_t launch_attention(const gsa_shape& sh, int row_begin, int row_end, const void* Q, const void* K, const void* V,
                             const void* g2, const void* g1, const int32_t* idx, int idx_rows, int idx_row0,
                             const int32_t* n_sel, int k_cap, float scale, void* out, hipStream_t st) {
@@ -355,17 +376,20 @@ hipError_t launch_attention(const gsa_shape& sh, int row_begin, int row_end, con
     a.scale = scale;
     const int64_t rows = (int64_t)sh.B * (row_end - row_begin);
     if (sh.dtype == GSA_BF16) {
-        const size_t smem = 4 * 32 * (sh.d_h * 2 + 32);
+        const int gpb = attn_groups_per_block(sh, rows);
+        const dim3 grid((unsigned)rows, (unsigned)(sh.H_kv / gpb));
+        const dim3 block(64 * gpb);
+        const size_t smem = (size_t)gpb * 32 * (sh.d_h * 2 + 32);
         if (sh.d_h == 128) {
             if (g2)
-                hipLaunchKernelGGL((attn_bf16_kernel<128, true>), dim3((unsigned)rows), dim3(256), smem, st, a);
+                hipLaunchKernelGGL((attn_bf16_kernel<128, true>), grid, block, smem, st, a);
             else
-                hipLaunchKernelGGL((attn_bf16_kernel<128, false>), dim3((unsigned)rows), dim3(256), smem, st, a);
+                hipLaunchKernelGGL((attn_bf16_kernel<128, false>), grid, block, smem, st, a);
         } else {
             if (g2)
-                hipLaunchKernelGGL((attn_bf16_kernel<64, true>), dim3((unsigned)rows), dim3(256), smem, st, a);
+                hipLaunchKernelGGL((attn_bf16_kernel<64, true>), grid, block, smem, st, a);
             else
-                hipLaunchKernelGGL((attn_bf16_kernel<64, false>), dim3((unsigned)rows), dim3(256), smem, st, a);
+                hipLaunchKernelGGL((attn_bf16_kernel<64, false>), grid, block, smem, st, a);
         }
     } else {
         if (sh.d_h == 128)

@@ -8,8 +8,9 @@
 // A 32x32 MFMA accumulator leaves, in every lane, sixteen rows of one key column; with the head
 // index fastest in M those sixteen rows are whole groups of heads of a few queries, so the
 // sigmoid, the head weighting and the head sum all happen inside one lane, with no cross-lane
-// traffic, and a lane's column index runs over consecutive keys so score rows are written in
-// 128-byte pieces.
+// traffic.  The keys of a 128-key tile are dealt to the four column blocks round-robin (column n of
+// block nb is key 4n + nb), so after a tile a lane owns four consecutive keys per row and score rows
+// are written with 16-byte stores, 512 contiguous bytes per wave and row.
 //
 // A workgroup is four waves; each wave owns 32 M-rows (32/HI queries) and keeps its A fragments
 // in registers for the whole key loop.  Key tiles of 128 tokens are staged through LDS (double
@@ -177,9 +178,9 @@ __global__ __launch_bounds__(256) void indexer_kernel(IndexerArgs a) {
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
                 const int ch = tid + c * 256;
-                const int r = ch / CHPR;
+                const int r = ch / CHPR;  // key within the tile; it is placed at LDS row (r % 4) * 32 + r / 4
                 const int col = ch % CHPR;
-                *reinterpret_cast<u32x4*>(dst + r * LDSROW + col * 16) = stage[c];
+                *reinterpret_cast<u32x4*>(dst + ((r & 3) * 32 + (r >> 2)) * LDSROW + col * 16) = stage[c];
             }
         };
         auto mfma_block = [&](const unsigned char* tileptr, int nb) -> f32x16 {
@@ -203,7 +204,9 @@ __global__ __launch_bounds__(256) void indexer_kernel(IndexerArgs a) {
             }
             return c;
         };
-        auto epilogue = [&](const f32x16& c, int scol, bool masked) {
+        // Sigmoid, head weights, head sum and statistics of one 32x32 accumulator.  Returns the score of
+        // every slot in sc[]; in the masked form it also stores them one by one.
+        auto epilogue = [&](const f32x16& c, int scol, bool masked, float (&sc_out)[NSLOT]) {
 #pragma unroll
             for (int s = 0; s < NSLOT; ++s) {
                 float sc = 0.f;
@@ -214,23 +217,70 @@ __global__ __launch_bounds__(256) void indexer_kernel(IndexerArgs a) {
                     sc = fmaf(wreg[i], fast_rcp(1.0f + e), sc);
                 }
                 if (HI == 8) sc += __shfl_xor(sc, 32, 64);
+                sc_out[s] = sc;
                 bool valid = (HI == 8) ? (h == 0) : true;
                 if (masked) valid = valid && (scol <= lim[s]);
                 if (valid) {
                     const float d = sc - center[s];
                     s1[s] += d;
                     s2[s] = fmaf(d, d, s2[s]);
-                    if constexpr (STORE) wave_scores[rowoff[s] + (uint32_t)scol] = sc;
+                    if constexpr (STORE)
+                        if (masked) wave_scores[rowoff[s] + (uint32_t)scol] = sc;
+                }
+            }
+        };
+        // All four column blocks of a fully visible tile.  Column n of block nb is key s0 + 4n + nb, so
+        // after the four blocks a lane owns four consecutive keys of each of its rows: one 16-byte store
+        // per row and tile, and a wave writes 512 contiguous bytes of a score row at a time.
+        auto full_tile = [&](const unsigned char* tileptr, int s0) {
+            float sc4[4][NSLOT];
+            f32x16 c = mfma_block(tileptr, 0);
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb) {
+                f32x16 cn;
+                if (nb < 3) cn = mfma_block(tileptr, nb + 1);
+                epilogue(c, s0 + 4 * n + nb, false, sc4[nb]);
+                if (nb < 3) c = cn;
+            }
+            if constexpr (STORE) {
+                if (HI != 8 || h == 0) {
+#pragma unroll
+                    for (int s = 0; s < NSLOT; ++s)
+                        *reinterpret_cast<float4*>(wave_scores + rowoff[s] + (uint32_t)(s0 + 4 * n)) =
+                            float4{sc4[0][s], sc4[1][s], sc4[2][s], sc4[3][s]};
                 }
             }
         };
 
         // ---- key loop ---------------------------------------------------------------------
         const int ntile = (int)cdiv(key_hi - key_lo, kBN);
+        // Leading tiles that are wholly visible to every row of the workgroup, and whose successor
+        // tile lies wholly inside the key range, run a branch-free body: the compiler can then count
+        // the score stores issued after the prefetch loads and wait for the loads alone
+        // (vmcnt(#stores)) instead of draining every outstanding store at each tile boundary.
+        int nlead = 0;
+        if (t_wg0 + QT <= a.row_end) {
+            const int lim_wg_first = min(a.q_offset + t_wg0, a.Lk - 1);
+            nlead = (lim_wg_first + 1 - key_lo) / kBN;
+            nlead = min(nlead, min(ntile - 1, (a.Lk - key_lo) / kBN - 1));
+            nlead = max(nlead, 0);
+        }
         load_tile(key_lo);
         store_tile(0);
         __syncthreads();
-        for (int it = 0; it < ntile; ++it) {
+        int it = 0;
+        for (; it < nlead; ++it) {
+            const int s0 = key_lo + it * kBN;
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {  // prefetch of the next tile, no bounds checks needed
+                const int ch = tid + c * 256;
+                stage[c] = *reinterpret_cast<const u32x4*>(kbase + (int64_t)(s0 + kBN + ch / CHPR) * ROWB + (ch % CHPR) * 16);
+            }
+            full_tile(smem + (it & 1) * (kBN * LDSROW), s0);
+            store_tile((it + 1) & 1);
+            __syncthreads();
+        }
+        for (; it < ntile; ++it) {
             const int s0 = key_lo + it * kBN;
             const bool more = (it + 1) < ntile;
             if (more) load_tile(s0 + kBN);
@@ -238,19 +288,12 @@ __global__ __launch_bounds__(256) void indexer_kernel(IndexerArgs a) {
             if (wave_has_rows && s0 <= lim_last) {
                 const bool full = wave_rows_full && (s0 + kBN - 1 <= lim_first);
                 if (full) {
-                    f32x16 c = mfma_block(tileptr, 0);
-#pragma unroll
-                    for (int nb = 0; nb < 4; ++nb) {
-                        f32x16 cn;
-                        if (nb < 3) cn = mfma_block(tileptr, nb + 1);
-                        epilogue(c, s0 + nb * 32 + n, false);
-                        if (nb < 3) c = cn;
-                    }
+                    full_tile(tileptr, s0);
                 } else {
                     for (int nb = 0; nb < 4; ++nb) {
-                        if (s0 + nb * 32 > lim_last) break;
+                        float sc[NSLOT];
                         f32x16 c = mfma_block(tileptr, nb);
-                        epilogue(c, s0 + nb * 32 + n, true);
+                        epilogue(c, s0 + 4 * n + nb, true, sc);
                     }
                 }
             }

@@ -15,6 +15,10 @@
 //   D. walk the two bitmaps in index order: all selection bits and the first m_eq tie bits
 //      are emitted, which yields ascending indices and the lowest-index tie-break for free.
 // The result is deterministic and independent of the order in which atomics land.
+// Long rows with a small budget first try a one-pass variant that gets its threshold bound from a
+// strided sample of the row (select_sampled below); its result is verified and identical.
+#include <cstdlib>
+
 #include "common.hpp"
 
 namespace gsa {
@@ -27,6 +31,7 @@ struct SelectArgs {
     int32_t B, Lq, Lk, q_offset, row_begin, row_end, k_cap;
     int32_t nw;  // bitmap words reserved per bitmap
     int32_t idx_rows, idx_row0;  // idx_out holds rows [idx_row0, idx_row0+idx_rows) of every batch element
+    int32_t sampled;             // allow the sampled one-pass path
 };
 
 constexpr int kSelThreads = 512;
@@ -38,7 +43,10 @@ constexpr int kBitsA = 13;
 constexpr int kCandCap = 2048;
 constexpr int kBinsC = 2048;  // 11 bits per LDS pass (size of hist_c)
 constexpr int kBitsC = 11;
-static_assert(2 * kCandCap + kBinsC <= kBinsA && (1 << kBitsC) == kBinsC, "LDS aliasing");
+constexpr int kCandFast = 5632;  // candidate capacity of the sampled one-pass path
+constexpr int kTieCap = 2048;    // ties at the threshold the sampled path resolves itself
+constexpr int kRegion0 = 2 * kCandFast;
+static_assert(2 * kCandCap + kBinsC <= kBinsA && (1 << kBitsC) == kBinsC && kBinsA <= kRegion0, "LDS aliasing");
 
 __device__ __forceinline__ uint32_t score_key(float x) {
     const uint32_t u = __float_as_uint(x);
@@ -120,32 +128,24 @@ __device__ __forceinline__ void stream_row(const float* __restrict__ row, int n,
     }
 }
 
-__global__ __launch_bounds__(kSelThreads) void topk_select_kernel(SelectArgs a) {
-    extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
-    uint32_t* hist = lds;                       // kBinsA words; later reused as below
-    uint32_t* cand_key = lds;                   // kCandCap
-    uint32_t* cand_idx = lds + kCandCap;        // kCandCap
-    uint32_t* hist_c = lds + 2 * kCandCap;      // kBinsC
-    uint32_t* bm_sel = lds + kBinsA;            // nw
-    uint32_t* bm_tie = bm_sel + a.nw;           // nw
-    uint32_t* scratch = bm_tie + a.nw;          // 32 words: [0,kSelWaves+2) threshold search, [kSelWaves+2] counter
-    unsigned long long* scan64 = reinterpret_cast<unsigned long long*>(scratch + 12);  // kSelWaves entries
+struct SelLds {
+    uint32_t* region0;  // kRegion0 words: histogram of a global pass, later the candidate lists
+    uint32_t* bm_sel;   // nw words: one bit per key of the row, set for sure winners
+    uint32_t* region2;  // max(nw, 4096) words: tie bitmap (exact path) or LDS histogram + tie list (sampled path)
+    uint32_t* scratch;  // 32 words
+};
 
+// Exact two-pass path (any input).  On return bm_sel / bm_tie are final and *m_eq_out is the number of
+// tie bits to take in index order.
+__device__ void select_exact(const float* __restrict__ row, int n, int m, const SelLds& L, uint32_t* m_eq_out) {
+    uint32_t* hist = L.region0;                 // kBinsA words
+    uint32_t* cand_key = L.region0;             // kCandCap
+    uint32_t* cand_idx = L.region0 + kCandCap;  // kCandCap
+    uint32_t* hist_c = L.region0 + 2 * kCandCap;  // kBinsC
+    uint32_t* bm_sel = L.bm_sel;
+    uint32_t* bm_tie = L.region2;
+    uint32_t* scratch = L.scratch;
     const int tid = threadIdx.x;
-    const int R = a.row_end - a.row_begin;
-    const int64_t rid = (int64_t)gridDim.x - 1 - blockIdx.x;  // longest rows of the slab first
-    const int b = (int)(rid / R);
-    const int t = a.row_begin + (int)(rid % R);
-    const int n = min(a.q_offset + t, a.Lk - 1) + 1;
-    int m = a.n_sel[(int64_t)b * a.Lq + t];
-    m = max(0, min(m, min(n, a.k_cap)));
-    int32_t* out = a.idx_out + ((int64_t)b * a.idx_rows + (t - a.idx_row0)) * a.k_cap;
-
-    if (m == n || m == 0) {  // everything visible is selected (or nothing is)
-        for (int j = tid; j < a.k_cap; j += kSelThreads) out[j] = j < m ? j : -1;
-        return;
-    }
-    const float* row = a.scores + ((int64_t)b * R + (t - a.row_begin)) * a.ld;
 
     // ---- A: radix descent over the row in global memory -------------------------------------
     uint32_t prefix = 0;
@@ -239,15 +239,164 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(SelectArgs a) 
         }
         __syncthreads();
     }
-    const uint32_t m_eq = need;
+    *m_eq_out = need;
+}
 
-    // ---- D: ordered emission from the bitmaps ----------------------------------------------------
+// One-pass path for long rows with a small budget.  A strided sample of the row (16 consecutive scores
+// out of every 256, i.e. one 64-byte piece per KiB) is histogrammed first; the sample's
+// (expected rank + 4 sigma)-th largest value gives a lower bound tau such that, with overwhelming
+// probability, at least m scores of the row lie above it and few enough to fit in LDS.  One pass over
+// the row then gathers every score >= tau, and the exact radix select with lowest-index tie-break runs
+// on that list.  The counts are verified: if fewer than m or more than the list capacity qualify (or
+// too many tie at the threshold) the function returns false and the caller takes the exact path, so the
+// sample only ever affects speed.  On success all m winners have their bit set in bm_sel.
+__device__ bool select_sampled(const float* __restrict__ row, int n, int m, const SelLds& L) {
+    uint32_t* hist = L.region0;                   // kBinsA words, dead before the lists are written
+    uint32_t* cand_key = L.region0;               // kCandFast
+    uint32_t* cand_idx = L.region0 + kCandFast;   // kCandFast
+    uint32_t* hist_c = L.region2;                 // kBinsC
+    uint32_t* tie_list = L.region2 + kBinsC;      // kTieCap
+    uint32_t* bm_sel = L.bm_sel;
+    uint32_t* scratch = L.scratch;
+    const int tid = threadIdx.x;
+
+    for (int i = tid; i < kBinsA; i += kSelThreads) hist[i] = 0;
+    __syncthreads();
+    for (int q0 = tid; (q0 >> 2) * 256 < n; q0 += 4 * kSelThreads) {  // four independent loads in flight
+        float4 v[4];
+        int base[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int q = q0 + u * kSelThreads;
+            base[u] = (q >> 2) * 256 + (q & 3) * 4;
+            v[u] = base[u] < n ? *reinterpret_cast<const float4*>(row + base[u]) : float4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float x[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (base[u] + e < n) atomicAdd(&hist[score_key(x[e]) >> (31 - kBitsA)], 1u);
+        }
+    }
+    __syncthreads();
+    const int ms = (n >> 8) * 16 + min(16, n & 255);  // sampled elements
+    const float lam = (float)m * (float)ms / (float)n;
+    const int r = (int)ceilf(lam + 4.0f * sqrtf(lam) + 2.0f);
+    if (r > ms) return false;
+    int b_lo;
+    uint32_t above;
+    find_threshold_bin(hist, kBinsA, (uint32_t)r, scratch, &b_lo, &above);
+
+    const int nw_row = (n + 31) >> 5;
+    for (int i = tid; i < nw_row; i += kSelThreads) bm_sel[i] = 0;
+    if (tid == 0) {
+        scratch[kSelWaves + 2] = 0;  // candidate counter
+        scratch[kSelWaves + 3] = 0;  // tie counter
+    }
+    __syncthreads();
+    stream_row(row, n, [&](int si, float xv) {
+        const uint32_t key = score_key(xv);
+        if ((int)(key >> (31 - kBitsA)) >= b_lo) {
+            const uint32_t pos = atomicAdd(&scratch[kSelWaves + 2], 1u);
+            if (pos < (uint32_t)kCandFast) {
+                cand_key[pos] = key;
+                cand_idx[pos] = (uint32_t)si;
+            }
+        }
+    });
+    __syncthreads();
+    const uint32_t nc = scratch[kSelWaves + 2];
+    if (nc < (uint32_t)m || nc > (uint32_t)kCandFast) return false;
+
+    // exact radix select inside the list: 11 + 11 + 9 bits
+    uint32_t prefix = 0, need = (uint32_t)m;
+    int rb = 31;
+    while (rb > 0) {
+        const int nb = min(kBitsC, rb);
+        const uint32_t mask = (1u << nb) - 1u;
+        for (int i = tid; i < (1 << nb); i += kSelThreads) hist_c[i] = 0;
+        __syncthreads();
+        for (uint32_t c = tid; c < nc; c += kSelThreads) {
+            const uint32_t key = cand_key[c];
+            if ((key >> rb) == prefix) atomicAdd(&hist_c[(key >> (rb - nb)) & mask], 1u);
+        }
+        __syncthreads();
+        int bin;
+        find_threshold_bin(hist_c, 1 << nb, need, scratch, &bin, &above);
+        need -= above;
+        prefix = (prefix << nb) | (uint32_t)bin;
+        rb -= nb;
+    }
+    // prefix = threshold key T; `need` of the elements equal to T are taken, lowest index first
+    for (uint32_t c = tid; c < nc; c += kSelThreads) {
+        const uint32_t key = cand_key[c];
+        const uint32_t s = cand_idx[c];
+        if (key > prefix) {
+            atomicOr(&bm_sel[s >> 5], 1u << (s & 31));
+        } else if (key == prefix) {
+            const uint32_t pos = atomicAdd(&scratch[kSelWaves + 3], 1u);
+            if (pos < (uint32_t)kTieCap) tie_list[pos] = s;
+        }
+    }
+    __syncthreads();
+    const uint32_t ne = scratch[kSelWaves + 3];
+    if (ne > (uint32_t)kTieCap) return false;
+    for (uint32_t i = tid; i < ne; i += kSelThreads) {
+        const uint32_t s = tie_list[i];
+        uint32_t rank = 0;
+        if (need < ne)
+            for (uint32_t j = 0; j < ne; ++j) rank += tie_list[j] < s ? 1u : 0u;
+        if (rank < need) atomicOr(&bm_sel[s >> 5], 1u << (s & 31));
+    }
+    __syncthreads();
+    return true;
+}
+
+__global__ __launch_bounds__(kSelThreads) void topk_select_kernel(SelectArgs a) {
+    extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+    SelLds L;
+    L.region0 = lds;
+    L.bm_sel = lds + kRegion0;
+    L.region2 = L.bm_sel + a.nw;
+    L.scratch = L.region2 + max(a.nw, kBinsC + kTieCap);
+    unsigned long long* scan64 = reinterpret_cast<unsigned long long*>(L.scratch + 12);  // kSelWaves entries
+
+    const int tid = threadIdx.x;
+    const int R = a.row_end - a.row_begin;
+    const int64_t rid = (int64_t)gridDim.x - 1 - blockIdx.x;  // longest rows of the slab first
+    const int b = (int)(rid / R);
+    const int t = a.row_begin + (int)(rid % R);
+    const int n = min(a.q_offset + t, a.Lk - 1) + 1;
+    int m = a.n_sel[(int64_t)b * a.Lq + t];
+    m = max(0, min(m, min(n, a.k_cap)));
+    int32_t* out = a.idx_out + ((int64_t)b * a.idx_rows + (t - a.idx_row0)) * a.k_cap;
+
+    if (m == n || m == 0) {  // everything visible is selected (or nothing is)
+        for (int j = tid; j < a.k_cap; j += kSelThreads) out[j] = j < m ? j : -1;
+        return;
+    }
+    const float* row = a.scores + ((int64_t)b * R + (t - a.row_begin)) * a.ld;
+
+    uint32_t m_eq = 0;
+    bool with_ties = false;
+    bool done = false;
+    if (a.sampled && n >= 16384 && n >= 8 * m) done = select_sampled(row, n, m, L);
+    if (!done) {
+        select_exact(row, n, m, L, &m_eq);
+        with_ties = true;
+    }
+    const uint32_t* bm_sel = L.bm_sel;
+    const uint32_t* bm_tie = L.region2;
+
+    // ---- ordered emission from the bitmaps ---------------------------------------------------------
+    const int nw_row = (n + 31) >> 5;
     const int wpt = (nw_row + kSelThreads - 1) / kSelThreads;
     const int w_lo = min(tid * wpt, nw_row), w_hi = min(w_lo + wpt, nw_row);
     uint32_t cs = 0, ct = 0;
     for (int wi = w_lo; wi < w_hi; ++wi) {
         cs += __popc(bm_sel[wi]);
-        ct += __popc(bm_tie[wi]);
+        if (with_ties) ct += __popc(bm_tie[wi]);
     }
     unsigned long long packed = ((unsigned long long)ct << 32) | cs;
     unsigned long long incl = packed;
@@ -265,7 +414,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(SelectArgs a) 
     uint32_t ties_before = (uint32_t)(excl >> 32);
     uint32_t pos = (uint32_t)(excl & 0xffffffffu) + min(ties_before, m_eq);
     for (int wi = w_lo; wi < w_hi; ++wi) {
-        uint32_t wt = bm_tie[wi];
+        uint32_t wt = with_ties ? bm_tie[wi] : 0u;
         const uint32_t ntie = __popc(wt);
         const uint32_t allow = m_eq - min(ties_before, m_eq);
         while ((uint32_t)__popc(wt) > allow) wt &= ~(0x80000000u >> __clz(wt));  // drop the highest tie bits
@@ -283,7 +432,8 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(SelectArgs a) 
 
 size_t select_lds_bytes(int Lk) {
     const int nw = (Lk + 31) / 32;
-    return (size_t)(kBinsA + 2 * nw + 32) * sizeof(uint32_t);
+    const int r2 = nw > kBinsC + kTieCap ? nw : kBinsC + kTieCap;
+    return (size_t)(kRegion0 + nw + r2 + 32) * sizeof(uint32_t);
 }
 
 hipError_t launch_select(const gsa_shape& sh, int row_begin, int row_end, const float* scores, int64_t ld,
@@ -303,6 +453,7 @@ hipError_t launch_select(const gsa_shape& sh, int row_begin, int row_end, const 
     a.nw = (sh.Lk + 31) / 32;
     a.idx_rows = idx_rows;
     a.idx_row0 = idx_row0;
+    a.sampled = getenv("GSA_SELECT_EXACT_ONLY") ? 0 : 1;  // tuning/diagnostic switch
     const size_t smem = select_lds_bytes(sh.Lk);
     if (smem > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(topk_select_kernel),
