@@ -117,13 +117,16 @@ def main():
     torch.cuda.empty_cache()
     scores = torch.empty((wl.B, R, ld), dtype=torch.float32, device=dev)
     Vg = torch.empty_like(t["V"])
+    ws_a = G.workspace(G.gsa_attn_workspace_bytes(sh, 0, R, k_cap), dev)
     names = ("value_gate", "indexer", "adaptive_k", "select", "attention")
     acc = {n: 0.0 for n in names}
     ssteps = args.stage_steps or args.steps
+    prepass = wl.Lq * min(k_cap, wl.Lk) >= 4 * wl.Lk     # the same rule gsa_forward applies to the value gate
     for it in range(ssteps + 1):
         evs = [ev() for _ in range(len(names) + 1)]
         evs[0].record()
-        G.gsa_value_gate(sh, t["V"], t["g2"], Vg)
+        if prepass:
+            G.gsa_value_gate(sh, t["V"], t["g2"], Vg)
         evs[1].record()
         G.gsa_indexer_scores(sh, t["qI"], t["kI"], t["w"], None, 0, R, scores, ld, None, var, ws_i)
         evs[2].record()
@@ -131,7 +134,8 @@ def main():
         evs[3].record()
         G.gsa_topk_select(sh, 0, R, scores, ld, n_sel, k_cap, idx)
         evs[4].record()
-        G.gsa_sparse_gated_attn(sh, 0, R, t["Q"], t["K"], Vg, None, t["g1"], idx, n_sel, k_cap, 0.0, out)
+        G.gsa_sparse_gated_attn(sh, 0, R, t["Q"], t["K"], Vg if prepass else t["V"], None if prepass else t["g2"], t["g1"],
+                                idx, n_sel, k_cap, 0.0, out, ws_a)
         evs[5].record()
         torch.cuda.synchronize()
         if it > 0:  # first pass is a warm-up
@@ -151,7 +155,7 @@ def main():
     pairs = CM.causal_pairs(wl.B, wl.Lq, wl.Lk, wl.q_offset)
     fl_idx = CM.indexer_flops(pairs, wl.HI, wl.dI)
     fl_att = CM.attention_flops(sum_nsel, wl.H, wl.d_h)
-    gbytes = CM.gathered_bytes(sum_nsel, wl.H_kv, wl.d_h, elt, gate_in_kernel=False)
+    gbytes = CM.gathered_bytes(sum_nsel, wl.H_kv, wl.d_h, elt, gate_in_kernel=not prepass)
     att_s = stage_ms["attention"] * 1e-3
     idx_s = stage_ms["indexer"] * 1e-3
     sel_s = stage_ms["select"] * 1e-3

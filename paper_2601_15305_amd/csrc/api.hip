@@ -20,7 +20,8 @@ hipError_t launch_adaptive_k(const gsa_shape& sh, const gsa_adaptive& c, int row
 hipError_t launch_value_gate(const gsa_shape& sh, const void* V, const void* g2, void* Vg, hipStream_t st);
 hipError_t launch_attention(const gsa_shape& sh, int row_begin, int row_end, const void* Q, const void* K, const void* V,
                             const void* g2, const void* g1, const int32_t* idx, int idx_rows, int idx_row0,
-                            const int32_t* n_sel, int k_cap, float scale, void* out, hipStream_t st);
+                            const int32_t* n_sel, int k_cap, float scale, void* out, void* workspace, hipStream_t st);
+size_t attn_workspace_bytes(const gsa_shape& sh, int row_begin, int row_end, int k_cap);
 
 static thread_local std::string g_last_error;
 
@@ -68,7 +69,7 @@ static int64_t slab_ld(const gsa_shape& s) { return ((int64_t)s.Lk + 31) & ~(int
 
 // ---- forward workspace plan ---------------------------------------------------------------------
 struct ForwardPlan {
-    size_t off_vg, off_var, off_k, off_nsel, off_idx, off_scores, off_partial, total;
+    size_t off_vg, off_var, off_k, off_nsel, off_idx, off_scores, off_partial, off_attn, total;
     int slab_rows;
 };
 
@@ -107,13 +108,17 @@ static ForwardPlan plan_forward(const gsa_shape& s, int k_cap, bool has_g2, bool
     p.off_scores = off;
     off += up256((size_t)s.B * Rs * (size_t)slab_ld(s) * 4);
     p.off_partial = off;
-    size_t part = 0;
+    size_t part = 0, attn = 0;
     for (int r0 = 0; r0 < s.Lq; r0 += Rs) {
         const int r1 = r0 + Rs < s.Lq ? r0 + Rs : s.Lq;
         const size_t b = indexer_workspace_bytes(s, r0, r1);
         if (b > part) part = b;
+        const size_t c = attn_workspace_bytes(s, r0, r1, k_cap);
+        if (c > attn) attn = c;
     }
     off += up256(part);
+    p.off_attn = off;
+    off += up256(attn);
     p.total = off;
     return p;
 }
@@ -189,19 +194,14 @@ int32_t gsa_topk_select(const gsa_shape* shape, int32_t row_begin, int32_t row_e
 }
 
 size_t gsa_attn_workspace_bytes(const gsa_shape* shape, int32_t row_begin, int32_t row_end, int32_t k_cap) {
-    (void)shape;
-    (void)row_begin;
-    (void)row_end;
-    (void)k_cap;
-    return 0;
+    if (check_shape(shape) != GSA_OK || check_rows(shape, row_begin, row_end) != GSA_OK || k_cap < 1 || k_cap > 8192) return 0;
+    return up256(attn_workspace_bytes(*shape, row_begin, row_end, k_cap));
 }
 
 int32_t gsa_sparse_gated_attn(const gsa_shape* shape, int32_t row_begin, int32_t row_end, const void* Q, const void* K,
                               const void* V, const void* g2_logits, const void* g1_logits, const int32_t* idx,
                               const int32_t* n_sel, int32_t k_cap, float softmax_scale, void* out, void* workspace,
                               size_t workspace_bytes, void* stream) {
-    (void)workspace;
-    (void)workspace_bytes;
     int32_t rc = check_shape(shape);
     if (rc != GSA_OK) return rc;
     if (!Q || !K || !V || !idx || !n_sel || !out) return GSA_ERR_NULL;
@@ -212,9 +212,11 @@ int32_t gsa_sparse_gated_attn(const gsa_shape* shape, int32_t row_begin, int32_t
     if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(out, 16) || (g1_logits && !aligned(g1_logits, 16)) ||
         (g2_logits && !aligned(g2_logits, 16)))
         return GSA_ERR_SHAPE;
+    const size_t need = attn_workspace_bytes(*shape, row_begin, row_end, k_cap);
+    if (need > 0 && (!workspace || !aligned(workspace, 256) || workspace_bytes < need)) return GSA_ERR_WORKSPACE;
     const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt((float)shape->d_h);
     hipError_t e = launch_attention(*shape, row_begin, row_end, Q, K, V, g2_logits, g1_logits, idx, shape->Lq, 0, n_sel,
-                                    k_cap, scale, out, static_cast<hipStream_t>(stream));
+                                    k_cap, scale, out, workspace, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_sparse_gated_attn");
 }
 
@@ -291,7 +293,8 @@ int32_t gsa_forward(const gsa_shape* shape, const gsa_adaptive* ctl, const void*
         const int idx_row0 = own_idx ? r0 : 0;
         e = launch_select(s, r0, r1, scores, ld, nsel, k_cap, idx, idx_rows, idx_row0, st);
         if (e != hipSuccess) return hip_fail(e, "gsa_forward/select");
-        e = launch_attention(s, r0, r1, Q, K, Vuse, g2use, g1_logits, idx, idx_rows, idx_row0, nsel, k_cap, scale, out, st);
+        e = launch_attention(s, r0, r1, Q, K, Vuse, g2use, g1_logits, idx, idx_rows, idx_row0, nsel, k_cap, scale, out,
+                             ws + plan.off_attn, st);
         if (e != hipSuccess) return hip_fail(e, "gsa_forward/attention");
     }
     return GSA_OK;

@@ -34,6 +34,8 @@ struct AttnArgs {
     int32_t B, Lq, Lk, H, H_kv, row_begin, row_end, k_cap;
     int32_t idx_rows, idx_row0;  // idx holds rows [idx_row0, idx_row0+idx_rows) of every batch element
     float scale;  // softmax scale
+    int32_t nsplit;  // > 1: a row's selected list is cut into nsplit pieces (grid.z), partial results go to `part`
+    float* part;     // [rows][H][nsplit][d_h + 4]: unnormalised O, running max (base 2), running sum, padding
 };
 
 constexpr float kNegBig = -1.0e30f;
@@ -67,7 +69,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     const int G = a.H / a.H_kv;
     const float sl2 = a.scale * kLog2e;
     const int64_t tokstride = (int64_t)a.H_kv * ROWB;  // bytes between consecutive tokens
-    const int ntile = (nsel + 31) >> 5;
+    const int ntile_all = (nsel + 31) >> 5;
+    const int tps = (ntile_all + a.nsplit - 1) / a.nsplit;  // tiles per split
+    const int it0 = min((int)blockIdx.z * tps, ntile_all);
+    const int ntile = min(it0 + tps, ntile_all);
 
     // blockDim.x / 64 kv heads per workgroup; blockIdx.y selects which ones.  Blocks are dispatched
     // x-fastest, so all queries work on one slice of kv heads before the next slice starts: the K/V'
@@ -116,8 +121,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
             }
         };
 
-        if (ntile > 0) load_tile(0);
-        for (int it = 0; it < ntile; ++it) {
+        if (it0 < ntile) load_tile(it0 * 32);
+        for (int it = it0; it < ntile; ++it) {
             const int j0 = it * 32;
             // ---- V' rows -> LDS (natural layout: row = token slot, 16 B per lane) -----------------
 #pragma unroll
@@ -195,6 +200,19 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
         // ---- normalise, G1, store ---------------------------------------------------------------------
         float ltot = lrun + __shfl_xor(lrun, 16, 64);
         ltot += __shfl_xor(ltot, 32, 64);
+        if (a.nsplit > 1) {  // partial result of this piece of the list; attn_merge_kernel finishes the row
+            if (head_ok) {
+                float* pp = a.part + (((rid * a.H) + head) * a.nsplit + blockIdx.z) * (DH + 4);
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+                    *reinterpret_cast<f32x4*>(pp + mb * 16 + 4 * q) = o[mb];
+                if (q == 0) {
+                    pp[DH] = mrun;
+                    pp[DH + 1] = ltot;
+                }
+            }
+            continue;
+        }
         if (head_ok) {
             const float inv = ltot > 0.f ? 1.0f / ltot : 0.f;
             const int64_t obase = (qrow * a.H + head) * DH;
@@ -216,6 +234,32 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
             }
         }
     }
+}
+
+// Combine the partial results of a split row: out = (sum_s 2^(m_s - M) O_s) / (sum_s 2^(m_s - M) l_s) * sigmoid(g1).
+template <int DH>
+__global__ __launch_bounds__(DH) void attn_merge_kernel(AttnArgs a) {
+    const int R = a.row_end - a.row_begin;
+    const int64_t rh = blockIdx.x;  // (row, head)
+    const int64_t rid = rh / a.H;
+    const int head = (int)(rh % a.H);
+    const int b = (int)(rid / R);
+    const int t = a.row_begin + (int)(rid % R);
+    const int d = threadIdx.x;
+    constexpr int PS = DH + 4;  // floats per partial record (16-byte multiple)
+    const float* pp = a.part + rh * a.nsplit * PS;
+    float M = kNegBig;
+    for (int sp = 0; sp < a.nsplit; ++sp) M = fmaxf(M, pp[sp * PS + DH]);
+    float L = 0.f, O = 0.f;
+    for (int sp = 0; sp < a.nsplit; ++sp) {
+        const float wgt = fast_exp2(pp[sp * PS + DH] - M);
+        L = fmaf(wgt, pp[sp * PS + DH + 1], L);
+        O = fmaf(wgt, pp[sp * PS + d], O);
+    }
+    float y = L > 0.f ? O / L : 0.f;
+    const int64_t oi = (((int64_t)b * a.Lq + t) * a.H + head) * DH + d;
+    if (a.g1) y *= sigmoid_f32(bf16_bits_to_f32(static_cast<const uint16_t*>(a.g1)[oi]));
+    static_cast<uint16_t*>(a.out)[oi] = (uint16_t)f32_to_bf16_bits(y);
 }
 
 // fp32 kernel: plain vector arithmetic, one wave per query head, online softmax over chunks of 64
@@ -351,9 +395,30 @@ static int attn_groups_per_block(const gsa_shape& sh, int64_t rows) {
     return gpb;
 }
 
+// Pieces a row's selected list is cut into (bf16 path): 1 when the launch has enough workgroups anyway,
+// otherwise enough to reach about a thousand workgroups, at least two 32-token tiles per piece.
+int attn_splits(const gsa_shape& sh, int64_t rows, int k_cap) {
+    if (sh.dtype != GSA_BF16) return 1;
+    const int gpb = attn_groups_per_block(sh, rows);
+    const int64_t wgs = rows * (sh.H_kv / gpb);
+    if (wgs >= 1024) return 1;
+    int64_t by_len = cdiv(cdiv(k_cap, 32), 2);
+    if (by_len < 1) by_len = 1;
+    int64_t ns = cdiv(1024, wgs);
+    if (ns > by_len) ns = by_len;
+    if (ns > 64) ns = 64;
+    return (int)(ns < 1 ? 1 : ns);
+}
+
+size_t attn_workspace_bytes(const gsa_shape& sh, int row_begin, int row_end, int k_cap) {
+    const int64_t rows = (int64_t)sh.B * (row_end - row_begin);
+    const int ns = attn_splits(sh, rows, k_cap);
+    return ns > 1 ? (size_t)rows * sh.H * ns * (sh.d_h + 4) * sizeof(float) : 0;
+}
+
 hipError_t launch_attention(const gsa_shape& sh, int row_begin, int row_end, const void* Q, const void* K, const void* V,
                             const void* g2, const void* g1, const int32_t* idx, int idx_rows, int idx_row0,
-                            const int32_t* n_sel, int k_cap, float scale, void* out, hipStream_t st) {
+                            const int32_t* n_sel, int k_cap, float scale, void* out, void* workspace, hipStream_t st) {
     AttnArgs a;
     a.Q = Q;
     a.K = K;
@@ -375,9 +440,11 @@ hipError_t launch_attention(const gsa_shape& sh, int row_begin, int row_end, con
     a.idx_row0 = idx_row0;
     a.scale = scale;
     const int64_t rows = (int64_t)sh.B * (row_end - row_begin);
+    a.nsplit = attn_splits(sh, rows, k_cap);
+    a.part = static_cast<float*>(workspace);
     if (sh.dtype == GSA_BF16) {
         const int gpb = attn_groups_per_block(sh, rows);
-        const dim3 grid((unsigned)rows, (unsigned)(sh.H_kv / gpb));
+        const dim3 grid((unsigned)rows, (unsigned)(sh.H_kv / gpb), (unsigned)a.nsplit);
         const dim3 block(64 * gpb);
         const size_t smem = (size_t)gpb * 32 * (sh.d_h * 2 + 32);
         if (sh.d_h == 128) {
@@ -390,6 +457,15 @@ hipError_t launch_attention(const gsa_shape& sh, int row_begin, int row_end, con
                 hipLaunchKernelGGL((attn_bf16_kernel<64, true>), grid, block, smem, st, a);
             else
                 hipLaunchKernelGGL((attn_bf16_kernel<64, false>), grid, block, smem, st, a);
+        }
+        if (a.nsplit > 1) {
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            const dim3 mgrid((unsigned)(rows * sh.H));
+            if (sh.d_h == 128)
+                hipLaunchKernelGGL(attn_merge_kernel<128>, mgrid, dim3(128), 0, st, a);
+            else
+                hipLaunchKernelGGL(attn_merge_kernel<64>, mgrid, dim3(64), 0, st, a);
         }
     } else {
         if (sh.d_h == 128)

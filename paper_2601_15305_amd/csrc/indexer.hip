@@ -33,7 +33,7 @@ struct IndexerArgs {
     const float* bI;
     float* scores;
     int64_t ld;
-    float2* partial;  // [B][R][nsplit]
+    float2* partial;  // [B][R][nsplit][4]
     int32_t B, Lq, Lk, q_offset, row_begin, row_end;
     int32_t kc;      // keys per split (multiple of 128)
     int32_t nsplit;
@@ -83,7 +83,10 @@ __global__ __launch_bounds__(256) void indexer_kernel(IndexerArgs a) {
     const int R = a.row_end - a.row_begin;
 
     const int t_wg0 = a.row_begin + tile * QT;
-    const int t_w0 = t_wg0 + wv * QW;
+    // A workgroup whose rows all fit in one wave's share (decode, or the ragged last tile) runs "narrow":
+    // its four waves take the same rows and split the column blocks of every key tile between them.
+    const bool narrow = (a.row_end - t_wg0) <= QW;
+    const int t_w0 = narrow ? t_wg0 : t_wg0 + wv * QW;
     const int t_wg_last = min(t_wg0 + QT, a.row_end) - 1;
     const int kmax_wg = min(a.q_offset + t_wg_last, a.Lk - 1);  // last key any row of the workgroup sees
     const int key_lo = split * a.kc;
@@ -98,6 +101,7 @@ __global__ __launch_bounds__(256) void indexer_kernel(IndexerArgs a) {
     float nbias[HL];        // -log2(e) * bias of the lane's r-th head
     float center[NSLOT];
     float s1[NSLOT], s2[NSLOT];
+    bool slot_live[NSLOT];  // wave-uniform: some lane of the wave has a valid row in this slot
 #pragma unroll
     for (int r = 0; r < HL; ++r) {
         const int j = (HI == 8) ? 4 * h + r : r;  // head of accumulator register s*HL + r
@@ -109,6 +113,7 @@ __global__ __launch_bounds__(256) void indexer_kernel(IndexerArgs a) {
         const int t = t_w0 + tl;
         const bool ok = t < a.row_end;
         lim[s] = ok ? min(a.q_offset + t, a.Lk - 1) : -1;
+        slot_live[s] = __any(ok) != 0;
         rowoff[s] = (uint32_t)tl * (uint32_t)a.ld;
         float c = 0.f;
 #pragma unroll
@@ -209,6 +214,7 @@ __global__ __launch_bounds__(256) void indexer_kernel(IndexerArgs a) {
         auto epilogue = [&](const f32x16& c, int scol, bool masked, float (&sc_out)[NSLOT]) {
 #pragma unroll
             for (int s = 0; s < NSLOT; ++s) {
+                if (masked && !slot_live[s]) continue;
                 float sc = 0.f;
 #pragma unroll
                 for (int r = 0; r < HL; ++r) {
@@ -286,11 +292,11 @@ __global__ __launch_bounds__(256) void indexer_kernel(IndexerArgs a) {
             if (more) load_tile(s0 + kBN);
             const unsigned char* tileptr = smem + (it & 1) * (kBN * LDSROW);
             if (wave_has_rows && s0 <= lim_last) {
-                const bool full = wave_rows_full && (s0 + kBN - 1 <= lim_first);
+                const bool full = !narrow && wave_rows_full && (s0 + kBN - 1 <= lim_first);
                 if (full) {
                     full_tile(tileptr, s0);
                 } else {
-                    for (int nb = 0; nb < 4; ++nb) {
+                    for (int nb = narrow ? wv : 0; nb < 4; nb += narrow ? 4 : 1) {
                         float sc[NSLOT];
                         f32x16 c = mfma_block(tileptr, nb);
                         epilogue(c, s0 + 4 * n + nb, true, sc);
@@ -312,8 +318,16 @@ __global__ __launch_bounds__(256) void indexer_kernel(IndexerArgs a) {
             x2 += __shfl_xor(x2, o, 64);
         }
         if (n == 0 && lim[s] >= 0 && !(HI == 8 && h == 1)) {
+            // four partial slots per (row, split): one per wave in narrow mode, else the owner wave fills
+            // slot 0 and clears the rest
             const int t = t_w0 + acc_row(s * HL, h) / HI;
-            a.partial[((int64_t)b * R + (t - a.row_begin)) * a.nsplit + split] = float2{x1, x2};
+            float2* dst = a.partial + (((int64_t)b * R + (t - a.row_begin)) * a.nsplit + split) * 4;
+            if (narrow) {
+                dst[wv] = float2{x1, x2};
+            } else {
+                dst[0] = float2{x1, x2};
+                dst[1] = dst[2] = dst[3] = float2{0.f, 0.f};
+            }
         }
     }
 }
@@ -329,8 +343,8 @@ __global__ void indexer_finalize_kernel(const float2* partial, const float* w, f
     const int b = (int)(gid / R);
     const int t = row_begin + (int)(gid % R);
     double S1 = 0.0, S2 = 0.0;
-    for (int s = 0; s < nsplit; ++s) {
-        const float2 p = partial[gid * nsplit + s];
+    for (int s = 0; s < nsplit * 4; ++s) {
+        const float2 p = partial[gid * nsplit * 4 + s];
         S1 += (double)p.x;
         S2 += (double)p.y;
     }
@@ -373,7 +387,7 @@ void indexer_plan(const gsa_shape& sh, int row_begin, int row_end, int* kc_out, 
 size_t indexer_workspace_bytes(const gsa_shape& sh, int row_begin, int row_end) {
     int kc, nsplit, ntiles;
     indexer_plan(sh, row_begin, row_end, &kc, &nsplit, &ntiles);
-    return (size_t)sh.B * (size_t)(row_end - row_begin) * (size_t)nsplit * sizeof(float2);
+    return (size_t)sh.B * (size_t)(row_end - row_begin) * (size_t)nsplit * 4 * sizeof(float2);
 }
 
 template <typename T, int DI, int HI>

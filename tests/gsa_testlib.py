@@ -62,8 +62,9 @@ def gpu_attention(wl, t, idx, n_sel, k_cap, use_g2=True, use_g1=True, scale=0.0,
     sh = G.shape_of(wl)
     row_end = wl.Lq if row_end is None else row_end
     out = torch.full_like(t["Q"], float("nan"))
+    ws = G.workspace(G.gsa_attn_workspace_bytes(sh, row_begin, row_end, k_cap), out.device)
     G.gsa_sparse_gated_attn(sh, row_begin, row_end, t["Q"], t["K"], t["V"] if V is None else V,
-                            t["g2"] if use_g2 else None, t["g1"] if use_g1 else None, idx, n_sel, k_cap, scale, out)
+                            t["g2"] if use_g2 else None, t["g1"] if use_g1 else None, idx, n_sel, k_cap, scale, out, ws)
     torch.cuda.synchronize()
     return out
 

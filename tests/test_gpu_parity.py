@@ -335,6 +335,7 @@ def test_forward_decode_shape_equals_prefill_last_row():
     same_k = dec["k"][:, 0] == pre["k"][:, 639]          # the two launches sum the variance in different orders
     assert same_k.sum().item() >= 2
     assert torch.equal(dec["idx"][:, 0][same_k], pre["idx"][:, 639][same_k])
-    assert torch.equal(dec["out"][:, 0][same_k], pre["out"][:, 639][same_k])
+    # the decode launch cuts each selected list into pieces and merges them: same values up to rounding
+    assert (dec["out"][:, 0][same_k].float() - pre["out"][:, 639][same_k].float()).abs().max().item() <= 1e-2
     td = {k: (v[:, 639:] if k in ("Q", "g1", "qI", "w") else v) for k, v in t.items()}
     _check_forward(wd, td, dec, kw)
