@@ -1,6 +1,7 @@
 // C ABI of libgsa: host-side argument validation, workspace carving and launch sequencing.
 // Every error that can be decided from the arguments is returned before anything is launched.
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 
@@ -11,10 +12,13 @@ namespace gsa {
 void indexer_plan(const gsa_shape& sh, int row_begin, int row_end, int* kc_out, int* nsplit_out, int* ntiles_out);
 size_t indexer_workspace_bytes(const gsa_shape& sh, int row_begin, int row_end);
 hipError_t launch_indexer(const gsa_shape& sh, const void* qI, const void* kI, const float* w, const float* bI,
-                          int row_begin, int row_end, float* scores, int64_t ld, float* row_mean, float* row_var,
-                          void* workspace, hipStream_t st);
+                          int row_begin, int row_end, float* scores, uint16_t* keys, int64_t ld, float* row_mean,
+                          float* row_var, void* workspace, hipStream_t st);
 hipError_t launch_select(const gsa_shape& sh, int row_begin, int row_end, const float* scores, int64_t ld,
                          const int32_t* n_sel, int k_cap, int32_t* idx_out, int idx_rows, int idx_row0, hipStream_t st);
+hipError_t launch_select16(const gsa_shape& sh, int row_begin, int row_end, const uint16_t* keys, int64_t ld,
+                           const int32_t* n_sel, int k_cap, int32_t* idx_out, int idx_rows, int idx_row0, const void* qI,
+                           const void* kI, const float* w, const float* bI, hipStream_t st);
 hipError_t launch_adaptive_k(const gsa_shape& sh, const gsa_adaptive& c, int row_begin, int row_end,
                              const float* row_var, int32_t* k_out, int32_t* n_sel_out, hipStream_t st);
 hipError_t launch_value_gate(const gsa_shape& sh, const void* V, const void* g2, void* Vg, hipStream_t st);
@@ -88,6 +92,14 @@ static bool gate_as_prepass(const gsa_shape& s, int k_cap) {
     return (int64_t)s.Lq * k_eff >= 4 * (int64_t)s.Lk;
 }
 
+// Inside the fused forward the indexer hands 16-bit fixed-point keys to the selection instead of fp32
+// scores (see select16.hip).  GSA_FORWARD_FP32_SCORES=1 in the environment keeps the fp32 slab, for
+// comparison runs.
+static bool forward_uses_keys() {
+    const char* e = getenv("GSA_FORWARD_FP32_SCORES");
+    return !(e && e[0] == '1');
+}
+
 static ForwardPlan plan_forward(const gsa_shape& s, int k_cap, bool has_g2, bool own_idx, int slab_rows) {
     ForwardPlan p;
     has_g2 = has_g2 && gate_as_prepass(s, k_cap);
@@ -106,7 +118,7 @@ static ForwardPlan plan_forward(const gsa_shape& s, int k_cap, bool has_g2, bool
     p.off_idx = off;
     if (own_idx) off += up256((size_t)s.B * Rs * (size_t)k_cap * 4);
     p.off_scores = off;
-    off += up256((size_t)s.B * Rs * (size_t)slab_ld(s) * 4);
+    off += up256((size_t)s.B * Rs * (size_t)slab_ld(s) * 4);  // sized for fp32 scores; 16-bit keys use half of it
     p.off_partial = off;
     size_t part = 0, attn = 0;
     for (int r0 = 0; r0 < s.Lq; r0 += Rs) {
@@ -163,7 +175,7 @@ int32_t gsa_indexer_scores(const gsa_shape* shape, const void* qI, const void* k
     if (!aligned(qI, 16) || !aligned(kI, 16) || (scores && !aligned(scores, 16))) return GSA_ERR_SHAPE;
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < indexer_workspace_bytes(*shape, row_begin, row_end))
         return GSA_ERR_WORKSPACE;
-    hipError_t e = launch_indexer(*shape, qI, kI, w, bI, row_begin, row_end, scores, ld_scores, row_mean, row_var,
+    hipError_t e = launch_indexer(*shape, qI, kI, w, bI, row_begin, row_end, scores, nullptr, ld_scores, row_mean, row_var,
                                   workspace, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_indexer_scores");
 }
@@ -280,18 +292,22 @@ int32_t gsa_forward(const gsa_shape* shape, const gsa_adaptive* ctl, const void*
     int32_t* kbuf = k_out ? k_out : reinterpret_cast<int32_t*>(ws + plan.off_k);
     int32_t* nsel = n_sel_out ? n_sel_out : reinterpret_cast<int32_t*>(ws + plan.off_nsel);
     float* scores = reinterpret_cast<float*>(ws + plan.off_scores);
+    uint16_t* keys = reinterpret_cast<uint16_t*>(ws + plan.off_scores);
+    const bool use_keys = forward_uses_keys();
     const int64_t ld = slab_ld(s);
     const int Rs = plan.slab_rows;
     for (int r0 = 0; r0 < s.Lq; r0 += Rs) {
         const int r1 = r0 + Rs < s.Lq ? r0 + Rs : s.Lq;
-        e = launch_indexer(s, qI, kI, w, bI, r0, r1, scores, ld, nullptr, var, ws + plan.off_partial, st);
+        e = launch_indexer(s, qI, kI, w, bI, r0, r1, use_keys ? nullptr : scores, use_keys ? keys : nullptr, ld, nullptr, var,
+                           ws + plan.off_partial, st);
         if (e != hipSuccess) return hip_fail(e, "gsa_forward/indexer");
         e = launch_adaptive_k(s, *ctl, r0, r1, var, kbuf, nsel, st);
         if (e != hipSuccess) return hip_fail(e, "gsa_forward/adaptive_k");
         int32_t* idx = own_idx ? reinterpret_cast<int32_t*>(ws + plan.off_idx) : idx_out;
         const int idx_rows = own_idx ? (r1 - r0) : s.Lq;
         const int idx_row0 = own_idx ? r0 : 0;
-        e = launch_select(s, r0, r1, scores, ld, nsel, k_cap, idx, idx_rows, idx_row0, st);
+        e = use_keys ? launch_select16(s, r0, r1, keys, ld, nsel, k_cap, idx, idx_rows, idx_row0, qI, kI, w, bI, st)
+                     : launch_select(s, r0, r1, scores, ld, nsel, k_cap, idx, idx_rows, idx_row0, st);
         if (e != hipSuccess) return hip_fail(e, "gsa_forward/select");
         e = launch_attention(s, r0, r1, Q, K, Vuse, g2use, g1_logits, idx, idx_rows, idx_row0, nsel, k_cap, scale, out,
                              ws + plan.off_attn, st);

@@ -32,6 +32,7 @@ struct IndexerArgs {
     const float* w;
     const float* bI;
     float* scores;
+    uint16_t* keys;  // alternative to scores: 16-bit keys, same indexing
     int64_t ld;
     float2* partial;  // [B][R][nsplit][4]
     int32_t B, Lq, Lk, q_offset, row_begin, row_end;
@@ -56,7 +57,9 @@ struct ElemTraits<float> {
 // Row (t,j) index m of accumulator register i in lane half h (l/32) of a 32x32 MFMA result.
 __device__ __forceinline__ constexpr int acc_row(int i, int h) { return 8 * (i / 4) + 4 * h + (i % 4); }
 
-template <typename T, int DI, int HI, bool STORE>
+// STORE: 0 = statistics only, 1 = fp32 scores, 2 = 16-bit fixed-point keys floor(score * 65536 / HI)
+// (saturated at 65535), a monotone compression of the score used inside the fused forward.
+template <typename T, int DI, int HI, int STORE>
 __global__ __launch_bounds__(256) void indexer_kernel(IndexerArgs a) {
     constexpr int EB = ElemTraits<T>::kBytes;
     constexpr int ROWB = DI * EB;            // bytes of one key row
@@ -94,7 +97,11 @@ __global__ __launch_bounds__(256) void indexer_kernel(IndexerArgs a) {
 
     // ---- per-lane slot bookkeeping -------------------------------------------------------
     // Score rows of this wave start at a wave-uniform base; a lane adds a 32-bit element offset.
-    float* const wave_scores = STORE ? a.scores + ((int64_t)b * R + (t_w0 - a.row_begin)) * a.ld : nullptr;
+    float* const wave_scores = STORE == 1 ? a.scores + ((int64_t)b * R + (t_w0 - a.row_begin)) * a.ld : nullptr;
+    uint16_t* const wave_keys = STORE == 2 ? a.keys + ((int64_t)b * R + (t_w0 - a.row_begin)) * a.ld : nullptr;
+    // In key mode the head weights carry the key scale 65536/HI (a power of two, so every product and
+    // sum is the scaled image of the unscaled one, bit for bit); the statistics are unscaled on the way out.
+    constexpr float kKeyScale = STORE == 2 ? 65536.0f / HI : 1.0f;
     int lim[NSLOT];         // last visible key of the slot's query, -1 if the query is outside the range
     uint32_t rowoff[NSLOT]; // element offset of the slot's score row from wave_scores
     float wreg[16];         // head weight of accumulator register i
@@ -120,8 +127,8 @@ __global__ __launch_bounds__(256) void indexer_kernel(IndexerArgs a) {
         for (int r = 0; r < HL; ++r) {
             const int j = (HI == 8) ? 4 * h + r : r;
             const float wv_ = ok ? a.w[((int64_t)b * a.Lq + t) * HI + j] : 0.f;
-            wreg[s * HL + r] = wv_;
-            c += 0.5f * wv_;
+            wreg[s * HL + r] = wv_ * kKeyScale;
+            c += 0.5f * (wv_ * kKeyScale);
         }
         if (HI == 8) c += __shfl_xor(c, 32, 64);
         center[s] = c;
@@ -230,8 +237,11 @@ __global__ __launch_bounds__(256) void indexer_kernel(IndexerArgs a) {
                     const float d = sc - center[s];
                     s1[s] += d;
                     s2[s] = fmaf(d, d, s2[s]);
-                    if constexpr (STORE)
+                    if constexpr (STORE == 1) {
                         if (masked) wave_scores[rowoff[s] + (uint32_t)scol] = sc;
+                    } else if constexpr (STORE == 2) {
+                        if (masked) wave_keys[rowoff[s] + (uint32_t)scol] = (uint16_t)min((uint32_t)sc, 65535u);
+                    }
                 }
             }
         };
@@ -248,12 +258,24 @@ __global__ __launch_bounds__(256) void indexer_kernel(IndexerArgs a) {
                 epilogue(c, s0 + 4 * n + nb, false, sc4[nb]);
                 if (nb < 3) c = cn;
             }
-            if constexpr (STORE) {
+            if constexpr (STORE == 1) {
                 if (HI != 8 || h == 0) {
 #pragma unroll
                     for (int s = 0; s < NSLOT; ++s)
                         *reinterpret_cast<float4*>(wave_scores + rowoff[s] + (uint32_t)(s0 + 4 * n)) =
                             float4{sc4[0][s], sc4[1][s], sc4[2][s], sc4[3][s]};
+                }
+            } else if constexpr (STORE == 2) {
+                if (HI != 8 || h == 0) {
+#pragma unroll
+                    for (int s = 0; s < NSLOT; ++s) {
+                        typedef __attribute__((ext_vector_type(2))) unsigned short u16x2;
+                        // float -> uint truncates towards zero, the pack saturates at 65535
+                        const u16x2 lo = __builtin_amdgcn_cvt_pk_u16((uint32_t)sc4[0][s], (uint32_t)sc4[1][s]);
+                        const u16x2 hi = __builtin_amdgcn_cvt_pk_u16((uint32_t)sc4[2][s], (uint32_t)sc4[3][s]);
+                        *reinterpret_cast<u32x2*>(wave_keys + rowoff[s] + (uint32_t)(s0 + 4 * n)) =
+                            u32x2{__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
+                    }
                 }
             }
         };
@@ -322,6 +344,8 @@ __global__ __launch_bounds__(256) void indexer_kernel(IndexerArgs a) {
             // slot 0 and clears the rest
             const int t = t_w0 + acc_row(s * HL, h) / HI;
             float2* dst = a.partial + (((int64_t)b * R + (t - a.row_begin)) * a.nsplit + split) * 4;
+            x1 *= 1.0f / kKeyScale;  // exact: power of two
+            x2 *= 1.0f / (kKeyScale * kKeyScale);
             if (narrow) {
                 dst[wv] = float2{x1, x2};
             } else {
@@ -394,7 +418,7 @@ template <typename T, int DI, int HI>
 static hipError_t launch_one(const IndexerArgs& a, hipStream_t st) {
     constexpr int LDSROW = DI * ElemTraits<T>::kBytes + 16;
     const size_t smem = 2 * kBN * LDSROW;
-    auto kern = a.scores ? indexer_kernel<T, DI, HI, true> : indexer_kernel<T, DI, HI, false>;
+    auto kern = a.keys ? indexer_kernel<T, DI, HI, 2> : (a.scores ? indexer_kernel<T, DI, HI, 1> : indexer_kernel<T, DI, HI, 0>);
     if (smem > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
@@ -426,9 +450,10 @@ static hipError_t launch_di(const IndexerArgs& a, int DI, int HI, hipStream_t st
 }
 
 hipError_t launch_indexer(const gsa_shape& sh, const void* qI, const void* kI, const float* w, const float* bI,
-                          int row_begin, int row_end, float* scores, int64_t ld, float* row_mean, float* row_var,
-                          void* workspace, hipStream_t st) {
+                          int row_begin, int row_end, float* scores, uint16_t* keys, int64_t ld, float* row_mean,
+                          float* row_var, void* workspace, hipStream_t st) {
     IndexerArgs a;
+    a.keys = keys;
     a.qI = qI;
     a.kI = kI;
     a.w = w;

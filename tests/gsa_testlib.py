@@ -107,7 +107,8 @@ def check_selection_vs_fp64(idx_row, n_sel, I64, band=SEL_BAND):
     thr = np.sort(I64)[n - n_sel]          # n_sel-th largest
     diff = np.setxor1d(want, got)
     dev = np.abs(I64[diff] - thr)
-    assert np.all(dev <= band * abs(thr)), "selection differs outside the threshold band: max rel dev %.3g" % (dev.max() / abs(thr))
+    # 1.2e-38: scores below the smallest normal fp32 number are flushed to zero on the GPU and cannot be ordered
+    assert np.all(dev <= band * abs(thr) + 1.2e-38), "selection differs outside the threshold band: max rel dev %.3g" % (dev.max() / abs(thr))
     return int(diff.shape[0])
 
 

@@ -339,3 +339,54 @@ def test_forward_decode_shape_equals_prefill_last_row():
     assert (dec["out"][:, 0][same_k].float() - pre["out"][:, 639][same_k].float()).abs().max().item() <= 1e-2
     td = {k: (v[:, 639:] if k in ("Q", "g1", "qI", "w") else v) for k, v in t.items()}
     _check_forward(wd, td, dec, kw)
+
+
+def test_forward_constant_and_saturated_rows_take_lowest_indices():
+    """Degenerate score rows inside the fused forward: q^I = 0 makes every score of a row equal (one 16-bit
+    key, thousands of exact fp32 ties), huge logits saturate every sigmoid (a handful of distinct values).
+    The selection must still be the oracle's: ties resolved towards the lowest index."""
+    wl = wl_("ties", 1, 20000, 20000, 0, 16, 4, 128, 4, 64, "bf16", kmin=40, kmax=2100, kbase=300, seed=21)
+    t = S.make_inputs(wl, "cpu")
+    t["qI"][:, ::2] = 0                      # even rows: constant scores
+    t["qI"][:, 1::2] *= 16                   # odd rows: saturated sigmoids
+    d = T.to_device(t)
+    ctl = G.make_adaptive(1.0, 1, 1, 1, k_fixed=2100)
+    res = T.gpu_forward(wl, d, ctl, k_cap=2100)
+    idx = res["idx"].cpu().numpy()
+    n_sel = res["n_sel"].cpu().numpy()
+    o = T.oracle_inputs(t)
+    for i in (0, 5, 2098, 2099, 2100, 2101, 4444, 17001, 19998, 19999):
+        n = i + 1
+        m = min(2100, n)
+        assert n_sel[0, i] == m
+        T.check_index_row_wellformed(idx[0, i], m, n, 2100)
+        I = O.indexer_scores_row(o["qI"][0, i], o["kI"][0, :n], o["w"][0, i], None)
+        if i % 2 == 0:
+            assert np.array_equal(idx[0, i, :m], np.arange(m)), "constant row %d" % i
+        T.check_selection_vs_fp64(idx[0, i], m, I)
+    assert torch.isfinite(res["out"].float()).all()
+
+
+def test_forward_matches_staged_calls():
+    """gsa_forward (16-bit keys between indexer and selection) against the four stage calls chained by hand
+    (fp32 scores): identical sets except where two fp32 scores are within rounding of each other."""
+    wl = wl_("staged", 1, 3000, 3000, 0, 16, 4, 128, 4, 64, "bf16", kmin=64, kmax=512, seed=31)
+    t = S.make_inputs(wl, "cpu")
+    d = T.to_device(t)
+    ctl, kw = _ctl_for(wl, _vbar_from_gpu(wl, d))
+    res = T.gpu_forward(wl, d, ctl)
+    scores, _, var = T.gpu_indexer(wl, d, want_mean=False)
+    k, n_sel = T.gpu_adaptive_k(wl, ctl, var)
+    idx = T.gpu_select(wl, scores, n_sel, wl.k_cap)
+    out = T.gpu_attention(wl, d, idx, n_sel, wl.k_cap)
+    assert torch.equal(res["var"], var) and torch.equal(res["k"], k) and torch.equal(res["n_sel"], n_sel)
+    same = (res["idx"] == idx).all(-1)
+    assert same.float().mean().item() >= 0.995
+    assert torch.equal(res["out"][same], out[same])
+    sc = T.to64(scores)
+    for (b, i) in (~same).nonzero().tolist():          # differing rows: only elements tied within fp32 rounding
+        m = int(n_sel[b, i])
+        a_, b_ = set(res["idx"][b, i, :m].tolist()), set(idx[b, i, :m].tolist())
+        diff = np.array(sorted(a_ ^ b_))
+        thr = np.sort(sc[b, i, :i + 1])[i + 1 - m]
+        assert np.all(np.abs(sc[b, i, diff] - thr) <= 4e-7 * thr)
