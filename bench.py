@@ -51,6 +51,22 @@ def ev():
     return torch.cuda.Event(enable_timing=True)
 
 
+def measured_traffic(workload, h_kv):
+    """HBM-side bytes of one attention launch as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    (calibrated against a plain copy); recorded in the committed profile summary of this workload."""
+    if h_kv != 4:
+        return None
+    path = os.path.join(ROOT, "profiles", "gsa_forward_%s.md" % workload)
+    try:
+        for line in open(path):
+            if line.startswith("TRAFFIC") and "kernel=attn_bf16_kernel" in line:
+                kv = dict(x.split("=") for x in line.split()[1:])
+                return int(kv["fetch_bytes"]) + int(kv["write_bytes"])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -188,7 +204,7 @@ def main():
         "tflops": round((fl_idx + fl_att) / (ms_per_step * 1e-3) / 1e12, 2),
         "roofline": {"kernel": "attn_bf16_kernel (gathered sparse gated attention)", "bound": "hbm",
                      "achieved": round(att_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                     "frac": round(att_gbs / PEAK_HBM_GBS, 4), "traffic": None,
+                     "frac": round(att_gbs / PEAK_HBM_GBS, 4), "traffic": measured_traffic(wl.name, wl.H_kv),
                      "algorithmic_bytes_per_launch": gbytes, "avg_launch_ms": round(stage_ms["attention"], 4)},
         "stages": stages,
     }
