@@ -147,6 +147,14 @@ int32_t gsa_value_gate(const gsa_shape* shape, const void* V, const void* g2_log
  * times more rows than there are key tokens (Lq * min(k_cap, Lk) >= 4 * Lk, prefill);
  * otherwise (decode) it is applied in registers to the gathered rows.  Both give the same
  * bits: V * sigmoid(g2) rounded to dtype.
+ * Between the indexer and the selection the fused call keeps 16-bit fixed-point keys
+ * min(65535, floor(I * 65536 / HI)) instead of fp32 scores (w must lie in [0,1] for the keys to
+ * resolve the scores; larger weights only cost speed).  Elements that share the threshold key are
+ * re-scored in fp32, so the selected sets equal those of gsa_indexer_scores + gsa_topk_select
+ * except between scores that agree to within fp32 rounding (about 1e-7 relative).
+ * Environment switches read at call time, for comparison runs only: GSA_FORWARD_FP32_SCORES=1
+ * (fp32 score slab instead of keys), GSA_SELECT_EXACT_ONLY=1 (no sampled one-pass selection),
+ * GSA_ATTN_GPB=1|2|4 (kv heads per attention workgroup).
  *   out          device, out [B, Lq, H, d_h]
  *   idx_out      device, out [B, Lq, k_cap] or NULL (then kept per slab in the workspace)
  *   n_sel_out, k_out   device, out [B, Lq] or NULL

@@ -390,3 +390,28 @@ def test_forward_matches_staged_calls():
         diff = np.array(sorted(a_ ^ b_))
         thr = np.sort(sc[b, i, :i + 1])[i + 1 - m]
         assert np.all(np.abs(sc[b, i, diff] - thr) <= 4e-7 * thr)
+
+
+FORWARD_VARIANTS = [
+    # dtype, HI, dI, H, Hkv, dh, B, Lq, Lk, off, bias, slab_rows
+    ("f32", 2, 128, 8, 8, 64, 2, 700, 700, 0, False, 256),
+    ("bf16", 8, 32, 16, 2, 64, 1, 900, 900, 0, True, None),
+    ("bf16", 1, 128, 4, 1, 128, 3, 500, 500, 0, True, 128),
+    ("bf16", 4, 64, 16, 4, 128, 2, 300, 1000, 700, False, None),   # a chunk of queries against a longer cache
+    ("f32", 4, 32, 4, 2, 128, 1, 1, 600, 599, False, None),        # single-query decode in fp32
+]
+
+
+@pytest.mark.parametrize("dtype,HI,dI,H,Hkv,dh,B,Lq,Lk,off,bias,slab", FORWARD_VARIANTS)
+def test_forward_shape_variants(dtype, HI, dI, H, Hkv, dh, B, Lq, Lk, off, bias, slab):
+    wl = wl_("var", B, Lq, Lk, off, H, Hkv, dh, HI, dI, dtype, kmin=16, kmax=96, seed=100 + HI + dI + H)
+    t = S.make_inputs(wl, "cpu", with_bias=bias)
+    d = T.to_device(t)
+    ctl, kw = _ctl_for(wl, _vbar_from_gpu(wl, d))
+    res = T.gpu_forward(wl, d, ctl, slab_rows=slab)
+    r = np.random.default_rng(9)
+    rows = [(int(b), int(i)) for b, i in zip(r.integers(0, B, 40), r.integers(0, Lq, 40))] + [(0, 0), (B - 1, Lq - 1)]
+    # (with a single indexer head and d^I = 128 most sigmoids saturate: many fp64 scores differ only beyond
+    # fp32 resolution, so the number of in-band substitutions is not bounded here, only their size is)
+    excused, kband, worst = _check_forward(wl, t, res, kw, rows)
+    assert kband <= 3
