@@ -60,7 +60,7 @@ __device__ __forceinline__ constexpr int acc_row(int i, int h) { return 8 * (i /
 // STORE: 0 = statistics only, 1 = fp32 scores, 2 = 16-bit fixed-point keys floor(score * 65536 / HI)
 // (saturated at 65535), a monotone compression of the score used inside the fused forward.
 template <typename T, int DI, int HI, int STORE>
-__global__ __launch_bounds__(256) void indexer_kernel(IndexerArgs a) {
+__global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(IndexerArgs a) {
     constexpr int EB = ElemTraits<T>::kBytes;
     constexpr int ROWB = DI * EB;            // bytes of one key row
     constexpr int LDSROW = ROWB + 16;        // padded LDS row stride
