@@ -22,6 +22,8 @@
 // variance formula.  The key range of a row may be split over several workgroups (grid.y); each
 // writes its partial sums to the workspace and a second small kernel merges them in double
 // precision into row_mean / row_var.
+#include <cstdlib>
+
 #include "common.hpp"
 
 namespace gsa {
@@ -397,7 +399,8 @@ void indexer_plan(const gsa_shape& sh, int row_begin, int row_end, int* kc_out, 
     const int QT = queries_per_wg(sh.HI);
     const int ntiles = (int)cdiv(row_end - row_begin, QT);
     const int maxvis = (sh.q_offset + row_end - 1 < sh.Lk - 1 ? sh.q_offset + row_end - 1 : sh.Lk - 1) + 1;
-    const int64_t want_wgs = 2048;
+    int64_t want_wgs = 2048;
+    if (const char* e = getenv("GSA_INDEXER_WGS")) want_wgs = atoi(e) > 0 ? atoi(e) : want_wgs;  // tuning override
     int64_t nsplit = cdiv(want_wgs, (int64_t)ntiles * sh.B);
     if (nsplit < 1) nsplit = 1;
     int64_t kc = cdiv(cdiv(maxvis, nsplit), kBN) * kBN;

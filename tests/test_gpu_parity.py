@@ -415,3 +415,22 @@ def test_forward_shape_variants(dtype, HI, dI, H, Hkv, dh, B, Lq, Lk, off, bias,
     # fp32 resolution, so the number of in-band substitutions is not bounded here, only their size is)
     excused, kband, worst = _check_forward(wl, t, res, kw, rows)
     assert kband <= 3
+
+
+@pytest.mark.parametrize("L", [1, 2, 5, 33, 129])
+def test_forward_tiny_lengths(L):
+    """Lengths below one tile of every kernel, budgets smaller and larger than the row."""
+    wl = wl_("tiny", 2, L, L, 0, 8, 2, 64, 4, 32, "bf16", kmin=2, kmax=7, kbase=4, seed=L)
+    t = S.make_inputs(wl, "cpu")
+    d = T.to_device(t)
+    ctl, kw = _ctl_for(wl, 0.05)
+    res = T.gpu_forward(wl, d, ctl)
+    _check_forward(wl, t, res, kw)
+
+
+def test_select_budget_up_to_8192():
+    """The largest supported k_cap on 128K-long rows: the one-pass list overflows and the exact path takes over."""
+    r = np.random.default_rng(5)
+    B, Lq, Lk, k_cap = 1, 4, 131072, 8192
+    sc = r.uniform(0, 4, (B, Lq, Lk)).astype(np.float32)
+    _select_case(sc, np.array([[8192, 8191, 5000, 4097]]), k_cap, Lk - Lq)
