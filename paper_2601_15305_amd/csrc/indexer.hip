@@ -22,8 +22,6 @@
 // variance formula.  The key range of a row may be split over several workgroups (grid.y); each
 // writes its partial sums to the workspace and a second small kernel merges them in double
 // precision into row_mean / row_var.
-#include <cstdlib>
-
 #include "common.hpp"
 
 namespace gsa {
@@ -299,6 +297,45 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
         store_tile(0);
         __syncthreads();
         int it = 0;
+        // Single-row workgroups (decode: one query against a long cache) are bound by the latency of the
+        // key stream, not by arithmetic: their leading tiles keep two tiles of loads in flight and do the
+        // arithmetic of the one live slot only, again without branches.
+        if (narrow && a.row_end - t_wg0 == 1 && HI <= 4) {
+            const int lim_row = min(a.q_offset + t_wg0, a.Lk - 1);
+            int nlead1 = (lim_row + 1 - key_lo) / kBN;  // wholly visible tiles
+            nlead1 = max(min(nlead1, ntile - 1), 0);
+            u32x4 stage2[NCH];
+            auto load_clamped = [&](int s0, u32x4* st) {  // rows beyond the range repeat the last key: never used unmasked
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) {
+                    const int ch = tid + c * 256;
+                    const int sidx = min(s0 + ch / CHPR, a.Lk - 1);
+                    st[c] = *reinterpret_cast<const u32x4*>(kbase + (int64_t)sidx * ROWB + (ch % CHPR) * 16);
+                }
+            };
+            if (nlead1 > 0) load_clamped(key_lo + kBN, stage);  // tile 1
+            for (; it < nlead1; ++it) {
+                const int s0 = key_lo + it * kBN;
+                load_clamped(s0 + 2 * kBN, stage2);  // tile it+2
+                const f32x16 c = mfma_block(smem + (it & 1) * (kBN * LDSROW), wv);
+                float sc = 0.f;
+#pragma unroll
+                for (int r = 0; r < HL; ++r)
+                    sc = fmaf(wreg[r], fast_rcp(1.0f + fast_exp2(fmaf(c[r], -kLog2e, nbias[r]))), sc);
+                if (h == 0) {  // the row lives in slot 0 of the lower lane half
+                    const float d = sc - center[0];
+                    s1[0] += d;
+                    s2[0] = fmaf(d, d, s2[0]);
+                    const uint32_t col = (uint32_t)(s0 + 4 * n + wv);
+                    if constexpr (STORE == 1) wave_scores[rowoff[0] + col] = sc;
+                    if constexpr (STORE == 2) wave_keys[rowoff[0] + col] = (uint16_t)min((uint32_t)sc, 65535u);
+                }
+                store_tile((it + 1) & 1);  // tile it+1
+                __syncthreads();
+#pragma unroll
+                for (int c2 = 0; c2 < NCH; ++c2) stage[c2] = stage2[c2];
+            }
+        }
         for (; it < nlead; ++it) {
             const int s0 = key_lo + it * kBN;
 #pragma unroll
@@ -399,8 +436,7 @@ void indexer_plan(const gsa_shape& sh, int row_begin, int row_end, int* kc_out, 
     const int QT = queries_per_wg(sh.HI);
     const int ntiles = (int)cdiv(row_end - row_begin, QT);
     const int maxvis = (sh.q_offset + row_end - 1 < sh.Lk - 1 ? sh.q_offset + row_end - 1 : sh.Lk - 1) + 1;
-    int64_t want_wgs = 2048;
-    if (const char* e = getenv("GSA_INDEXER_WGS")) want_wgs = atoi(e) > 0 ? atoi(e) : want_wgs;  // tuning override
+    const int64_t want_wgs = 2048;  // measured flat between 1500 and 2300 on 256 CUs
     int64_t nsplit = cdiv(want_wgs, (int64_t)ntiles * sh.B);
     if (nsplit < 1) nsplit = 1;
     int64_t kc = cdiv(cdiv(maxvis, nsplit), kBN) * kBN;
