@@ -3,7 +3,9 @@
 //   A[s] = softmax_{s in S_t}(scale * Q[t,h,:] . K[s,g,:]),  O = sum_s A[s] (V[s,g,:] * sigmoid(g2[s,g,:])),
 //   out[t,h,:] = O * sigmoid(g1[t,h,:]),   g = h / (H / H_kv).
 //
-// bf16 kernel.  One workgroup per query; wave w handles kv heads w, w+4, ...  For one kv head the
+// bf16 kernel.  One wave per (query, kv head); a workgroup holds the waves of one query for one to four
+// kv heads, grid.y walks over the kv-head slices and grid.z over pieces of the selected list (decode).
+// For one kv head the
 // G = H/H_kv query heads that share it form the N dimension of the MFMAs (padded to 16), the
 // gathered tokens form M for the score product and K for the value product:
 //   S^T[token, head] = K[token, :] . Q[head, :]       A operand = gathered K rows, read from global

@@ -2,7 +2,8 @@
 // controller itself (Eq. "adaptive_k").
 //
 // Selection is an exact radix select on the fp32 bit pattern of the non-negative scores (which
-// orders like the value), one workgroup of four wavefronts per query row:
+// orders like the value), one workgroup of eight wavefronts per query row (steps A-C: select_exact in
+// select_common.hpp, step D: emit_selection):
 //   A. histogram the next 13 key bits of every element that still matches the resolved prefix
 //      (LDS atomics), locate the bin holding the n_sel-th largest; repeat only while that bin
 //      holds more candidates than fit in LDS (at most three passes: 13 + 13 + 5 bits);
