@@ -104,9 +104,12 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
         u32x4 kf[2][KK];
         u32x4 vf[NVL];
         u32x4 gf[HAS_G2 ? NVL : 1];
+        // indices of the tile after the one whose rows are being requested: fetched one tile early so that
+        // the row loads never wait on a dependent index load
+        int tok_pref = (it0 < ntile) ? idxrow[min(it0 * 32 + (lane & 31), nsel - 1)] : 0;
         auto load_tile = [&](int j0) {
-            int tok = idxrow[min(j0 + (lane & 31), nsel - 1)];
-            tok = max(0, min(tok, a.Lk - 1));
+            int tok = max(0, min(tok_pref, a.Lk - 1));
+            tok_pref = idxrow[min(j0 + 32 + (lane & 31), nsel - 1)];
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub) {
                 const int tk = __shfl(tok, sub * 16 + n, 64);
@@ -218,6 +221,12 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
         if (head_ok) {
             const float inv = ltot > 0.f ? 1.0f / ltot : 0.f;
             const int64_t obase = (qrow * a.H + head) * DH;
+            u32x2 gall[MB];  // all output-gate logits of this lane first, so that the loads overlap
+            if (a.g1) {
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+                    gall[mb] = *reinterpret_cast<const u32x2*>(static_cast<const __bf16*>(a.g1) + obase + mb * 16 + 4 * q);
+            }
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
                 const int d0 = mb * 16 + 4 * q;
@@ -225,7 +234,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) y[i] = o[mb][i] * inv;
                 if (a.g1) {
-                    const u32x2 gw = *reinterpret_cast<const u32x2*>(static_cast<const __bf16*>(a.g1) + obase + d0);
+                    const u32x2 gw = gall[mb];
                     y[0] *= sigmoid_f32(bf16_bits_to_f32(gw[0] & 0xffffu));
                     y[1] *= sigmoid_f32(bf16_bits_to_f32(gw[0] >> 16));
                     y[2] *= sigmoid_f32(bf16_bits_to_f32(gw[1] & 0xffffu));
