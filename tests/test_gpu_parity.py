@@ -434,3 +434,34 @@ def test_select_budget_up_to_8192():
     B, Lq, Lk, k_cap = 1, 4, 131072, 8192
     sc = r.uniform(0, 4, (B, Lq, Lk)).astype(np.float32)
     _select_case(sc, np.array([[8192, 8191, 5000, 4097]]), k_cap, Lk - Lq)
+
+
+def _random_case(r):
+    dtype = ["bf16", "f32"][int(r.integers(0, 2))]
+    HI = int(r.choice([1, 2, 4, 8]))
+    dI = int(r.choice([32, 64, 128]))
+    dh = int(r.choice([64, 128]))
+    Hkv = int(r.choice([1, 2, 4, 8]))
+    G_ = int(r.choice([1, 2, 4, 16]))
+    B = int(r.integers(1, 4))
+    Lk = int(r.integers(3, 900))
+    Lq = int(r.integers(1, Lk + 1))
+    off = int(r.integers(0, Lk - Lq + 1))
+    kmin = int(r.integers(1, 40))
+    kmax = kmin + int(r.integers(0, 120))
+    slab = [None, 128, 256][int(r.integers(0, 3))]
+    return dtype, HI, dI, Hkv * G_, Hkv, dh, B, Lq, Lk, off, bool(r.integers(0, 2)), slab, kmin, kmax
+
+
+@pytest.mark.parametrize("case", range(48))
+def test_forward_random_shapes(case):
+    """Seeded random shapes (all supported head counts and dimensions, ragged lengths, offsets, slabs)."""
+    r = np.random.default_rng(1000 + case)
+    dtype, HI, dI, H, Hkv, dh, B, Lq, Lk, off, bias, slab, kmin, kmax = _random_case(r)
+    wl = wl_("rnd", B, Lq, Lk, off, H, Hkv, dh, HI, dI, dtype, kmin=kmin, kmax=kmax, seed=2000 + case)
+    t = S.make_inputs(wl, "cpu", with_bias=bias)
+    d = T.to_device(t)
+    ctl, kw = _ctl_for(wl, _vbar_from_gpu(wl, d) + 1e-6)
+    res = T.gpu_forward(wl, d, ctl, slab_rows=slab)
+    rows = {(int(b), int(i)) for b, i in zip(r.integers(0, B, 12), r.integers(0, Lq, 12))} | {(0, 0), (B - 1, Lq - 1)}
+    _check_forward(wl, t, res, kw, sorted(rows))
