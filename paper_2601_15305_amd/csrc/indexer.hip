@@ -59,7 +59,9 @@ __device__ __forceinline__ constexpr int acc_row(int i, int h) { return 8 * (i /
 
 // STORE: 0 = statistics only, 1 = fp32 scores, 2 = 16-bit fixed-point keys floor(score * 65536 / HI)
 // (saturated at 65535), a monotone compression of the score used inside the fused forward.
-template <typename T, int DI, int HI, int STORE>
+// ROW1: the launch covers one query row per batch element (decode); such launches get a kernel of their
+// own so that the deeper prefetch of that case does not cost the prefill loops any registers.
+template <typename T, int DI, int HI, int STORE, bool ROW1>
 __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(IndexerArgs a) {
     constexpr int EB = ElemTraits<T>::kBytes;
     constexpr int ROWB = DI * EB;            // bytes of one key row
@@ -102,8 +104,19 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
     // In key mode the head weights carry the key scale 65536/HI (a power of two, so every product and
     // sum is the scaled image of the unscaled one, bit for bit); the statistics are unscaled on the way out.
     constexpr float kKeyScale = STORE == 2 ? 65536.0f / HI : 1.0f;
-    int lim[NSLOT];         // last visible key of the slot's query, -1 if the query is outside the range
-    uint32_t rowoff[NSLOT]; // element offset of the slot's score row from wave_scores
+    // Query of slot s relative to the wave: a wave-uniform part plus a multiple of the lane half.
+    //   tl(s, h) = acc_row(s * HL, h) / HI = slot_row(s) + kHalfRows * h
+    constexpr int kHalfRows = HI <= 4 ? 4 / HI : 0;
+    auto slot_row = [](int s) { return acc_row(s * HL, 0) / HI; };
+    // last visible key of the slot's query, -1 if the query is outside the row range (recomputed where
+    // it is needed: the masked tiles at the diagonal and the final reduction)
+    auto lim_of = [&](int s) {
+        const int t = t_w0 + slot_row(s) + kHalfRows * h;
+        return t < a.row_end ? min(a.q_offset + t, a.Lk - 1) : -1;
+    };
+    // element offset of a slot's score row from the wave's base: lane part here, uniform part at the use
+    const uint32_t half_off = (uint32_t)(kHalfRows * h) * (uint32_t)a.ld;
+    auto row_off = [&](int s) { return (uint32_t)slot_row(s) * (uint32_t)a.ld; };  // wave-uniform
     float wreg[16];         // head weight of accumulator register i
     float nbias[HL];        // -log2(e) * bias of the lane's r-th head
     float center[NSLOT];
@@ -119,9 +132,7 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
         const int tl = acc_row(s * HL, h) / HI;  // query of the slot, relative to the wave
         const int t = t_w0 + tl;
         const bool ok = t < a.row_end;
-        lim[s] = ok ? min(a.q_offset + t, a.Lk - 1) : -1;
         slot_live[s] = __any(ok) != 0;
-        rowoff[s] = (uint32_t)tl * (uint32_t)a.ld;
         float c = 0.f;
 #pragma unroll
         for (int r = 0; r < HL; ++r) {
@@ -232,15 +243,15 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
                 if (HI == 8) sc += __shfl_xor(sc, 32, 64);
                 sc_out[s] = sc;
                 bool valid = (HI == 8) ? (h == 0) : true;
-                if (masked) valid = valid && (scol <= lim[s]);
+                if (masked) valid = valid && (scol <= lim_of(s));
                 if (valid) {
                     const float d = sc - center[s];
                     s1[s] += d;
                     s2[s] = fmaf(d, d, s2[s]);
                     if constexpr (STORE == 1) {
-                        if (masked) wave_scores[rowoff[s] + (uint32_t)scol] = sc;
+                        if (masked) (wave_scores + row_off(s))[half_off + (uint32_t)scol] = sc;
                     } else if constexpr (STORE == 2) {
-                        if (masked) wave_keys[rowoff[s] + (uint32_t)scol] = (uint16_t)min((uint32_t)sc, 65535u);
+                        if (masked) (wave_keys + row_off(s))[half_off + (uint32_t)scol] = (uint16_t)min((uint32_t)sc, 65535u);
                     }
                 }
             }
@@ -250,6 +261,7 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
         // per row and tile, and a wave writes 512 contiguous bytes of a score row at a time.
         auto full_tile = [&](const unsigned char* tileptr, int s0) {
             float sc4[4][NSLOT];
+            uint32_t pk[2][NSLOT];  // key mode: pairs of keys, packed as soon as both exist
             f32x16 c = mfma_block(tileptr, 0);
 #pragma unroll
             for (int nb = 0; nb < 4; ++nb) {
@@ -257,25 +269,29 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
                 if (nb < 3) cn = mfma_block(tileptr, nb + 1);
                 epilogue(c, s0 + 4 * n + nb, false, sc4[nb]);
                 if (nb < 3) c = cn;
+                if constexpr (STORE == 2) {
+                    if (nb & 1) {
+                        typedef __attribute__((ext_vector_type(2))) unsigned short u16x2;
+#pragma unroll
+                        for (int s = 0; s < NSLOT; ++s)  // float -> uint truncates towards zero, the pack saturates at 65535
+                            pk[nb >> 1][s] = __builtin_bit_cast(
+                                uint32_t, (u16x2)__builtin_amdgcn_cvt_pk_u16((uint32_t)sc4[nb - 1][s], (uint32_t)sc4[nb][s]));
+                    }
+                }
             }
             if constexpr (STORE == 1) {
                 if (HI != 8 || h == 0) {
 #pragma unroll
                     for (int s = 0; s < NSLOT; ++s)
-                        *reinterpret_cast<float4*>(wave_scores + rowoff[s] + (uint32_t)(s0 + 4 * n)) =
+                        *reinterpret_cast<float4*>(wave_scores + row_off(s) + (half_off + (uint32_t)(s0 + 4 * n))) =
                             float4{sc4[0][s], sc4[1][s], sc4[2][s], sc4[3][s]};
                 }
             } else if constexpr (STORE == 2) {
                 if (HI != 8 || h == 0) {
 #pragma unroll
-                    for (int s = 0; s < NSLOT; ++s) {
-                        typedef __attribute__((ext_vector_type(2))) unsigned short u16x2;
-                        // float -> uint truncates towards zero, the pack saturates at 65535
-                        const u16x2 lo = __builtin_amdgcn_cvt_pk_u16((uint32_t)sc4[0][s], (uint32_t)sc4[1][s]);
-                        const u16x2 hi = __builtin_amdgcn_cvt_pk_u16((uint32_t)sc4[2][s], (uint32_t)sc4[3][s]);
-                        *reinterpret_cast<u32x2*>(wave_keys + rowoff[s] + (uint32_t)(s0 + 4 * n)) =
-                            u32x2{__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
-                    }
+                    for (int s = 0; s < NSLOT; ++s)
+                        *reinterpret_cast<u32x2*>(wave_keys + row_off(s) + (half_off + (uint32_t)(s0 + 4 * n))) =
+                            u32x2{pk[0][s], pk[1][s]};
                 }
             }
         };
@@ -287,7 +303,7 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
         // the score stores issued after the prefetch loads and wait for the loads alone
         // (vmcnt(#stores)) instead of draining every outstanding store at each tile boundary.
         int nlead = 0;
-        if (t_wg0 + QT <= a.row_end) {
+        if (!ROW1 && t_wg0 + QT <= a.row_end) {
             const int lim_wg_first = min(a.q_offset + t_wg0, a.Lk - 1);
             nlead = (lim_wg_first + 1 - key_lo) / kBN;
             nlead = min(nlead, min(ntile - 1, (a.Lk - key_lo) / kBN - 1));
@@ -300,7 +316,7 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
         // Single-row workgroups (decode: one query against a long cache) are bound by the latency of the
         // key stream, not by arithmetic: their leading tiles keep two tiles of loads in flight and do the
         // arithmetic of the one live slot only, again without branches.
-        if (narrow && a.row_end - t_wg0 == 1 && HI <= 4) {
+        if constexpr (ROW1 && HI <= 4) {
             const int lim_row = min(a.q_offset + t_wg0, a.Lk - 1);
             int nlead1 = (lim_row + 1 - key_lo) / kBN;  // wholly visible tiles
             nlead1 = max(min(nlead1, ntile - 1), 0);
@@ -327,8 +343,8 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
                     s1[0] += d;
                     s2[0] = fmaf(d, d, s2[0]);
                     const uint32_t col = (uint32_t)(s0 + 4 * n + wv);
-                    if constexpr (STORE == 1) wave_scores[rowoff[0] + col] = sc;
-                    if constexpr (STORE == 2) wave_keys[rowoff[0] + col] = (uint16_t)min((uint32_t)sc, 65535u);
+                    if constexpr (STORE == 1) wave_scores[col] = sc;
+                    if constexpr (STORE == 2) wave_keys[col] = (uint16_t)min((uint32_t)sc, 65535u);
                 }
                 store_tile((it + 1) & 1);  // tile it+1
                 __syncthreads();
@@ -336,7 +352,7 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
                 for (int c2 = 0; c2 < NCH; ++c2) stage[c2] = stage2[c2];
             }
         }
-        for (; it < nlead; ++it) {
+        for (; !ROW1 && it < nlead; ++it) {
             const int s0 = key_lo + it * kBN;
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {  // prefetch of the next tile, no bounds checks needed
@@ -378,7 +394,7 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
             x1 += __shfl_xor(x1, o, 64);
             x2 += __shfl_xor(x2, o, 64);
         }
-        if (n == 0 && lim[s] >= 0 && !(HI == 8 && h == 1)) {
+        if (n == 0 && lim_of(s) >= 0 && !(HI == 8 && h == 1)) {
             // four partial slots per (row, split): one per wave in narrow mode, else the owner wave fills
             // slot 0 and clears the rest
             const int t = t_w0 + acc_row(s * HL, h) / HI;
@@ -457,7 +473,11 @@ template <typename T, int DI, int HI>
 static hipError_t launch_one(const IndexerArgs& a, hipStream_t st) {
     constexpr int LDSROW = DI * ElemTraits<T>::kBytes + 16;
     const size_t smem = 2 * kBN * LDSROW;
-    auto kern = a.keys ? indexer_kernel<T, DI, HI, 2> : (a.scores ? indexer_kernel<T, DI, HI, 1> : indexer_kernel<T, DI, HI, 0>);
+    const bool row1 = (a.row_end - a.row_begin) == 1;
+    auto kern = row1 ? (a.keys ? indexer_kernel<T, DI, HI, 2, true>
+                               : (a.scores ? indexer_kernel<T, DI, HI, 1, true> : indexer_kernel<T, DI, HI, 0, true>))
+                     : (a.keys ? indexer_kernel<T, DI, HI, 2, false>
+                               : (a.scores ? indexer_kernel<T, DI, HI, 1, false> : indexer_kernel<T, DI, HI, 0, false>));
     if (smem > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
