@@ -36,8 +36,14 @@ struct AttnArgs {
     int32_t B, Lq, Lk, H, H_kv, row_begin, row_end, k_cap;
     int32_t idx_rows, idx_row0;  // idx holds rows [idx_row0, idx_row0+idx_rows) of every batch element
     float scale;  // softmax scale
-    int32_t nsplit;  // > 1: a row's selected list is cut into nsplit pieces (grid.z), partial results go to `part`
+    int32_t nsplit;  // > 1: a row's selected list is cut into nsplit pieces, partial results go to `part`
     float* part;     // [rows][H][nsplit][d_h + 4]: unnormalised O, running max (base 2), running sum, padding
+    // Key-window mode (winoff != nullptr): piece z of a row is the part of its (ascending) list that falls
+    // into keys [z*window, (z+1)*window); one launch handles one window for the rows that can see it.
+    const int32_t* winoff;  // [rows][nsplit + 1] list positions of the window boundaries
+    int32_t window, win;    // keys per window, window of this launch
+    int32_t q_offset;
+    int32_t part_row0, part_rows;  // rows of the slab that `part` and `winoff` are laid out for
 };
 
 constexpr float kNegBig = -1.0e30f;
@@ -71,10 +77,22 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     const int G = a.H / a.H_kv;
     const float sl2 = a.scale * kLog2e;
     const int64_t tokstride = (int64_t)a.H_kv * ROWB;  // bytes between consecutive tokens
-    const int ntile_all = (nsel + 31) >> 5;
-    const int tps = (ntile_all + a.nsplit - 1) / a.nsplit;  // tiles per split
-    const int it0 = min((int)blockIdx.z * tps, ntile_all);
-    const int ntile = min(it0 + tps, ntile_all);
+    // the piece [jbeg, jend) of the list this workgroup handles, and where its partial record goes
+    // (a row that sees a single key window is finished here, like an unsplit row)
+    const bool partial = a.nsplit > 1 && !(a.winoff && min(a.q_offset + t, a.Lk - 1) < a.window);
+    const int64_t prow = (int64_t)b * a.part_rows + (t - a.part_row0);
+    int jbeg, jend, piece;
+    if (a.winoff) {
+        piece = a.win;
+        jbeg = min(a.winoff[prow * (a.nsplit + 1) + piece], nsel);
+        jend = min(a.winoff[prow * (a.nsplit + 1) + piece + 1], nsel);
+    } else {
+        const int ntile_all = (nsel + 31) >> 5;
+        const int tps = (ntile_all + a.nsplit - 1) / a.nsplit;  // tiles per split
+        piece = blockIdx.z;
+        jbeg = min(piece * tps, ntile_all) * 32;
+        jend = min(min(piece * tps + tps, ntile_all) * 32, nsel);
+    }
 
     // blockDim.x / 64 kv heads per workgroup; blockIdx.y selects which ones.  Blocks are dispatched
     // x-fastest, so all queries work on one slice of kv heads before the next slice starts: the K/V'
@@ -106,10 +124,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
         u32x4 gf[HAS_G2 ? NVL : 1];
         // indices of the tile after the one whose rows are being requested: fetched one tile early so that
         // the row loads never wait on a dependent index load
-        int tok_pref = (it0 < ntile) ? idxrow[min(it0 * 32 + (lane & 31), nsel - 1)] : 0;
+        int tok_pref = (jbeg < jend) ? idxrow[min(jbeg + (lane & 31), jend - 1)] : 0;
         auto load_tile = [&](int j0) {
             int tok = max(0, min(tok_pref, a.Lk - 1));
-            tok_pref = idxrow[min(j0 + 32 + (lane & 31), nsel - 1)];
+            tok_pref = idxrow[min(j0 + 32 + (lane & 31), jend - 1)];
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub) {
                 const int tk = __shfl(tok, sub * 16 + n, 64);
@@ -126,9 +144,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
             }
         };
 
-        if (it0 < ntile) load_tile(it0 * 32);
-        for (int it = it0; it < ntile; ++it) {
-            const int j0 = it * 32;
+        if (jbeg < jend) load_tile(jbeg);
+        for (int j0 = jbeg; j0 < jend; j0 += 32) {
             // ---- V' rows -> LDS (natural layout: row = token slot, 16 B per lane) -----------------
 #pragma unroll
             for (int r = 0; r < NVL; ++r) {
@@ -148,7 +165,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
             for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
                 for (int kk = 0; kk < KK; ++kk) kc[sub][kk] = kf[sub][kk];
-            if (it + 1 < ntile) load_tile(j0 + 32);
+            if (j0 + 32 < jend) load_tile(j0 + 32);
 
             // ---- S^T = K . Q^T for two 16-token sub-tiles ------------------------------------------
             f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
@@ -162,8 +179,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
             float tmax = kNegBig;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                x[i] = (j0 + 4 * q + i < nsel) ? s0[i] * sl2 : kNegBig;
-                x[4 + i] = (j0 + 16 + 4 * q + i < nsel) ? s1[i] * sl2 : kNegBig;
+                x[i] = (j0 + 4 * q + i < jend) ? s0[i] * sl2 : kNegBig;
+                x[4 + i] = (j0 + 16 + 4 * q + i < jend) ? s1[i] * sl2 : kNegBig;
                 tmax = fmaxf(tmax, fmaxf(x[i], x[4 + i]));
             }
             tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
@@ -205,9 +222,9 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
         // ---- normalise, G1, store ---------------------------------------------------------------------
         float ltot = lrun + __shfl_xor(lrun, 16, 64);
         ltot += __shfl_xor(ltot, 32, 64);
-        if (a.nsplit > 1) {  // partial result of this piece of the list; attn_merge_kernel finishes the row
+        if (partial) {  // partial result of this piece of the list; attn_merge_kernel finishes the row
             if (head_ok) {
-                float* pp = a.part + (((rid * a.H) + head) * a.nsplit + blockIdx.z) * (DH + 4);
+                float* pp = a.part + (((prow * a.H) + head) * a.nsplit + piece) * (DH + 4);
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
                     *reinterpret_cast<f32x4*>(pp + mb * 16 + 4 * q) = o[mb];
@@ -248,29 +265,98 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
 }
 
 // Combine the partial results of a split row: out = (sum_s 2^(m_s - M) O_s) / (sum_s 2^(m_s - M) l_s) * sigmoid(g1).
+// One wave per (row, head); lane s first takes the statistics of piece s (at most 64 pieces), then every
+// lane sums DH/64 output features over the pieces.
 template <int DH>
-__global__ __launch_bounds__(DH) void attn_merge_kernel(AttnArgs a) {
+__global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
+    constexpr int PS = DH + 4;  // floats per partial record (16-byte multiple)
+    constexpr int DPL = DH / 64;
+    const int lane = threadIdx.x & 63;
     const int R = a.row_end - a.row_begin;
-    const int64_t rh = blockIdx.x;  // (row, head)
+    const int64_t rh = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // (row, head)
+    if (rh >= (int64_t)a.B * R * a.H) return;
     const int64_t rid = rh / a.H;
     const int head = (int)(rh % a.H);
     const int b = (int)(rid / R);
     const int t = a.row_begin + (int)(rid % R);
-    const int d = threadIdx.x;
-    constexpr int PS = DH + 4;  // floats per partial record (16-byte multiple)
+    // key-window mode: only the windows the row can see have a record, and a row that sees one window
+    // was finished by the attention kernel
+    const int ns = a.winoff ? min(a.nsplit, min(a.q_offset + t, a.Lk - 1) / a.window + 1) : a.nsplit;
+    if (a.winoff && ns == 1) return;
     const float* pp = a.part + rh * a.nsplit * PS;
-    float M = kNegBig;
-    for (int sp = 0; sp < a.nsplit; ++sp) M = fmaxf(M, pp[sp * PS + DH]);
-    float L = 0.f, O = 0.f;
-    for (int sp = 0; sp < a.nsplit; ++sp) {
-        const float wgt = fast_exp2(pp[sp * PS + DH] - M);
-        L = fmaf(wgt, pp[sp * PS + DH + 1], L);
-        O = fmaf(wgt, pp[sp * PS + d], O);
+    const float m = lane < ns ? pp[lane * PS + DH] : kNegBig;
+    const float l = lane < ns ? pp[lane * PS + DH + 1] : 0.f;
+    float M = m;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o, 64));
+    const float wgt = lane < ns ? fast_exp2(m - M) : 0.f;
+    const float L = wave_sum(wgt * l);
+    float acc[DPL];
+#pragma unroll
+    for (int e = 0; e < DPL; ++e) acc[e] = 0.f;
+#pragma unroll 4
+    for (int sp = 0; sp < ns; ++sp) {
+        const float w = __shfl(wgt, sp, 64);
+#pragma unroll
+        for (int e = 0; e < DPL; ++e) acc[e] = fmaf(w, pp[sp * PS + lane * DPL + e], acc[e]);
     }
-    float y = L > 0.f ? O / L : 0.f;
-    const int64_t oi = (((int64_t)b * a.Lq + t) * a.H + head) * DH + d;
-    if (a.g1) y *= sigmoid_f32(bf16_bits_to_f32(static_cast<const uint16_t*>(a.g1)[oi]));
-    static_cast<uint16_t*>(a.out)[oi] = (uint16_t)f32_to_bf16_bits(y);
+    const int64_t oi = (((int64_t)b * a.Lq + t) * a.H + head) * DH + lane * DPL;
+    uint32_t packed = 0;
+#pragma unroll
+    for (int e = 0; e < DPL; ++e) {
+        float y = L > 0.f ? acc[e] / L : 0.f;
+        if (a.g1) y *= sigmoid_f32(bf16_bits_to_f32(static_cast<const uint16_t*>(a.g1)[oi + e]));
+        packed |= f32_to_bf16_bits(y) << (16 * e);
+    }
+    if (DPL == 2)
+        *reinterpret_cast<uint32_t*>(static_cast<uint16_t*>(a.out) + oi) = packed;
+    else
+        static_cast<uint16_t*>(a.out)[oi] = (uint16_t)packed;
+}
+
+// Key-window mode: positions in a row's ascending index list where the key windows begin.
+//   winoff[row][z] = number of selected keys below z * window   (z = 0 .. nwin; winoff[row][nwin] = n_sel)
+// One wave per row: 64 evenly spaced probes of the list bracket every boundary, a second probe of the
+// bracket pins it down.
+__global__ __launch_bounds__(256) void attn_window_offsets_kernel(AttnArgs a, int32_t* winoff) {
+    const int lane = threadIdx.x & 63;
+    const int R = a.row_end - a.row_begin;
+    const int64_t rid = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (rid >= (int64_t)a.B * R) return;
+    const int b = (int)(rid / R);
+    const int t = a.row_begin + (int)(rid % R);
+    const int nsel = max(0, min(a.n_sel[(int64_t)b * a.Lq + t], a.k_cap));
+    const int32_t* idxrow = a.idx + ((int64_t)b * a.idx_rows + (t - a.idx_row0)) * a.k_cap;
+    int32_t* off = winoff + rid * (a.nsplit + 1);
+    const int nwin = a.nsplit;
+    if (lane == 0) {
+        off[0] = 0;
+        off[nwin] = nsel;
+    }
+    if (nsel == 0) {
+        for (int z = 1 + lane; z < nwin; z += 64) off[z] = 0;
+        return;
+    }
+    const int step = (nsel + 63) >> 6;
+    const bool probe_ok = lane * step < nsel;
+    const int probe = probe_ok ? idxrow[lane * step] : 0;
+    for (int z = 1; z < nwin; ++z) {
+        const int target = z * a.window;
+        // c probes are below the target: the boundary lies in ((c-1)*step, c*step]
+        const int c = __popcll(__ballot(probe_ok && probe < target));
+        int pos = 0;
+        if (c > 0) {
+            const int s0 = (c - 1) * step + 1;
+            const int s1 = min(c * step, nsel);  // exclusive end of the bracket
+            pos = s0;
+            for (int j0 = s0; j0 < s1; j0 += 64) {
+                const int j = j0 + lane;
+                const bool below = j < s1 && idxrow[j] < target;
+                pos += __popcll(__ballot(below));
+            }
+        }
+        if (lane == 0) off[z] = pos;
+    }
 }
 
 // fp32 kernel: plain vector arithmetic, one wave per query head, online softmax over chunks of 64
@@ -421,8 +507,29 @@ int attn_splits(const gsa_shape& sh, int64_t rows, int k_cap) {
     return (int)(ns < 1 ? 1 : ns);
 }
 
+// Key-window mode (bf16, many rows, long context): keys per window, 0 = off.  The K/V' rows of one window
+// and kv-head slice (window * d_h * 4 bytes) then stay resident in the L2 of every XCD while all rows
+// gather from them, instead of every gather going out to the memory-side cache.
+static int attn_window(const gsa_shape& sh, int64_t rows) {
+    int w = 16384;
+    bool forced = false;
+    if (const char* e = getenv("GSA_ATTN_WINDOW")) {  // tuning / test override; 0 turns the mode off
+        w = atoi(e);
+        forced = true;
+    }
+    if (w <= 0 || sh.dtype != GSA_BF16 || sh.Lk <= w) return 0;
+    if (!forced && (rows < 8192 || sh.Lk < 2 * w)) return 0;
+    if (cdiv(sh.Lk, w) > 64) w = (int)((cdiv(sh.Lk, 64) + 31) / 32 * 32);  // at most 64 windows
+    return w;
+}
+
 size_t attn_workspace_bytes(const gsa_shape& sh, int row_begin, int row_end, int k_cap) {
     const int64_t rows = (int64_t)sh.B * (row_end - row_begin);
+    if (const int w = attn_window(sh, rows)) {
+        const int64_t nwin = cdiv(sh.Lk, w);
+        const size_t offs = ((size_t)rows * (nwin + 1) * sizeof(int32_t) + 255) & ~(size_t)255;
+        return offs + (size_t)rows * sh.H * nwin * (sh.d_h + 4) * sizeof(float);
+    }
     const int ns = attn_splits(sh, rows, k_cap);
     return ns > 1 ? (size_t)rows * sh.H * ns * (sh.d_h + 4) * sizeof(float) : 0;
 }
@@ -451,32 +558,58 @@ hipError_t launch_attention(const gsa_shape& sh, int row_begin, int row_end, con
     a.idx_row0 = idx_row0;
     a.scale = scale;
     const int64_t rows = (int64_t)sh.B * (row_end - row_begin);
-    a.nsplit = attn_splits(sh, rows, k_cap);
-    a.part = static_cast<float*>(workspace);
+    a.winoff = nullptr;
+    a.window = attn_window(sh, rows);
+    a.win = 0;
+    a.q_offset = sh.q_offset;
+    a.part_row0 = row_begin;
+    a.part_rows = row_end - row_begin;
+    if (a.window) {
+        a.nsplit = (int)cdiv(sh.Lk, a.window);
+        const size_t offs = ((size_t)rows * (a.nsplit + 1) * sizeof(int32_t) + 255) & ~(size_t)255;
+        int32_t* winoff = static_cast<int32_t*>(workspace);
+        a.part = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + offs);
+        hipLaunchKernelGGL(attn_window_offsets_kernel, dim3((unsigned)cdiv(rows, 4)), dim3(256), 0, st, a, winoff);
+        a.winoff = winoff;
+    } else {
+        a.nsplit = attn_splits(sh, rows, k_cap);
+        a.part = static_cast<float*>(workspace);
+    }
     if (sh.dtype == GSA_BF16) {
         const int gpb = attn_groups_per_block(sh, rows);
-        const dim3 grid((unsigned)rows, (unsigned)(sh.H_kv / gpb), (unsigned)a.nsplit);
         const dim3 block(64 * gpb);
         const size_t smem = (size_t)gpb * 32 * (sh.d_h * 2 + 32);
-        if (sh.d_h == 128) {
-            if (g2)
-                hipLaunchKernelGGL((attn_bf16_kernel<128, true>), grid, block, smem, st, a);
-            else
-                hipLaunchKernelGGL((attn_bf16_kernel<128, false>), grid, block, smem, st, a);
-        } else {
-            if (g2)
-                hipLaunchKernelGGL((attn_bf16_kernel<64, true>), grid, block, smem, st, a);
-            else
-                hipLaunchKernelGGL((attn_bf16_kernel<64, false>), grid, block, smem, st, a);
+        // one launch, or in key-window mode one launch per window over the rows that can see it
+        const int nlaunch = a.window ? a.nsplit : 1;
+        for (int z = 0; z < nlaunch; ++z) {
+            if (a.window) {
+                a.win = z;
+                a.row_begin = row_begin > z * a.window - sh.q_offset ? row_begin : z * a.window - sh.q_offset;
+                if (a.row_begin >= row_end) break;
+            }
+            const int64_t lrows = (int64_t)sh.B * (row_end - a.row_begin);
+            const dim3 grid((unsigned)lrows, (unsigned)(sh.H_kv / gpb), (unsigned)(a.window ? 1 : a.nsplit));
+            if (sh.d_h == 128) {
+                if (g2)
+                    hipLaunchKernelGGL((attn_bf16_kernel<128, true>), grid, block, smem, st, a);
+                else
+                    hipLaunchKernelGGL((attn_bf16_kernel<128, false>), grid, block, smem, st, a);
+            } else {
+                if (g2)
+                    hipLaunchKernelGGL((attn_bf16_kernel<64, true>), grid, block, smem, st, a);
+                else
+                    hipLaunchKernelGGL((attn_bf16_kernel<64, false>), grid, block, smem, st, a);
+            }
         }
+        a.row_begin = row_begin;
         if (a.nsplit > 1) {
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
-            const dim3 mgrid((unsigned)(rows * sh.H));
+            const dim3 mgrid((unsigned)cdiv(rows * sh.H, 4));
             if (sh.d_h == 128)
-                hipLaunchKernelGGL(attn_merge_kernel<128>, mgrid, dim3(128), 0, st, a);
+                hipLaunchKernelGGL(attn_merge_kernel<128>, mgrid, dim3(256), 0, st, a);
             else
-                hipLaunchKernelGGL(attn_merge_kernel<64>, mgrid, dim3(64), 0, st, a);
+                hipLaunchKernelGGL(attn_merge_kernel<64>, mgrid, dim3(256), 0, st, a);
         }
     } else {
         if (sh.d_h == 128)

@@ -180,6 +180,20 @@ ATTN_CASES = [
 
 @pytest.mark.parametrize("dtype,H,Hkv,dh,B,Lq,Lk,off,k_cap", ATTN_CASES)
 def test_sparse_gated_attention(dtype, H, Hkv, dh, B, Lq, Lk, off, k_cap):
+    _attention_case(dtype, H, Hkv, dh, B, Lq, Lk, off, k_cap)
+
+
+@pytest.mark.parametrize("window", [16, 50, 64])
+@pytest.mark.parametrize("dtype,H,Hkv,dh,B,Lq,Lk,off,k_cap", [c for c in ATTN_CASES if c[0] == "bf16"])
+def test_sparse_gated_attention_key_windows(monkeypatch, window, dtype, H, Hkv, dh, B, Lq, Lk, off, k_cap):
+    """The key-window launch scheme of long prefills (one launch per window of keys, partial results merged
+    afterwards), forced onto small shapes so that the oracle covers every row: windows that a row does not
+    reach, windows without a selected key, lists that end inside a window."""
+    monkeypatch.setenv("GSA_ATTN_WINDOW", str(window))
+    _attention_case(dtype, H, Hkv, dh, B, Lq, Lk, off, k_cap)
+
+
+def _attention_case(dtype, H, Hkv, dh, B, Lq, Lk, off, k_cap):
     wl = wl_("att", B, Lq, Lk, off, H, Hkv, dh, 4, 32, dtype, seed=40 + H + Hkv, gate_std=1.5)
     t = S.make_inputs(wl, "cpu")
     r = np.random.default_rng(7)
@@ -318,6 +332,30 @@ def test_forward_bf16_mid_size(heavy):
     # determinism
     res4 = T.gpu_forward(wl, d, ctl)
     assert torch.equal(res4["out"], res["out"]) and torch.equal(res4["idx"], res["idx"]) and torch.equal(res4["var"], res["var"])
+
+
+def test_forward_key_windows_match_single_launch(monkeypatch):
+    """Attention by key windows (forced here; chosen automatically for long prefills) against the single-launch
+    attention of the same forward, and against the oracle on sampled rows."""
+    wl = wl_("win", 2, 1100, 1100, 0, 16, 4, 128, 4, 64, "bf16", kmin=48, kmax=200, seed=78, gate_std=2.0)
+    t = S.make_inputs(wl, "cpu")
+    d = T.to_device(t)
+    ctl, kw = _ctl_for(wl, _vbar_from_gpu(wl, d))
+    monkeypatch.setenv("GSA_ATTN_WINDOW", "0")
+    one = T.gpu_forward(wl, d, ctl)
+    for window in (96, 256, 1024):
+        monkeypatch.setenv("GSA_ATTN_WINDOW", str(window))
+        res = T.gpu_forward(wl, d, ctl)
+        assert torch.equal(res["idx"], one["idx"]) and torch.equal(res["n_sel"], one["n_sel"])
+        assert (res["out"].float() - one["out"].float()).abs().max().item() <= 1e-2
+        r = np.random.default_rng(window)
+        rows = [(int(b), int(i)) for b, i in zip(r.integers(0, 2, 24), r.integers(0, 1100, 24))] + [(0, 0), (1, 1099), (0, window - 1), (1, window)]
+        _check_forward(wl, t, res, kw, rows)
+        # slabs whose first row lies beyond the first windows
+        res2 = T.gpu_forward(wl, d, ctl, slab_rows=384)
+        same_k = (res2["k"] == res["k"])
+        assert same_k.float().mean().item() > 0.995
+        assert (res2["out"][same_k].float() - res["out"][same_k].float()).abs().max().item() <= 1e-2
 
 
 def test_forward_decode_shape_equals_prefill_last_row():
