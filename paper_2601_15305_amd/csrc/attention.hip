@@ -294,7 +294,6 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
     float acc[DPL];
 #pragma unroll
     for (int e = 0; e < DPL; ++e) acc[e] = 0.f;
-#pragma unroll 4
     for (int sp = 0; sp < ns; ++sp) {
         const float w = __shfl(wgt, sp, 64);
 #pragma unroll
