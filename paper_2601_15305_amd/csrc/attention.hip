@@ -507,10 +507,13 @@ int attn_splits(const gsa_shape& sh, int64_t rows, int k_cap) {
 }
 
 // Key-window mode (bf16, many rows, long context): keys per window, 0 = off.  The K/V' rows of one window
-// and kv-head slice (window * d_h * 4 bytes) then stay resident in the L2 of every XCD while all rows
-// gather from them, instead of every gather going out to the memory-side cache.
-static int attn_window(const gsa_shape& sh, int64_t rows) {
-    int w = 16384;
+// and kv-head slice (window * d_h * 4 bytes) then stay largely resident in the L2 of every XCD while all rows
+// gather from them, instead of every gather going out to the memory-side cache.  A smaller window is hit
+// more often but leaves a row fewer keys per window to amortise its start-up on; about k_cap/8 keys per
+// window for the longest rows measured best on both the 32K and the 128K shapes.
+static int attn_window(const gsa_shape& sh, int64_t rows, int k_cap) {
+    int w = 4096;
+    while (w < 32768 && (int64_t)w * k_cap < 512 * (int64_t)sh.Lk) w *= 2;
     bool forced = false;
     if (const char* e = getenv("GSA_ATTN_WINDOW")) {  // tuning / test override; 0 turns the mode off
         w = atoi(e);
@@ -524,7 +527,7 @@ static int attn_window(const gsa_shape& sh, int64_t rows) {
 
 size_t attn_workspace_bytes(const gsa_shape& sh, int row_begin, int row_end, int k_cap) {
     const int64_t rows = (int64_t)sh.B * (row_end - row_begin);
-    if (const int w = attn_window(sh, rows)) {
+    if (const int w = attn_window(sh, rows, k_cap)) {
         const int64_t nwin = cdiv(sh.Lk, w);
         const size_t offs = ((size_t)rows * (nwin + 1) * sizeof(int32_t) + 255) & ~(size_t)255;
         return offs + (size_t)rows * sh.H * nwin * (sh.d_h + 4) * sizeof(float);
@@ -558,7 +561,7 @@ hipError_t launch_attention(const gsa_shape& sh, int row_begin, int row_end, con
     a.scale = scale;
     const int64_t rows = (int64_t)sh.B * (row_end - row_begin);
     a.winoff = nullptr;
-    a.window = attn_window(sh, rows);
+    a.window = attn_window(sh, rows, k_cap);
     a.win = 0;
     a.q_offset = sh.q_offset;
     a.part_row0 = row_begin;
