@@ -52,8 +52,8 @@ def ev():
 
 
 def measured_traffic(workload, h_kv):
-    """HBM-side bytes of one attention launch as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-    (calibrated against a plain copy); recorded in the committed profile summary of this workload."""
+    """HBM-side bytes of one attention call (all its launches) as measured with rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE (calibrated against a plain copy); recorded in the committed profile summary of this workload."""
     if h_kv != 4:
         return None
     path = os.path.join(ROOT, "profiles", "gsa_forward_%s.md" % workload)
@@ -202,7 +202,7 @@ def main():
                    "HI": wl.HI, "dI": wl.dI, "k_min": wl.k_min, "k_max": wl.k_max, "k_base": wl.k_base, "vbar": vbar,
                    "slab_rows": slab},
         "tflops": round((fl_idx + fl_att) / (ms_per_step * 1e-3) / 1e12, 2),
-        "roofline": {"kernel": "attn_bf16_kernel (gathered sparse gated attention)", "bound": "hbm",
+        "roofline": {"kernel": "attn_bf16_kernel (gathered sparse gated attention: one call = its key-window launches + merge)", "bound": "hbm",
                      "achieved": round(att_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": round(att_gbs / PEAK_HBM_GBS, 4), "traffic": measured_traffic(wl.name, wl.H_kv),
                      "algorithmic_bytes_per_launch": gbytes, "avg_launch_ms": round(stage_ms["attention"], 4)},

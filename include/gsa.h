@@ -128,8 +128,11 @@ int32_t gsa_topk_select(const gsa_shape* shape, int32_t row_begin, int32_t row_e
  * n_sel == 0 produces zeros.  Indices are clamped into [0, Lk-1] before use.
  * bf16: products on the matrix cores with fp32 accumulation, probabilities and gated
  * values rounded to bf16 before the PV product, result rounded to bf16.  f32: fp32 throughout.
- *   workspace: gsa_attn_workspace_bytes(...) bytes (0 unless the kernel splits a row's
- *   selected set over several workgroups, which it does when B*(row_end-row_begin) is small). */
+ * The rows of one call may be worked through in pieces whose partial softmax states are merged at
+ * the end (pieces of each selected list when B*(row_end-row_begin) is small; one piece per window of
+ * keys for bf16 calls with at least 8192 rows and a context of at least two windows, so that the
+ * rows being gathered stay in the on-die caches): same result up to fp32 summation order.
+ *   workspace: gsa_attn_workspace_bytes(...) bytes (0 when neither applies). */
 int32_t gsa_sparse_gated_attn(const gsa_shape* shape, int32_t row_begin, int32_t row_end, const void* Q,
                               const void* K, const void* V, const void* g2_logits, const void* g1_logits,
                               const int32_t* idx, const int32_t* n_sel, int32_t k_cap, float softmax_scale,
@@ -154,7 +157,9 @@ int32_t gsa_value_gate(const gsa_shape* shape, const void* V, const void* g2_log
  * except between scores that agree to within fp32 rounding (about 1e-7 relative).
  * Environment switches read at call time, for comparison runs only: GSA_FORWARD_FP32_SCORES=1
  * (fp32 score slab instead of keys), GSA_SELECT_EXACT_ONLY=1 (no sampled one-pass selection),
- * GSA_ATTN_GPB=1|2|4 (kv heads per attention workgroup).
+ * GSA_ATTN_GPB=1|2|4 (kv heads per attention workgroup), GSA_ATTN_WINDOW=<keys> (size of the
+ * attention's key windows, 0 = none; also forces them onto small calls, which the tests use).
+ * The workspace size helpers read the same switches: size and call under the same environment.
  *   out          device, out [B, Lq, H, d_h]
  *   idx_out      device, out [B, Lq, k_cap] or NULL (then kept per slab in the workspace)
  *   n_sel_out, k_out   device, out [B, Lq] or NULL

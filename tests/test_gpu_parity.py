@@ -334,10 +334,11 @@ def test_forward_bf16_mid_size(heavy):
     assert torch.equal(res4["out"], res["out"]) and torch.equal(res4["idx"], res["idx"]) and torch.equal(res4["var"], res["var"])
 
 
-def test_forward_key_windows_match_single_launch(monkeypatch):
+@pytest.mark.parametrize("Lq,Lk,off", [(1100, 1100, 0), (300, 1000, 700)], ids=["prefill", "chunk-after-context"])
+def test_forward_key_windows_match_single_launch(monkeypatch, Lq, Lk, off):
     """Attention by key windows (forced here; chosen automatically for long prefills) against the single-launch
     attention of the same forward, and against the oracle on sampled rows."""
-    wl = wl_("win", 2, 1100, 1100, 0, 16, 4, 128, 4, 64, "bf16", kmin=48, kmax=200, seed=78, gate_std=2.0)
+    wl = wl_("win", 2, Lq, Lk, off, 16, 4, 128, 4, 64, "bf16", kmin=48, kmax=200, seed=78, gate_std=2.0)
     t = S.make_inputs(wl, "cpu")
     d = T.to_device(t)
     ctl, kw = _ctl_for(wl, _vbar_from_gpu(wl, d))
@@ -349,10 +350,11 @@ def test_forward_key_windows_match_single_launch(monkeypatch):
         assert torch.equal(res["idx"], one["idx"]) and torch.equal(res["n_sel"], one["n_sel"])
         assert (res["out"].float() - one["out"].float()).abs().max().item() <= 1e-2
         r = np.random.default_rng(window)
-        rows = [(int(b), int(i)) for b, i in zip(r.integers(0, 2, 24), r.integers(0, 1100, 24))] + [(0, 0), (1, 1099), (0, window - 1), (1, window)]
+        rows = [(int(b), int(i)) for b, i in zip(r.integers(0, 2, 24), r.integers(0, Lq, 24))]
+        rows += [(0, 0), (1, Lq - 1), (0, min(Lq - 1, max(0, window - 1 - off))), (1, min(Lq - 1, max(0, window - off)))]
         _check_forward(wl, t, res, kw, rows)
         # slabs whose first row lies beyond the first windows
-        res2 = T.gpu_forward(wl, d, ctl, slab_rows=384)
+        res2 = T.gpu_forward(wl, d, ctl, slab_rows=128 if Lq < 512 else 384)
         same_k = (res2["k"] == res["k"])
         assert same_k.float().mean().item() > 0.995
         assert (res2["out"][same_k].float() - res["out"][same_k].float()).abs().max().item() <= 1e-2
