@@ -521,6 +521,7 @@ static int attn_window(const gsa_shape& sh, int64_t rows, int k_cap) {
     }
     if (w <= 0 || sh.dtype != GSA_BF16 || sh.Lk <= w) return 0;
     if (!forced && (rows < 8192 || sh.Lk < 2 * w)) return 0;
+    if (!forced && (int64_t)w * k_cap < 128 * (int64_t)sh.Lk) return 0;  // too few keys per window to pay for a launch each
     if (cdiv(sh.Lk, w) > 64) w = (int)((cdiv(sh.Lk, 64) + 31) / 32 * 32);  // at most 64 windows
     return w;
 }
