@@ -55,7 +55,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     constexpr int KK = DH / 32;        // MFMA k-steps of the score product
     constexpr int MB = DH / 16;        // 16-feature blocks of the value product
     constexpr int ROWB = DH * 2;       // bytes of one head row
-    constexpr int VROW = ROWB + 32;    // padded LDS row
+    constexpr int VROW = ROWB + 32;    // padded LDS row of the V' tile
+    constexpr int KROW = ROWB + 16;    // padded LDS row of the K tile
     constexpr int VCH = ROWB / 16;     // 16-byte chunks per row
     constexpr int TPI = 64 / VCH;      // tokens covered by one V load instruction
     constexpr int NVL = 32 / TPI;      // V load instructions per 32-token tile
@@ -65,7 +66,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     const int lane = tid & 63, wv = tid >> 6;
     const int n = lane & 15;   // head within the group / token within a 16-token sub-tile
     const int q = lane >> 4;   // k-chunk selector
-    unsigned char* vlds = smem + wv * (32 * VROW);
+    unsigned char* vlds = smem + wv * (32 * (VROW + KROW));
+    unsigned char* klds = vlds + 32 * VROW;
 
     const int R = a.row_end - a.row_begin;
     const int64_t rid = blockIdx.x;
@@ -119,7 +121,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
         const unsigned char* Vb = static_cast<const unsigned char*>(a.V) + ((int64_t)b * a.Lk * a.H_kv + g) * ROWB;
         const unsigned char* Gb = HAS_G2 ? static_cast<const unsigned char*>(a.g2) + ((int64_t)b * a.Lk * a.H_kv + g) * ROWB : nullptr;
 
-        u32x4 kf[2][KK];
+        u32x4 kr[NVL];
         u32x4 vf[NVL];
         u32x4 gf[HAS_G2 ? NVL : 1];
         // indices of the tile after the one whose rows are being requested: fetched one tile early so that
@@ -129,16 +131,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
             int tok = max(0, min(tok_pref, a.Lk - 1));
             tok_pref = idxrow[min(j0 + 32 + (lane & 31), jend - 1)];
 #pragma unroll
-            for (int sub = 0; sub < 2; ++sub) {
-                const int tk = __shfl(tok, sub * 16 + n, 64);
-                const unsigned char* p = Kb + (int64_t)tk * tokstride + q * 16;
-#pragma unroll
-                for (int kk = 0; kk < KK; ++kk) kf[sub][kk] = *reinterpret_cast<const u32x4*>(p + kk * 64);
-            }
-#pragma unroll
-            for (int r = 0; r < NVL; ++r) {
+            for (int r = 0; r < NVL; ++r) {  // whole rows, 16 bytes per lane: K and V' of a token at the same offset
                 const int tk = __shfl(tok, r * TPI + lane / VCH, 64);
                 const int64_t off = (int64_t)tk * tokstride + (lane % VCH) * 16;
+                kr[r] = *reinterpret_cast<const u32x4*>(Kb + off);
                 vf[r] = *reinterpret_cast<const u32x4*>(Vb + off);
                 if constexpr (HAS_G2) gf[r] = *reinterpret_cast<const u32x4*>(Gb + off);
             }
@@ -146,7 +142,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
 
         if (jbeg < jend) load_tile(jbeg);
         for (int j0 = jbeg; j0 < jend; j0 += 32) {
-            // ---- V' rows -> LDS (natural layout: row = token slot, 16 B per lane) -----------------
+            // ---- K and V' rows -> LDS (natural layout: row = token slot, 16 B per lane) ------------
+#pragma unroll
+            for (int r = 0; r < NVL; ++r)
+                *reinterpret_cast<u32x4*>(klds + (r * TPI + lane / VCH) * KROW + (lane % VCH) * 16) = kr[r];
 #pragma unroll
             for (int r = 0; r < NVL; ++r) {
                 u32x4 v = vf[r];
@@ -160,19 +159,22 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
                 }
                 *reinterpret_cast<u32x4*>(vlds + (r * TPI + lane / VCH) * VROW + (lane % VCH) * 16) = v;
             }
-            u32x4 kc[2][KK];
-#pragma unroll
-            for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-                for (int kk = 0; kk < KK; ++kk) kc[sub][kk] = kf[sub][kk];
-            if (j0 + 32 < jend) load_tile(j0 + 32);
+            if (j0 + 32 < jend) load_tile(j0 + 32);  // the row registers are free again
 
-            // ---- S^T = K . Q^T for two 16-token sub-tiles ------------------------------------------
+            // ---- S^T = K . Q^T for two 16-token sub-tiles; the A operand (token n, features (4*kk+q)*8 .. +8)
+            // is read back from the K tile --------------------------------------------------------------
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave's LDS writes have landed
             f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+            {
+                const unsigned char* k0 = klds + n * KROW + q * 16;
+                const unsigned char* k1 = k0 + 16 * KROW;
 #pragma unroll
-            for (int kk = 0; kk < KK; ++kk) {
-                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kc[0][kk]), qf[kk], s0, 0, 0, 0);
-                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kc[1][kk]), qf[kk], s1, 0, 0, 0);
+                for (int kk = 0; kk < KK; ++kk) {
+                    const u32x4 a0 = *reinterpret_cast<const u32x4*>(k0 + kk * 64);
+                    const u32x4 a1 = *reinterpret_cast<const u32x4*>(k1 + kk * 64);
+                    s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a0), qf[kk], s0, 0, 0, 0);
+                    s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a1), qf[kk], s1, 0, 0, 0);
+                }
             }
             // lane (head n, q): s0[i] is token j0 + 4q + i, s1[i] is token j0 + 16 + 4q + i
             float x[8];
@@ -581,7 +583,7 @@ hipError_t launch_attention(const gsa_shape& sh, int row_begin, int row_end, con
     if (sh.dtype == GSA_BF16) {
         const int gpb = attn_groups_per_block(sh, rows);
         const dim3 block(64 * gpb);
-        const size_t smem = (size_t)gpb * 32 * (sh.d_h * 2 + 32);
+        const size_t smem = (size_t)gpb * 32 * ((sh.d_h * 2 + 32) + (sh.d_h * 2 + 16));  // V' tile + K tile per wave
         // one launch, or in key-window mode one launch per window over the rows that can see it
         const int nlaunch = a.window ? a.nsplit : 1;
         for (int z = 0; z < nlaunch; ++z) {
@@ -592,17 +594,13 @@ hipError_t launch_attention(const gsa_shape& sh, int row_begin, int row_end, con
             }
             const int64_t lrows = (int64_t)sh.B * (row_end - a.row_begin);
             const dim3 grid((unsigned)lrows, (unsigned)(sh.H_kv / gpb), (unsigned)(a.window ? 1 : a.nsplit));
-            if (sh.d_h == 128) {
-                if (g2)
-                    hipLaunchKernelGGL((attn_bf16_kernel<128, true>), grid, block, smem, st, a);
-                else
-                    hipLaunchKernelGGL((attn_bf16_kernel<128, false>), grid, block, smem, st, a);
-            } else {
-                if (g2)
-                    hipLaunchKernelGGL((attn_bf16_kernel<64, true>), grid, block, smem, st, a);
-                else
-                    hipLaunchKernelGGL((attn_bf16_kernel<64, false>), grid, block, smem, st, a);
+            void (*kern)(AttnArgs) = sh.d_h == 128 ? (g2 ? attn_bf16_kernel<128, true> : attn_bf16_kernel<128, false>)
+                                                   : (g2 ? attn_bf16_kernel<64, true> : attn_bf16_kernel<64, false>);
+            if (z == 0 && smem > 48 * 1024) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+                if (e != hipSuccess) return e;
             }
+            hipLaunchKernelGGL(kern, grid, block, smem, st, a);
         }
         a.row_begin = row_begin;
         if (a.nsplit > 1) {
