@@ -511,11 +511,12 @@ int attn_splits(const gsa_shape& sh, int64_t rows, int k_cap) {
 // Key-window mode (bf16, many rows, long context): keys per window, 0 = off.  The K/V' rows of one window
 // and kv-head slice (window * d_h * 4 bytes) then stay largely resident in the L2 of every XCD while all rows
 // gather from them, instead of every gather going out to the memory-side cache.  A smaller window is hit
-// more often but leaves a row fewer keys per window to amortise its start-up on; about k_cap/8 keys per
-// window for the longest rows measured best on both the 32K and the 128K shapes.
+// more often but leaves a row fewer keys per window to amortise its start-up on; 384 * Lk / k_cap keys per
+// window (the longest rows then keep about k_cap/10 selected keys per window) measured best on both the
+// 32K and the 128K shapes.
 static int attn_window(const gsa_shape& sh, int64_t rows, int k_cap) {
-    int w = 4096;
-    while (w < 32768 && (int64_t)w * k_cap < 512 * (int64_t)sh.Lk) w *= 2;
+    int64_t w64 = (384 * (int64_t)sh.Lk / (k_cap > 0 ? k_cap : 1) + 512) / 1024 * 1024;
+    int w = (int)(w64 < 4096 ? 4096 : (w64 > 32768 ? 32768 : w64));
     bool forced = false;
     if (const char* e = getenv("GSA_ATTN_WINDOW")) {  // tuning / test override; 0 turns the mode off
         w = atoi(e);
