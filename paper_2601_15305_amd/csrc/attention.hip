@@ -4,20 +4,20 @@
 //   out[t,h,:] = O * sigmoid(g1[t,h,:]),   g = h / (H / H_kv).
 //
 // bf16 kernel.  One wave per (query, kv head); a workgroup holds the waves of one query for one to four
-// kv heads, grid.y walks over the kv-head slices and grid.z over pieces of the selected list (decode).
-// For one kv head the
+// kv heads, grid.y walks over the kv-head slices and grid.z over pieces of the selected list (decode);
+// long prefills are launched once per window of keys (see launch_attention).  For one kv head the
 // G = H/H_kv query heads that share it form the N dimension of the MFMAs (padded to 16), the
 // gathered tokens form M for the score product and K for the value product:
-//   S^T[token, head] = K[token, :] . Q[head, :]       A operand = gathered K rows, read from global
-//                                                     memory straight into the MFMA register layout
-//                                                     (a lane owns 16 consecutive bytes of a row);
+//   S^T[token, head] = K[token, :] . Q[head, :]
 //   O^T[d, head]    += V'^T[d, token] . P^T[token, head]
 // The accumulator layout of S^T (a lane holds four tokens of one head) is exactly the B-operand
-// layout the second product needs, so probabilities never move between lanes.  V' rows go through
-// a wave-private LDS tile and come back transposed with the LDS transpose read of gfx950
-// (ds_read_b64_tr_b16), which turns 4 tokens x 16 features into the "feature row, token
-// contraction" A operand.  Softmax is the usual online form in base 2; G2 is applied to the V
-// rows in registers on their way to LDS, G1 to the accumulators before the store.
+// layout the second product needs, so probabilities never move between lanes.  The gathered K and V'
+// rows are loaded whole (16 lanes x 16 bytes per row, the access shape the memory pipeline serves
+// fastest) into two wave-private LDS tiles.  K comes back as the A operand of the first product with
+// plain 16-byte reads (a lane owns 16 consecutive bytes of a token's row), V' comes back transposed with
+// the LDS transpose read of gfx950 (ds_read_b64_tr_b16), which turns 4 tokens x 16 features into the
+// "feature row, token contraction" A operand of the second.  Softmax is the usual online form in base 2;
+// G2 is applied to the V rows in registers on their way to LDS, G1 to the accumulators before the store.
 #include <cstdlib>
 
 #include "common.hpp"
