@@ -48,6 +48,8 @@ constexpr int kRegion0_16 = 2 * kRecCap;  // words
 static_assert(kRegion0_16 >= kBinsA && kRegion0_16 >= kBinsS && kRegion0_16 >= 2 * kTieCap, "LDS aliasing");
 
 // Two 16-bit saturating differences in one instruction: each half of the result is max(x.half - y.half, 0).
+// (Written as an instruction on purpose: with hipcc 7.2 the portable form, __builtin_elementwise_sub_sat on a
+// 2 x u16 vector cast from one element of a 4 x u32 vector, used the first element's result for all four.)
 __device__ __forceinline__ uint32_t pk_sub_sat_u16(uint32_t x, uint32_t y) {
     uint32_t d;
     asm("v_pk_sub_u16 %0, %1, %2 clamp" : "=v"(d) : "v"(x), "v"(y));
