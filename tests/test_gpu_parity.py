@@ -505,3 +505,19 @@ def test_forward_random_shapes(case):
     res = T.gpu_forward(wl, d, ctl, slab_rows=slab)
     rows = {(int(b), int(i)) for b, i in zip(r.integers(0, B, 12), r.integers(0, Lq, 12))} | {(0, 0), (B - 1, Lq - 1)}
     _check_forward(wl, t, res, kw, sorted(rows))
+
+
+@pytest.mark.parametrize("case", range(24))
+def test_forward_random_shapes_key_windows(monkeypatch, case):
+    """The same kind of random shapes (bf16 only) with the attention forced into key windows of a random size."""
+    r = np.random.default_rng(5000 + case)
+    _, HI, dI, H, Hkv, dh, B, Lq, Lk, off, bias, slab, kmin, kmax = _random_case(r)
+    window = int(r.integers(8, 300))
+    monkeypatch.setenv("GSA_ATTN_WINDOW", str(window))
+    wl = wl_("rndw", B, Lq, Lk, off, H, Hkv, dh, HI, dI, "bf16", kmin=kmin, kmax=kmax, seed=6000 + case)
+    t = S.make_inputs(wl, "cpu", with_bias=bias)
+    d = T.to_device(t)
+    ctl, kw = _ctl_for(wl, _vbar_from_gpu(wl, d) + 1e-6)
+    res = T.gpu_forward(wl, d, ctl, slab_rows=slab)
+    rows = {(int(b), int(i)) for b, i in zip(r.integers(0, B, 12), r.integers(0, Lq, 12))} | {(0, 0), (B - 1, Lq - 1)}
+    _check_forward(wl, t, res, kw, sorted(rows))
