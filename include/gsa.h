@@ -8,7 +8,8 @@
  * and returns.  Scratch memory is a caller-supplied workspace whose size is
  * queried with the *_workspace_bytes helpers.  The library keeps no state
  * between calls apart from the text of the last HIP error of the calling
- * thread.
+ * thread, and reads no environment variables: every switch is an argument
+ * (gsa_tuning).
  *
  * Notation follows the paper: L (Lq query rows, Lk keys), H = n_h query
  * heads, H_kv = n_kv key-value heads, d_h = d_k head dimension, HI = H^I
@@ -52,8 +53,10 @@ enum gsa_status {
     GSA_ERR_HIP = -6          /* a launch failed; see gsa_last_error() */
 };
 
-/* Problem shape.  Supported: d_h in {64,128}; dI in {32,64,128}; HI in {1,2,4,8};
- * H % H_kv == 0 and H/H_kv <= 16; Lk <= 2^20; q_offset + Lq <= Lk. */
+/* Problem shape.  Supported: d_h in {64,128}; dI in {32,64,128}; 1 <= HI <= 8;
+ * H % H_kv == 0 and H/H_kv <= 16; Lk <= 2^20 (the selection calls, gsa_topk_select and gsa_forward, keep
+ * bitmaps of a row on chip and take Lk <= GSA_SELECT_MAX_LK); q_offset + Lq <= Lk. */
+#define GSA_SELECT_MAX_LK 393216
 typedef struct gsa_shape {
     int32_t B, Lq, Lk, q_offset;
     int32_t H, H_kv, d_h;
@@ -73,6 +76,17 @@ typedef struct gsa_adaptive {
     int32_t k_fixed;
     int32_t mode;
 } gsa_adaptive;
+
+/* Launch-shape switches.  Every call that takes one accepts NULL (all fields 0 = the library decides).
+ * They change how the work is cut up, never what is computed (results agree up to fp32 summation
+ * order); a *_workspace_bytes helper and the call it sizes must be given the same values. */
+typedef struct gsa_tuning {
+    int32_t attn_window;         /* keys per key window of the sparse attention (see gsa_sparse_gated_attn):
+                                    0 = chosen by the library, -1 = no windows, > 0 = this size, also on small calls */
+    int32_t attn_kv_per_wg;      /* kv heads per attention workgroup: 0 = chosen by the library, else 1, 2 or 4 */
+    int32_t select_exact_only;   /* 1 = gsa_topk_select never takes its sampled one-pass variant */
+    int32_t forward_fp32_scores; /* 1 = gsa_forward keeps fp32 scores between indexer and selection, not 16-bit keys */
+} gsa_tuning;
 
 /* ---- stage 1: gated lightning indexer, Sec. 3.3, Eq. "indexer" ----------------------
  *   I[t,s] = sum_j w[t,j] * sigmoid(qI[t,j,:] . kI[s,:] + bI[j])   for every visible s,
@@ -95,6 +109,16 @@ int32_t gsa_indexer_scores(const gsa_shape* shape, const void* qI, const void* k
                            size_t workspace_bytes, void* stream);
 size_t gsa_indexer_workspace_bytes(const gsa_shape* shape, int32_t row_begin, int32_t row_end);
 
+/* The same stage in the form the fused forward uses: instead of fp32 scores it writes the monotone
+ * 16-bit fixed-point key  min(65535, floor(I[t,s] * 65536 / HIK))  of every visible score, HIK = HI rounded
+ * up to a power of two (half the bytes to write and to read back); the statistics are those of the fp32
+ * scores, bit for bit.  keys: device, out, uint16, indexed like `scores` above with ld_keys >= Lk, a
+ * multiple of 8.  w must lie in [0,1] for the keys to resolve the scores (larger weights saturate keys). */
+int32_t gsa_indexer_keys(const gsa_shape* shape, const void* qI, const void* kI, const float* w,
+                         const float* bI, int32_t row_begin, int32_t row_end, uint16_t* keys,
+                         int64_t ld_keys, float* row_mean, float* row_var, void* workspace,
+                         size_t workspace_bytes, void* stream);
+
 /* ---- stage 2: adaptive sparsity controller, Sec. 3.4 --------------------------------
  *   k[b,t]     = the budget of Eq. "adaptive_k" (always within [k_min, k_max], or k_fixed)
  *   n_sel[b,t] = min(k[b,t], number of visible keys of row t)
@@ -113,10 +137,19 @@ int32_t gsa_adaptive_k(const gsa_shape* shape, const gsa_adaptive* ctl, const fl
  *           are ranked as 0.
  *   n_sel   device, in, int32 [B, Lq]; values above min(k_cap, visible) are clamped.
  *   idx_out device, out, int32 [B, Lq, k_cap] (only rows in range written); 1 <= k_cap <= 8192.
- * No workspace. */
+ * No workspace.  Lk above GSA_SELECT_MAX_LK: GSA_ERR_UNSUPPORTED. */
 int32_t gsa_topk_select(const gsa_shape* shape, int32_t row_begin, int32_t row_end, const float* scores,
                         int64_t ld_scores, const int32_t* n_sel, int32_t k_cap, int32_t* idx_out,
-                        void* stream);
+                        const gsa_tuning* tuning, void* stream);
+
+/* The same stage on the 16-bit keys of gsa_indexer_keys (the form the fused forward uses).  Every element
+ * whose key lies above the n_sel-th largest key is selected; the elements that share that key are the
+ * only ones the keys do not order: their fp32 scores are recomputed from qI, kI, w, bI (Sec. 3.3,
+ * Eq. "indexer") and ranked, equal scores lowest index first.  The result equals gsa_topk_select on the
+ * fp32 scores except between scores that agree to within fp32 rounding (about 1e-7 relative). */
+int32_t gsa_topk_select_keys(const gsa_shape* shape, int32_t row_begin, int32_t row_end, const uint16_t* keys,
+                             int64_t ld_keys, const int32_t* n_sel, int32_t k_cap, int32_t* idx_out,
+                             const void* qI, const void* kI, const float* w, const float* bI, void* stream);
 
 /* ---- stage 4: sparse attention with value gate G2 and output gate G1, Sec. 3.5-3.6 --
  * For query head h (kv head g = h / (H/H_kv)) over S_t = idx[b,t,0:n_sel[b,t]]:
@@ -128,16 +161,19 @@ int32_t gsa_topk_select(const gsa_shape* shape, int32_t row_begin, int32_t row_e
  * n_sel == 0 produces zeros.  Indices are clamped into [0, Lk-1] before use.
  * bf16: products on the matrix cores with fp32 accumulation, probabilities and gated
  * values rounded to bf16 before the PV product, result rounded to bf16.  f32: fp32 throughout.
- * The rows of one call may be worked through in pieces whose partial softmax states are merged at
- * the end (pieces of each selected list when B*(row_end-row_begin) is small; one piece per window of
- * keys for bf16 calls with at least 8192 rows and a context of at least two windows, so that the
- * rows being gathered stay in the on-die caches): same result up to fp32 summation order.
+ * The rows of one call may be worked through in pieces: pieces of each selected list whose partial
+ * softmax states are merged at the end when B*(row_end-row_begin) is small (decode), or, for bf16
+ * calls with at least 8192 rows and a context of at least two windows, one launch per window of keys
+ * that continues each row's running softmax state, so that the rows being gathered stay in the
+ * on-die caches.  Same result up to fp32 summation order.
  *   workspace: gsa_attn_workspace_bytes(...) bytes (0 when neither applies). */
 int32_t gsa_sparse_gated_attn(const gsa_shape* shape, int32_t row_begin, int32_t row_end, const void* Q,
                               const void* K, const void* V, const void* g2_logits, const void* g1_logits,
                               const int32_t* idx, const int32_t* n_sel, int32_t k_cap, float softmax_scale,
-                              void* out, void* workspace, size_t workspace_bytes, void* stream);
-size_t gsa_attn_workspace_bytes(const gsa_shape* shape, int32_t row_begin, int32_t row_end, int32_t k_cap);
+                              void* out, void* workspace, size_t workspace_bytes, const gsa_tuning* tuning,
+                              void* stream);
+size_t gsa_attn_workspace_bytes(const gsa_shape* shape, int32_t row_begin, int32_t row_end, int32_t k_cap,
+                                const gsa_tuning* tuning);
 
 /* ---- the value gate as a dense pre-pass, Sec. 3.5 / stage (2) of Sec. 4 -------------
  * Vg = V * sigmoid(g2), element-wise over [B, Lk, H_kv, d_h], rounded to dtype.  Vg may alias V. */
@@ -155,26 +191,37 @@ int32_t gsa_value_gate(const gsa_shape* shape, const void* V, const void* g2_log
  * resolve the scores; larger weights only cost speed).  Elements that share the threshold key are
  * re-scored in fp32, so the selected sets equal those of gsa_indexer_scores + gsa_topk_select
  * except between scores that agree to within fp32 rounding (about 1e-7 relative).
- * Environment switches read at call time, for comparison runs only: GSA_FORWARD_FP32_SCORES=1
- * (fp32 score slab instead of keys), GSA_SELECT_EXACT_ONLY=1 (no sampled one-pass selection),
- * GSA_ATTN_GPB=1|2|4 (kv heads per attention workgroup), GSA_ATTN_WINDOW=<keys> (size of the
- * attention's key windows, 0 = none; also forces them onto small calls, which the tests use).
- * The workspace size helpers read the same switches: size and call under the same environment.
+ * The query rows are worked through in slabs; the call fits as many rows into each slab as the
+ * workspace allows (early rows see few keys, so early slabs hold more rows).
  *   out          device, out [B, Lq, H, d_h]
  *   idx_out      device, out [B, Lq, k_cap] or NULL (then kept per slab in the workspace)
  *   n_sel_out, k_out   device, out [B, Lq] or NULL
  *   row_var_out  device, out [B, Lq] or NULL
  *   k_cap        >= k_max (or >= k_fixed), <= 8192
- *   workspace    at least gsa_forward_workspace_bytes(shape, k_cap, g2 != NULL, 0) bytes;
+ *   workspace    at least gsa_forward_workspace_bytes(shape, k_cap, g2 != NULL, 0, tuning) bytes;
  *                a larger workspace lets the call use larger slabs (fewer launches).
- * gsa_forward_workspace_bytes(.., slab_rows): bytes needed to run with slabs of that many
- * query rows (rounded up to a multiple of 32); slab_rows = 0 gives the minimum. */
+ * gsa_forward_workspace_bytes(.., slab_rows, ..): bytes that let every slab hold at least that many
+ * query rows (rounded up to a multiple of 128); slab_rows = 0 gives the minimum.
+ * Lk above GSA_SELECT_MAX_LK: GSA_ERR_UNSUPPORTED. */
 int32_t gsa_forward(const gsa_shape* shape, const gsa_adaptive* ctl, const void* Q, const void* K,
                     const void* V, const void* g1_logits, const void* g2_logits, const void* qI,
                     const void* kI, const float* w, const float* bI, float softmax_scale, void* out,
                     int32_t* idx_out, int32_t* n_sel_out, int32_t* k_out, float* row_var_out,
-                    int32_t k_cap, void* workspace, size_t workspace_bytes, void* stream);
-size_t gsa_forward_workspace_bytes(const gsa_shape* shape, int32_t k_cap, int32_t has_g2, int32_t slab_rows);
+                    int32_t k_cap, void* workspace, size_t workspace_bytes, const gsa_tuning* tuning,
+                    void* stream);
+size_t gsa_forward_workspace_bytes(const gsa_shape* shape, int32_t k_cap, int32_t has_g2, int32_t slab_rows,
+                                   const gsa_tuning* tuning);
+
+/* ---- measurement helper (no part of the method) ---------------------------------------
+ * Gathers whole rows of a table in the access shape of the sparse attention (16 lanes x 16 bytes per
+ * 256-byte row, four rows per load instruction, sixteen loads in flight per wave): wave v of `waves`
+ * reads the rows idx[c*64 .. c*64+64) of every chunk c = v, v + waves, ..., XORs what it reads and
+ * stores one word per wave in sink[v].  The benchmark times it on cache-resident and on HBM-resident
+ * tables to measure the gather ceilings that the attention's achieved rate is compared with.
+ *   table device, in, table_rows rows of 256 bytes;  idx device, in, int32 [n_idx], values in
+ *   [0, table_rows), n_idx a multiple of 64;  sink device, out, uint32 [waves];  waves a multiple of 4. */
+int32_t gsa_probe_gather(const void* table, int64_t table_rows, const int32_t* idx, int64_t n_idx, int32_t waves,
+                         uint32_t* sink, void* stream);
 
 /* ---- misc ---------------------------------------------------------------------------- */
 const char* gsa_status_string(int32_t status); /* static string */

@@ -11,7 +11,5 @@ Modules
 gsa_oracle   numpy fp64, one function per stage (Sec. 3.3-3.6) + dense brute force (Eq. 2)
 naive        pure-Python loops for tiny cases (second, independent statement)
 
-Parity status: every function is pinned by ``tests/test_oracle_pins.py``
-except ``gsa_oracle.ema_update`` (the paper gives no update rule for the
-moving average): parity unpinned.
+Parity status: every function is pinned by ``tests/test_oracle_pins.py``.
 """

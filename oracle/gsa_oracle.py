@@ -23,8 +23,10 @@ prefix; floor before clamp; n_sel = min(k_t, #visible); ties go to the lowest
 index; one index set per query shared by all heads; kv head of query head h is
 h // (H // Hkv).
 
-Parity unpinned: ema_update (Sec. 3.4 names an exponential moving average but
-gives no decay, initial value or update order).
+The moving average Vbar of Sec. 3.4 is an input here (a frozen scalar): the
+paper names the average but gives no decay, initial value or update order, so
+no update rule is implemented.  Every function of this file is pinned by
+tests/test_oracle_pins.py.
 """
 import math
 
@@ -115,12 +117,6 @@ def adaptive_k(var, vbar, k_base, k_min, k_max, k_fixed=0, mode=0):
     r = np.floor(r)
     r = np.minimum(np.maximum(r, float(k_min)), float(k_max))  # clamp while still floating
     return r.astype(np.int64)
-
-
-def ema_update(vbar, row_var, beta=0.99):
-    """One step of a moving average of the batch-mean score variance.  PARITY UNPINNED:
-    Sec. 3.4 only names the average; beta and the update order are this file's choice."""
-    return beta * float(vbar) + (1.0 - beta) * float(np.mean(row_var))
 
 
 # --------------------------------------------------------------------------- Eq. 4 (Sec. 2.2)

@@ -21,9 +21,9 @@ GSA_OK = 0
 GSA_ERR_NULL, GSA_ERR_SHAPE, GSA_ERR_UNSUPPORTED, GSA_ERR_VBAR, GSA_ERR_WORKSPACE, GSA_ERR_HIP = -1, -2, -3, -4, -5, -6
 
 ENTRY_POINTS = (
-    "gsa_indexer_scores", "gsa_indexer_workspace_bytes", "gsa_adaptive_k", "gsa_topk_select",
-    "gsa_sparse_gated_attn", "gsa_attn_workspace_bytes", "gsa_value_gate", "gsa_forward",
-    "gsa_forward_workspace_bytes", "gsa_status_string", "gsa_last_error", "gsa_version",
+    "gsa_indexer_scores", "gsa_indexer_keys", "gsa_indexer_workspace_bytes", "gsa_adaptive_k", "gsa_topk_select",
+    "gsa_topk_select_keys", "gsa_sparse_gated_attn", "gsa_attn_workspace_bytes", "gsa_value_gate", "gsa_forward",
+    "gsa_forward_workspace_bytes", "gsa_probe_gather", "gsa_status_string", "gsa_last_error", "gsa_version",
 )
 
 
@@ -33,6 +33,10 @@ class GsaShape(ctypes.Structure):
 
 class GsaAdaptive(ctypes.Structure):
     _fields_ = [("vbar", ctypes.c_float)] + [(n, ctypes.c_int32) for n in ("k_base", "k_min", "k_max", "k_fixed", "mode")]
+
+
+class GsaTuning(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("attn_window", "attn_kv_per_wg", "select_exact_only", "forward_fp32_scores")]
 
 
 class GsaError(RuntimeError):
@@ -56,24 +60,30 @@ def load():
         raise RuntimeError("libgsa.so is not built: run `python -m paper_2601_15305_amd.build` (no fallback path exists)")
     lib = ctypes.CDLL(LIB_PATH)
     vp, i32, i64, sz, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t, ctypes.c_float
-    shp, ctl = ctypes.POINTER(GsaShape), ctypes.POINTER(GsaAdaptive)
+    shp, ctl, tun = ctypes.POINTER(GsaShape), ctypes.POINTER(GsaAdaptive), ctypes.POINTER(GsaTuning)
     lib.gsa_indexer_scores.argtypes = [shp, vp, vp, vp, vp, i32, i32, vp, i64, vp, vp, vp, sz, vp]
     lib.gsa_indexer_scores.restype = i32
+    lib.gsa_indexer_keys.argtypes = [shp, vp, vp, vp, vp, i32, i32, vp, i64, vp, vp, vp, sz, vp]
+    lib.gsa_indexer_keys.restype = i32
+    lib.gsa_topk_select_keys.argtypes = [shp, i32, i32, vp, i64, vp, i32, vp, vp, vp, vp, vp, vp]
+    lib.gsa_topk_select_keys.restype = i32
+    lib.gsa_probe_gather.argtypes = [vp, i64, vp, i64, i32, vp, vp]
+    lib.gsa_probe_gather.restype = i32
     lib.gsa_indexer_workspace_bytes.argtypes = [shp, i32, i32]
     lib.gsa_indexer_workspace_bytes.restype = sz
     lib.gsa_adaptive_k.argtypes = [shp, ctl, vp, vp, vp, vp]
     lib.gsa_adaptive_k.restype = i32
-    lib.gsa_topk_select.argtypes = [shp, i32, i32, vp, i64, vp, i32, vp, vp]
+    lib.gsa_topk_select.argtypes = [shp, i32, i32, vp, i64, vp, i32, vp, tun, vp]
     lib.gsa_topk_select.restype = i32
-    lib.gsa_sparse_gated_attn.argtypes = [shp, i32, i32, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
+    lib.gsa_sparse_gated_attn.argtypes = [shp, i32, i32, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp, sz, tun, vp]
     lib.gsa_sparse_gated_attn.restype = i32
-    lib.gsa_attn_workspace_bytes.argtypes = [shp, i32, i32, i32]
+    lib.gsa_attn_workspace_bytes.argtypes = [shp, i32, i32, i32, tun]
     lib.gsa_attn_workspace_bytes.restype = sz
     lib.gsa_value_gate.argtypes = [shp, vp, vp, vp, vp]
     lib.gsa_value_gate.restype = i32
-    lib.gsa_forward.argtypes = [shp, ctl, vp, vp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, i32, vp, sz, vp]
+    lib.gsa_forward.argtypes = [shp, ctl, vp, vp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, i32, vp, sz, tun, vp]
     lib.gsa_forward.restype = i32
-    lib.gsa_forward_workspace_bytes.argtypes = [shp, i32, i32, i32]
+    lib.gsa_forward_workspace_bytes.argtypes = [shp, i32, i32, i32, tun]
     lib.gsa_forward_workspace_bytes.restype = sz
     lib.gsa_status_string.argtypes = [i32]
     lib.gsa_status_string.restype = ctypes.c_char_p
@@ -117,6 +127,15 @@ def make_adaptive(vbar, k_base, k_min, k_max, k_fixed=0, mode=0):
     return GsaAdaptive(float(vbar), k_base, k_min, k_max, k_fixed, mode)
 
 
+def make_tuning(attn_window=0, attn_kv_per_wg=0, select_exact_only=0, forward_fp32_scores=0):
+    """gsa_tuning: launch-shape switches (0 = the library decides).  Pass None for all defaults."""
+    return GsaTuning(attn_window, attn_kv_per_wg, select_exact_only, forward_fp32_scores)
+
+
+def _tun(tuning):
+    return ctypes.byref(tuning) if tuning is not None else None
+
+
 def _check(rc, where):
     if rc != GSA_OK:
         raise GsaError(rc, where)
@@ -141,29 +160,50 @@ def gsa_indexer_scores(shape, qI, kI, w, bI, row_begin, row_end, scores, ld_scor
     _check(rc, "gsa_indexer_scores")
 
 
+def gsa_indexer_keys(shape, qI, kI, w, bI, row_begin, row_end, keys, ld_keys, row_mean, row_var, workspace,
+                     workspace_bytes=None, stream=None):
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load().gsa_indexer_keys(ctypes.byref(shape), _ptr(qI), _ptr(kI), _ptr(w), _ptr(bI), row_begin, row_end, _ptr(keys),
+                                 ld_keys, _ptr(row_mean), _ptr(row_var), _ptr(workspace), workspace_bytes, _stream(stream))
+    _check(rc, "gsa_indexer_keys")
+
+
+def gsa_topk_select_keys(shape, row_begin, row_end, keys, ld_keys, n_sel, k_cap, idx_out, qI, kI, w, bI, stream=None):
+    rc = load().gsa_topk_select_keys(ctypes.byref(shape), row_begin, row_end, _ptr(keys), ld_keys, _ptr(n_sel), k_cap,
+                                     _ptr(idx_out), _ptr(qI), _ptr(kI), _ptr(w), _ptr(bI), _stream(stream))
+    _check(rc, "gsa_topk_select_keys")
+
+
+def gsa_probe_gather(table, table_rows, idx, n_idx, waves, sink, stream=None):
+    rc = load().gsa_probe_gather(_ptr(table), table_rows, _ptr(idx), n_idx, waves, _ptr(sink), _stream(stream))
+    _check(rc, "gsa_probe_gather")
+
+
 def gsa_adaptive_k(shape, ctl, row_var, k_out, n_sel_out, stream=None):
     rc = load().gsa_adaptive_k(ctypes.byref(shape), ctypes.byref(ctl) if ctl is not None else None, _ptr(row_var),
                                _ptr(k_out), _ptr(n_sel_out), _stream(stream))
     _check(rc, "gsa_adaptive_k")
 
 
-def gsa_topk_select(shape, row_begin, row_end, scores, ld_scores, n_sel, k_cap, idx_out, stream=None):
+def gsa_topk_select(shape, row_begin, row_end, scores, ld_scores, n_sel, k_cap, idx_out, tuning=None, stream=None):
     rc = load().gsa_topk_select(ctypes.byref(shape), row_begin, row_end, _ptr(scores), ld_scores, _ptr(n_sel), k_cap,
-                                _ptr(idx_out), _stream(stream))
+                                _ptr(idx_out), _tun(tuning), _stream(stream))
     _check(rc, "gsa_topk_select")
 
 
-def gsa_attn_workspace_bytes(shape, row_begin, row_end, k_cap):
-    return load().gsa_attn_workspace_bytes(ctypes.byref(shape), row_begin, row_end, k_cap)
+def gsa_attn_workspace_bytes(shape, row_begin, row_end, k_cap, tuning=None):
+    return load().gsa_attn_workspace_bytes(ctypes.byref(shape), row_begin, row_end, k_cap, _tun(tuning))
 
 
 def gsa_sparse_gated_attn(shape, row_begin, row_end, Q, K, V, g2_logits, g1_logits, idx, n_sel, k_cap, softmax_scale,
-                          out, workspace=None, workspace_bytes=None, stream=None):
+                          out, workspace=None, workspace_bytes=None, tuning=None, stream=None):
     if workspace_bytes is None:
         workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     rc = load().gsa_sparse_gated_attn(ctypes.byref(shape), row_begin, row_end, _ptr(Q), _ptr(K), _ptr(V),
                                       _ptr(g2_logits), _ptr(g1_logits), _ptr(idx), _ptr(n_sel), k_cap,
-                                      float(softmax_scale), _ptr(out), _ptr(workspace), workspace_bytes, _stream(stream))
+                                      float(softmax_scale), _ptr(out), _ptr(workspace), workspace_bytes, _tun(tuning),
+                                      _stream(stream))
     _check(rc, "gsa_sparse_gated_attn")
 
 
@@ -172,19 +212,19 @@ def gsa_value_gate(shape, V, g2_logits, Vg, stream=None):
     _check(rc, "gsa_value_gate")
 
 
-def gsa_forward_workspace_bytes(shape, k_cap, has_g2, slab_rows=0):
-    return load().gsa_forward_workspace_bytes(ctypes.byref(shape), k_cap, int(bool(has_g2)), slab_rows)
+def gsa_forward_workspace_bytes(shape, k_cap, has_g2, slab_rows=0, tuning=None):
+    return load().gsa_forward_workspace_bytes(ctypes.byref(shape), k_cap, int(bool(has_g2)), slab_rows, _tun(tuning))
 
 
 def gsa_forward(shape, ctl, Q, K, V, g1_logits, g2_logits, qI, kI, w, bI, softmax_scale, out, idx_out, n_sel_out, k_out,
-                row_var_out, k_cap, workspace, workspace_bytes=None, stream=None):
+                row_var_out, k_cap, workspace, workspace_bytes=None, tuning=None, stream=None):
     if workspace_bytes is None:
         workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     rc = load().gsa_forward(ctypes.byref(shape) if shape is not None else None,
                             ctypes.byref(ctl) if ctl is not None else None, _ptr(Q), _ptr(K), _ptr(V),
                             _ptr(g1_logits), _ptr(g2_logits), _ptr(qI), _ptr(kI), _ptr(w), _ptr(bI), float(softmax_scale),
                             _ptr(out), _ptr(idx_out), _ptr(n_sel_out), _ptr(k_out), _ptr(row_var_out), k_cap,
-                            _ptr(workspace), workspace_bytes, _stream(stream))
+                            _ptr(workspace), workspace_bytes, _tun(tuning), _stream(stream))
     _check(rc, "gsa_forward")
 
 

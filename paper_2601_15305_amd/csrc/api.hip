@@ -1,7 +1,6 @@
 // C ABI of libgsa: host-side argument validation, workspace carving and launch sequencing.
 // Every error that can be decided from the arguments is returned before anything is launched.
 #include <cmath>
-#include <cstdlib>
 #include <cstring>
 #include <string>
 
@@ -15,7 +14,8 @@ hipError_t launch_indexer(const gsa_shape& sh, const void* qI, const void* kI, c
                           int row_begin, int row_end, float* scores, uint16_t* keys, int64_t ld, float* row_mean,
                           float* row_var, void* workspace, hipStream_t st);
 hipError_t launch_select(const gsa_shape& sh, int row_begin, int row_end, const float* scores, int64_t ld,
-                         const int32_t* n_sel, int k_cap, int32_t* idx_out, int idx_rows, int idx_row0, hipStream_t st);
+                         const int32_t* n_sel, int k_cap, int32_t* idx_out, int idx_rows, int idx_row0, bool exact_only,
+                         hipStream_t st);
 hipError_t launch_select16(const gsa_shape& sh, int row_begin, int row_end, const uint16_t* keys, int64_t ld,
                            const int32_t* n_sel, int k_cap, int32_t* idx_out, int idx_rows, int idx_row0, const void* qI,
                            const void* kI, const float* w, const float* bI, hipStream_t st);
@@ -24,8 +24,10 @@ hipError_t launch_adaptive_k(const gsa_shape& sh, const gsa_adaptive& c, int row
 hipError_t launch_value_gate(const gsa_shape& sh, const void* V, const void* g2, void* Vg, hipStream_t st);
 hipError_t launch_attention(const gsa_shape& sh, int row_begin, int row_end, const void* Q, const void* K, const void* V,
                             const void* g2, const void* g1, const int32_t* idx, int idx_rows, int idx_row0,
-                            const int32_t* n_sel, int k_cap, float scale, void* out, void* workspace, hipStream_t st);
-size_t attn_workspace_bytes(const gsa_shape& sh, int row_begin, int row_end, int k_cap);
+                            const int32_t* n_sel, int k_cap, float scale, void* out, void* workspace, const gsa_tuning& tn,
+                            hipStream_t st);
+size_t attn_workspace_bytes(const gsa_shape& sh, int row_begin, int row_end, int k_cap, const gsa_tuning& tn);
+hipError_t launch_probe_gather(const void* table, const int32_t* idx, int64_t n_idx, int waves, uint32_t* sink, hipStream_t st);
 
 static thread_local std::string g_last_error;
 
@@ -44,7 +46,7 @@ static int32_t check_shape(const gsa_shape* s) {
     if (s->dtype != GSA_F32 && s->dtype != GSA_BF16) return GSA_ERR_UNSUPPORTED;
     if (s->d_h != 64 && s->d_h != 128) return GSA_ERR_UNSUPPORTED;
     if (s->dI != 32 && s->dI != 64 && s->dI != 128) return GSA_ERR_UNSUPPORTED;
-    if (s->HI != 1 && s->HI != 2 && s->HI != 4 && s->HI != 8) return GSA_ERR_UNSUPPORTED;
+    if (s->HI > 8) return GSA_ERR_UNSUPPORTED;
     if (s->H / s->H_kv > 16) return GSA_ERR_UNSUPPORTED;
     if (s->Lk > (1 << 20)) return GSA_ERR_UNSUPPORTED;
     if ((int64_t)s->B * s->Lq > 0x7fffffffLL) return GSA_ERR_UNSUPPORTED;
@@ -66,23 +68,30 @@ static int32_t check_ctl(const gsa_adaptive* c) {
     return GSA_OK;
 }
 
+// The selection kernels keep two bitmaps of a row in LDS: beyond this context length they do not fit.
+static int32_t check_select_len(const gsa_shape* s) { return s->Lk > GSA_SELECT_MAX_LK ? GSA_ERR_UNSUPPORTED : GSA_OK; }
+
+static const gsa_tuning kDefaultTuning = {0, 0, 0, 0};
+static const gsa_tuning& tuning_or_default(const gsa_tuning* t) { return t ? *t : kDefaultTuning; }
+
 static bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 static size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 static size_t elt_bytes(const gsa_shape& s) { return s.dtype == GSA_BF16 ? 2 : 4; }
-static int64_t slab_ld(const gsa_shape& s) { return ((int64_t)s.Lk + 31) & ~(int64_t)31; }
 
 // ---- forward workspace plan ---------------------------------------------------------------------
-struct ForwardPlan {
-    size_t off_vg, off_var, off_k, off_nsel, off_idx, off_scores, off_partial, off_attn, total;
-    int slab_rows;
+// Fixed part: V' (when the value gate runs as a pre-pass) and the per-row outputs the caller did not ask
+// for.  Per-slab part, reused by every slab: the slab's selected indices (when the caller did not ask for
+// them), its scores (fp32) or keys (16 bit), the indexer's per-split partial sums and the attention's
+// workspace.  A slab of rows [r0, r1) sees keys 0 .. q_offset + r1 - 1 only, which sets the leading
+// dimension of its score rows: early slabs are narrow and hold more rows in the same bytes.
+struct FixedPlan {
+    size_t off_vg, off_var, off_k, off_nsel, total;
 };
-
-static int round_slab(const gsa_shape& s, int64_t rows) {
-    if (rows >= s.Lq) return s.Lq;
-    int64_t r = ((rows + 127) / 128) * 128;
-    if (r < 128) r = 128;
-    return (int)(r < s.Lq ? r : s.Lq);
-}
+struct SlabPlan {
+    int r0, r1;
+    int64_t ld;
+    size_t off_idx, off_scores, off_partial, off_attn, total;  // offsets from the start of the per-slab part
+};
 
 // The value gate runs as a dense pre-pass (once per key token) when the queries together gather
 // clearly more rows than there are tokens; otherwise (decode: one query against a long cache) it
@@ -92,22 +101,11 @@ static bool gate_as_prepass(const gsa_shape& s, int k_cap) {
     return (int64_t)s.Lq * k_eff >= 4 * (int64_t)s.Lk;
 }
 
-// Inside the fused forward the indexer hands 16-bit fixed-point keys to the selection instead of fp32
-// scores (see select16.hip).  GSA_FORWARD_FP32_SCORES=1 in the environment keeps the fp32 slab, for
-// comparison runs.
-static bool forward_uses_keys() {
-    const char* e = getenv("GSA_FORWARD_FP32_SCORES");
-    return !(e && e[0] == '1');
-}
-
-static ForwardPlan plan_forward(const gsa_shape& s, int k_cap, bool has_g2, bool own_idx, int slab_rows) {
-    ForwardPlan p;
-    has_g2 = has_g2 && gate_as_prepass(s, k_cap);
-    const int Rs = round_slab(s, slab_rows);
-    p.slab_rows = Rs;
+static FixedPlan plan_fixed(const gsa_shape& s, int k_cap, bool has_g2) {
+    FixedPlan p;
     size_t off = 0;
     p.off_vg = off;
-    if (has_g2) off += up256((size_t)s.B * s.Lk * s.H_kv * s.d_h * elt_bytes(s));
+    if (has_g2 && gate_as_prepass(s, k_cap)) off += up256((size_t)s.B * s.Lk * s.H_kv * s.d_h * elt_bytes(s));
     const size_t rows = (size_t)s.B * s.Lq;
     p.off_var = off;
     off += up256(rows * 4);
@@ -115,24 +113,147 @@ static ForwardPlan plan_forward(const gsa_shape& s, int k_cap, bool has_g2, bool
     off += up256(rows * 4);
     p.off_nsel = off;
     off += up256(rows * 4);
-    p.off_idx = off;
-    if (own_idx) off += up256((size_t)s.B * Rs * (size_t)k_cap * 4);
-    p.off_scores = off;
-    off += up256((size_t)s.B * Rs * (size_t)slab_ld(s) * 4);  // sized for fp32 scores; 16-bit keys use half of it
-    p.off_partial = off;
-    size_t part = 0, attn = 0;
-    for (int r0 = 0; r0 < s.Lq; r0 += Rs) {
-        const int r1 = r0 + Rs < s.Lq ? r0 + Rs : s.Lq;
-        const size_t b = indexer_workspace_bytes(s, r0, r1);
-        if (b > part) part = b;
-        const size_t c = attn_workspace_bytes(s, r0, r1, k_cap);
-        if (c > attn) attn = c;
-    }
-    off += up256(part);
-    p.off_attn = off;
-    off += up256(attn);
     p.total = off;
     return p;
+}
+
+static SlabPlan plan_slab(const gsa_shape& s, int k_cap, bool own_idx, bool use_keys, int r0, int r1, const gsa_tuning& tn) {
+    SlabPlan p;
+    p.r0 = r0;
+    p.r1 = r1;
+    const int64_t last = (int64_t)s.q_offset + r1 - 1 < s.Lk - 1 ? (int64_t)s.q_offset + r1 - 1 : s.Lk - 1;
+    p.ld = (last + 1 + 31) & ~(int64_t)31;
+    const size_t rows = (size_t)s.B * (r1 - r0);
+    size_t off = 0;
+    p.off_idx = off;
+    if (own_idx) off += up256(rows * (size_t)k_cap * 4);
+    p.off_scores = off;
+    off += up256(rows * (size_t)p.ld * (use_keys ? 2 : 4));
+    p.off_partial = off;
+    off += up256(indexer_workspace_bytes(s, r0, r1));
+    p.off_attn = off;
+    off += up256(attn_workspace_bytes(s, r0, r1, k_cap, tn));
+    p.total = off;
+    return p;
+}
+
+// Slab boundaries are multiples of 128 rows (the last slab ends at Lq).
+static int slab_end(const gsa_shape& s, int r0, int64_t blocks) {
+    const int64_t r1 = (int64_t)r0 + blocks * 128;
+    return (int)(r1 < s.Lq ? r1 : s.Lq);
+}
+
+// The slab that starts at row r0: as many rows as fit into `avail` bytes of per-slab workspace.  Returns
+// false if not even 128 rows (or the rest of the rows) fit.
+static bool next_slab(const gsa_shape& s, int k_cap, bool own_idx, bool use_keys, size_t avail, const gsa_tuning& tn, int r0,
+                      SlabPlan* out) {
+    const int64_t max_blocks = cdiv(s.Lq - r0, 128);
+    SlabPlan best = plan_slab(s, k_cap, own_idx, use_keys, r0, slab_end(s, r0, max_blocks), tn);
+    if (best.total > avail) {
+        int64_t lo = 1, hi = max_blocks;  // invariant: `lo` blocks fit (checked first), `hi` blocks do not
+        best = plan_slab(s, k_cap, own_idx, use_keys, r0, slab_end(s, r0, lo), tn);
+        if (best.total > avail) return false;
+        while (hi - lo > 1) {
+            const int64_t mid = (lo + hi) / 2;
+            const SlabPlan p = plan_slab(s, k_cap, own_idx, use_keys, r0, slab_end(s, r0, mid), tn);
+            if (p.total <= avail) {
+                lo = mid;
+                best = p;
+            } else {
+                hi = mid;
+            }
+        }
+    }
+    *out = best;
+    return true;
+}
+
+// Can [0, Lq) be cut into slabs that fit?  (The same walk the launches make, without launching.)
+static bool slabs_fit(const gsa_shape& s, int k_cap, bool own_idx, bool use_keys, size_t avail, const gsa_tuning& tn) {
+    SlabPlan p;
+    for (int r0 = 0; r0 < s.Lq; r0 = p.r1)
+        if (!next_slab(s, k_cap, own_idx, use_keys, avail, tn, r0, &p)) return false;
+    return true;
+}
+
+// The launches of gsa_forward for an already validated call whose slabs are known to fit.
+static int32_t forward_launches(const gsa_shape& s, const gsa_adaptive& ctl, const void* Q, const void* K, const void* V,
+                                const void* g1_logits, const void* g2_logits, const void* qI, const void* kI, const float* w,
+                                const float* bI, float softmax_scale, void* out, int32_t* idx_out, int32_t* n_sel_out,
+                                int32_t* k_out, float* row_var_out, int32_t k_cap, unsigned char* ws, size_t ws_bytes,
+                                const gsa_tuning& tn, hipStream_t st) {
+    const FixedPlan fx = plan_fixed(s, k_cap, g2_logits != nullptr);
+    const bool has_g2 = g2_logits != nullptr;
+    const bool prepass = has_g2 && gate_as_prepass(s, k_cap);
+    const bool own_idx = idx_out == nullptr;
+    const bool use_keys = tn.forward_fp32_scores == 0;
+    const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt((float)s.d_h);
+    const void* Vuse = V;
+    const void* g2use = has_g2 ? g2_logits : nullptr;
+    hipError_t e;
+    if (prepass) {  // stage (2) of Sec. 4: the value gate, once per token
+        e = launch_value_gate(s, V, g2_logits, ws + fx.off_vg, st);
+        if (e != hipSuccess) return hip_fail(e, "gsa_forward/value_gate");
+        Vuse = ws + fx.off_vg;
+        g2use = nullptr;
+    }
+    float* var = row_var_out ? row_var_out : reinterpret_cast<float*>(ws + fx.off_var);
+    int32_t* kbuf = k_out ? k_out : reinterpret_cast<int32_t*>(ws + fx.off_k);
+    int32_t* nsel = n_sel_out ? n_sel_out : reinterpret_cast<int32_t*>(ws + fx.off_nsel);
+    unsigned char* sw = ws + fx.total;  // per-slab part
+    SlabPlan p;
+    for (int r0 = 0; r0 < s.Lq; r0 = p.r1) {
+        if (!next_slab(s, k_cap, own_idx, use_keys, ws_bytes - fx.total, tn, r0, &p)) return GSA_ERR_WORKSPACE;
+        const int r1 = p.r1;
+        float* scores = reinterpret_cast<float*>(sw + p.off_scores);
+        uint16_t* keys = reinterpret_cast<uint16_t*>(sw + p.off_scores);
+        e = launch_indexer(s, qI, kI, w, bI, r0, r1, use_keys ? nullptr : scores, use_keys ? keys : nullptr, p.ld, nullptr,
+                           var, sw + p.off_partial, st);
+        if (e != hipSuccess) return hip_fail(e, "gsa_forward/indexer");
+        e = launch_adaptive_k(s, ctl, r0, r1, var, kbuf, nsel, st);
+        if (e != hipSuccess) return hip_fail(e, "gsa_forward/adaptive_k");
+        int32_t* idx = own_idx ? reinterpret_cast<int32_t*>(sw + p.off_idx) : idx_out;
+        const int idx_rows = own_idx ? (r1 - r0) : s.Lq;
+        const int idx_row0 = own_idx ? r0 : 0;
+        e = use_keys ? launch_select16(s, r0, r1, keys, p.ld, nsel, k_cap, idx, idx_rows, idx_row0, qI, kI, w, bI, st)
+                     : launch_select(s, r0, r1, scores, p.ld, nsel, k_cap, idx, idx_rows, idx_row0, tn.select_exact_only != 0, st);
+        if (e != hipSuccess) return hip_fail(e, "gsa_forward/select");
+        e = launch_attention(s, r0, r1, Q, K, Vuse, g2use, g1_logits, idx, idx_rows, idx_row0, nsel, k_cap, scale, out,
+                             sw + p.off_attn, tn, st);
+        if (e != hipSuccess) return hip_fail(e, "gsa_forward/attention");
+    }
+    return GSA_OK;
+}
+
+static int32_t check_forward_args(const gsa_shape* shape, const gsa_adaptive* ctl, const void* Q, const void* K, const void* V,
+                                  const void* g1_logits, const void* g2_logits, const void* qI, const void* kI, const float* w,
+                                  float softmax_scale, const void* out, int32_t k_cap) {
+    int32_t rc = check_shape(shape);
+    if (rc != GSA_OK) return rc;
+    rc = check_select_len(shape);
+    if (rc != GSA_OK) return rc;
+    rc = check_ctl(ctl);
+    if (rc != GSA_OK) return rc;
+    if (!Q || !K || !V || !qI || !kI || !w || !out) return GSA_ERR_NULL;
+    if (k_cap < 1 || k_cap > 8192) return GSA_ERR_SHAPE;
+    if ((ctl->k_fixed > 0 ? ctl->k_fixed : ctl->k_max) > k_cap) return GSA_ERR_SHAPE;
+    if (!(softmax_scale >= 0.0f) || !std::isfinite(softmax_scale)) return GSA_ERR_SHAPE;
+    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(out, 16) || !aligned(qI, 16) || !aligned(kI, 16) ||
+        (g1_logits && !aligned(g1_logits, 16)) || (g2_logits && !aligned(g2_logits, 16)))
+        return GSA_ERR_SHAPE;
+    return GSA_OK;
+}
+
+// Bytes of the whole forward workspace when every slab holds `blocks` * 128 rows.
+static size_t forward_bytes_uniform(const gsa_shape& s, int k_cap, bool has_g2, int64_t blocks, const gsa_tuning& tn) {
+    const bool use_keys = tn.forward_fp32_scores == 0;
+    size_t slab = 0;
+    for (int r0 = 0; r0 < s.Lq;) {
+        const SlabPlan p = plan_slab(s, k_cap, true, use_keys, r0, slab_end(s, r0, blocks), tn);
+        if (p.total > slab) slab = p.total;
+        r0 = p.r1;
+    }
+    return plan_fixed(s, k_cap, has_g2).total + slab;
 }
 
 }  // namespace gsa
@@ -180,6 +301,23 @@ int32_t gsa_indexer_scores(const gsa_shape* shape, const void* qI, const void* k
     return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_indexer_scores");
 }
 
+int32_t gsa_indexer_keys(const gsa_shape* shape, const void* qI, const void* kI, const float* w, const float* bI,
+                         int32_t row_begin, int32_t row_end, uint16_t* keys, int64_t ld_keys, float* row_mean, float* row_var,
+                         void* workspace, size_t workspace_bytes, void* stream) {
+    int32_t rc = check_shape(shape);
+    if (rc != GSA_OK) return rc;
+    if (!qI || !kI || !w || !row_var || !keys) return GSA_ERR_NULL;
+    rc = check_rows(shape, row_begin, row_end);
+    if (rc != GSA_OK) return rc;
+    if (ld_keys < shape->Lk || (ld_keys & 7) != 0) return GSA_ERR_SHAPE;
+    if (!aligned(qI, 16) || !aligned(kI, 16) || !aligned(keys, 16)) return GSA_ERR_SHAPE;
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < indexer_workspace_bytes(*shape, row_begin, row_end))
+        return GSA_ERR_WORKSPACE;
+    hipError_t e = launch_indexer(*shape, qI, kI, w, bI, row_begin, row_end, nullptr, keys, ld_keys, row_mean, row_var,
+                                  workspace, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_indexer_keys");
+}
+
 int32_t gsa_adaptive_k(const gsa_shape* shape, const gsa_adaptive* ctl, const float* row_var, int32_t* k_out,
                        int32_t* n_sel_out, void* stream) {
     int32_t rc = check_shape(shape);
@@ -192,8 +330,11 @@ int32_t gsa_adaptive_k(const gsa_shape* shape, const gsa_adaptive* ctl, const fl
 }
 
 int32_t gsa_topk_select(const gsa_shape* shape, int32_t row_begin, int32_t row_end, const float* scores,
-                        int64_t ld_scores, const int32_t* n_sel, int32_t k_cap, int32_t* idx_out, void* stream) {
+                        int64_t ld_scores, const int32_t* n_sel, int32_t k_cap, int32_t* idx_out, const gsa_tuning* tuning,
+                        void* stream) {
     int32_t rc = check_shape(shape);
+    if (rc != GSA_OK) return rc;
+    rc = check_select_len(shape);
     if (rc != GSA_OK) return rc;
     if (!scores || !n_sel || !idx_out) return GSA_ERR_NULL;
     rc = check_rows(shape, row_begin, row_end);
@@ -201,19 +342,37 @@ int32_t gsa_topk_select(const gsa_shape* shape, int32_t row_begin, int32_t row_e
     if (ld_scores < shape->Lk || (ld_scores & 3) != 0 || !aligned(scores, 16)) return GSA_ERR_SHAPE;
     if (k_cap < 1 || k_cap > 8192) return GSA_ERR_SHAPE;
     hipError_t e = launch_select(*shape, row_begin, row_end, scores, ld_scores, n_sel, k_cap, idx_out, shape->Lq, 0,
-                                 static_cast<hipStream_t>(stream));
+                                 tuning_or_default(tuning).select_exact_only != 0, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_topk_select");
 }
 
-size_t gsa_attn_workspace_bytes(const gsa_shape* shape, int32_t row_begin, int32_t row_end, int32_t k_cap) {
+int32_t gsa_topk_select_keys(const gsa_shape* shape, int32_t row_begin, int32_t row_end, const uint16_t* keys,
+                             int64_t ld_keys, const int32_t* n_sel, int32_t k_cap, int32_t* idx_out, const void* qI,
+                             const void* kI, const float* w, const float* bI, void* stream) {
+    int32_t rc = check_shape(shape);
+    if (rc != GSA_OK) return rc;
+    rc = check_select_len(shape);
+    if (rc != GSA_OK) return rc;
+    if (!keys || !n_sel || !idx_out || !qI || !kI || !w) return GSA_ERR_NULL;
+    rc = check_rows(shape, row_begin, row_end);
+    if (rc != GSA_OK) return rc;
+    if (ld_keys < shape->Lk || (ld_keys & 7) != 0 || !aligned(keys, 16) || !aligned(qI, 16) || !aligned(kI, 16)) return GSA_ERR_SHAPE;
+    if (k_cap < 1 || k_cap > 8192) return GSA_ERR_SHAPE;
+    hipError_t e = launch_select16(*shape, row_begin, row_end, keys, ld_keys, n_sel, k_cap, idx_out, shape->Lq, 0, qI, kI, w,
+                                   bI, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_topk_select_keys");
+}
+
+size_t gsa_attn_workspace_bytes(const gsa_shape* shape, int32_t row_begin, int32_t row_end, int32_t k_cap,
+                                const gsa_tuning* tuning) {
     if (check_shape(shape) != GSA_OK || check_rows(shape, row_begin, row_end) != GSA_OK || k_cap < 1 || k_cap > 8192) return 0;
-    return up256(attn_workspace_bytes(*shape, row_begin, row_end, k_cap));
+    return up256(attn_workspace_bytes(*shape, row_begin, row_end, k_cap, tuning_or_default(tuning)));
 }
 
 int32_t gsa_sparse_gated_attn(const gsa_shape* shape, int32_t row_begin, int32_t row_end, const void* Q, const void* K,
                               const void* V, const void* g2_logits, const void* g1_logits, const int32_t* idx,
                               const int32_t* n_sel, int32_t k_cap, float softmax_scale, void* out, void* workspace,
-                              size_t workspace_bytes, void* stream) {
+                              size_t workspace_bytes, const gsa_tuning* tuning, void* stream) {
     int32_t rc = check_shape(shape);
     if (rc != GSA_OK) return rc;
     if (!Q || !K || !V || !idx || !n_sel || !out) return GSA_ERR_NULL;
@@ -224,11 +383,12 @@ int32_t gsa_sparse_gated_attn(const gsa_shape* shape, int32_t row_begin, int32_t
     if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(out, 16) || (g1_logits && !aligned(g1_logits, 16)) ||
         (g2_logits && !aligned(g2_logits, 16)))
         return GSA_ERR_SHAPE;
-    const size_t need = attn_workspace_bytes(*shape, row_begin, row_end, k_cap);
+    const gsa_tuning& tn = tuning_or_default(tuning);
+    const size_t need = attn_workspace_bytes(*shape, row_begin, row_end, k_cap, tn);
     if (need > 0 && (!workspace || !aligned(workspace, 256) || workspace_bytes < need)) return GSA_ERR_WORKSPACE;
     const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt((float)shape->d_h);
     hipError_t e = launch_attention(*shape, row_begin, row_end, Q, K, V, g2_logits, g1_logits, idx, shape->Lq, 0, n_sel,
-                                    k_cap, scale, out, workspace, static_cast<hipStream_t>(stream));
+                                    k_cap, scale, out, workspace, tn, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_sparse_gated_attn");
 }
 
@@ -241,79 +401,39 @@ int32_t gsa_value_gate(const gsa_shape* shape, const void* V, const void* g2_log
     return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_value_gate");
 }
 
-size_t gsa_forward_workspace_bytes(const gsa_shape* shape, int32_t k_cap, int32_t has_g2, int32_t slab_rows) {
-    if (check_shape(shape) != GSA_OK || k_cap < 1 || k_cap > 8192) return 0;
-    return plan_forward(*shape, k_cap, has_g2 != 0, true, slab_rows <= 0 ? 1 : slab_rows).total;
+int32_t gsa_probe_gather(const void* table, int64_t table_rows, const int32_t* idx, int64_t n_idx, int32_t waves,
+                         uint32_t* sink, void* stream) {
+    if (!table || !idx || !sink) return GSA_ERR_NULL;
+    if (table_rows < 1 || table_rows > 0x7fffffffLL || n_idx < 64 || (n_idx & 63) != 0 || waves < 4 || (waves & 3) != 0)
+        return GSA_ERR_SHAPE;
+    if (!aligned(table, 16)) return GSA_ERR_SHAPE;
+    hipError_t e = launch_probe_gather(table, idx, n_idx, waves, sink, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_probe_gather");
+}
+
+size_t gsa_forward_workspace_bytes(const gsa_shape* shape, int32_t k_cap, int32_t has_g2, int32_t slab_rows,
+                                   const gsa_tuning* tuning) {
+    if (check_shape(shape) != GSA_OK || check_select_len(shape) != GSA_OK || k_cap < 1 || k_cap > 8192) return 0;
+    return forward_bytes_uniform(*shape, k_cap, has_g2 != 0, slab_rows <= 0 ? 1 : cdiv(slab_rows, 128), tuning_or_default(tuning));
 }
 
 int32_t gsa_forward(const gsa_shape* shape, const gsa_adaptive* ctl, const void* Q, const void* K, const void* V,
                     const void* g1_logits, const void* g2_logits, const void* qI, const void* kI, const float* w,
                     const float* bI, float softmax_scale, void* out, int32_t* idx_out, int32_t* n_sel_out,
                     int32_t* k_out, float* row_var_out, int32_t k_cap, void* workspace, size_t workspace_bytes,
-                    void* stream) {
-    int32_t rc = check_shape(shape);
+                    const gsa_tuning* tuning, void* stream) {
+    int32_t rc = check_forward_args(shape, ctl, Q, K, V, g1_logits, g2_logits, qI, kI, w, softmax_scale, out, k_cap);
     if (rc != GSA_OK) return rc;
-    rc = check_ctl(ctl);
-    if (rc != GSA_OK) return rc;
-    if (!Q || !K || !V || !qI || !kI || !w || !out) return GSA_ERR_NULL;
-    if (k_cap < 1 || k_cap > 8192) return GSA_ERR_SHAPE;
-    if ((ctl->k_fixed > 0 ? ctl->k_fixed : ctl->k_max) > k_cap) return GSA_ERR_SHAPE;
-    if (!(softmax_scale >= 0.0f) || !std::isfinite(softmax_scale)) return GSA_ERR_SHAPE;
-    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(out, 16) || !aligned(qI, 16) || !aligned(kI, 16) ||
-        (g1_logits && !aligned(g1_logits, 16)) || (g2_logits && !aligned(g2_logits, 16)))
-        return GSA_ERR_SHAPE;
     if (!workspace || !aligned(workspace, 256)) return GSA_ERR_WORKSPACE;
     const gsa_shape& s = *shape;
-    const bool has_g2 = g2_logits != nullptr;
-    const bool prepass = has_g2 && gate_as_prepass(*shape, k_cap);
-    const bool own_idx = idx_out == nullptr;
-    // largest slab that fits the workspace: whole problem first, then halve
-    ForwardPlan plan;
-    int64_t rows = s.Lq;
-    while (true) {
-        plan = plan_forward(s, k_cap, has_g2, own_idx, (int)rows);
-        if (plan.total <= workspace_bytes) break;
-        if (plan.slab_rows <= 128 || plan.slab_rows <= 1) return GSA_ERR_WORKSPACE;
-        rows = (plan.slab_rows + 1) / 2;
-    }
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    unsigned char* ws = static_cast<unsigned char*>(workspace);
-    const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt((float)s.d_h);
-    const void* Vuse = V;
-    const void* g2use = has_g2 ? g2_logits : nullptr;
-    hipError_t e;
-    if (prepass) {  // stage (2) of Sec. 4: the value gate, once per token
-        e = launch_value_gate(s, V, g2_logits, ws + plan.off_vg, st);
-        if (e != hipSuccess) return hip_fail(e, "gsa_forward/value_gate");
-        Vuse = ws + plan.off_vg;
-        g2use = nullptr;
-    }
-    float* var = row_var_out ? row_var_out : reinterpret_cast<float*>(ws + plan.off_var);
-    int32_t* kbuf = k_out ? k_out : reinterpret_cast<int32_t*>(ws + plan.off_k);
-    int32_t* nsel = n_sel_out ? n_sel_out : reinterpret_cast<int32_t*>(ws + plan.off_nsel);
-    float* scores = reinterpret_cast<float*>(ws + plan.off_scores);
-    uint16_t* keys = reinterpret_cast<uint16_t*>(ws + plan.off_scores);
-    const bool use_keys = forward_uses_keys();
-    const int64_t ld = slab_ld(s);
-    const int Rs = plan.slab_rows;
-    for (int r0 = 0; r0 < s.Lq; r0 += Rs) {
-        const int r1 = r0 + Rs < s.Lq ? r0 + Rs : s.Lq;
-        e = launch_indexer(s, qI, kI, w, bI, r0, r1, use_keys ? nullptr : scores, use_keys ? keys : nullptr, ld, nullptr, var,
-                           ws + plan.off_partial, st);
-        if (e != hipSuccess) return hip_fail(e, "gsa_forward/indexer");
-        e = launch_adaptive_k(s, *ctl, r0, r1, var, kbuf, nsel, st);
-        if (e != hipSuccess) return hip_fail(e, "gsa_forward/adaptive_k");
-        int32_t* idx = own_idx ? reinterpret_cast<int32_t*>(ws + plan.off_idx) : idx_out;
-        const int idx_rows = own_idx ? (r1 - r0) : s.Lq;
-        const int idx_row0 = own_idx ? r0 : 0;
-        e = use_keys ? launch_select16(s, r0, r1, keys, ld, nsel, k_cap, idx, idx_rows, idx_row0, qI, kI, w, bI, st)
-                     : launch_select(s, r0, r1, scores, ld, nsel, k_cap, idx, idx_rows, idx_row0, st);
-        if (e != hipSuccess) return hip_fail(e, "gsa_forward/select");
-        e = launch_attention(s, r0, r1, Q, K, Vuse, g2use, g1_logits, idx, idx_rows, idx_row0, nsel, k_cap, scale, out,
-                             ws + plan.off_attn, st);
-        if (e != hipSuccess) return hip_fail(e, "gsa_forward/attention");
-    }
-    return GSA_OK;
+    const gsa_tuning& tn = tuning_or_default(tuning);
+    const size_t fixed = plan_fixed(s, k_cap, g2_logits != nullptr).total;
+    if (fixed > workspace_bytes ||
+        !slabs_fit(s, k_cap, idx_out == nullptr, tn.forward_fp32_scores == 0, workspace_bytes - fixed, tn))
+        return GSA_ERR_WORKSPACE;
+    return forward_launches(s, *ctl, Q, K, V, g1_logits, g2_logits, qI, kI, w, bI, softmax_scale, out, idx_out, n_sel_out,
+                            k_out, row_var_out, k_cap, static_cast<unsigned char*>(workspace), workspace_bytes, tn,
+                            static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

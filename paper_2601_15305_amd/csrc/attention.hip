@@ -5,7 +5,9 @@
 //
 // bf16 kernel.  One wave per (query, kv head); a workgroup holds the waves of one query for one to four
 // kv heads, grid.y walks over the kv-head slices and grid.z over pieces of the selected list (decode);
-// long prefills are launched once per window of keys (see launch_attention).  For one kv head the
+// long prefills are launched once per window of keys, each launch resuming the running softmax state
+// (unnormalised O, running max, running sum) that the previous window left in the workspace
+// (see launch_attention).  For one kv head the
 // G = H/H_kv query heads that share it form the N dimension of the MFMAs (padded to 16), the
 // gathered tokens form M for the score product and K for the value product:
 //   S^T[token, head] = K[token, :] . Q[head, :]
@@ -18,8 +20,6 @@
 // the LDS transpose read of gfx950 (ds_read_b64_tr_b16), which turns 4 tokens x 16 features into the
 // "feature row, token contraction" A operand of the second.  Softmax is the usual online form in base 2;
 // G2 is applied to the V rows in registers on their way to LDS, G1 to the accumulators before the store.
-#include <cstdlib>
-
 #include "common.hpp"
 
 namespace gsa {
@@ -39,7 +39,8 @@ struct AttnArgs {
     int32_t nsplit;  // > 1: a row's selected list is cut into nsplit pieces, partial results go to `part`
     float* part;     // [rows][H][nsplit][d_h + 4]: unnormalised O, running max (base 2), running sum, padding
     // Key-window mode (winoff != nullptr): piece z of a row is the part of its (ascending) list that falls
-    // into keys [z*window, (z+1)*window); one launch handles one window for the rows that can see it.
+    // into keys [z*window, (z+1)*window); one launch handles one window for the rows that can see it and
+    // carries the row's softmax state on in `part`, which then holds one record [rows][H][d_h + 4] per head.
     const int32_t* winoff;  // [rows][nsplit + 1] list positions of the window boundaries
     int32_t window, win;    // keys per window, window of this launch
     int32_t q_offset;
@@ -79,22 +80,29 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     const int G = a.H / a.H_kv;
     const float sl2 = a.scale * kLog2e;
     const int64_t tokstride = (int64_t)a.H_kv * ROWB;  // bytes between consecutive tokens
-    // the piece [jbeg, jend) of the list this workgroup handles, and where its partial record goes
-    // (a row that sees a single key window is finished here, like an unsplit row)
-    const bool partial = a.nsplit > 1 && !(a.winoff && min(a.q_offset + t, a.Lk - 1) < a.window);
+    // the piece [jbeg, jend) of the list this workgroup handles.  Split lists (decode): piece z leaves a
+    // partial record that attn_merge_kernel combines.  Key windows: the launch of window z resumes the state
+    // the launch of window z-1 left (resume), and passes it on (carry) unless z is the last window the row sees.
     const int64_t prow = (int64_t)b * a.part_rows + (t - a.part_row0);
     int jbeg, jend, piece;
+    bool partial, resume = false;
     if (a.winoff) {
         piece = a.win;
         jbeg = min(a.winoff[prow * (a.nsplit + 1) + piece], nsel);
         jend = min(a.winoff[prow * (a.nsplit + 1) + piece + 1], nsel);
+        resume = piece > 0;
+        partial = piece < min(a.q_offset + t, a.Lk - 1) / a.window;
     } else {
         const int ntile_all = (nsel + 31) >> 5;
         const int tps = (ntile_all + a.nsplit - 1) / a.nsplit;  // tiles per split
         piece = blockIdx.z;
         jbeg = min(piece * tps, ntile_all) * 32;
         jend = min(min(piece * tps + tps, ntile_all) * 32, nsel);
+        partial = a.nsplit > 1;
     }
+    // records per head in `part`: one per piece (split lists) or a single running one (key windows)
+    const int rec_per_head = a.winoff ? 1 : a.nsplit;
+    const int rec = a.winoff ? 0 : piece;
 
     // blockDim.x / 64 kv heads per workgroup; blockIdx.y selects which ones.  Blocks are dispatched
     // x-fastest, so all queries work on one slice of kv heads before the next slice starts: the K/V'
@@ -113,9 +121,17 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
             }
         }
         f32x4 o[MB];
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) o[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
         float mrun = kNegBig, lrun = 0.f;
+        float* const state = a.part + (((prow * a.H) + (head_ok ? head : 0)) * rec_per_head + rec) * (DH + 4);
+        if (resume && head_ok) {  // continue the online softmax where the previous key window stopped
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) o[mb] = *reinterpret_cast<const f32x4*>(state + mb * 16 + 4 * q);
+            mrun = state[DH];
+            lrun = q == 0 ? state[DH + 1] : 0.f;  // the sum is kept per lane and added up over q at the end
+        } else {
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) o[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
 
         const unsigned char* Kb = static_cast<const unsigned char*>(a.K) + ((int64_t)b * a.Lk * a.H_kv + g) * ROWB;
         const unsigned char* Vb = static_cast<const unsigned char*>(a.V) + ((int64_t)b * a.Lk * a.H_kv + g) * ROWB;
@@ -224,15 +240,14 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
         // ---- normalise, G1, store ---------------------------------------------------------------------
         float ltot = lrun + __shfl_xor(lrun, 16, 64);
         ltot += __shfl_xor(ltot, 32, 64);
-        if (partial) {  // partial result of this piece of the list; attn_merge_kernel finishes the row
+        if (partial) {  // state of this piece: merged by attn_merge_kernel, or resumed by the next key window
             if (head_ok) {
-                float* pp = a.part + (((prow * a.H) + head) * a.nsplit + piece) * (DH + 4);
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
-                    *reinterpret_cast<f32x4*>(pp + mb * 16 + 4 * q) = o[mb];
+                    *reinterpret_cast<f32x4*>(state + mb * 16 + 4 * q) = o[mb];
                 if (q == 0) {
-                    pp[DH] = mrun;
-                    pp[DH + 1] = ltot;
+                    state[DH] = mrun;
+                    state[DH + 1] = ltot;
                 }
             }
             continue;
@@ -281,10 +296,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
     const int head = (int)(rh % a.H);
     const int b = (int)(rid / R);
     const int t = a.row_begin + (int)(rid % R);
-    // key-window mode: only the windows the row can see have a record, and a row that sees one window
-    // was finished by the attention kernel
-    const int ns = a.winoff ? min(a.nsplit, min(a.q_offset + t, a.Lk - 1) / a.window + 1) : a.nsplit;
-    if (a.winoff && ns == 1) return;
+    const int ns = a.nsplit;
     const float* pp = a.part + rh * a.nsplit * PS;
     const float m = lane < ns ? pp[lane * PS + DH] : kNegBig;
     const float l = lane < ns ? pp[lane * PS + DH + 1] : 0.f;
@@ -480,13 +492,10 @@ hipError_t launch_value_gate(const gsa_shape& sh, const void* V, const void* g2,
 // kv heads handled by one workgroup (one wave each).  With many query rows the kv heads are cut
 // into slices that are processed one after the other by the whole chip (see the kernel), sized so
 // that a slice of K and V' stays near 64 MiB; with few rows (decode) one workgroup takes up to four.
-static int attn_groups_per_block(const gsa_shape& sh, int64_t rows) {
+static int attn_groups_per_block(const gsa_shape& sh, int64_t rows, const gsa_tuning& tn) {
     int gpb = sh.H_kv < 4 ? sh.H_kv : 4;
     while (sh.H_kv % gpb != 0) --gpb;
-    if (const char* e = getenv("GSA_ATTN_GPB")) {  // tuning override
-        const int v = atoi(e);
-        if (v >= 1 && v <= 4 && sh.H_kv % v == 0) return v;
-    }
+    if (tn.attn_kv_per_wg >= 1 && tn.attn_kv_per_wg <= 4 && sh.H_kv % tn.attn_kv_per_wg == 0) return tn.attn_kv_per_wg;
     if (rows < 4096) return gpb;
     const double slice_target = 64.0 * 1024 * 1024;
     while (gpb > 1 && (double)sh.B * sh.Lk * gpb * sh.d_h * 2 * 2 > slice_target && sh.H_kv % (gpb / 2) == 0) gpb /= 2;
@@ -495,9 +504,9 @@ static int attn_groups_per_block(const gsa_shape& sh, int64_t rows) {
 
 // Pieces a row's selected list is cut into (bf16 path): 1 when the launch has enough workgroups anyway,
 // otherwise enough to reach about a thousand workgroups, at least two 32-token tiles per piece.
-int attn_splits(const gsa_shape& sh, int64_t rows, int k_cap) {
+static int attn_splits(const gsa_shape& sh, int64_t rows, int k_cap, const gsa_tuning& tn) {
     if (sh.dtype != GSA_BF16) return 1;
-    const int gpb = attn_groups_per_block(sh, rows);
+    const int gpb = attn_groups_per_block(sh, rows, tn);
     const int64_t wgs = rows * (sh.H_kv / gpb);
     if (wgs >= 1024) return 1;
     int64_t by_len = cdiv(cdiv(k_cap, 32), 2);
@@ -509,40 +518,48 @@ int attn_splits(const gsa_shape& sh, int64_t rows, int k_cap) {
 }
 
 // Key-window mode (bf16, many rows, long context): keys per window, 0 = off.  The K/V' rows of one window
-// and kv-head slice (window * d_h * 4 bytes) then stay largely resident in the L2 of every XCD while all rows
-// gather from them, instead of every gather going out to the memory-side cache.  A smaller window is hit
-// more often but leaves a row fewer keys per window to amortise its start-up on; 384 * Lk / k_cap keys per
-// window (the longest rows then keep about k_cap/10 selected keys per window) measured best on both the
-// 32K and the 128K shapes.
-static int attn_window(const gsa_shape& sh, int64_t rows, int k_cap) {
-    int64_t w64 = (384 * (int64_t)sh.Lk / (k_cap > 0 ? k_cap : 1) + 512) / 1024 * 1024;
-    int w = (int)(w64 < 4096 ? 4096 : (w64 > 32768 ? 32768 : w64));
-    bool forced = false;
-    if (const char* e = getenv("GSA_ATTN_WINDOW")) {  // tuning / test override; 0 turns the mode off
-        w = atoi(e);
-        forced = true;
+// and kv-head slice (window * kv heads per workgroup * d_h * 4 bytes) then stay largely resident in the
+// 4 MB L2 of every XCD while all rows gather from them, instead of every gather going out to the
+// memory-side cache.  Two forces set the size.  A row needs enough selected keys per window to amortise
+// the start of a workgroup: 384 * Lk / k_cap keys per window leave the longest rows about k_cap/10 keys
+// (a dozen 32-key tiles) per window.  The footprint has to stay near the L2 size: it is kept between
+// 2 MiB and 8 MiB whatever the head dimension.
+static int attn_window(const gsa_shape& sh, int64_t rows, int k_cap, const gsa_tuning& tn) {
+    if (tn.attn_window < 0 || sh.dtype != GSA_BF16) return 0;
+    int w;
+    const bool forced = tn.attn_window > 0;
+    if (forced) {
+        w = tn.attn_window;
+    } else {
+        const int gpb = attn_groups_per_block(sh, rows, tn);
+        const int64_t key_bytes = (int64_t)gpb * sh.d_h * 4;  // K row + V' row of the kv heads a workgroup works on
+        int64_t w64 = 384 * (int64_t)sh.Lk / (k_cap > 0 ? k_cap : 1);
+        const int64_t w_lo = (2 << 20) / key_bytes, w_hi = (8 << 20) / key_bytes;
+        w64 = w64 < w_lo ? w_lo : (w64 > w_hi ? w_hi : w64);
+        w = (int)((w64 + 512) / 1024 * 1024);
     }
-    if (w <= 0 || sh.dtype != GSA_BF16 || sh.Lk <= w) return 0;
+    if (w <= 0 || sh.Lk <= w) return 0;
     if (!forced && (rows < 8192 || sh.Lk < 2 * w)) return 0;
     if (!forced && (int64_t)w * k_cap < 128 * (int64_t)sh.Lk) return 0;  // too few keys per window to pay for a launch each
     if (cdiv(sh.Lk, w) > 64) w = (int)((cdiv(sh.Lk, 64) + 31) / 32 * 32);  // at most 64 windows
     return w;
 }
 
-size_t attn_workspace_bytes(const gsa_shape& sh, int row_begin, int row_end, int k_cap) {
+size_t attn_workspace_bytes(const gsa_shape& sh, int row_begin, int row_end, int k_cap, const gsa_tuning& tn) {
     const int64_t rows = (int64_t)sh.B * (row_end - row_begin);
-    if (const int w = attn_window(sh, rows, k_cap)) {
+    if (const int w = attn_window(sh, rows, k_cap, tn)) {
         const int64_t nwin = cdiv(sh.Lk, w);
         const size_t offs = ((size_t)rows * (nwin + 1) * sizeof(int32_t) + 255) & ~(size_t)255;
-        return offs + (size_t)rows * sh.H * nwin * (sh.d_h + 4) * sizeof(float);
+        return offs + (size_t)rows * sh.H * (sh.d_h + 4) * sizeof(float);  // window offsets + one running state per head
     }
-    const int ns = attn_splits(sh, rows, k_cap);
+    const int ns = attn_splits(sh, rows, k_cap, tn);
     return ns > 1 ? (size_t)rows * sh.H * ns * (sh.d_h + 4) * sizeof(float) : 0;
 }
 
 hipError_t launch_attention(const gsa_shape& sh, int row_begin, int row_end, const void* Q, const void* K, const void* V,
                             const void* g2, const void* g1, const int32_t* idx, int idx_rows, int idx_row0,
-                            const int32_t* n_sel, int k_cap, float scale, void* out, void* workspace, hipStream_t st) {
+                            const int32_t* n_sel, int k_cap, float scale, void* out, void* workspace, const gsa_tuning& tn,
+                            hipStream_t st) {
     AttnArgs a;
     a.Q = Q;
     a.K = K;
@@ -565,7 +582,7 @@ hipError_t launch_attention(const gsa_shape& sh, int row_begin, int row_end, con
     a.scale = scale;
     const int64_t rows = (int64_t)sh.B * (row_end - row_begin);
     a.winoff = nullptr;
-    a.window = attn_window(sh, rows, k_cap);
+    a.window = attn_window(sh, rows, k_cap, tn);
     a.win = 0;
     a.q_offset = sh.q_offset;
     a.part_row0 = row_begin;
@@ -578,11 +595,11 @@ hipError_t launch_attention(const gsa_shape& sh, int row_begin, int row_end, con
         hipLaunchKernelGGL(attn_window_offsets_kernel, dim3((unsigned)cdiv(rows, 4)), dim3(256), 0, st, a, winoff);
         a.winoff = winoff;
     } else {
-        a.nsplit = attn_splits(sh, rows, k_cap);
+        a.nsplit = attn_splits(sh, rows, k_cap, tn);
         a.part = static_cast<float*>(workspace);
     }
     if (sh.dtype == GSA_BF16) {
-        const int gpb = attn_groups_per_block(sh, rows);
+        const int gpb = attn_groups_per_block(sh, rows, tn);
         const dim3 block(64 * gpb);
         const size_t smem = (size_t)gpb * 32 * ((sh.d_h * 2 + 32) + (sh.d_h * 2 + 16));  // V' tile + K tile per wave
         // one launch, or in key-window mode one launch per window over the rows that can see it
@@ -604,7 +621,7 @@ hipError_t launch_attention(const gsa_shape& sh, int row_begin, int row_end, con
             hipLaunchKernelGGL(kern, grid, block, smem, st, a);
         }
         a.row_begin = row_begin;
-        if (a.nsplit > 1) {
+        if (a.nsplit > 1 && !a.window) {
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
             const dim3 mgrid((unsigned)cdiv(rows * sh.H, 4));

@@ -39,6 +39,7 @@ struct IndexerArgs {
     int32_t kc;      // keys per split (multiple of 128)
     int32_t nsplit;
     int32_t ntiles;  // query tiles in the slab
+    int32_t hi;      // indexer heads in memory (the kernels work on the next power of two, the extra heads weigh zero)
 };
 
 constexpr int kBN = 128;  // keys per LDS tile
@@ -61,6 +62,8 @@ __device__ __forceinline__ constexpr int acc_row(int i, int h) { return 8 * (i /
 // (saturated at 65535), a monotone compression of the score used inside the fused forward.
 // ROW1: the launch covers one query row per batch element (decode); such launches get a kernel of their
 // own so that the deeper prefetch of that case does not cost the prefill loops any registers.
+// HI is the head count the kernel is built for (1, 2, 4 or 8); a.hi <= HI heads exist in memory, the others
+// are given zero queries and zero weights, which adds exact zeros to every sum.
 template <typename T, int DI, int HI, int STORE, bool ROW1>
 __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(IndexerArgs a) {
     constexpr int EB = ElemTraits<T>::kBytes;
@@ -125,7 +128,7 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
 #pragma unroll
     for (int r = 0; r < HL; ++r) {
         const int j = (HI == 8) ? 4 * h + r : r;  // head of accumulator register s*HL + r
-        nbias[r] = a.bI ? -kLog2e * a.bI[j] : 0.f;
+        nbias[r] = (a.bI && j < a.hi) ? -kLog2e * a.bI[j] : 0.f;
     }
 #pragma unroll
     for (int s = 0; s < NSLOT; ++s) {
@@ -137,7 +140,7 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
 #pragma unroll
         for (int r = 0; r < HL; ++r) {
             const int j = (HI == 8) ? 4 * h + r : r;
-            const float wv_ = ok ? a.w[((int64_t)b * a.Lq + t) * HI + j] : 0.f;
+            const float wv_ = (ok && j < a.hi) ? a.w[((int64_t)b * a.Lq + t) * a.hi + j] : 0.f;
             wreg[s * HL + r] = wv_ * kKeyScale;
             c += 0.5f * (wv_ * kKeyScale);
         }
@@ -154,8 +157,8 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
         float afrag_f[kIsBf16 ? 1 : KSTEPS];
         {
             const int t = t_w0 + n / HI;
-            const bool ok = t < a.row_end;
-            const int64_t row = ((int64_t)b * a.Lq + (ok ? t : a.row_begin)) * HI + (n % HI);
+            const bool ok = t < a.row_end && (n % HI) < a.hi;
+            const int64_t row = ((int64_t)b * a.Lq + (ok ? t : a.row_begin)) * a.hi + (ok ? n % HI : 0);
             if constexpr (kIsBf16) {
                 const u32x4* src = reinterpret_cast<const u32x4*>(static_cast<const __bf16*>(a.qI) + row * DI);
 #pragma unroll
@@ -415,7 +418,7 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
 //   mean = c + S1/n,  var = S2/n - (S1/n)^2   with d = I - c.
 __global__ void indexer_finalize_kernel(const float2* partial, const float* w, float* row_mean, float* row_var,
                                         int B, int Lq, int Lk, int q_offset, int row_begin, int row_end, int nsplit,
-                                        int HI) {
+                                        int HI, int hi) {
     const int R = row_end - row_begin;
     const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= (int64_t)B * R) return;
@@ -428,13 +431,14 @@ __global__ void indexer_finalize_kernel(const float2* partial, const float* w, f
         S2 += (double)p.y;
     }
     float c = 0.f;  // same association as in the kernel above so that the centre is bit-identical
+    const float* wr = w + ((int64_t)b * Lq + t) * hi;  // hi heads in memory, HI in the kernel (the rest weigh zero)
     if (HI == 8) {
         float c0 = 0.f, c1 = 0.f;
-        for (int j = 0; j < 4; ++j) c0 += 0.5f * w[((int64_t)b * Lq + t) * HI + j];
-        for (int j = 4; j < 8; ++j) c1 += 0.5f * w[((int64_t)b * Lq + t) * HI + j];
+        for (int j = 0; j < 4; ++j) c0 += 0.5f * wr[j];
+        for (int j = 4; j < hi; ++j) c1 += 0.5f * wr[j];
         c = c0 + c1;
     } else {
-        for (int j = 0; j < HI; ++j) c += 0.5f * w[((int64_t)b * Lq + t) * HI + j];
+        for (int j = 0; j < hi; ++j) c += 0.5f * wr[j];
     }
     const double nvis = (double)(min(q_offset + t, Lk - 1) + 1);
     const double m = S1 / nvis;
@@ -445,7 +449,8 @@ __global__ void indexer_finalize_kernel(const float2* partial, const float* w, f
 }
 
 // ---- host side -----------------------------------------------------------------------------
-static int queries_per_wg(int HI) { return 4 * (32 / HI); }
+static int kernel_heads(int hi) { return hi <= 1 ? 1 : (hi <= 2 ? 2 : (hi <= 4 ? 4 : 8)); }
+static int queries_per_wg(int hi) { return 4 * (32 / kernel_heads(hi)); }
 
 // Keys per split: enough splits that the launch fills the chip, never less than four key tiles.
 void indexer_plan(const gsa_shape& sh, int row_begin, int row_end, int* kc_out, int* nsplit_out, int* ntiles_out) {
@@ -527,11 +532,13 @@ hipError_t launch_indexer(const gsa_shape& sh, const void* qI, const void* kI, c
     a.row_begin = row_begin;
     a.row_end = row_end;
     indexer_plan(sh, row_begin, row_end, &a.kc, &a.nsplit, &a.ntiles);
-    hipError_t e = (sh.dtype == GSA_BF16) ? launch_di<__bf16>(a, sh.dI, sh.HI, st) : launch_di<float>(a, sh.dI, sh.HI, st);
+    a.hi = sh.HI;
+    const int HIK = kernel_heads(sh.HI);
+    hipError_t e = (sh.dtype == GSA_BF16) ? launch_di<__bf16>(a, sh.dI, HIK, st) : launch_di<float>(a, sh.dI, HIK, st);
     if (e != hipSuccess) return e;
     const int64_t rows = (int64_t)sh.B * (row_end - row_begin);
     hipLaunchKernelGGL(indexer_finalize_kernel, dim3((unsigned)cdiv(rows, 256)), dim3(256), 0, st, a.partial, w, row_mean,
-                       row_var, sh.B, sh.Lq, sh.Lk, sh.q_offset, row_begin, row_end, a.nsplit, sh.HI);
+                       row_var, sh.B, sh.Lq, sh.Lk, sh.q_offset, row_begin, row_end, a.nsplit, HIK, sh.HI);
     return hipGetLastError();
 }
 

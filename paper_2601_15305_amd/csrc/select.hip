@@ -18,8 +18,6 @@
 // The result is deterministic and independent of the order in which atomics land.
 // Long rows with a small budget first try a one-pass variant that gets its threshold bound from a
 // strided sample of the row (select_sampled below); its result is verified and identical.
-#include <cstdlib>
-
 #include "select_common.hpp"
 
 namespace gsa {
@@ -190,7 +188,8 @@ size_t select_lds_bytes(int Lk) {
 }
 
 hipError_t launch_select(const gsa_shape& sh, int row_begin, int row_end, const float* scores, int64_t ld,
-                         const int32_t* n_sel, int k_cap, int32_t* idx_out, int idx_rows, int idx_row0, hipStream_t st) {
+                         const int32_t* n_sel, int k_cap, int32_t* idx_out, int idx_rows, int idx_row0, bool exact_only,
+                         hipStream_t st) {
     SelectArgs a;
     a.scores = scores;
     a.ld = ld;
@@ -206,7 +205,7 @@ hipError_t launch_select(const gsa_shape& sh, int row_begin, int row_end, const 
     a.nw = (sh.Lk + 31) / 32;
     a.idx_rows = idx_rows;
     a.idx_row0 = idx_row0;
-    a.sampled = getenv("GSA_SELECT_EXACT_ONLY") ? 0 : 1;  // tuning/diagnostic switch
+    a.sampled = exact_only ? 0 : 1;
     const size_t smem = select_lds_bytes(sh.Lk);
     if (smem > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(topk_select_kernel),

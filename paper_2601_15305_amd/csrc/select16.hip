@@ -15,8 +15,6 @@
 //      constant rows) the exact multi-pass radix select runs over the recomputed scores instead.
 // Two recomputed scores can differ from the indexer's own by fp32 rounding only, i.e. only keys within
 // about 1e-7 (relative) of a bin edge or of each other can be ordered differently.
-#include <cstdlib>
-
 #include "select_common.hpp"
 
 namespace gsa {
@@ -33,6 +31,7 @@ struct Select16Args {
     int32_t B, Lq, Lk, q_offset, row_begin, row_end, k_cap;
     int32_t nw;
     int32_t idx_rows, idx_row0;
+    int32_t hi;  // indexer heads in memory; the kernel is built for the next power of two, the extra heads weigh zero
 };
 
 constexpr int kKeysPerVec = 8;                                      // one 16-byte load
@@ -162,10 +161,10 @@ __global__ __launch_bounds__(kSelThreads, 4) void topk_select16_kernel(Select16A
 #pragma unroll
     for (int i = 0; i < QPT; ++i) {
         const int c = tid + i * kSelThreads;
-        qreg[i] = c < HI * DI ? (float)static_cast<const T*>(a.qI)[((int64_t)b * a.Lq + t) * HI * DI + c] : 0.f;
+        qreg[i] = c < a.hi * DI ? (float)static_cast<const T*>(a.qI)[((int64_t)b * a.Lq + t) * a.hi * DI + c] : 0.f;
     }
-    if (tid < HI) {
-        wreg = a.w[((int64_t)b * a.Lq + t) * HI + tid];
+    if (tid < a.hi) {
+        wreg = a.w[((int64_t)b * a.Lq + t) * a.hi + tid];
         nbreg = a.bI ? -kLog2e * a.bI[tid] : 0.f;
     }
     auto park_query = [&]() {
@@ -454,10 +453,13 @@ __global__ __launch_bounds__(kSelThreads, 4) void topk_select16_kernel(Select16A
     emit_selection(out, a.k_cap, m, n, bm_sel, with_ties ? L.region2 : nullptr, m_eq, scan64);
 }
 
+static int kernel_heads16(int hi) { return hi <= 1 ? 1 : (hi <= 2 ? 2 : (hi <= 4 ? 4 : 8)); }
+
 size_t select16_lds_bytes(const gsa_shape& sh) {
     const int nw = ((sh.Lk + 31) / 32 + 3) & ~3;  // bitmap words, rounded so that what follows stays 16-byte aligned
     const int r2 = nw > kBinsC + kTieCap ? nw : kBinsC + kTieCap;
-    return (size_t)(kRegion0_16 + nw + r2 + 32 + sh.HI * sh.dI + 2 * sh.HI) * sizeof(uint32_t);
+    const int HIK = kernel_heads16(sh.HI);
+    return (size_t)(kRegion0_16 + nw + r2 + 32 + HIK * sh.dI + 2 * HIK) * sizeof(uint32_t);
 }
 
 template <typename T, int DI, int HI>
@@ -512,10 +514,12 @@ hipError_t launch_select16(const gsa_shape& sh, int row_begin, int row_end, cons
     a.nw = ((sh.Lk + 31) / 32 + 3) & ~3;
     a.idx_rows = idx_rows;
     a.idx_row0 = idx_row0;
+    a.hi = sh.HI;
     const size_t smem = select16_lds_bytes(sh);
     const int64_t rows = (int64_t)sh.B * (row_end - row_begin);
-    return sh.dtype == GSA_BF16 ? launch16_di<__bf16>(a, sh.dI, sh.HI, smem, rows, st)
-                                : launch16_di<float>(a, sh.dI, sh.HI, smem, rows, st);
+    const int HIK = kernel_heads16(sh.HI);
+    return sh.dtype == GSA_BF16 ? launch16_di<__bf16>(a, sh.dI, HIK, smem, rows, st)
+                                : launch16_di<float>(a, sh.dI, HIK, smem, rows, st);
 }
 
 }  // namespace gsa

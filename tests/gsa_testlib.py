@@ -49,27 +49,30 @@ def gpu_adaptive_k(wl, ctl, var):
     return k, n_sel
 
 
-def gpu_select(wl, scores, n_sel, k_cap, row_begin=0, row_end=None):
+def gpu_select(wl, scores, n_sel, k_cap, row_begin=0, row_end=None, tuning=None):
     sh = G.shape_of(wl)
     row_end = wl.Lq if row_end is None else row_end
     idx = torch.full((wl.B, wl.Lq, k_cap), -7, dtype=torch.int32, device=scores.device)
-    G.gsa_topk_select(sh, row_begin, row_end, scores, scores.shape[-1], n_sel, k_cap, idx)
+    G.gsa_topk_select(sh, row_begin, row_end, scores, scores.shape[-1], n_sel, k_cap, idx, tuning)
     torch.cuda.synchronize()
     return idx
 
 
-def gpu_attention(wl, t, idx, n_sel, k_cap, use_g2=True, use_g1=True, scale=0.0, row_begin=0, row_end=None, V=None):
+def gpu_attention(wl, t, idx, n_sel, k_cap, use_g2=True, use_g1=True, scale=0.0, row_begin=0, row_end=None, V=None,
+                  tuning=None):
     sh = G.shape_of(wl)
     row_end = wl.Lq if row_end is None else row_end
     out = torch.full_like(t["Q"], float("nan"))
-    ws = G.workspace(G.gsa_attn_workspace_bytes(sh, row_begin, row_end, k_cap), out.device)
+    ws = G.workspace(G.gsa_attn_workspace_bytes(sh, row_begin, row_end, k_cap, tuning), out.device)
+    ws.fill_(0xFF)   # NaN patterns: stale workspace contents must never reach the result
     G.gsa_sparse_gated_attn(sh, row_begin, row_end, t["Q"], t["K"], t["V"] if V is None else V,
-                            t["g2"] if use_g2 else None, t["g1"] if use_g1 else None, idx, n_sel, k_cap, scale, out, ws)
+                            t["g2"] if use_g2 else None, t["g1"] if use_g1 else None, idx, n_sel, k_cap, scale, out, ws,
+                            tuning=tuning)
     torch.cuda.synchronize()
     return out
 
 
-def gpu_forward(wl, t, ctl, k_cap=None, slab_rows=None, want_idx=True, scale=0.0, use_g2=True, use_g1=True):
+def gpu_forward(wl, t, ctl, k_cap=None, slab_rows=None, want_idx=True, scale=0.0, use_g2=True, use_g1=True, tuning=None):
     sh = G.shape_of(wl)
     k_cap = wl.k_cap if k_cap is None else k_cap
     dev = t["Q"].device
@@ -78,10 +81,11 @@ def gpu_forward(wl, t, ctl, k_cap=None, slab_rows=None, want_idx=True, scale=0.0
     n_sel = torch.empty((wl.B, wl.Lq), dtype=torch.int32, device=dev)
     k = torch.empty_like(n_sel)
     var = torch.empty((wl.B, wl.Lq), dtype=torch.float32, device=dev)
-    nbytes = G.gsa_forward_workspace_bytes(sh, k_cap, use_g2, wl.Lq if slab_rows is None else slab_rows)
+    nbytes = G.gsa_forward_workspace_bytes(sh, k_cap, use_g2, wl.Lq if slab_rows is None else slab_rows, tuning)
     ws = G.workspace(nbytes, dev)
+    ws.fill_(0xFF)   # NaN patterns: stale workspace contents must never reach the result
     G.gsa_forward(sh, ctl, t["Q"], t["K"], t["V"], t["g1"] if use_g1 else None, t["g2"] if use_g2 else None, t["qI"],
-                  t["kI"], t["w"], t["bI"], scale, out, idx, n_sel, k, var, k_cap, ws)
+                  t["kI"], t["w"], t["bI"], scale, out, idx, n_sel, k, var, k_cap, ws, tuning=tuning)
     torch.cuda.synchronize()
     return dict(out=out, idx=idx, n_sel=n_sel, k=k, var=var)
 
@@ -96,9 +100,16 @@ def check_index_row_wellformed(idx_row, n_sel, n_vis, k_cap):
     assert np.all(np.diff(sel) > 0), "indices must be strictly ascending (unique)"
 
 
+FP32_MIN_NORMAL = 2.0 ** -126
+
+
 def check_selection_vs_fp64(idx_row, n_sel, I64, band=SEL_BAND):
     """Set equality with the fp64 oracle except for elements whose fp64 score lies within `band`
-    (relative) of the n_sel-th largest fp64 score.  Returns the number of excused elements."""
+    (relative) of the n_sel-th largest fp64 score.  Returns the number of excused elements.
+
+    Scores below the smallest normal fp32 number cannot be ordered by an fp32 pipeline (Sec. 3.3's open
+    interval (0, H^I) does not survive there: the hardware flushes them to zero).  Only when the threshold
+    score itself is that small are elements up to 2^-126 away from it excused as well."""
     n = I64.shape[0]
     want = O.topk_select_row(I64, n_sel)
     got = np.asarray(idx_row[:n_sel], np.int64)
@@ -107,8 +118,10 @@ def check_selection_vs_fp64(idx_row, n_sel, I64, band=SEL_BAND):
     thr = np.sort(I64)[n - n_sel]          # n_sel-th largest
     diff = np.setxor1d(want, got)
     dev = np.abs(I64[diff] - thr)
-    # 1.2e-38: scores below the smallest normal fp32 number are flushed to zero on the GPU and cannot be ordered
-    assert np.all(dev <= band * abs(thr) + 1.2e-38), "selection differs outside the threshold band: max rel dev %.3g" % (dev.max() / abs(thr))
+    slack = band * abs(thr)
+    if abs(thr) < FP32_MIN_NORMAL:
+        slack += FP32_MIN_NORMAL
+    assert np.all(dev <= slack), "selection differs outside the threshold band: max rel dev %.3g" % (dev.max() / max(abs(thr), 1e-300))
     return int(diff.shape[0])
 
 

@@ -32,6 +32,11 @@ INDEXER_CASES = [
     ("f32", 8, 64, 1, 130, 130, 0, True),
     ("f32", 2, 128, 1, 200, 200, 0, False),
     ("f32", 1, 64, 1, 257, 257, 0, False),
+    # head counts that are not a power of two: the kernels pad them with zero-weight heads
+    ("bf16", 3, 64, 1, 300, 300, 0, True),
+    ("bf16", 6, 32, 2, 200, 260, 60, False),
+    ("f32", 5, 64, 1, 150, 150, 0, True),
+    ("bf16", 7, 128, 1, 140, 140, 0, True),
 ]
 
 
@@ -60,6 +65,58 @@ def test_indexer_scores_and_stats(dtype, HI, dI, B, Lq, Lk, off, bias):
     g3 = T.to64(s3)[:, :, :Lk]
     assert np.array_equal(np.nan_to_num(g3, nan=-1.0), np.nan_to_num(got[:, r0:r1], nan=-1.0))
     assert np.all(np.abs(T.to64(var3)[:, r0:r1] - rvar[:, r0:r1]) <= 2e-5 * rvar[:, r0:r1] + 5e-8)
+
+
+KEY_CASES = [
+    # dtype, HI, dI, B, Lq, Lk, q_offset, bias, k_cap
+    ("bf16", 4, 64, 2, 700, 700, 0, True, 96),
+    ("bf16", 3, 64, 1, 300, 1000, 700, False, 128),
+    ("f32", 5, 32, 1, 400, 400, 0, True, 64),
+    ("bf16", 8, 32, 1, 260, 260, 0, False, 200),
+    ("bf16", 1, 128, 1, 9000, 9000, 0, False, 512),     # rows long enough for the one-pass sampled selection
+]
+
+
+@pytest.mark.parametrize("dtype,HI,dI,B,Lq,Lk,off,bias,k_cap", KEY_CASES)
+def test_indexer_keys_and_selection_on_keys(dtype, HI, dI, B, Lq, Lk, off, bias, k_cap):
+    """The two stage calls in the form the fused forward uses: 16-bit fixed-point keys of the scores
+    (Sec. 3.3) and the top-k_t selection on them (Eq. 4), against the fp64 oracle."""
+    wl = wl_("keys", B, Lq, Lk, off, 4, 2, 64, HI, dI, dtype, seed=300 + HI + dI)
+    t = S.make_inputs(wl, "cpu", with_bias=bias)
+    d = T.to_device(t)
+    sh = G.shape_of(wl)
+    ld = (Lk + 31) // 32 * 32
+    keys = torch.full((B, Lq, ld), 0x7777, dtype=torch.int16, device="cuda")
+    mean = torch.empty((B, Lq), dtype=torch.float32, device="cuda")
+    var = torch.empty_like(mean)
+    ws = G.workspace(G.gsa_indexer_workspace_bytes(sh, 0, Lq), "cuda")
+    G.gsa_indexer_keys(sh, d["qI"], d["kI"], d["w"], d["bI"], 0, Lq, keys, ld, mean, var, ws)
+    _, mean2, var2 = T.gpu_indexer(wl, d, want_scores=False)
+    assert torch.equal(mean, mean2) and torch.equal(var, var2), "the statistics do not depend on the output mode"
+    r = np.random.default_rng(HI)
+    n_sel = torch.from_numpy(r.integers(1, k_cap + 1, (B, Lq)).astype(np.int32)).cuda()
+    idx = torch.full((B, Lq, k_cap), -7, dtype=torch.int32, device="cuda")
+    G.gsa_topk_select_keys(sh, 0, Lq, keys, ld, n_sel, k_cap, idx, d["qI"], d["kI"], d["w"], d["bI"])
+    torch.cuda.synchronize()
+    HIK = 1 << (HI - 1).bit_length()
+    kh = keys.cpu().numpy().view(np.uint16).astype(np.int64)
+    o = T.oracle_inputs(t)
+    idx_h, n_h = idx.cpu().numpy(), n_sel.cpu().numpy()
+    rows = [(int(b), int(i)) for b, i in zip(r.integers(0, B, 50), r.integers(0, Lq, 50))] + [(0, 0), (B - 1, Lq - 1)]
+    exact = total = excused = 0
+    for (b, i) in rows:
+        n = O.n_visible(i, off, Lk)
+        I = O.indexer_scores_row(o["qI"][b, i], o["kI"][b, :n], o["w"][b, i], o["bI"])
+        want = np.minimum(65535, np.floor(I * (65536.0 / HIK))).astype(np.int64)
+        assert np.abs(kh[b, i, :n] - want).max() <= 1, "a key is the floor of the scaled score up to fp32 rounding"
+        assert np.all(kh[b, i, n:Lk] == 0x7777), "positions of invisible keys are left untouched"
+        exact += int((kh[b, i, :n] == want).sum())
+        total += n
+        m = int(min(n_h[b, i], n))
+        T.check_index_row_wellformed(idx_h[b, i], m, n, k_cap)
+        excused += T.check_selection_vs_fp64(idx_h[b, i], m, I)
+    assert exact >= 0.9 * total
+    assert excused <= len(rows) // 4
 
 
 def test_indexer_closed_forms_on_gpu():
@@ -185,15 +242,14 @@ def test_sparse_gated_attention(dtype, H, Hkv, dh, B, Lq, Lk, off, k_cap):
 
 @pytest.mark.parametrize("window", [16, 50, 64])
 @pytest.mark.parametrize("dtype,H,Hkv,dh,B,Lq,Lk,off,k_cap", [c for c in ATTN_CASES if c[0] == "bf16"])
-def test_sparse_gated_attention_key_windows(monkeypatch, window, dtype, H, Hkv, dh, B, Lq, Lk, off, k_cap):
+def test_sparse_gated_attention_key_windows(window, dtype, H, Hkv, dh, B, Lq, Lk, off, k_cap):
     """The key-window launch scheme of long prefills (one launch per window of keys, partial results merged
     afterwards), forced onto small shapes so that the oracle covers every row: windows that a row does not
     reach, windows without a selected key, lists that end inside a window."""
-    monkeypatch.setenv("GSA_ATTN_WINDOW", str(window))
-    _attention_case(dtype, H, Hkv, dh, B, Lq, Lk, off, k_cap)
+    _attention_case(dtype, H, Hkv, dh, B, Lq, Lk, off, k_cap, G.make_tuning(attn_window=window))
 
 
-def _attention_case(dtype, H, Hkv, dh, B, Lq, Lk, off, k_cap):
+def _attention_case(dtype, H, Hkv, dh, B, Lq, Lk, off, k_cap, tuning=None):
     wl = wl_("att", B, Lq, Lk, off, H, Hkv, dh, 4, 32, dtype, seed=40 + H + Hkv, gate_std=1.5)
     t = S.make_inputs(wl, "cpu")
     r = np.random.default_rng(7)
@@ -216,16 +272,16 @@ def _attention_case(dtype, H, Hkv, dh, B, Lq, Lk, off, k_cap):
         return out
 
     full = ref(True, True)
-    T.check_out(T.gpu_attention(wl, d, di, dn, k_cap), full, dtype)
-    T.check_out(T.gpu_attention(wl, d, di, dn, k_cap, use_g1=False), ref(True, False), dtype)
-    T.check_out(T.gpu_attention(wl, d, di, dn, k_cap, use_g2=False, use_g1=False, scale=0.2), ref(False, False, 0.2), dtype)
+    T.check_out(T.gpu_attention(wl, d, di, dn, k_cap, tuning=tuning), full, dtype)
+    T.check_out(T.gpu_attention(wl, d, di, dn, k_cap, use_g1=False, tuning=tuning), ref(True, False), dtype)
+    T.check_out(T.gpu_attention(wl, d, di, dn, k_cap, use_g2=False, use_g1=False, scale=0.2, tuning=tuning), ref(False, False, 0.2), dtype)
     # G2 as a dense pre-pass followed by the ungated-V kernel is the same computation
     Vg = torch.empty_like(d["V"])
     G.gsa_value_gate(G.shape_of(wl), d["V"], d["g2"], Vg)
-    T.check_out(T.gpu_attention(wl, d, di, dn, k_cap, use_g2=False, V=Vg), full, dtype)
+    T.check_out(T.gpu_attention(wl, d, di, dn, k_cap, use_g2=False, V=Vg, tuning=tuning), full, dtype)
     # a row range leaves the other rows alone
     if Lq > 8:
-        part = T.gpu_attention(wl, d, di, dn, k_cap, row_begin=3, row_end=Lq - 2)
+        part = T.gpu_attention(wl, d, di, dn, k_cap, row_begin=3, row_end=Lq - 2, tuning=tuning)
         assert torch.isnan(part[:, :3]).all() and torch.isnan(part[:, Lq - 2:]).all()
         T.check_out(part[:, 3:Lq - 2], full[:, 3:Lq - 2], dtype)
 
@@ -335,18 +391,17 @@ def test_forward_bf16_mid_size(heavy):
 
 
 @pytest.mark.parametrize("Lq,Lk,off", [(1100, 1100, 0), (300, 1000, 700)], ids=["prefill", "chunk-after-context"])
-def test_forward_key_windows_match_single_launch(monkeypatch, Lq, Lk, off):
+def test_forward_key_windows_match_single_launch(Lq, Lk, off):
     """Attention by key windows (forced here; chosen automatically for long prefills) against the single-launch
     attention of the same forward, and against the oracle on sampled rows."""
     wl = wl_("win", 2, Lq, Lk, off, 16, 4, 128, 4, 64, "bf16", kmin=48, kmax=200, seed=78, gate_std=2.0)
     t = S.make_inputs(wl, "cpu")
     d = T.to_device(t)
     ctl, kw = _ctl_for(wl, _vbar_from_gpu(wl, d))
-    monkeypatch.setenv("GSA_ATTN_WINDOW", "0")
-    one = T.gpu_forward(wl, d, ctl)
+    one = T.gpu_forward(wl, d, ctl, tuning=G.make_tuning(attn_window=-1))
     for window in (96, 256, 1024):
-        monkeypatch.setenv("GSA_ATTN_WINDOW", str(window))
-        res = T.gpu_forward(wl, d, ctl)
+        tn = G.make_tuning(attn_window=window)
+        res = T.gpu_forward(wl, d, ctl, tuning=tn)
         assert torch.equal(res["idx"], one["idx"]) and torch.equal(res["n_sel"], one["n_sel"])
         assert (res["out"].float() - one["out"].float()).abs().max().item() <= 1e-2
         r = np.random.default_rng(window)
@@ -354,7 +409,7 @@ def test_forward_key_windows_match_single_launch(monkeypatch, Lq, Lk, off):
         rows += [(0, 0), (1, Lq - 1), (0, min(Lq - 1, max(0, window - 1 - off))), (1, min(Lq - 1, max(0, window - off)))]
         _check_forward(wl, t, res, kw, rows)
         # slabs whose first row lies beyond the first windows
-        res2 = T.gpu_forward(wl, d, ctl, slab_rows=128 if Lq < 512 else 384)
+        res2 = T.gpu_forward(wl, d, ctl, slab_rows=128 if Lq < 512 else 384, tuning=tn)
         same_k = (res2["k"] == res["k"])
         assert same_k.float().mean().item() > 0.995
         assert (res2["out"][same_k].float() - res["out"][same_k].float()).abs().max().item() <= 1e-2
@@ -433,17 +488,21 @@ def test_forward_matches_staged_calls():
 
 
 FORWARD_VARIANTS = [
-    # dtype, HI, dI, H, Hkv, dh, B, Lq, Lk, off, bias, slab_rows
-    ("f32", 2, 128, 8, 8, 64, 2, 700, 700, 0, False, 256),
-    ("bf16", 8, 32, 16, 2, 64, 1, 900, 900, 0, True, None),
-    ("bf16", 1, 128, 4, 1, 128, 3, 500, 500, 0, True, 128),
-    ("bf16", 4, 64, 16, 4, 128, 2, 300, 1000, 700, False, None),   # a chunk of queries against a longer cache
-    ("f32", 4, 32, 4, 2, 128, 1, 1, 600, 599, False, None),        # single-query decode in fp32
+    # dtype, HI, dI, H, Hkv, dh, B, Lq, Lk, off, bias, slab_rows, largest number of in-band substitutions over the 42 rows
+    ("f32", 2, 128, 8, 8, 64, 2, 700, 700, 0, False, 256, 40),
+    ("bf16", 8, 32, 16, 2, 64, 1, 900, 900, 0, True, None, 4),
+    ("bf16", 1, 128, 4, 1, 128, 3, 500, 500, 0, True, 128, 40),
+    ("bf16", 4, 64, 16, 4, 128, 2, 300, 1000, 700, False, None, 4),   # a chunk of queries against a longer cache
+    ("f32", 4, 32, 4, 2, 128, 1, 1, 600, 599, False, None, 4),        # single-query decode in fp32
+    ("bf16", 3, 64, 16, 4, 128, 1, 700, 700, 0, True, None, 4),       # head counts that need padding
+    ("bf16", 7, 32, 8, 2, 64, 2, 400, 400, 0, False, 128, 4),
+    ("f32", 5, 64, 4, 4, 64, 1, 300, 300, 0, True, None, 4),
+    ("bf16", 6, 64, 4, 1, 128, 1, 1, 800, 799, True, None, 4),
 ]
 
 
-@pytest.mark.parametrize("dtype,HI,dI,H,Hkv,dh,B,Lq,Lk,off,bias,slab", FORWARD_VARIANTS)
-def test_forward_shape_variants(dtype, HI, dI, H, Hkv, dh, B, Lq, Lk, off, bias, slab):
+@pytest.mark.parametrize("dtype,HI,dI,H,Hkv,dh,B,Lq,Lk,off,bias,slab,max_excused", FORWARD_VARIANTS)
+def test_forward_shape_variants(dtype, HI, dI, H, Hkv, dh, B, Lq, Lk, off, bias, slab, max_excused):
     wl = wl_("var", B, Lq, Lk, off, H, Hkv, dh, HI, dI, dtype, kmin=16, kmax=96, seed=100 + HI + dI + H)
     t = S.make_inputs(wl, "cpu", with_bias=bias)
     d = T.to_device(t)
@@ -451,10 +510,11 @@ def test_forward_shape_variants(dtype, HI, dI, H, Hkv, dh, B, Lq, Lk, off, bias,
     res = T.gpu_forward(wl, d, ctl, slab_rows=slab)
     r = np.random.default_rng(9)
     rows = [(int(b), int(i)) for b, i in zip(r.integers(0, B, 40), r.integers(0, Lq, 40))] + [(0, 0), (B - 1, Lq - 1)]
-    # (with a single indexer head and d^I = 128 most sigmoids saturate: many fp64 scores differ only beyond
-    # fp32 resolution, so the number of in-band substitutions is not bounded here, only their size is)
+    # (with one or two indexer heads and d^I = 128 most sigmoids saturate: many fp64 scores differ only beyond
+    # fp32 resolution, so those cases are allowed more in-band substitutions than the others)
     excused, kband, worst = _check_forward(wl, t, res, kw, rows)
-    assert kband <= 3
+    print("in-band substitutions: %d (bound %d), k_t band: %d" % (excused, max_excused, kband))
+    assert kband <= 3 and excused <= max_excused
 
 
 @pytest.mark.parametrize("L", [1, 2, 5, 33, 129])
@@ -476,9 +536,25 @@ def test_select_budget_up_to_8192():
     _select_case(sc, np.array([[8192, 8191, 5000, 4097]]), k_cap, Lk - Lq)
 
 
+def test_forward_head_weights_above_one():
+    """Head weights above 1 (outside what Sec. 3.3 produces, allowed by the interface): scores above the range
+    of the 16-bit keys saturate them, and the saturated elements are ordered by their recomputed fp32 scores."""
+    wl = wl_("bigw", 1, 2500, 2500, 0, 16, 4, 128, 4, 64, "bf16", kmin=32, kmax=300, seed=41)
+    t = S.make_inputs(wl, "cpu")
+    t["w"] = (t["w"] * 3.0).contiguous()
+    d = T.to_device(t)
+    ctl, kw = _ctl_for(wl, _vbar_from_gpu(wl, d))
+    res = T.gpu_forward(wl, d, ctl)
+    r = np.random.default_rng(3)
+    rows = [(0, int(i)) for i in r.integers(0, 2500, 40)] + [(0, 0), (0, 2499)]
+    excused, kband, worst = _check_forward(wl, t, res, kw, rows)
+    assert excused <= 6 and kband <= 3
+    assert len(np.unique(res["k"].cpu().numpy())) > 20
+
+
 def _random_case(r):
     dtype = ["bf16", "f32"][int(r.integers(0, 2))]
-    HI = int(r.choice([1, 2, 4, 8]))
+    HI = int(r.choice([1, 2, 3, 4, 5, 6, 7, 8]))
     dI = int(r.choice([32, 64, 128]))
     dh = int(r.choice([64, 128]))
     Hkv = int(r.choice([1, 2, 4, 8]))
@@ -502,22 +578,22 @@ def test_forward_random_shapes(case):
     t = S.make_inputs(wl, "cpu", with_bias=bias)
     d = T.to_device(t)
     ctl, kw = _ctl_for(wl, _vbar_from_gpu(wl, d) + 1e-6)
-    res = T.gpu_forward(wl, d, ctl, slab_rows=slab)
+    res = T.gpu_forward(wl, d, ctl, slab_rows=slab, tuning=None)
     rows = {(int(b), int(i)) for b, i in zip(r.integers(0, B, 12), r.integers(0, Lq, 12))} | {(0, 0), (B - 1, Lq - 1)}
     _check_forward(wl, t, res, kw, sorted(rows))
 
 
 @pytest.mark.parametrize("case", range(24))
-def test_forward_random_shapes_key_windows(monkeypatch, case):
+def test_forward_random_shapes_key_windows(case):
     """The same kind of random shapes (bf16 only) with the attention forced into key windows of a random size."""
     r = np.random.default_rng(5000 + case)
     _, HI, dI, H, Hkv, dh, B, Lq, Lk, off, bias, slab, kmin, kmax = _random_case(r)
     window = int(r.integers(8, 300))
-    monkeypatch.setenv("GSA_ATTN_WINDOW", str(window))
+    tn = G.make_tuning(attn_window=window)
     wl = wl_("rndw", B, Lq, Lk, off, H, Hkv, dh, HI, dI, "bf16", kmin=kmin, kmax=kmax, seed=6000 + case)
     t = S.make_inputs(wl, "cpu", with_bias=bias)
     d = T.to_device(t)
     ctl, kw = _ctl_for(wl, _vbar_from_gpu(wl, d) + 1e-6)
-    res = T.gpu_forward(wl, d, ctl, slab_rows=slab)
+    res = T.gpu_forward(wl, d, ctl, slab_rows=slab, tuning=tn)
     rows = {(int(b), int(i)) for b, i in zip(r.integers(0, B, 12), r.integers(0, Lq, 12))} | {(0, 0), (B - 1, Lq - 1)}
     _check_forward(wl, t, res, kw, sorted(rows))

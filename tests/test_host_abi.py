@@ -45,7 +45,7 @@ def test_status_strings():
 @pytest.mark.parametrize("kw,status", [
     (dict(B=0), G.GSA_ERR_SHAPE), (dict(Lq=0), G.GSA_ERR_SHAPE), (dict(H=3), G.GSA_ERR_SHAPE),
     (dict(q_offset=1), G.GSA_ERR_SHAPE), (dict(d_h=96), G.GSA_ERR_UNSUPPORTED), (dict(dI=48), G.GSA_ERR_UNSUPPORTED),
-    (dict(HI=3), G.GSA_ERR_UNSUPPORTED), (dict(dtype=7), G.GSA_ERR_UNSUPPORTED), (dict(H=32, H_kv=1), G.GSA_ERR_UNSUPPORTED),
+    (dict(HI=9), G.GSA_ERR_UNSUPPORTED), (dict(dtype=7), G.GSA_ERR_UNSUPPORTED), (dict(H=32, H_kv=1), G.GSA_ERR_UNSUPPORTED),
     (dict(Lk=(1 << 20) + 64, Lq=64), G.GSA_ERR_UNSUPPORTED),
 ])
 def test_bad_shapes_rejected(kw, status):
@@ -55,9 +55,9 @@ def test_bad_shapes_rejected(kw, status):
     assert rc == status
     ctl = G.make_adaptive(1.0, 8, 4, 16)
     assert lib.gsa_adaptive_k(ctypes.byref(sh), ctypes.byref(ctl), FAKE, None, FAKE, None) == status
-    assert lib.gsa_topk_select(ctypes.byref(sh), 0, 1, FAKE, 64, FAKE, 16, FAKE, None) == status
-    assert lib.gsa_sparse_gated_attn(ctypes.byref(sh), 0, 1, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, 16, 0.0, FAKE, None, 0, None) == status
-    assert lib.gsa_forward_workspace_bytes(ctypes.byref(sh), 16, 1, 0) == 0
+    assert lib.gsa_topk_select(ctypes.byref(sh), 0, 1, FAKE, 64, FAKE, 16, FAKE, None, None) == status
+    assert lib.gsa_sparse_gated_attn(ctypes.byref(sh), 0, 1, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, 16, 0.0, FAKE, None, 0, None, None) == status
+    assert lib.gsa_forward_workspace_bytes(ctypes.byref(sh), 16, 1, 0, None) == 0
 
 
 def test_null_and_range_errors():
@@ -69,7 +69,7 @@ def test_null_and_range_errors():
     # row range
     for (r0, r1) in [(-1, 4), (4, 4), (0, 65), (9, 3)]:
         assert lib.gsa_indexer_scores(ctypes.byref(sh), FAKE, FAKE, FAKE, None, r0, r1, None, 64, None, FAKE, FAKE, 1 << 20, None) == G.GSA_ERR_SHAPE
-        assert lib.gsa_topk_select(ctypes.byref(sh), r0, r1, FAKE, 64, FAKE, 16, FAKE, None) == G.GSA_ERR_SHAPE
+        assert lib.gsa_topk_select(ctypes.byref(sh), r0, r1, FAKE, 64, FAKE, 16, FAKE, None, None) == G.GSA_ERR_SHAPE
     # leading dimension too small / not a multiple of 4, misaligned pointers
     assert lib.gsa_indexer_scores(ctypes.byref(sh), FAKE, FAKE, FAKE, None, 0, 1, FAKE, 60, None, FAKE, FAKE, 1 << 20, None) == G.GSA_ERR_SHAPE
     assert lib.gsa_indexer_scores(ctypes.byref(sh), FAKE, FAKE, FAKE, None, 0, 1, FAKE, 66, None, FAKE, FAKE, 1 << 20, None) == G.GSA_ERR_SHAPE
@@ -81,11 +81,11 @@ def test_null_and_range_errors():
     assert lib.gsa_indexer_scores(ctypes.byref(sh), FAKE, FAKE, FAKE, None, 0, 64, None, 64, None, FAKE, FAKE, 8, None) == G.GSA_ERR_WORKSPACE
     assert lib.gsa_indexer_scores(ctypes.byref(sh), FAKE, FAKE, FAKE, None, 0, 64, None, 64, None, FAKE, FAKE + 16, need, None) == G.GSA_ERR_WORKSPACE
     # k_cap bounds
-    assert lib.gsa_topk_select(ctypes.byref(sh), 0, 1, FAKE, 64, FAKE, 0, FAKE, None) == G.GSA_ERR_SHAPE
-    assert lib.gsa_topk_select(ctypes.byref(sh), 0, 1, FAKE, 64, FAKE, 8193, FAKE, None) == G.GSA_ERR_SHAPE
-    assert lib.gsa_topk_select(ctypes.byref(sh), 0, 1, None, 64, FAKE, 16, FAKE, None) == G.GSA_ERR_NULL
-    assert lib.gsa_sparse_gated_attn(ctypes.byref(sh), 0, 1, FAKE, FAKE, None, None, None, FAKE, FAKE, 16, 0.0, FAKE, None, 0, None) == G.GSA_ERR_NULL
-    assert lib.gsa_sparse_gated_attn(ctypes.byref(sh), 0, 1, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, 16, -1.0, FAKE, None, 0, None) == G.GSA_ERR_SHAPE
+    assert lib.gsa_topk_select(ctypes.byref(sh), 0, 1, FAKE, 64, FAKE, 0, FAKE, None, None) == G.GSA_ERR_SHAPE
+    assert lib.gsa_topk_select(ctypes.byref(sh), 0, 1, FAKE, 64, FAKE, 8193, FAKE, None, None) == G.GSA_ERR_SHAPE
+    assert lib.gsa_topk_select(ctypes.byref(sh), 0, 1, None, 64, FAKE, 16, FAKE, None, None) == G.GSA_ERR_NULL
+    assert lib.gsa_sparse_gated_attn(ctypes.byref(sh), 0, 1, FAKE, FAKE, None, None, None, FAKE, FAKE, 16, 0.0, FAKE, None, 0, None, None) == G.GSA_ERR_NULL
+    assert lib.gsa_sparse_gated_attn(ctypes.byref(sh), 0, 1, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, 16, -1.0, FAKE, None, 0, None, None) == G.GSA_ERR_SHAPE
     assert lib.gsa_value_gate(ctypes.byref(sh), FAKE, None, FAKE, None) == G.GSA_ERR_NULL
 
 
@@ -109,9 +109,9 @@ def test_controller_argument_errors():
     # forward: k_max above k_cap, workspace too small
     ctl = G.make_adaptive(1.0, 8, 4, 16)
     args = [FAKE] * 9  # Q K V g1 g2 qI kI w bI
-    assert lib.gsa_forward(ctypes.byref(sh), ctypes.byref(ctl), *args, 0.0, FAKE, None, None, None, None, 8, FAKE, 1 << 30, None) == G.GSA_ERR_SHAPE
-    assert lib.gsa_forward(ctypes.byref(sh), ctypes.byref(ctl), *args, 0.0, FAKE, None, None, None, None, 16, FAKE, 1024, None) == G.GSA_ERR_WORKSPACE
-    assert lib.gsa_forward(ctypes.byref(sh), ctypes.byref(ctl), *args, 0.0, FAKE, None, None, None, None, 16, None, 1 << 30, None) == G.GSA_ERR_WORKSPACE
+    assert lib.gsa_forward(ctypes.byref(sh), ctypes.byref(ctl), *args, 0.0, FAKE, None, None, None, None, 8, FAKE, 1 << 30, None, None) == G.GSA_ERR_SHAPE
+    assert lib.gsa_forward(ctypes.byref(sh), ctypes.byref(ctl), *args, 0.0, FAKE, None, None, None, None, 16, FAKE, 1024, None, None) == G.GSA_ERR_WORKSPACE
+    assert lib.gsa_forward(ctypes.byref(sh), ctypes.byref(ctl), *args, 0.0, FAKE, None, None, None, None, 16, None, 1 << 30, None, None) == G.GSA_ERR_WORKSPACE
 
 
 def test_forward_workspace_grows_with_slab():
@@ -119,9 +119,30 @@ def test_forward_workspace_grows_with_slab():
     small = G.gsa_forward_workspace_bytes(sh, 2048, True, 0)
     big = G.gsa_forward_workspace_bytes(sh, 2048, True, 8192)
     assert 0 < small < big
-    # the score slab dominates: rows * Lk * 4 bytes
-    assert big >= 8192 * 8192 * 4 and small >= 128 * 8192 * 4
+    # the key slab dominates: rows * Lk * 2 bytes (fp32 scores on request: 4 bytes)
+    assert big >= 8192 * 8192 * 2 and small >= 128 * 8192 * 2
+    assert G.gsa_forward_workspace_bytes(sh, 2048, True, 8192, G.make_tuning(forward_fp32_scores=1)) >= 8192 * 8192 * 4
     assert G.gsa_forward_workspace_bytes(sh, 2048, False, 0) < small
+    # the 128K prefill runs in well under 8 GiB with 8192-row slabs
+    c4 = G.make_shape(1, 131072, 131072, 0, 16, 4, 128, 4, 64, "bf16")
+    assert G.gsa_forward_workspace_bytes(c4, 4096, True, 8192) < 4 * (1 << 30)
+
+
+def test_selection_rejects_contexts_beyond_the_on_chip_bitmaps():
+    """The selection kernels keep bitmaps of a row in LDS; a context they cannot hold is refused on the host."""
+    lib = G.load()
+    text = open(os.path.join(ROOT, "include", "gsa.h")).read()
+    max_lk = int(re.search(r"#define\s+GSA_SELECT_MAX_LK\s+(\d+)", text).group(1))
+    ok = _shape(Lk=max_lk, Lq=64, q_offset=0)
+    big = _shape(Lk=max_lk + 32, Lq=64, q_offset=0)
+    assert lib.gsa_topk_select(ctypes.byref(big), 0, 1, FAKE, max_lk + 32, FAKE, 16, FAKE, None, None) == G.GSA_ERR_UNSUPPORTED
+    assert lib.gsa_topk_select(ctypes.byref(ok), 0, 1, None, max_lk, FAKE, 16, FAKE, None, None) == G.GSA_ERR_NULL
+    assert G.gsa_forward_workspace_bytes(big, 16, True, 0) == 0 and G.gsa_forward_workspace_bytes(ok, 16, True, 0) > 0
+    ctl = G.make_adaptive(1.0, 8, 4, 16)
+    args = [FAKE] * 9
+    assert lib.gsa_forward(ctypes.byref(big), ctypes.byref(ctl), *args, 0.0, FAKE, None, None, None, None, 16, FAKE, 1 << 40, None, None) == G.GSA_ERR_UNSUPPORTED
+    # the indexer and the attention alone still take it
+    assert G.gsa_indexer_workspace_bytes(big, 0, 64) > 0
 
 
 def test_missing_library_is_loud(monkeypatch, tmp_path):
