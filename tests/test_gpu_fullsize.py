@@ -72,7 +72,9 @@ def _sampled_check(wl, rows):
     kI_cache = {}
     excused = kband = 0
     worst = 0.0
-    for (b, i) in sorted(rows):
+    for done, (b, i) in enumerate(sorted(rows)):
+        if done % 100 == 99:
+            print("  %s H_kv=%d: %d of %d sampled rows checked" % (wl.name, wl.H_kv, done + 1, len(rows)), flush=True)
         if b not in kI_cache:
             kI_cache.clear()
             kI_cache[b] = t["kI"][b].double().cpu().numpy()
