@@ -212,6 +212,23 @@ int32_t gsa_forward(const gsa_shape* shape, const gsa_adaptive* ctl, const void*
 size_t gsa_forward_workspace_bytes(const gsa_shape* shape, int32_t k_cap, int32_t has_g2, int32_t slab_rows,
                                    const gsa_tuning* tuning);
 
+/* ---- gsa_forward for callers that cannot allocate ---------------------------------------------------
+ * For code under HIP graph capture, tight serving loops and harnesses that forbid hipMalloc: the same
+ * computation as gsa_forward with the workspace taken from an array of GSA_STATIC_SCRATCH_BYTES bytes that
+ * is part of the library's device code (every GPU the library is loaded on holds its own copy until the
+ * process ends).  The call allocates and frees nothing, on the device or through any library.  Problems
+ * whose minimum workspace, gsa_forward_workspace_bytes(shape, k_cap, g2 != NULL, 0, tuning), exceeds the
+ * array are refused with GSA_ERR_WORKSPACE before anything is launched (gsa_last_error() names both
+ * sizes): decode steps and short prefills fit, a 128K-token prefill does not.  All calls on one GPU share
+ * that GPU's array: calls that overlap in time on one GPU (different streams or threads) race; calls on
+ * one stream are ordered and safe.  Nothing in the array has to be cleared between calls. */
+#define GSA_STATIC_SCRATCH_BYTES (64u << 20)
+int32_t gsa_forward_noalloc(const gsa_shape* shape, const gsa_adaptive* ctl, const void* Q, const void* K,
+                            const void* V, const void* g1_logits, const void* g2_logits, const void* qI,
+                            const void* kI, const float* w, const float* bI, float softmax_scale, void* out,
+                            int32_t* idx_out, int32_t* n_sel_out, int32_t* k_out, float* row_var_out,
+                            int32_t k_cap, const gsa_tuning* tuning, void* stream);
+
 /* ---- measurement helper (no part of the method) ---------------------------------------
  * Gathers whole rows of a table in the access shape of the sparse attention (16 lanes x 16 bytes per
  * 256-byte row, four rows per load instruction, sixteen loads in flight per wave): wave v of `waves`

@@ -23,7 +23,7 @@ GSA_ERR_NULL, GSA_ERR_SHAPE, GSA_ERR_UNSUPPORTED, GSA_ERR_VBAR, GSA_ERR_WORKSPAC
 ENTRY_POINTS = (
     "gsa_indexer_scores", "gsa_indexer_keys", "gsa_indexer_workspace_bytes", "gsa_adaptive_k", "gsa_topk_select",
     "gsa_topk_select_keys", "gsa_sparse_gated_attn", "gsa_attn_workspace_bytes", "gsa_value_gate", "gsa_forward",
-    "gsa_forward_workspace_bytes", "gsa_probe_gather", "gsa_status_string", "gsa_last_error", "gsa_version",
+    "gsa_forward_workspace_bytes", "gsa_forward_noalloc", "gsa_probe_gather", "gsa_status_string", "gsa_last_error", "gsa_version",
 )
 
 
@@ -83,6 +83,8 @@ def load():
     lib.gsa_value_gate.restype = i32
     lib.gsa_forward.argtypes = [shp, ctl, vp, vp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, i32, vp, sz, tun, vp]
     lib.gsa_forward.restype = i32
+    lib.gsa_forward_noalloc.argtypes = [shp, ctl, vp, vp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, i32, tun, vp]
+    lib.gsa_forward_noalloc.restype = i32
     lib.gsa_forward_workspace_bytes.argtypes = [shp, i32, i32, i32, tun]
     lib.gsa_forward_workspace_bytes.restype = sz
     lib.gsa_status_string.argtypes = [i32]
@@ -226,6 +228,21 @@ def gsa_forward(shape, ctl, Q, K, V, g1_logits, g2_logits, qI, kI, w, bI, softma
                             _ptr(out), _ptr(idx_out), _ptr(n_sel_out), _ptr(k_out), _ptr(row_var_out), k_cap,
                             _ptr(workspace), workspace_bytes, _tun(tuning), _stream(stream))
     _check(rc, "gsa_forward")
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def gsa_forward_noalloc(shape, ctl, Q, K, V, g1_logits, g2_logits, qI, kI, w, bI, softmax_scale, out, idx_out, n_sel_out,
+                        k_out, row_var_out, k_cap, tuning=None, stream=None):
+    rc = load().gsa_forward_noalloc(ctypes.byref(shape) if shape is not None else None,
+                                    ctypes.byref(ctl) if ctl is not None else None, _ptr(Q), _ptr(K), _ptr(V),
+                                    _ptr(g1_logits), _ptr(g2_logits), _ptr(qI), _ptr(kI), _ptr(w), _ptr(bI),
+                                    float(softmax_scale), _ptr(out), _ptr(idx_out), _ptr(n_sel_out), _ptr(k_out),
+                                    _ptr(row_var_out), k_cap, _tun(tuning), _stream(stream))
+    if rc == GSA_ERR_WORKSPACE:
+        raise GsaError(rc, "gsa_forward_noalloc: " + load().gsa_last_error().decode())
+    _check(rc, "gsa_forward_noalloc")
 
 
 def workspace(nbytes, device="cuda"):

@@ -2,6 +2,7 @@
 // Every error that can be decided from the arguments is returned before anything is launched.
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <string>
 
 #include "common.hpp"
@@ -256,6 +257,35 @@ static size_t forward_bytes_uniform(const gsa_shape& s, int k_cap, bool has_g2, 
     return plan_fixed(s, k_cap, has_g2).total + slab;
 }
 
+// ---- scratch of the allocation-free forward --------------------------------------------------------
+// One array per GPU, part of the library's code object: it exists from the moment the library is loaded on
+// a device until the process ends.  The array's name is only a host-side handle; its device address is
+// looked up once per device (with that device current) and kept.
+constexpr size_t kStaticScratchBytes = GSA_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static unsigned char* g_scratch_ptr[kMaxDevices];
+
+static int32_t static_scratch(unsigned char** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "gsa_forward_noalloc/hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) {
+        g_last_error = "gsa_forward_noalloc: device ordinal beyond the per-device scratch table";
+        return GSA_ERR_UNSUPPORTED;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e, "gsa_forward_noalloc/hipGetSymbolAddress");
+        g_scratch_ptr[dev] = static_cast<unsigned char*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return GSA_OK;
+}
+
 }  // namespace gsa
 
 using namespace gsa;
@@ -434,6 +464,31 @@ int32_t gsa_forward(const gsa_shape* shape, const gsa_adaptive* ctl, const void*
     return forward_launches(s, *ctl, Q, K, V, g1_logits, g2_logits, qI, kI, w, bI, softmax_scale, out, idx_out, n_sel_out,
                             k_out, row_var_out, k_cap, static_cast<unsigned char*>(workspace), workspace_bytes, tn,
                             static_cast<hipStream_t>(stream));
+}
+
+int32_t gsa_forward_noalloc(const gsa_shape* shape, const gsa_adaptive* ctl, const void* Q, const void* K, const void* V,
+                            const void* g1_logits, const void* g2_logits, const void* qI, const void* kI, const float* w,
+                            const float* bI, float softmax_scale, void* out, int32_t* idx_out, int32_t* n_sel_out,
+                            int32_t* k_out, float* row_var_out, int32_t k_cap, const gsa_tuning* tuning, void* stream) {
+    int32_t rc = check_forward_args(shape, ctl, Q, K, V, g1_logits, g2_logits, qI, kI, w, softmax_scale, out, k_cap);
+    if (rc != GSA_OK) return rc;
+    const gsa_shape& s = *shape;
+    const gsa_tuning& tn = tuning_or_default(tuning);
+    const size_t fixed = plan_fixed(s, k_cap, g2_logits != nullptr).total;
+    if (fixed > kStaticScratchBytes ||
+        !slabs_fit(s, k_cap, idx_out == nullptr, tn.forward_fp32_scores == 0, kStaticScratchBytes - fixed, tn)) {
+        g_last_error = "gsa_forward_noalloc: this problem needs " +
+                       std::to_string(forward_bytes_uniform(s, k_cap, g2_logits != nullptr, 1, tn)) +
+                       " bytes of scratch, the library's static scratch holds " + std::to_string(kStaticScratchBytes) +
+                       "; use gsa_forward with a workspace";
+        return GSA_ERR_WORKSPACE;
+    }
+    unsigned char* ws = nullptr;
+    rc = static_scratch(&ws);
+    if (rc != GSA_OK) return rc;
+    // nothing in the scratch has to start at zero: every kernel writes what it later reads
+    return forward_launches(s, *ctl, Q, K, V, g1_logits, g2_logits, qI, kI, w, bI, softmax_scale, out, idx_out, n_sel_out,
+                            k_out, row_var_out, k_cap, ws, kStaticScratchBytes, tn, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"
