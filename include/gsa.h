@@ -54,7 +54,8 @@ enum gsa_status {
 };
 
 /* Problem shape.  Supported: d_h in {64,128}; dI in {32,64,128}; 1 <= HI <= 8;
- * H % H_kv == 0 and H/H_kv <= 16; Lk <= 2^20 (the selection calls, gsa_topk_select and gsa_forward, keep
+ * H % H_kv == 0 and H/H_kv <= 16; Lk * H_kv * d_h * sizeof(element) <= 2^32 (the keys of one batch element
+ * span at most 4 GiB); Lk <= 2^20 (the selection calls, gsa_topk_select and gsa_forward, keep
  * bitmaps of a row on chip and take Lk <= GSA_SELECT_MAX_LK); q_offset + Lq <= Lk. */
 #define GSA_SELECT_MAX_LK 393216
 typedef struct gsa_shape {
@@ -86,6 +87,7 @@ typedef struct gsa_tuning {
     int32_t attn_kv_per_wg;      /* kv heads per attention workgroup: 0 = chosen by the library, else 1, 2 or 4 */
     int32_t select_exact_only;   /* 1 = gsa_topk_select never takes its sampled one-pass variant */
     int32_t forward_fp32_scores; /* 1 = gsa_forward keeps fp32 scores between indexer and selection, not 16-bit keys */
+    int32_t attn_rows_per_wave;  /* query rows one wave of the bf16 attention streams through: 0 = chosen by the library, else 1..64 */
 } gsa_tuning;
 
 /* ---- stage 1: gated lightning indexer, Sec. 3.3, Eq. "indexer" ----------------------

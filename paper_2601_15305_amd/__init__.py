@@ -36,7 +36,8 @@ class GsaAdaptive(ctypes.Structure):
 
 
 class GsaTuning(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("attn_window", "attn_kv_per_wg", "select_exact_only", "forward_fp32_scores")]
+    _fields_ = [(n, ctypes.c_int32) for n in ("attn_window", "attn_kv_per_wg", "select_exact_only", "forward_fp32_scores",
+                                                  "attn_rows_per_wave")]
 
 
 class GsaError(RuntimeError):
@@ -129,9 +130,9 @@ def make_adaptive(vbar, k_base, k_min, k_max, k_fixed=0, mode=0):
     return GsaAdaptive(float(vbar), k_base, k_min, k_max, k_fixed, mode)
 
 
-def make_tuning(attn_window=0, attn_kv_per_wg=0, select_exact_only=0, forward_fp32_scores=0):
+def make_tuning(attn_window=0, attn_kv_per_wg=0, select_exact_only=0, forward_fp32_scores=0, attn_rows_per_wave=0):
     """gsa_tuning: launch-shape switches (0 = the library decides).  Pass None for all defaults."""
-    return GsaTuning(attn_window, attn_kv_per_wg, select_exact_only, forward_fp32_scores)
+    return GsaTuning(attn_window, attn_kv_per_wg, select_exact_only, forward_fp32_scores, attn_rows_per_wave)
 
 
 def _tun(tuning):

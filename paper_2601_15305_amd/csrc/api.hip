@@ -50,6 +50,8 @@ static int32_t check_shape(const gsa_shape* s) {
     if (s->HI > 8) return GSA_ERR_UNSUPPORTED;
     if (s->H / s->H_kv > 16) return GSA_ERR_UNSUPPORTED;
     if (s->Lk > (1 << 20)) return GSA_ERR_UNSUPPORTED;
+    // the attention addresses a K / V row as a 64-bit base plus a 32-bit byte offset inside one batch element
+    if ((int64_t)s->Lk * s->H_kv * s->d_h * (s->dtype == GSA_BF16 ? 2 : 4) > (1LL << 32)) return GSA_ERR_UNSUPPORTED;
     if ((int64_t)s->B * s->Lq > 0x7fffffffLL) return GSA_ERR_UNSUPPORTED;
     return GSA_OK;
 }
@@ -72,7 +74,7 @@ static int32_t check_ctl(const gsa_adaptive* c) {
 // The selection kernels keep two bitmaps of a row in LDS: beyond this context length they do not fit.
 static int32_t check_select_len(const gsa_shape* s) { return s->Lk > GSA_SELECT_MAX_LK ? GSA_ERR_UNSUPPORTED : GSA_OK; }
 
-static const gsa_tuning kDefaultTuning = {0, 0, 0, 0};
+static const gsa_tuning kDefaultTuning = {0, 0, 0, 0, 0};
 static const gsa_tuning& tuning_or_default(const gsa_tuning* t) { return t ? *t : kDefaultTuning; }
 
 static bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }

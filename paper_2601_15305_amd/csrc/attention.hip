@@ -45,12 +45,33 @@ struct AttnArgs {
     int32_t window, win;    // keys per window, window of this launch
     int32_t q_offset;
     int32_t part_row0, part_rows;  // rows of the slab that `part` and `winoff` are laid out for
+    int32_t rpw;                   // query rows a wave of the bf16 kernel works through (1 .. 64)
 };
 
 constexpr float kNegBig = -1.0e30f;
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
+// max over lanes {l, l^16, l^32, l^48} without a trip through LDS (row swaps of gfx950)
+__device__ __forceinline__ float quad_row_max(float x) {
+    auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float quad_row_sum(float x) {
+    auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// A wave works through the pieces of `a.rpw` consecutive query rows (same batch element, same kv head) as ONE
+// stream of 32-token tiles: while a tile is being multiplied, the K/V' rows of the next tile and the indices of
+// the one after it are already on their way, also when those tiles belong to the next query row.  The list
+// bounds of all rows of the wave are fetched once, up front (lane i keeps those of row i).  A row therefore
+// costs no start-up chain of dependent loads (bounds -> indices -> rows), which is what a short piece -- a
+// row's share of one key window -- would otherwise spend most of its time on.
 template <int DH, bool HAS_G2>
 __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     constexpr int KK = DH / 32;        // MFMA k-steps of the score product
@@ -70,187 +91,222 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     unsigned char* vlds = smem + wv * (32 * (VROW + KROW));
     unsigned char* klds = vlds + 32 * VROW;
 
-    const int R = a.row_end - a.row_begin;
-    const int64_t rid = blockIdx.x;
-    const int b = (int)(rid / R);
-    const int t = a.row_begin + (int)(rid % R);
-    const int64_t qrow = (int64_t)b * a.Lq + t;
-    const int nsel = max(0, min(a.n_sel[qrow], a.k_cap));
-    const int32_t* idxrow = a.idx + ((int64_t)b * a.idx_rows + (t - a.idx_row0)) * a.k_cap;
-    const int G = a.H / a.H_kv;
-    const float sl2 = a.scale * kLog2e;
-    const int64_t tokstride = (int64_t)a.H_kv * ROWB;  // bytes between consecutive tokens
-    // the piece [jbeg, jend) of the list this workgroup handles.  Split lists (decode): piece z leaves a
-    // partial record that attn_merge_kernel combines.  Key windows: the launch of window z resumes the state
-    // the launch of window z-1 left (resume), and passes it on (carry) unless z is the last window the row sees.
-    const int64_t prow = (int64_t)b * a.part_rows + (t - a.part_row0);
-    int jbeg, jend, piece;
-    bool partial, resume = false;
-    if (a.winoff) {
-        piece = a.win;
-        jbeg = min(a.winoff[prow * (a.nsplit + 1) + piece], nsel);
-        jend = min(a.winoff[prow * (a.nsplit + 1) + piece + 1], nsel);
-        resume = piece > 0;
-        partial = piece < min(a.q_offset + t, a.Lk - 1) / a.window;
-    } else {
-        const int ntile_all = (nsel + 31) >> 5;
-        const int tps = (ntile_all + a.nsplit - 1) / a.nsplit;  // tiles per split
-        piece = blockIdx.z;
-        jbeg = min(piece * tps, ntile_all) * 32;
-        jend = min(min(piece * tps + tps, ntile_all) * 32, nsel);
-        partial = a.nsplit > 1;
-    }
-    // records per head in `part`: one per piece (split lists) or a single running one (key windows)
-    const int rec_per_head = a.winoff ? 1 : a.nsplit;
-    const int rec = a.winoff ? 0 : piece;
-
     // blockDim.x / 64 kv heads per workgroup; blockIdx.y selects which ones.  Blocks are dispatched
     // x-fastest, so all queries work on one slice of kv heads before the next slice starts: the K/V'
     // columns in use at any time then fit the on-die memory-side cache even when the whole K/V' does not.
-    for (int g = blockIdx.y * (blockDim.x >> 6) + wv; g < a.H_kv; g += a.H_kv) {
-        const int head = g * G + n;
-        const bool head_ok = n < G;
-        // ---- Q fragments (B operand): lane (head n, chunk q) holds features (4*kk+q)*8 .. +8 --------
-        bf16x8 qf[KK];
+    const int g = __builtin_amdgcn_readfirstlane(blockIdx.y * (blockDim.x >> 6) + wv);  // uniform over the wave
+    if (g >= a.H_kv) return;  // (the waves of a workgroup never synchronise with each other)
+    const int R = a.row_end - a.row_begin;
+    const int chunks = (R + a.rpw - 1) / a.rpw;
+    const int b = blockIdx.x / chunks;
+    const int t0 = a.row_begin + (blockIdx.x % chunks) * a.rpw;   // first row of this wave
+    const int nrows = min(a.rpw, a.row_end - t0);
+    const int G = a.H / a.H_kv;
+    const int head = g * G + n;
+    const bool head_ok = n < G;
+    const float sl2 = a.scale * kLog2e;
+    // Bytes between consecutive tokens.  The K, V' (and g2) rows of one batch element span less than 4 GiB
+    // (checked on the host), so a row is addressed as a wave-uniform 64-bit base plus a 32-bit lane offset.
+    const uint32_t tokstride = (uint32_t)a.H_kv * ROWB;
+    // records per head in `part`: one per piece (split lists) or a single running one (key windows)
+    const int rec_per_head = a.winoff ? 1 : a.nsplit;
+    const int rec = a.winoff ? 0 : (int)blockIdx.z;
+
+    // ---- the piece [jb, je) of every row's list that this wave handles; lane i holds row t0 + i -------------
+    // Split lists (decode): piece z leaves a partial record that attn_merge_kernel combines.  Key windows: the
+    // launch of window z adds what windows 0..z-1 left in the row's state record (resume) and passes the sum on
+    // (carry) unless z is the last window the row sees.
+    int m_jb = 0, m_je = 0, m_flags = 0;  // flags: bit 0 = resume, bit 1 = carry / partial
+    if (lane < nrows) {
+        const int t = t0 + lane;
+        const int nsel = max(0, min(a.n_sel[(int64_t)b * a.Lq + t], a.k_cap));
+        if (a.winoff) {
+            const int64_t prow = (int64_t)b * a.part_rows + (t - a.part_row0);
+            m_jb = min(a.winoff[prow * (a.nsplit + 1) + a.win], nsel);
+            m_je = min(a.winoff[prow * (a.nsplit + 1) + a.win + 1], nsel);
+            m_flags = (a.win > 0 ? 1 : 0) | (a.win < min(a.q_offset + t, a.Lk - 1) / a.window ? 2 : 0);
+        } else {
+            const int ntile_all = (nsel + 31) >> 5;
+            const int tps = (ntile_all + a.nsplit - 1) / a.nsplit;  // tiles per split
+            const int piece = blockIdx.z;
+            m_jb = min(piece * tps, ntile_all) * 32;
+            m_je = min(min(piece * tps + tps, ntile_all) * 32, nsel);
+            m_flags = a.nsplit > 1 ? 2 : 0;
+        }
+    }
+    // first row at or after ri that has a tile; j0/je are set to its bounds (ri == nrows: the stream has ended)
+    auto seek = [&](int ri, int& j0, int& je) {
+        while (ri < nrows) {
+            j0 = __builtin_amdgcn_readlane(m_jb, ri);
+            je = __builtin_amdgcn_readlane(m_je, ri);
+            if (j0 < je) break;
+            ++ri;
+        }
+        return ri;
+    };
+    auto advance = [&](int& ri, int& j0, int& je) {
+        j0 += 32;
+        if (j0 >= je) ri = seek(ri + 1, j0, je);
+    };
+
+    const unsigned char* Kb = static_cast<const unsigned char*>(a.K) + ((int64_t)b * a.Lk * a.H_kv + g) * ROWB;
+    const unsigned char* Vb = static_cast<const unsigned char*>(a.V) + ((int64_t)b * a.Lk * a.H_kv + g) * ROWB;
+    const unsigned char* Gb = HAS_G2 ? static_cast<const unsigned char*>(a.g2) + ((int64_t)b * a.Lk * a.H_kv + g) * ROWB : nullptr;
+    const int32_t* idx0 = a.idx + ((int64_t)b * a.idx_rows + (t0 - a.idx_row0)) * a.k_cap;  // index list of row t0
+
+    bf16x8 qf[KK], qf_next[KK];
+    f32x4 o[MB];
+    float mrun = kNegBig, lrun = 0.f;
+    u32x4 kr[NVL];
+    u32x4 vf[NVL];
+    u32x4 gf[HAS_G2 ? NVL : 1];
+
+    // this lane's token (lane & 31) of the tile at list position j0 of row ri; clamped, so always a valid load
+    auto load_idx = [&](int ri, int j0, int je) { return idx0[(int64_t)ri * a.k_cap + min(j0 + (lane & 31), je - 1)]; };
+    // Q fragments of row ri (B operand): lane (head n, chunk q) holds features (4*kk+q)*8 .. +8
+    auto load_q = [&](int ri) {
+        const u32x4* src = reinterpret_cast<const u32x4*>(static_cast<const __bf16*>(a.Q) +
+                                                          (((int64_t)b * a.Lq + t0 + ri) * a.H + (head_ok ? head : 0)) * DH);
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            u32x4 v = head_ok ? src[kk * 4 + q] : u32x4{0, 0, 0, 0};
+            qf_next[kk] = __builtin_bit_cast(bf16x8, v);
+        }
+    };
+    auto issue = [&](int tokv) {
+        const int tok = max(0, min(tokv, a.Lk - 1));
+#pragma unroll
+        for (int r = 0; r < NVL; ++r) {  // whole rows, 16 bytes per lane: K and V' of a token at the same offset
+            const int tk = __shfl(tok, r * TPI + lane / VCH, 64);
+            const uint32_t off = __umul24((uint32_t)tk, tokstride) + (uint32_t)(lane % VCH) * 16u;  // token < 2^24, stride < 2^24
+            kr[r] = *reinterpret_cast<const u32x4*>(Kb + off);
+            vf[r] = *reinterpret_cast<const u32x4*>(Vb + off);
+            if constexpr (HAS_G2) gf[r] = *reinterpret_cast<const u32x4*>(Gb + off);
+        }
+    };
+    // K and V' rows -> LDS (natural layout: row = token slot, 16 B per lane)
+    auto stage = [&]() {
+#pragma unroll
+        for (int r = 0; r < NVL; ++r)
+            *reinterpret_cast<u32x4*>(klds + (r * TPI + lane / VCH) * KROW + (lane % VCH) * 16) = kr[r];
+#pragma unroll
+        for (int r = 0; r < NVL; ++r) {
+            u32x4 v = vf[r];
+            if constexpr (HAS_G2) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float v0 = bf16_bits_to_f32(v[e] & 0xffffu) * sigmoid_f32(bf16_bits_to_f32(gf[r][e] & 0xffffu));
+                    const float v1 = bf16_bits_to_f32(v[e] >> 16) * sigmoid_f32(bf16_bits_to_f32(gf[r][e] >> 16));
+                    v[e] = pack_bf16x2(v0, v1);
+                }
+            }
+            *reinterpret_cast<u32x4*>(vlds + (r * TPI + lane / VCH) * VROW + (lane % VCH) * 16) = v;
+        }
+    };
+    // the arithmetic of the tile that sits in LDS: list positions j0 .. j0+31 of a row whose piece ends at je
+    auto compute = [&](int j0, int je) {
+        // ---- S^T = K . Q^T for two 16-token sub-tiles; the A operand (token n, features (4*kk+q)*8 .. +8)
+        // is read back from the K tile --------------------------------------------------------------
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave's LDS writes have landed
+        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
         {
-            const u32x4* src = reinterpret_cast<const u32x4*>(static_cast<const __bf16*>(a.Q) + (qrow * a.H + (head_ok ? head : 0)) * DH);
+            const unsigned char* k0 = klds + n * KROW + q * 16;
+            const unsigned char* k1 = k0 + 16 * KROW;
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk) {
-                u32x4 v = head_ok ? src[kk * 4 + q] : u32x4{0, 0, 0, 0};
-                qf[kk] = __builtin_bit_cast(bf16x8, v);
+                const u32x4 a0 = *reinterpret_cast<const u32x4*>(k0 + kk * 64);
+                const u32x4 a1 = *reinterpret_cast<const u32x4*>(k1 + kk * 64);
+                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a0), qf[kk], s0, 0, 0, 0);
+                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a1), qf[kk], s1, 0, 0, 0);
             }
         }
-        f32x4 o[MB];
-        float mrun = kNegBig, lrun = 0.f;
-        float* const state = a.part + (((prow * a.H) + (head_ok ? head : 0)) * rec_per_head + rec) * (DH + 4);
-        if (resume && head_ok) {  // continue the online softmax where the previous key window stopped
+        // lane (head n, q): s0[i] is token j0 + 4q + i, s1[i] is token j0 + 16 + 4q + i
+        float x[8];
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb) o[mb] = *reinterpret_cast<const f32x4*>(state + mb * 16 + 4 * q);
-            mrun = state[DH];
-            lrun = q == 0 ? state[DH + 1] : 0.f;  // the sum is kept per lane and added up over q at the end
-        } else {
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) o[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < 4; ++i) {
+            x[i] = s0[i] * sl2;
+            x[4 + i] = s1[i] * sl2;
         }
-
-        const unsigned char* Kb = static_cast<const unsigned char*>(a.K) + ((int64_t)b * a.Lk * a.H_kv + g) * ROWB;
-        const unsigned char* Vb = static_cast<const unsigned char*>(a.V) + ((int64_t)b * a.Lk * a.H_kv + g) * ROWB;
-        const unsigned char* Gb = HAS_G2 ? static_cast<const unsigned char*>(a.g2) + ((int64_t)b * a.Lk * a.H_kv + g) * ROWB : nullptr;
-
-        u32x4 kr[NVL];
-        u32x4 vf[NVL];
-        u32x4 gf[HAS_G2 ? NVL : 1];
-        // indices of the tile after the one whose rows are being requested: fetched one tile early so that
-        // the row loads never wait on a dependent index load
-        int tok_pref = (jbeg < jend) ? idxrow[min(jbeg + (lane & 31), jend - 1)] : 0;
-        auto load_tile = [&](int j0) {
-            int tok = max(0, min(tok_pref, a.Lk - 1));
-            tok_pref = idxrow[min(j0 + 32 + (lane & 31), jend - 1)];
-#pragma unroll
-            for (int r = 0; r < NVL; ++r) {  // whole rows, 16 bytes per lane: K and V' of a token at the same offset
-                const int tk = __shfl(tok, r * TPI + lane / VCH, 64);
-                const int64_t off = (int64_t)tk * tokstride + (lane % VCH) * 16;
-                kr[r] = *reinterpret_cast<const u32x4*>(Kb + off);
-                vf[r] = *reinterpret_cast<const u32x4*>(Vb + off);
-                if constexpr (HAS_G2) gf[r] = *reinterpret_cast<const u32x4*>(Gb + off);
-            }
-        };
-
-        if (jbeg < jend) load_tile(jbeg);
-        for (int j0 = jbeg; j0 < jend; j0 += 32) {
-            // ---- K and V' rows -> LDS (natural layout: row = token slot, 16 B per lane) ------------
-#pragma unroll
-            for (int r = 0; r < NVL; ++r)
-                *reinterpret_cast<u32x4*>(klds + (r * TPI + lane / VCH) * KROW + (lane % VCH) * 16) = kr[r];
-#pragma unroll
-            for (int r = 0; r < NVL; ++r) {
-                u32x4 v = vf[r];
-                if constexpr (HAS_G2) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float v0 = bf16_bits_to_f32(v[e] & 0xffffu) * sigmoid_f32(bf16_bits_to_f32(gf[r][e] & 0xffffu));
-                        const float v1 = bf16_bits_to_f32(v[e] >> 16) * sigmoid_f32(bf16_bits_to_f32(gf[r][e] >> 16));
-                        v[e] = pack_bf16x2(v0, v1);
-                    }
-                }
-                *reinterpret_cast<u32x4*>(vlds + (r * TPI + lane / VCH) * VROW + (lane % VCH) * 16) = v;
-            }
-            if (j0 + 32 < jend) load_tile(j0 + 32);  // the row registers are free again
-
-            // ---- S^T = K . Q^T for two 16-token sub-tiles; the A operand (token n, features (4*kk+q)*8 .. +8)
-            // is read back from the K tile --------------------------------------------------------------
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave's LDS writes have landed
-            f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-            {
-                const unsigned char* k0 = klds + n * KROW + q * 16;
-                const unsigned char* k1 = k0 + 16 * KROW;
-#pragma unroll
-                for (int kk = 0; kk < KK; ++kk) {
-                    const u32x4 a0 = *reinterpret_cast<const u32x4*>(k0 + kk * 64);
-                    const u32x4 a1 = *reinterpret_cast<const u32x4*>(k1 + kk * 64);
-                    s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a0), qf[kk], s0, 0, 0, 0);
-                    s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a1), qf[kk], s1, 0, 0, 0);
-                }
-            }
-            // lane (head n, q): s0[i] is token j0 + 4q + i, s1[i] is token j0 + 16 + 4q + i
-            float x[8];
-            float tmax = kNegBig;
+        if (j0 + 32 > je) {  // last tile of a piece: slots beyond the list do not count
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                x[i] = (j0 + 4 * q + i < jend) ? s0[i] * sl2 : kNegBig;
-                x[4 + i] = (j0 + 16 + 4 * q + i < jend) ? s1[i] * sl2 : kNegBig;
-                tmax = fmaxf(tmax, fmaxf(x[i], x[4 + i]));
+                if (j0 + 4 * q + i >= je) x[i] = kNegBig;
+                if (j0 + 16 + 4 * q + i >= je) x[4 + i] = kNegBig;
             }
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-            const float mnew = fmaxf(mrun, tmax);
-            const float alpha = fast_exp2(mrun - mnew);
-            float psum = 0.f;
-            float p[8];
+        }
+        float tmax = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+        tmax = quad_row_max(tmax);
+        const float mnew = fmaxf(mrun, tmax);
+        const float alpha = fast_exp2(mrun - mnew);
+        float psum = 0.f;
+        float p[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                p[i] = fast_exp2(x[i] - mnew);
-                psum += p[i];
-            }
-            lrun = lrun * alpha + psum;
-            mrun = mnew;
+        for (int i = 0; i < 8; ++i) {
+            p[i] = fast_exp2(x[i] - mnew);
+            psum += p[i];
+        }
+        lrun = lrun * alpha + psum;
+        mrun = mnew;
+        if (__any(alpha != 1.0f)) {  // the running maximum of some head rose: rescale (rare after a row's first tiles)
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) o[mb] *= alpha;
-            u32x4 pw = {pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]), pack_bf16x2(p[4], p[5]), pack_bf16x2(p[6], p[7])};
-            const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
-
-            // ---- O^T += V'^T . P^T --------------------------------------------------------------------
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave's LDS writes have landed
-            {
-                const int r4 = (lane & 15) >> 2, c4 = lane & 3;
-                const unsigned char* p0 = vlds + (4 * q + r4) * VROW + c4 * 8;
-                const unsigned char* p1 = p0 + 16 * VROW;
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    s16x4 a0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p0 + mb * 32));
-                    s16x4 a1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p1 + mb * 32));
-                    typedef __attribute__((ext_vector_type(8))) short s16x8;
-                    s16x8 av = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
-                    o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av), pf, o[mb], 0, 0, 0);
-                }
-            }
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // transpose reads done before the tile is overwritten
         }
+        u32x4 pw = {pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]), pack_bf16x2(p[4], p[5]), pack_bf16x2(p[6], p[7])};
+        const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
 
-        // ---- normalise, G1, store ---------------------------------------------------------------------
-        float ltot = lrun + __shfl_xor(lrun, 16, 64);
-        ltot += __shfl_xor(ltot, 32, 64);
-        if (partial) {  // state of this piece: merged by attn_merge_kernel, or resumed by the next key window
+        // ---- O^T += V'^T . P^T --------------------------------------------------------------------
+        {
+            const int r4 = (lane & 15) >> 2, c4 = lane & 3;
+            const unsigned char* p0 = vlds + (4 * q + r4) * VROW + c4 * 8;
+            const unsigned char* p1 = p0 + 16 * VROW;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                s16x4 a0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p0 + mb * 32));
+                s16x4 a1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p1 + mb * 32));
+                typedef __attribute__((ext_vector_type(8))) short s16x8;
+                s16x8 av = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+                o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av), pf, o[mb], 0, 0, 0);
+            }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // transpose reads done before the tile is overwritten
+    };
+    auto reset_acc = [&]() {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) o[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        mrun = kNegBig;
+        lrun = 0.f;
+    };
+    // A row's piece is complete (accumulators o, mrun, lrun): add what earlier key windows left, then either
+    // pass the state on / leave the partial record, or normalise, apply G1 and store the output row.
+    auto finish_row = [&](int ri) {
+        const int flags = __builtin_amdgcn_readlane(m_flags, ri);
+        const int t = t0 + ri;
+        const int64_t qrow = (int64_t)b * a.Lq + t;
+        const int64_t prow = (int64_t)b * a.part_rows + (t - a.part_row0);
+        float ltot = quad_row_sum(lrun);
+        float* const state = a.part + (((prow * a.H) + (head_ok ? head : 0)) * rec_per_head + rec) * (DH + 4);
+        if ((flags & 1) && head_ok) {  // merge with the state of the previous key windows
+            f32x4 po[MB];
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) po[mb] = *reinterpret_cast<const f32x4*>(state + mb * 16 + 4 * q);
+            const float pm = state[DH], pl = state[DH + 1];
+            const float M = fmaxf(mrun, pm);
+            const float wa = fast_exp2(mrun - M), wb = fast_exp2(pm - M);
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) o[mb] = o[mb] * wa + po[mb] * wb;
+            ltot = ltot * wa + pl * wb;
+            mrun = M;
+        }
+        if (flags & 2) {
             if (head_ok) {
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb)
-                    *reinterpret_cast<f32x4*>(state + mb * 16 + 4 * q) = o[mb];
+                for (int mb = 0; mb < MB; ++mb) *reinterpret_cast<f32x4*>(state + mb * 16 + 4 * q) = o[mb];
                 if (q == 0) {
                     state[DH] = mrun;
                     state[DH + 1] = ltot;
                 }
             }
-            continue;
+            return;
         }
         if (head_ok) {
             const float inv = ltot > 0.f ? 1.0f / ltot : 0.f;
@@ -278,6 +334,56 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
                 *reinterpret_cast<u32x2*>(static_cast<__bf16*>(a.out) + obase + d0) = ow;
             }
         }
+    };
+
+    // ---- the tile stream: c = tile being worked on, nx = tile whose rows are requested next, p = tile whose
+    // indices are requested next ------------------------------------------------------------------------------
+    int c_ri, c_j0 = 0, c_je = 0;
+    c_ri = seek(0, c_j0, c_je);
+    int n_ri = c_ri, n_j0 = c_j0, n_je = c_je;
+    int p_ri = nrows, p_j0 = 0, p_je = 0;
+    int tok_pref = 0;
+    if (c_ri < nrows) {
+        issue(load_idx(c_ri, c_j0, c_je));  // the one start-up chain of the wave: indices, then rows
+        load_q(c_ri);
+        advance(n_ri, n_j0, n_je);
+        p_ri = n_ri, p_j0 = n_j0, p_je = n_je;
+        if (n_ri < nrows) {
+            tok_pref = load_idx(n_ri, n_j0, n_je);
+            advance(p_ri, p_j0, p_je);
+        }
+    }
+    int rows_done = 0;  // rows [0, rows_done) have been finished
+    int cur_row = -1;   // row whose accumulators are live
+    while (c_ri < nrows) {
+        if (c_ri != cur_row) {  // first tile of a row
+            for (; rows_done < c_ri; ++rows_done) {  // rows without a tile in this piece: only their state moves on
+                reset_acc();
+                finish_row(rows_done);
+            }
+            reset_acc();
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) qf[kk] = qf_next[kk];  // (before the next row's heads may be requested)
+            cur_row = c_ri;
+        }
+        stage();
+        if (n_ri < nrows) {  // the row registers are free again
+            issue(tok_pref);
+            if (n_ri != c_ri) load_q(n_ri);  // first tile of another row: its query heads come along
+            if (p_ri < nrows) tok_pref = load_idx(p_ri, p_j0, p_je);
+        }
+        compute(c_j0, c_je);
+        if (c_j0 + 32 >= c_je) {
+            finish_row(c_ri);
+            rows_done = c_ri + 1;
+        }
+        c_ri = n_ri, c_j0 = n_j0, c_je = n_je;
+        n_ri = p_ri, n_j0 = p_j0, n_je = p_je;
+        if (p_ri < nrows) advance(p_ri, p_j0, p_je);
+    }
+    for (; rows_done < nrows; ++rows_done) {
+        reset_acc();
+        finish_row(rows_done);
     }
 }
 
@@ -517,6 +623,13 @@ static int attn_splits(const gsa_shape& sh, int64_t rows, int k_cap, const gsa_t
     return (int)(ns < 1 ? 1 : ns);
 }
 
+// Query rows a wave of the bf16 kernel streams through: as many as still leave about four thousand workgroups.
+static int attn_rows_per_wave(int64_t lrows, int slices, const gsa_tuning& tn) {
+    if (tn.attn_rows_per_wave > 0) return tn.attn_rows_per_wave < 64 ? tn.attn_rows_per_wave : 64;
+    const int64_t r = lrows * slices / 4096;
+    return (int)(r < 1 ? 1 : (r > 8 ? 8 : r));
+}
+
 // Key-window mode (bf16, many rows, long context): keys per window, 0 = off.  The K/V' rows of one window
 // and kv-head slice (window * kv heads per workgroup * d_h * 4 bytes) then stay largely resident in the
 // 4 MB L2 of every XCD while all rows gather from them, instead of every gather going out to the
@@ -587,6 +700,7 @@ hipError_t launch_attention(const gsa_shape& sh, int row_begin, int row_end, con
     a.q_offset = sh.q_offset;
     a.part_row0 = row_begin;
     a.part_rows = row_end - row_begin;
+    a.rpw = 1;
     if (a.window) {
         a.nsplit = (int)cdiv(sh.Lk, a.window);
         const size_t offs = ((size_t)rows * (a.nsplit + 1) * sizeof(int32_t) + 255) & ~(size_t)255;
@@ -610,8 +724,9 @@ hipError_t launch_attention(const gsa_shape& sh, int row_begin, int row_end, con
                 a.row_begin = row_begin > z * a.window - sh.q_offset ? row_begin : z * a.window - sh.q_offset;
                 if (a.row_begin >= row_end) break;
             }
-            const int64_t lrows = (int64_t)sh.B * (row_end - a.row_begin);
-            const dim3 grid((unsigned)lrows, (unsigned)(sh.H_kv / gpb), (unsigned)(a.window ? 1 : a.nsplit));
+            const int lrows = row_end - a.row_begin;  // per batch element
+            a.rpw = attn_rows_per_wave((int64_t)sh.B * lrows, sh.H_kv / gpb, tn);
+            const dim3 grid((unsigned)(sh.B * cdiv(lrows, a.rpw)), (unsigned)(sh.H_kv / gpb), (unsigned)(a.window ? 1 : a.nsplit));
             void (*kern)(AttnArgs) = sh.d_h == 128 ? (g2 ? attn_bf16_kernel<128, true> : attn_bf16_kernel<128, false>)
                                                    : (g2 ? attn_bf16_kernel<64, true> : attn_bf16_kernel<64, false>);
             if (z == 0 && smem > 48 * 1024) {

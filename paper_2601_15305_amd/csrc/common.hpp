@@ -24,17 +24,16 @@ __device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcp
 // sigmoid(z) = 1 / (1 + 2^(-z log2 e)).  Saturates cleanly: 2^x -> inf gives 0, 2^x -> 0 gives 1.
 __device__ __forceinline__ float sigmoid_f32(float z) { return fast_rcp(1.0f + fast_exp2(-kLog2e * z)); }
 
-// bf16 <-> fp32 on raw bits.  Round to nearest even; NaN kept quiet.
+// bf16 <-> fp32.  fp32 -> bf16 rounds to nearest even with the conversion instruction of gfx950 (one
+// instruction per pair of values).
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t hi16) { return __uint_as_float(hi16 << 16); }
-__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return u >> 16;
-}
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+    typedef __attribute__((ext_vector_type(2))) float f32x2_;
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_;
+    const f32x2_ v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_));
 }
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) { return pack_bf16x2(f, 0.f) & 0xffffu; }
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
 

@@ -240,13 +240,21 @@ def test_sparse_gated_attention(dtype, H, Hkv, dh, B, Lq, Lk, off, k_cap):
     _attention_case(dtype, H, Hkv, dh, B, Lq, Lk, off, k_cap)
 
 
+@pytest.mark.parametrize("rpw", [2, 7, 64])
+@pytest.mark.parametrize("dtype,H,Hkv,dh,B,Lq,Lk,off,k_cap", [c for c in ATTN_CASES if c[0] == "bf16"])
+def test_sparse_gated_attention_rows_per_wave(rpw, dtype, H, Hkv, dh, B, Lq, Lk, off, k_cap):
+    """Several query rows streamed through one wave (what long prefills do), forced onto small shapes: rows whose
+    list is empty, rows that end inside a tile, a last wave with fewer rows than the others."""
+    _attention_case(dtype, H, Hkv, dh, B, Lq, Lk, off, k_cap, G.make_tuning(attn_rows_per_wave=rpw))
+
+
 @pytest.mark.parametrize("window", [16, 50, 64])
 @pytest.mark.parametrize("dtype,H,Hkv,dh,B,Lq,Lk,off,k_cap", [c for c in ATTN_CASES if c[0] == "bf16"])
 def test_sparse_gated_attention_key_windows(window, dtype, H, Hkv, dh, B, Lq, Lk, off, k_cap):
     """The key-window launch scheme of long prefills (one launch per window of keys, partial results merged
     afterwards), forced onto small shapes so that the oracle covers every row: windows that a row does not
     reach, windows without a selected key, lists that end inside a window."""
-    _attention_case(dtype, H, Hkv, dh, B, Lq, Lk, off, k_cap, G.make_tuning(attn_window=window))
+    _attention_case(dtype, H, Hkv, dh, B, Lq, Lk, off, k_cap, G.make_tuning(attn_window=window, attn_rows_per_wave=1 + window % 5))
 
 
 def _attention_case(dtype, H, Hkv, dh, B, Lq, Lk, off, k_cap, tuning=None):
@@ -401,7 +409,7 @@ def test_forward_key_windows_match_single_launch(Lq, Lk, off):
     ctl, kw = _ctl_for(wl, _vbar_from_gpu(wl, d))
     one = T.gpu_forward(wl, d, ctl, tuning=G.make_tuning(attn_window=-1))
     for window in (96, 256, 1024):
-        tn = G.make_tuning(attn_window=window)
+        tn = G.make_tuning(attn_window=window, attn_rows_per_wave=window // 90)
         res = T.gpu_forward(wl, d, ctl, tuning=tn)
         assert torch.equal(res["idx"], one["idx"]) and torch.equal(res["n_sel"], one["n_sel"])
         assert (res["out"].float() - one["out"].float()).abs().max().item() <= 1e-2
@@ -590,7 +598,7 @@ def test_forward_random_shapes_key_windows(case):
     r = np.random.default_rng(5000 + case)
     _, HI, dI, H, Hkv, dh, B, Lq, Lk, off, bias, slab, kmin, kmax = _random_case(r)
     window = int(r.integers(8, 300))
-    tn = G.make_tuning(attn_window=window)
+    tn = G.make_tuning(attn_window=window, attn_rows_per_wave=int(r.integers(1, 10)))
     wl = wl_("rndw", B, Lq, Lk, off, H, Hkv, dh, HI, dI, "bf16", kmin=kmin, kmax=kmax, seed=6000 + case)
     t = S.make_inputs(wl, "cpu", with_bias=bias)
     d = T.to_device(t)
