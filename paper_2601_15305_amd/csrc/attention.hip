@@ -161,8 +161,16 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     u32x4 vf[NVL];
     u32x4 gf[HAS_G2 ? NVL : 1];
 
-    // this lane's token (lane & 31) of the tile at list position j0 of row ri; clamped, so always a valid load
-    auto load_idx = [&](int ri, int j0, int je) { return idx0[(int64_t)ri * a.k_cap + min(j0 + (lane & 31), je - 1)]; };
+    // The tokens of a tile are dealt to the lanes the way the row loads want them: load instruction r of a tile
+    // fetches, in lane group lane / VCH, the row of tile slot (lane / VCH) * NVL + r.  A lane therefore reads the
+    // NVL consecutive list entries of its group itself (clamped to the end of the piece, so always valid loads):
+    // no cross-lane exchange sits between the index loads and the row loads.
+    const int slot0 = (lane / VCH) * NVL;
+    auto load_idx = [&](int ri, int j0, int je, int (&tk)[NVL]) {
+        const int32_t* row = idx0 + (int64_t)ri * a.k_cap;
+#pragma unroll
+        for (int r = 0; r < NVL; ++r) tk[r] = row[min(j0 + slot0 + r, je - 1)];
+    };
     // Q fragments of row ri (B operand): lane (head n, chunk q) holds features (4*kk+q)*8 .. +8
     auto load_q = [&](int ri) {
         const u32x4* src = reinterpret_cast<const u32x4*>(static_cast<const __bf16*>(a.Q) +
@@ -173,11 +181,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
             qf_next[kk] = __builtin_bit_cast(bf16x8, v);
         }
     };
-    auto issue = [&](int tokv) {
-        const int tok = max(0, min(tokv, a.Lk - 1));
+    auto issue = [&](const int (&tokv)[NVL]) {
 #pragma unroll
         for (int r = 0; r < NVL; ++r) {  // whole rows, 16 bytes per lane: K and V' of a token at the same offset
-            const int tk = __shfl(tok, r * TPI + lane / VCH, 64);
+            const int tk = max(0, min(tokv[r], a.Lk - 1));
             const uint32_t off = __umul24((uint32_t)tk, tokstride) + (uint32_t)(lane % VCH) * 16u;  // token < 2^24, stride < 2^24
             kr[r] = *reinterpret_cast<const u32x4*>(Kb + off);
             vf[r] = *reinterpret_cast<const u32x4*>(Vb + off);
@@ -188,7 +195,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     auto stage = [&]() {
 #pragma unroll
         for (int r = 0; r < NVL; ++r)
-            *reinterpret_cast<u32x4*>(klds + (r * TPI + lane / VCH) * KROW + (lane % VCH) * 16) = kr[r];
+            *reinterpret_cast<u32x4*>(klds + (slot0 + r) * KROW + (lane % VCH) * 16) = kr[r];
 #pragma unroll
         for (int r = 0; r < NVL; ++r) {
             u32x4 v = vf[r];
@@ -200,7 +207,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
                     v[e] = pack_bf16x2(v0, v1);
                 }
             }
-            *reinterpret_cast<u32x4*>(vlds + (r * TPI + lane / VCH) * VROW + (lane % VCH) * 16) = v;
+            *reinterpret_cast<u32x4*>(vlds + (slot0 + r) * VROW + (lane % VCH) * 16) = v;
         }
     };
     // the arithmetic of the tile that sits in LDS: list positions j0 .. j0+31 of a row whose piece ends at je
@@ -342,14 +349,17 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     c_ri = seek(0, c_j0, c_je);
     int n_ri = c_ri, n_j0 = c_j0, n_je = c_je;
     int p_ri = nrows, p_j0 = 0, p_je = 0;
-    int tok_pref = 0;
+    int tok_pref[NVL];
+#pragma unroll
+    for (int r = 0; r < NVL; ++r) tok_pref[r] = 0;
     if (c_ri < nrows) {
-        issue(load_idx(c_ri, c_j0, c_je));  // the one start-up chain of the wave: indices, then rows
+        load_idx(c_ri, c_j0, c_je, tok_pref);
+        issue(tok_pref);  // the one start-up chain of the wave: indices, then rows
         load_q(c_ri);
         advance(n_ri, n_j0, n_je);
         p_ri = n_ri, p_j0 = n_j0, p_je = n_je;
         if (n_ri < nrows) {
-            tok_pref = load_idx(n_ri, n_j0, n_je);
+            load_idx(n_ri, n_j0, n_je, tok_pref);
             advance(p_ri, p_j0, p_je);
         }
     }
@@ -370,7 +380,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
         if (n_ri < nrows) {  // the row registers are free again
             issue(tok_pref);
             if (n_ri != c_ri) load_q(n_ri);  // first tile of another row: its query heads come along
-            if (p_ri < nrows) tok_pref = load_idx(p_ri, p_j0, p_je);
+            if (p_ri < nrows) load_idx(p_ri, p_j0, p_je, tok_pref);
         }
         compute(c_j0, c_je);
         if (c_j0 + 32 >= c_je) {
