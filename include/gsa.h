@@ -214,6 +214,18 @@ int32_t gsa_forward(const gsa_shape* shape, const gsa_adaptive* ctl, const void*
 size_t gsa_forward_workspace_bytes(const gsa_shape* shape, int32_t k_cap, int32_t has_g2, int32_t slab_rows,
                                    const gsa_tuning* tuning);
 
+/* ---- comparison variants: dense causal attention, Sec. 2.1 Eq. 2 ------------------------------------
+ * Every visible key, no indexer and no selection: with g2 and g1 given this is the "gated only" variant of
+ * Sec. 7.1 (Eq. 2 with V' = V * sigmoid(g2) and the result multiplied by sigmoid(g1)), with both NULL the
+ * "standard" attention the paper's ratios are quoted against, and in either case what the sparse path
+ * equals when the budget covers every visible key.  bf16 only (GSA_ERR_UNSUPPORTED otherwise).
+ * Rows [row_begin,row_end).  workspace: gsa_dense_attn_workspace_bytes(shape, g2 != NULL) bytes (the gated
+ * values; 0 when g2 == NULL). */
+int32_t gsa_dense_gated_attn(const gsa_shape* shape, int32_t row_begin, int32_t row_end, const void* Q,
+                             const void* K, const void* V, const void* g2_logits, const void* g1_logits,
+                             float softmax_scale, void* out, void* workspace, size_t workspace_bytes, void* stream);
+size_t gsa_dense_attn_workspace_bytes(const gsa_shape* shape, int32_t has_g2);
+
 /* ---- gsa_forward for callers that cannot allocate ---------------------------------------------------
  * For code under HIP graph capture, tight serving loops and harnesses that forbid hipMalloc: the same
  * computation as gsa_forward with the workspace taken from an array of GSA_STATIC_SCRATCH_BYTES bytes that

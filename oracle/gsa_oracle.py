@@ -51,8 +51,11 @@ def n_visible(i, q_offset, Lk):
 
 
 # --------------------------------------------------------------------------- Sec. 3.3
-def indexer_scores_row(qI_t, kI_vis, w_t, bI=None):
+def indexer_scores_row(qI_t, kI_vis, w_t, bI=None, act="sigmoid"):
     """Eq. "indexer" (Sec. 3.3) for one query: I_{t,s} = sum_j w_{t,j} sigma(q^I_{t,j}.k^I_s + b^I_j).
+
+    act="relu" is the comparison variant of Sec. 2.2 Eq. 3 (the ungated lightning indexer):
+    I_{t,s} = sum_j w_{t,j} ReLU(q^I_{t,j}.k^I_s); a bias, if given, is added before the activation there too.
 
     qI_t [HI, dI], kI_vis [n, dI] (the visible keys only), w_t [HI] -> I [n].
     """
@@ -65,7 +68,12 @@ def indexer_scores_row(qI_t, kI_vis, w_t, bI=None):
         z = kI_vis @ qI_t[j]
         if bI is not None:
             z = z + float(bI[j])
-        I += w_t[j] * sigmoid(z)
+        if act == "sigmoid":
+            I += w_t[j] * sigmoid(z)
+        elif act == "relu":
+            I += w_t[j] * np.maximum(z, 0.0)
+        else:
+            raise ValueError("unknown indexer activation: %r" % (act,))
     return I
 
 
@@ -78,7 +86,7 @@ def row_stats(I_vis):
     return mean, var
 
 
-def indexer_scores(qI, kI, w, bI=None, q_offset=0):
+def indexer_scores(qI, kI, w, bI=None, q_offset=0, act="sigmoid"):
     """All rows of Sec. 3.3.  Returns scores [B, Lq, Lk] (NaN where the key is not
     visible), row_mean [B, Lq], row_var [B, Lq]."""
     B, Lq, HI, dI = qI.shape
@@ -89,7 +97,7 @@ def indexer_scores(qI, kI, w, bI=None, q_offset=0):
     for b in range(B):
         for i in range(Lq):
             n = n_visible(i, q_offset, Lk)
-            I = indexer_scores_row(qI[b, i], kI[b, :n], w[b, i], bI)
+            I = indexer_scores_row(qI[b, i], kI[b, :n], w[b, i], bI, act)
             scores[b, i, :n] = I
             mean[b, i], var[b, i] = row_stats(I)
     return scores, mean, var
@@ -169,12 +177,12 @@ def sparse_gated_attn_row(Q_t, K, V, g2, g1_t, idx, scale=None):
 
 
 # --------------------------------------------------------------------------- whole path
-def gsa_forward_row(b, i, Q, K, V, g1, g2, qI, kI, w, bI, q_offset, ctl, scale=None):
+def gsa_forward_row(b, i, Q, K, V, g1, g2, qI, kI, w, bI, q_offset, ctl, scale=None, act="sigmoid"):
     """The four stages for one query row (b, i).  ctl: dict(vbar, k_base, k_min, k_max,
     k_fixed, mode).  Returns dict with I, mean, var, k, n_sel, idx, out."""
     Lk = kI.shape[1]
     n = n_visible(i, q_offset, Lk)
-    I = indexer_scores_row(qI[b, i], kI[b, :n], w[b, i], bI)
+    I = indexer_scores_row(qI[b, i], kI[b, :n], w[b, i], bI, act)
     mean, var = row_stats(I)
     k = int(adaptive_k(np.array(var), ctl["vbar"], ctl["k_base"], ctl["k_min"], ctl["k_max"],
                        ctl.get("k_fixed", 0), ctl.get("mode", 0)))

@@ -14,8 +14,8 @@ def _sig(z):
     return e / (1.0 + e)
 
 
-def indexer_scores(qI, kI, w, bI, q_offset, B, Lq, Lk, HI, dI):
-    """Sec. 3.3: I[b][t][s] for visible s (list of length n per row)."""
+def indexer_scores(qI, kI, w, bI, q_offset, B, Lq, Lk, HI, dI, relu=False):
+    """Sec. 3.3: I[b][t][s] for visible s (list of length n per row); relu=True: Sec. 2.2 Eq. 3 instead."""
     out = []
     for b in range(B):
         rows = []
@@ -30,7 +30,7 @@ def indexer_scores(qI, kI, w, bI, q_offset, B, Lq, Lk, HI, dI):
                         z += float(qI[b][t][j][c]) * float(kI[b][s][c])
                     if bI is not None:
                         z += float(bI[j])
-                    acc += float(w[b][t][j]) * _sig(z)
+                    acc += float(w[b][t][j]) * ((z if z > 0.0 else 0.0) if relu else _sig(z))
                 row.append(acc)
             rows.append(row)
         out.append(rows)

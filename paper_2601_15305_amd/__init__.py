@@ -23,7 +23,8 @@ GSA_ERR_NULL, GSA_ERR_SHAPE, GSA_ERR_UNSUPPORTED, GSA_ERR_VBAR, GSA_ERR_WORKSPAC
 ENTRY_POINTS = (
     "gsa_indexer_scores", "gsa_indexer_keys", "gsa_indexer_workspace_bytes", "gsa_adaptive_k", "gsa_topk_select",
     "gsa_topk_select_keys", "gsa_sparse_gated_attn", "gsa_attn_workspace_bytes", "gsa_value_gate", "gsa_forward",
-    "gsa_forward_workspace_bytes", "gsa_forward_noalloc", "gsa_probe_gather", "gsa_status_string", "gsa_last_error", "gsa_version",
+    "gsa_forward_workspace_bytes", "gsa_forward_noalloc", "gsa_dense_gated_attn", "gsa_dense_attn_workspace_bytes",
+    "gsa_probe_gather", "gsa_status_string", "gsa_last_error", "gsa_version",
 )
 
 
@@ -86,6 +87,10 @@ def load():
     lib.gsa_forward.restype = i32
     lib.gsa_forward_noalloc.argtypes = [shp, ctl, vp, vp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, i32, tun, vp]
     lib.gsa_forward_noalloc.restype = i32
+    lib.gsa_dense_gated_attn.argtypes = [shp, i32, i32, vp, vp, vp, vp, vp, f32, vp, vp, sz, vp]
+    lib.gsa_dense_gated_attn.restype = i32
+    lib.gsa_dense_attn_workspace_bytes.argtypes = [shp, i32]
+    lib.gsa_dense_attn_workspace_bytes.restype = sz
     lib.gsa_forward_workspace_bytes.argtypes = [shp, i32, i32, i32, tun]
     lib.gsa_forward_workspace_bytes.restype = sz
     lib.gsa_status_string.argtypes = [i32]
@@ -244,6 +249,20 @@ def gsa_forward_noalloc(shape, ctl, Q, K, V, g1_logits, g2_logits, qI, kI, w, bI
     if rc == GSA_ERR_WORKSPACE:
         raise GsaError(rc, "gsa_forward_noalloc: " + load().gsa_last_error().decode())
     _check(rc, "gsa_forward_noalloc")
+
+
+def gsa_dense_attn_workspace_bytes(shape, has_g2):
+    return load().gsa_dense_attn_workspace_bytes(ctypes.byref(shape), int(bool(has_g2)))
+
+
+def gsa_dense_gated_attn(shape, row_begin, row_end, Q, K, V, g2_logits, g1_logits, softmax_scale, out, workspace=None,
+                         workspace_bytes=None, stream=None):
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load().gsa_dense_gated_attn(ctypes.byref(shape), row_begin, row_end, _ptr(Q), _ptr(K), _ptr(V), _ptr(g2_logits),
+                                     _ptr(g1_logits), float(softmax_scale), _ptr(out), _ptr(workspace), workspace_bytes,
+                                     _stream(stream))
+    _check(rc, "gsa_dense_gated_attn")
 
 
 def workspace(nbytes, device="cuda"):

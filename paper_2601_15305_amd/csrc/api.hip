@@ -28,6 +28,8 @@ hipError_t launch_attention(const gsa_shape& sh, int row_begin, int row_end, con
                             const int32_t* n_sel, int k_cap, float scale, void* out, void* workspace, const gsa_tuning& tn,
                             hipStream_t st);
 size_t attn_workspace_bytes(const gsa_shape& sh, int row_begin, int row_end, int k_cap, const gsa_tuning& tn);
+hipError_t launch_dense_attention(const gsa_shape& sh, int row_begin, int row_end, const void* Q, const void* K, const void* Vg,
+                                  const void* g1, float scale, void* out, hipStream_t st);
 hipError_t launch_probe_gather(const void* table, const int32_t* idx, int64_t n_idx, int waves, uint32_t* sink, hipStream_t st);
 
 static thread_local std::string g_last_error;
@@ -422,6 +424,38 @@ int32_t gsa_sparse_gated_attn(const gsa_shape* shape, int32_t row_begin, int32_t
     hipError_t e = launch_attention(*shape, row_begin, row_end, Q, K, V, g2_logits, g1_logits, idx, shape->Lq, 0, n_sel,
                                     k_cap, scale, out, workspace, tn, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_sparse_gated_attn");
+}
+
+size_t gsa_dense_attn_workspace_bytes(const gsa_shape* shape, int32_t has_g2) {
+    if (check_shape(shape) != GSA_OK || !has_g2) return 0;
+    return up256((size_t)shape->B * shape->Lk * shape->H_kv * shape->d_h * elt_bytes(*shape));
+}
+
+int32_t gsa_dense_gated_attn(const gsa_shape* shape, int32_t row_begin, int32_t row_end, const void* Q, const void* K,
+                             const void* V, const void* g2_logits, const void* g1_logits, float softmax_scale, void* out,
+                             void* workspace, size_t workspace_bytes, void* stream) {
+    int32_t rc = check_shape(shape);
+    if (rc != GSA_OK) return rc;
+    if (shape->dtype != GSA_BF16) return GSA_ERR_UNSUPPORTED;
+    if (!Q || !K || !V || !out) return GSA_ERR_NULL;
+    rc = check_rows(shape, row_begin, row_end);
+    if (rc != GSA_OK) return rc;
+    if (!(softmax_scale >= 0.0f) || !std::isfinite(softmax_scale)) return GSA_ERR_SHAPE;
+    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(out, 16) || (g1_logits && !aligned(g1_logits, 16)) ||
+        (g2_logits && !aligned(g2_logits, 16)))
+        return GSA_ERR_SHAPE;
+    const size_t need = gsa_dense_attn_workspace_bytes(shape, g2_logits != nullptr);
+    if (need > 0 && (!workspace || !aligned(workspace, 256) || workspace_bytes < need)) return GSA_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const void* Vuse = V;
+    if (g2_logits) {
+        hipError_t e = launch_value_gate(*shape, V, g2_logits, workspace, st);
+        if (e != hipSuccess) return hip_fail(e, "gsa_dense_gated_attn/value_gate");
+        Vuse = workspace;
+    }
+    const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt((float)shape->d_h);
+    hipError_t e = launch_dense_attention(*shape, row_begin, row_end, Q, K, Vuse, g1_logits, scale, out, st);
+    return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_dense_gated_attn");
 }
 
 int32_t gsa_value_gate(const gsa_shape* shape, const void* V, const void* g2_logits, void* Vg, void* stream) {

@@ -294,6 +294,71 @@ def _attention_case(dtype, H, Hkv, dh, B, Lq, Lk, off, k_cap, tuning=None):
         T.check_out(part[:, 3:Lq - 2], full[:, 3:Lq - 2], dtype)
 
 
+DENSE_CASES = [
+    # H, Hkv, dh, B, Lq, Lk, off
+    (16, 4, 128, 2, 300, 300, 0),
+    (16, 16, 128, 1, 200, 200, 0),      # one head per kv head
+    (16, 1, 128, 1, 130, 130, 0),       # sixteen heads share one kv head
+    (12, 4, 64, 1, 150, 150, 0),        # a group of three heads (padded to four columns)
+    (8, 2, 64, 2, 100, 500, 400),       # a chunk of queries after a context
+    (16, 4, 128, 3, 1, 700, 699),       # decode shape
+]
+
+
+@pytest.mark.parametrize("H,Hkv,dh,B,Lq,Lk,off", DENSE_CASES)
+def test_dense_causal_gated_attention(H, Hkv, dh, B, Lq, Lk, off):
+    """The comparison variants (Sec. 2.1 Eq. 2; Sec. 7.1 "gated only" and "standard"): every visible key."""
+    wl = wl_("dense", B, Lq, Lk, off, H, Hkv, dh, 4, 32, "bf16", seed=60 + H + Hkv, gate_std=1.5)
+    t = S.make_inputs(wl, "cpu")
+    d = T.to_device(t)
+    o = T.oracle_inputs(t)
+    sh = G.shape_of(wl)
+
+    def gpu(use_g2, use_g1, scale=0.0, rows=(0, Lq)):
+        out = torch.full_like(d["Q"], float("nan"))
+        ws = G.workspace(G.gsa_dense_attn_workspace_bytes(sh, use_g2))
+        ws.fill_(0xFF)
+        G.gsa_dense_gated_attn(sh, rows[0], rows[1], d["Q"], d["K"], d["V"], d["g2"] if use_g2 else None,
+                               d["g1"] if use_g1 else None, scale, out, ws)
+        torch.cuda.synchronize()
+        return out
+
+    def ref(use_g2, use_g1, scale=None):
+        out = np.zeros((B, Lq, H, dh))
+        for b in range(B):
+            for i in range(Lq):
+                n = O.n_visible(i, off, Lk)
+                out[b, i], _ = O.sparse_gated_attn_row(o["Q"][b, i], o["K"][b], o["V"][b], o["g2"][b] if use_g2 else None,
+                                                       o["g1"][b, i] if use_g1 else None, np.arange(n), scale)
+        return out
+
+    full = ref(True, True)
+    T.check_out(gpu(True, True), full, "bf16")
+    T.check_out(gpu(False, False, 0.15), ref(False, False, 0.15), "bf16")
+    T.check_out(gpu(True, False), ref(True, False), "bf16")
+    if Lq > 8:
+        part = gpu(True, True, rows=(3, Lq - 2))
+        assert torch.isnan(part[:, :3]).all() and torch.isnan(part[:, Lq - 2:]).all()
+        T.check_out(part[:, 3:Lq - 2], full[:, 3:Lq - 2], "bf16")
+    if Lq * Lk <= 45000:     # the brute-force statement of Eq. 2 itself, where it is affordable
+        brute = O.dense_causal_gated_attn(o["Q"], o["K"], o["V"], o["g1"], o["g2"], off)
+        T.check_out(gpu(True, True), brute, "bf16")
+
+
+def test_sparse_path_with_full_budget_equals_dense_kernel():
+    """k_t >= number of visible keys: the sparse forward and the dense kernel compute the same thing."""
+    wl = wl_("full", 2, 400, 400, 0, 16, 4, 128, 4, 64, "bf16", kmin=400, kmax=400, kbase=400, seed=8)
+    t = S.make_inputs(wl, "cpu")
+    d = T.to_device(t)
+    res = T.gpu_forward(wl, d, G.make_adaptive(1.0, 1, 1, 1, k_fixed=400), k_cap=400)
+    sh = G.shape_of(wl)
+    out = torch.empty_like(d["Q"])
+    ws = G.workspace(G.gsa_dense_attn_workspace_bytes(sh, True))
+    G.gsa_dense_gated_attn(sh, 0, 400, d["Q"], d["K"], d["V"], d["g2"], d["g1"], 0.0, out, ws)
+    torch.cuda.synchronize()
+    assert (out.float() - res["out"].float()).abs().max().item() <= 1e-2
+
+
 def test_attention_gate_limits_on_gpu():
     """Saturated gate logits: +40 makes both sigmoids 1 in fp32 (plain SDPA on the set), -40 kills the output."""
     wl = wl_("attlim", 1, 64, 64, 0, 8, 2, 128, 4, 32, "bf16", seed=9)

@@ -96,6 +96,48 @@ def test_indexer_index_roles_not_transposed():
             assert abs(S[0, t, s] - want) < 1e-14
 
 
+# ---------------------------------------------------------------- Sec. 2.2 Eq. 3: the ungated (ReLU) indexer
+def test_relu_indexer_alternating_keys_closed_form():
+    """Eq. 3 with H^I = 1, q = e_1, k_s = +-c e_1 alternating: scores alternate w c and 0; mean = w c / 2 and
+    Var = (w c)^2 / 4 over an even count.  A sigmoid in place of the ReLU, or a dropped weight, fails."""
+    c, L, dI, wt = 1.7, 8, 4, 0.6
+    qI = np.zeros((1, L, 1, dI)); qI[..., 0] = 1.0
+    kI = np.zeros((1, L, dI)); kI[0, :, 0] = c * np.where(np.arange(L) % 2 == 0, 1.0, -1.0)
+    kI[0, :, 1:] = 5.0        # orthogonal to q: must not matter
+    w = np.full((1, L, 1), wt)
+    S, mean, var = O.indexer_scores(qI, kI, w, None, 0, act="relu")
+    assert np.allclose(S[0, L - 1, 0::2], wt * c, rtol=1e-15) and np.all(S[0, L - 1, 1::2] == 0.0)
+    for i in (1, 3, 5, 7):
+        assert abs(mean[0, i] - wt * c / 2) < 1e-15 and abs(var[0, i] - (wt * c) ** 2 / 4) < 1e-15
+
+
+def test_relu_indexer_properties_and_naive_loops():
+    """Eq. 3: non-negative for non-negative weights, positively homogeneous in the keys (the sigmoid form is not),
+    linear in the weights, equal to sum_j w_j max(q_j.k, 0) computed entry by entry, and to the pure-Python loops."""
+    t = _tiny(11, B=2, Lq=6, Lk=9, q_offset=3)
+    S, _, _ = O.indexer_scores(t["qI"], t["kI"], t["w"], None, 3, act="relu")
+    vis = ~np.isnan(S)
+    assert np.all(S[vis] >= 0.0) and (S[vis] == 0.0).sum() > 0 and (S[vis] > 0.0).sum() > 0
+    S3, _, _ = O.indexer_scores(t["qI"], 3.0 * t["kI"], t["w"], None, 3, act="relu")
+    assert np.allclose(S3[vis], 3.0 * S[vis], rtol=1e-14)
+    Sg, _, _ = O.indexer_scores(t["qI"], 3.0 * t["kI"], t["w"], None, 3)
+    Sg1, _, _ = O.indexer_scores(t["qI"], t["kI"], t["w"], None, 3)
+    assert not np.allclose(Sg[vis], 3.0 * Sg1[vis], rtol=1e-3)
+    S2w, _, _ = O.indexer_scores(t["qI"], t["kI"], 2.0 * t["w"], None, 3, act="relu")
+    assert np.allclose(S2w[vis], 2.0 * S[vis], rtol=1e-14)
+    for (b, i, s) in [(0, 0, 0), (1, 5, 8), (0, 3, 2)]:
+        want = sum(t["w"][b, i, j] * max(float(t["qI"][b, i, j] @ t["kI"][b, s]), 0.0) for j in range(3))
+        assert abs(S[b, i, s] - want) < 1e-14
+    Sb, _, _ = O.indexer_scores(t["qI"], t["kI"], t["w"], t["bI"], 3, act="relu")
+    Sn = N.indexer_scores(t["qI"], t["kI"], t["w"], t["bI"], 3, 2, 6, 9, 3, 5, relu=True)
+    for b in range(2):
+        for i in range(6):
+            n = O.n_visible(i, 3, 9)
+            assert np.allclose(Sb[b, i, :n], Sn[b][i], rtol=1e-13, atol=1e-15)
+    with pytest.raises(ValueError):
+        O.indexer_scores_row(t["qI"][0, 0], t["kI"][0], t["w"][0, 0], None, act="tanh")
+
+
 def test_indexer_matches_naive_loops():
     t = _tiny(7, B=2, Lq=5, Lk=9, q_offset=4)
     S, mean, var = O.indexer_scores(t["qI"], t["kI"], t["w"], t["bI"], 4)
