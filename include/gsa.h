@@ -43,6 +43,13 @@ extern "C" {
 
 enum gsa_dtype { GSA_F32 = 0, GSA_BF16 = 1 };
 
+/* Activation of the indexer.  GSA_ACT_SIGMOID is the gated lightning indexer of Sec. 3.3 (the method).
+ * GSA_ACT_RELU is the comparison variant of Sec. 2.2 Eq. 3, I[t,s] = sum_j w[t,j] * ReLU(qI[t,j,:] . kI[s,:] (+ bI[j])):
+ * with k_fixed and no gates it gives the "sparse only" baseline of Sec. 7.1.  Its scores are unbounded, so the
+ * fused forward keeps fp32 scores for it (no 16-bit keys); w must be >= 0 (the selection ranks negative
+ * scores as zero). */
+enum gsa_indexer_act { GSA_ACT_SIGMOID = 0, GSA_ACT_RELU = 1 };
+
 enum gsa_status {
     GSA_OK = 0,
     GSA_ERR_NULL = -1,        /* a required pointer is NULL */
@@ -62,7 +69,8 @@ typedef struct gsa_shape {
     int32_t B, Lq, Lk, q_offset;
     int32_t H, H_kv, d_h;
     int32_t HI, dI;
-    int32_t dtype; /* gsa_dtype */
+    int32_t dtype;       /* gsa_dtype */
+    int32_t indexer_act; /* gsa_indexer_act */
 } gsa_shape;
 
 /* Adaptive sparsity controller, Sec. 3.4, Eq. "adaptive_k":

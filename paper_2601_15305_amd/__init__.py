@@ -17,6 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgsa.so")
 
 GSA_F32, GSA_BF16 = 0, 1
+GSA_ACT_SIGMOID, GSA_ACT_RELU = 0, 1
 GSA_OK = 0
 GSA_ERR_NULL, GSA_ERR_SHAPE, GSA_ERR_UNSUPPORTED, GSA_ERR_VBAR, GSA_ERR_WORKSPACE, GSA_ERR_HIP = -1, -2, -3, -4, -5, -6
 
@@ -29,7 +30,7 @@ ENTRY_POINTS = (
 
 
 class GsaShape(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("B", "Lq", "Lk", "q_offset", "H", "H_kv", "d_h", "HI", "dI", "dtype")]
+    _fields_ = [(n, ctypes.c_int32) for n in ("B", "Lq", "Lk", "q_offset", "H", "H_kv", "d_h", "HI", "dI", "dtype", "indexer_act")]
 
 
 class GsaAdaptive(ctypes.Structure):
@@ -121,14 +122,15 @@ def _stream(stream):
     return None
 
 
-def make_shape(B, Lq, Lk, q_offset, H, H_kv, d_h, HI, dI, dtype):
+def make_shape(B, Lq, Lk, q_offset, H, H_kv, d_h, HI, dI, dtype, indexer_act="sigmoid"):
     code = {"f32": GSA_F32, "bf16": GSA_BF16, torch.float32: GSA_F32, torch.bfloat16: GSA_BF16}.get(dtype, dtype)
-    return GsaShape(B, Lq, Lk, q_offset, H, H_kv, d_h, HI, dI, code)
+    act = {"sigmoid": GSA_ACT_SIGMOID, "relu": GSA_ACT_RELU}.get(indexer_act, indexer_act)
+    return GsaShape(B, Lq, Lk, q_offset, H, H_kv, d_h, HI, dI, code, act)
 
 
 def shape_of(wl):
     """gsa_shape of a synthetic.Workload."""
-    return make_shape(wl.B, wl.Lq, wl.Lk, wl.q_offset, wl.H, wl.H_kv, wl.d_h, wl.HI, wl.dI, wl.dtype)
+    return make_shape(wl.B, wl.Lq, wl.Lk, wl.q_offset, wl.H, wl.H_kv, wl.d_h, wl.HI, wl.dI, wl.dtype, wl.indexer_act)
 
 
 def make_adaptive(vbar, k_base, k_min, k_max, k_fixed=0, mode=0):

@@ -47,6 +47,7 @@ static int32_t check_shape(const gsa_shape* s) {
     if (s->H % s->H_kv != 0) return GSA_ERR_SHAPE;
     if ((int64_t)s->q_offset + s->Lq > (int64_t)s->Lk) return GSA_ERR_SHAPE;
     if (s->dtype != GSA_F32 && s->dtype != GSA_BF16) return GSA_ERR_UNSUPPORTED;
+    if (s->indexer_act != GSA_ACT_SIGMOID && s->indexer_act != GSA_ACT_RELU) return GSA_ERR_UNSUPPORTED;
     if (s->d_h != 64 && s->d_h != 128) return GSA_ERR_UNSUPPORTED;
     if (s->dI != 32 && s->dI != 64 && s->dI != 128) return GSA_ERR_UNSUPPORTED;
     if (s->HI > 8) return GSA_ERR_UNSUPPORTED;
@@ -148,6 +149,11 @@ static int slab_end(const gsa_shape& s, int r0, int64_t blocks) {
     return (int)(r1 < s.Lq ? r1 : s.Lq);
 }
 
+// 16-bit keys between indexer and selection need bounded scores: the sigmoid indexer only.
+static bool forward_keys(const gsa_shape& s, const gsa_tuning& tn) {
+    return tn.forward_fp32_scores == 0 && s.indexer_act == GSA_ACT_SIGMOID;
+}
+
 // The slab that starts at row r0: as many rows as fit into `avail` bytes of per-slab workspace.  Returns
 // false if not even 128 rows (or the rest of the rows) fit.
 static bool next_slab(const gsa_shape& s, int k_cap, bool own_idx, bool use_keys, size_t avail, const gsa_tuning& tn, int r0,
@@ -191,7 +197,7 @@ static int32_t forward_launches(const gsa_shape& s, const gsa_adaptive& ctl, con
     const bool has_g2 = g2_logits != nullptr;
     const bool prepass = has_g2 && gate_as_prepass(s, k_cap);
     const bool own_idx = idx_out == nullptr;
-    const bool use_keys = tn.forward_fp32_scores == 0;
+    const bool use_keys = forward_keys(s, tn);
     const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt((float)s.d_h);
     const void* Vuse = V;
     const void* g2use = has_g2 ? g2_logits : nullptr;
@@ -251,7 +257,7 @@ static int32_t check_forward_args(const gsa_shape* shape, const gsa_adaptive* ct
 
 // Bytes of the whole forward workspace when every slab holds `blocks` * 128 rows.
 static size_t forward_bytes_uniform(const gsa_shape& s, int k_cap, bool has_g2, int64_t blocks, const gsa_tuning& tn) {
-    const bool use_keys = tn.forward_fp32_scores == 0;
+    const bool use_keys = forward_keys(s, tn);
     size_t slab = 0;
     for (int r0 = 0; r0 < s.Lq;) {
         const SlabPlan p = plan_slab(s, k_cap, true, use_keys, r0, slab_end(s, r0, blocks), tn);
@@ -340,6 +346,7 @@ int32_t gsa_indexer_keys(const gsa_shape* shape, const void* qI, const void* kI,
                          void* workspace, size_t workspace_bytes, void* stream) {
     int32_t rc = check_shape(shape);
     if (rc != GSA_OK) return rc;
+    if (shape->indexer_act != GSA_ACT_SIGMOID) return GSA_ERR_UNSUPPORTED;  // keys need scores below HI
     if (!qI || !kI || !w || !row_var || !keys) return GSA_ERR_NULL;
     rc = check_rows(shape, row_begin, row_end);
     if (rc != GSA_OK) return rc;
@@ -387,6 +394,7 @@ int32_t gsa_topk_select_keys(const gsa_shape* shape, int32_t row_begin, int32_t 
     if (rc != GSA_OK) return rc;
     rc = check_select_len(shape);
     if (rc != GSA_OK) return rc;
+    if (shape->indexer_act != GSA_ACT_SIGMOID) return GSA_ERR_UNSUPPORTED;
     if (!keys || !n_sel || !idx_out || !qI || !kI || !w) return GSA_ERR_NULL;
     rc = check_rows(shape, row_begin, row_end);
     if (rc != GSA_OK) return rc;
@@ -495,7 +503,7 @@ int32_t gsa_forward(const gsa_shape* shape, const gsa_adaptive* ctl, const void*
     const gsa_tuning& tn = tuning_or_default(tuning);
     const size_t fixed = plan_fixed(s, k_cap, g2_logits != nullptr).total;
     if (fixed > workspace_bytes ||
-        !slabs_fit(s, k_cap, idx_out == nullptr, tn.forward_fp32_scores == 0, workspace_bytes - fixed, tn))
+        !slabs_fit(s, k_cap, idx_out == nullptr, forward_keys(s, tn), workspace_bytes - fixed, tn))
         return GSA_ERR_WORKSPACE;
     return forward_launches(s, *ctl, Q, K, V, g1_logits, g2_logits, qI, kI, w, bI, softmax_scale, out, idx_out, n_sel_out,
                             k_out, row_var_out, k_cap, static_cast<unsigned char*>(workspace), workspace_bytes, tn,
@@ -512,7 +520,7 @@ int32_t gsa_forward_noalloc(const gsa_shape* shape, const gsa_adaptive* ctl, con
     const gsa_tuning& tn = tuning_or_default(tuning);
     const size_t fixed = plan_fixed(s, k_cap, g2_logits != nullptr).total;
     if (fixed > kStaticScratchBytes ||
-        !slabs_fit(s, k_cap, idx_out == nullptr, tn.forward_fp32_scores == 0, kStaticScratchBytes - fixed, tn)) {
+        !slabs_fit(s, k_cap, idx_out == nullptr, forward_keys(s, tn), kStaticScratchBytes - fixed, tn)) {
         g_last_error = "gsa_forward_noalloc: this problem needs " +
                        std::to_string(forward_bytes_uniform(s, k_cap, g2_logits != nullptr, 1, tn)) +
                        " bytes of scratch, the library's static scratch holds " + std::to_string(kStaticScratchBytes) +

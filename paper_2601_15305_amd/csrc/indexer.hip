@@ -64,8 +64,10 @@ __device__ __forceinline__ constexpr int acc_row(int i, int h) { return 8 * (i /
 // own so that the deeper prefetch of that case does not cost the prefill loops any registers.
 // HI is the head count the kernel is built for (1, 2, 4 or 8); a.hi <= HI heads exist in memory, the others
 // are given zero queries and zero weights, which adds exact zeros to every sum.
-template <typename T, int DI, int HI, int STORE, bool ROW1>
+// RELU: the comparison variant of Sec. 2.2 Eq. 3 (ReLU instead of the sigmoid; statistics centred at zero).
+template <typename T, int DI, int HI, int STORE, bool ROW1, bool RELU = false>
 __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(IndexerArgs a) {
+    static_assert(!(RELU && STORE == 2), "16-bit keys need the bounded scores of the sigmoid indexer");
     constexpr int EB = ElemTraits<T>::kBytes;
     constexpr int ROWB = DI * EB;            // bytes of one key row
     constexpr int LDSROW = ROWB + 16;        // padded LDS row stride
@@ -128,7 +130,7 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
 #pragma unroll
     for (int r = 0; r < HL; ++r) {
         const int j = (HI == 8) ? 4 * h + r : r;  // head of accumulator register s*HL + r
-        nbias[r] = (a.bI && j < a.hi) ? -kLog2e * a.bI[j] : 0.f;
+        nbias[r] = (a.bI && j < a.hi) ? (RELU ? a.bI[j] : -kLog2e * a.bI[j]) : 0.f;  // ReLU: the bias itself
     }
 #pragma unroll
     for (int s = 0; s < NSLOT; ++s) {
@@ -145,7 +147,7 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
             c += 0.5f * (wv_ * kKeyScale);
         }
         if (HI == 8) c += __shfl_xor(c, 32, 64);
-        center[s] = c;
+        center[s] = RELU ? 0.f : c;
         s1[s] = 0.f;
         s2[s] = 0.f;
     }
@@ -240,8 +242,12 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
 #pragma unroll
                 for (int r = 0; r < HL; ++r) {
                     const int i = s * HL + r;
-                    const float e = fast_exp2(fmaf(c[i], -kLog2e, nbias[r]));
-                    sc = fmaf(wreg[i], fast_rcp(1.0f + e), sc);
+                    if constexpr (RELU) {
+                        sc = fmaf(wreg[i], fmaxf(c[i] + nbias[r], 0.f), sc);
+                    } else {
+                        const float e = fast_exp2(fmaf(c[i], -kLog2e, nbias[r]));
+                        sc = fmaf(wreg[i], fast_rcp(1.0f + e), sc);
+                    }
                 }
                 if (HI == 8) sc += __shfl_xor(sc, 32, 64);
                 sc_out[s] = sc;
@@ -418,7 +424,7 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
 //   mean = c + S1/n,  var = S2/n - (S1/n)^2   with d = I - c.
 __global__ void indexer_finalize_kernel(const float2* partial, const float* w, float* row_mean, float* row_var,
                                         int B, int Lq, int Lk, int q_offset, int row_begin, int row_end, int nsplit,
-                                        int HI, int hi) {
+                                        int HI, int hi, int relu) {
     const int R = row_end - row_begin;
     const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= (int64_t)B * R) return;
@@ -432,7 +438,9 @@ __global__ void indexer_finalize_kernel(const float2* partial, const float* w, f
     }
     float c = 0.f;  // same association as in the kernel above so that the centre is bit-identical
     const float* wr = w + ((int64_t)b * Lq + t) * hi;  // hi heads in memory, HI in the kernel (the rest weigh zero)
-    if (HI == 8) {
+    if (relu) {
+        c = 0.f;  // the ReLU variant sums its scores uncentred
+    } else if (HI == 8) {
         float c0 = 0.f, c1 = 0.f;
         for (int j = 0; j < 4; ++j) c0 += 0.5f * wr[j];
         for (int j = 4; j < hi; ++j) c1 += 0.5f * wr[j];
@@ -475,11 +483,12 @@ size_t indexer_workspace_bytes(const gsa_shape& sh, int row_begin, int row_end) 
 }
 
 template <typename T, int DI, int HI>
-static hipError_t launch_one(const IndexerArgs& a, hipStream_t st) {
+static hipError_t launch_one(const IndexerArgs& a, bool relu, hipStream_t st) {
     constexpr int LDSROW = DI * ElemTraits<T>::kBytes + 16;
     const size_t smem = 2 * kBN * LDSROW;
-    const bool row1 = (a.row_end - a.row_begin) == 1;
-    auto kern = row1 ? (a.keys ? indexer_kernel<T, DI, HI, 2, true>
+    const bool row1 = (a.row_end - a.row_begin) == 1 && !relu;  // (the variant has no kernel of its own for single rows)
+    auto kern = relu ? (a.scores ? indexer_kernel<T, DI, HI, 1, false, true> : indexer_kernel<T, DI, HI, 0, false, true>)
+              : row1 ? (a.keys ? indexer_kernel<T, DI, HI, 2, true>
                                : (a.scores ? indexer_kernel<T, DI, HI, 1, true> : indexer_kernel<T, DI, HI, 0, true>))
                      : (a.keys ? indexer_kernel<T, DI, HI, 2, false>
                                : (a.scores ? indexer_kernel<T, DI, HI, 1, false> : indexer_kernel<T, DI, HI, 0, false>));
@@ -493,22 +502,22 @@ static hipError_t launch_one(const IndexerArgs& a, hipStream_t st) {
 }
 
 template <typename T, int DI>
-static hipError_t launch_hi(const IndexerArgs& a, int HI, hipStream_t st) {
+static hipError_t launch_hi(const IndexerArgs& a, int HI, bool relu, hipStream_t st) {
     switch (HI) {
-        case 1: return launch_one<T, DI, 1>(a, st);
-        case 2: return launch_one<T, DI, 2>(a, st);
-        case 4: return launch_one<T, DI, 4>(a, st);
-        case 8: return launch_one<T, DI, 8>(a, st);
+        case 1: return launch_one<T, DI, 1>(a, relu, st);
+        case 2: return launch_one<T, DI, 2>(a, relu, st);
+        case 4: return launch_one<T, DI, 4>(a, relu, st);
+        case 8: return launch_one<T, DI, 8>(a, relu, st);
     }
     return hipErrorInvalidValue;
 }
 
 template <typename T>
-static hipError_t launch_di(const IndexerArgs& a, int DI, int HI, hipStream_t st) {
+static hipError_t launch_di(const IndexerArgs& a, int DI, int HI, bool relu, hipStream_t st) {
     switch (DI) {
-        case 32: return launch_hi<T, 32>(a, HI, st);
-        case 64: return launch_hi<T, 64>(a, HI, st);
-        case 128: return launch_hi<T, 128>(a, HI, st);
+        case 32: return launch_hi<T, 32>(a, HI, relu, st);
+        case 64: return launch_hi<T, 64>(a, HI, relu, st);
+        case 128: return launch_hi<T, 128>(a, HI, relu, st);
     }
     return hipErrorInvalidValue;
 }
@@ -534,11 +543,13 @@ hipError_t launch_indexer(const gsa_shape& sh, const void* qI, const void* kI, c
     indexer_plan(sh, row_begin, row_end, &a.kc, &a.nsplit, &a.ntiles);
     a.hi = sh.HI;
     const int HIK = kernel_heads(sh.HI);
-    hipError_t e = (sh.dtype == GSA_BF16) ? launch_di<__bf16>(a, sh.dI, HIK, st) : launch_di<float>(a, sh.dI, HIK, st);
+    const bool relu = sh.indexer_act == GSA_ACT_RELU;
+    if (relu && keys) return hipErrorInvalidValue;
+    hipError_t e = (sh.dtype == GSA_BF16) ? launch_di<__bf16>(a, sh.dI, HIK, relu, st) : launch_di<float>(a, sh.dI, HIK, relu, st);
     if (e != hipSuccess) return e;
     const int64_t rows = (int64_t)sh.B * (row_end - row_begin);
     hipLaunchKernelGGL(indexer_finalize_kernel, dim3((unsigned)cdiv(rows, 256)), dim3(256), 0, st, a.partial, w, row_mean,
-                       row_var, sh.B, sh.Lq, sh.Lk, sh.q_offset, row_begin, row_end, a.nsplit, HIK, sh.HI);
+                       row_var, sh.B, sh.Lq, sh.Lk, sh.q_offset, row_begin, row_end, a.nsplit, HIK, sh.HI, relu ? 1 : 0);
     return hipGetLastError();
 }
 

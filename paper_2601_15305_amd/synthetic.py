@@ -33,6 +33,7 @@ class Workload:
     heavy_frac: float = 0.0   # fraction of tokens whose indexer key is scaled
     heavy_scale: float = 1.0
     seed: int = 0
+    indexer_act: str = "sigmoid"   # "relu": the ungated indexer of the comparison variants
 
     @property
     def k_cap(self):
