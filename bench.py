@@ -241,6 +241,44 @@ def stage_breakdown(G, CM, wl, t, run, ssteps):
     return ms, sum_nsel, prepass
 
 
+def comparison_variants(G, S, CM, wl, t, run, gsa_ms):
+    """The paper's comparison systems (Sec. 7.1) on the same tensors and the same GPU: dense causal attention with both
+    gates ("gated only") and without ("standard"), and the ReLU-indexer / fixed-k / ungated forward ("sparse only")."""
+    import torch
+    dev = t["Q"].device
+    sh = run.sh
+    out = torch.empty_like(t["Q"])
+    ws_d = G.workspace(G.gsa_dense_attn_workspace_bytes(sh, True), dev)
+    gated = timed(lambda: G.gsa_dense_gated_attn(sh, 0, wl.Lq, t["Q"], t["K"], t["V"], t["g2"], t["g1"], 0.0, out, ws_d), 2)
+    plain = timed(lambda: G.gsa_dense_gated_attn(sh, 0, wl.Lq, t["Q"], t["K"], t["V"], None, None, 0.0, out, None), 2)
+    pairs = CM.causal_pairs(wl.B, wl.Lq, wl.Lk, wl.q_offset)
+    dense_flops = 4 * wl.d_h * wl.H * pairs
+    res = {"dense_gated_ms": round(gated, 3), "dense_standard_ms": round(plain, 3),
+           "dense_standard_tflops": round(dense_flops / (plain * 1e-3) / 1e12, 1),
+           "dense_standard_frac_mfma_bf16_peak": round(dense_flops / (plain * 1e-3) / 1e12 / PEAK_MFMA_BF16_TFLOPS, 4),
+           "gsa_ms": round(gsa_ms, 3)}
+    del ws_d
+    if wl.k_fixed == 0:
+        wr = wl.with_(indexer_act="relu", k_fixed=wl.k_base)
+        shr = G.shape_of(wr)
+        ctl = G.make_adaptive(1.0, 1, 1, 1, k_fixed=wl.k_base)
+        ws = G.workspace(run.ws_bytes, dev)
+        idx = torch.empty((wl.B, wl.Lq, wl.k_base), dtype=torch.int32, device=dev)
+        so = timed(lambda: G.gsa_forward(shr, ctl, t["Q"], t["K"], t["V"], None, None, t["qI"], t["kI"], t["w"], None, 0.0, out, idx,
+                                         run.n_sel, None, None, wl.k_base, ws), 2)
+        res["sparse_only_ms"] = round(so, 3)
+        res["sparse_only_k"] = wl.k_base
+        del ws, idx
+    res["speedup_gsa_vs_standard"] = round(plain / gsa_ms, 2)
+    res["speedup_gated_only_vs_standard"] = round(plain / gated, 3)
+    if "sparse_only_ms" in res:
+        res["speedup_sparse_only_vs_standard"] = round(plain / res["sparse_only_ms"], 2)
+    res["paper_ratios_context"] = ("Table 9 (128K, 1.7B model, 8x H100, precision not stated): prefill latency relative to standard "
+                                   "0.09 (GSA), 0.08 (sparse only), 1.02 (gated only); abstract: 12-16x")
+    torch.cuda.empty_cache()
+    return res
+
+
 def small_leg(G, S, CM, wl, steps, warmup, workspace_gib):
     """queries/s of another configuration (fresh inputs), with the indexer's key-scan rate for decode shapes."""
     import torch
@@ -410,6 +448,11 @@ def main():
     }
     if one_slab:
         result["one_slab"] = one_slab
+    if not args.no_extras and wl.dtype == "bf16":
+        print("[bench] comparison variants (dense gated / standard, sparse only) ...", file=sys.stderr, flush=True)
+        n_keep = run.n_sel.clone()
+        result["comparison"] = comparison_variants(G, S, CM, wl, t, run, ms_per_step)
+        run.n_sel = n_keep
 
     if args.cpu_seconds > 0:
         print("[bench] CPU oracle leg ...", file=sys.stderr, flush=True)

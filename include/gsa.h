@@ -84,6 +84,9 @@ typedef struct gsa_adaptive {
     int32_t k_base, k_min, k_max;
     int32_t k_fixed;
     int32_t mode;
+    int32_t dense_below; /* gsa_forward only: a context shorter than this many keys (Lk < dense_below) is attended
+                            densely -- no indexer, no selection, every visible key (Sec. 8: below about 4K tokens the
+                            indexer costs more than it saves).  0 = never.  See gsa_forward. */
 } gsa_adaptive;
 
 /* Launch-shape switches.  Every call that takes one accepts NULL (all fields 0 = the library decides).
@@ -212,7 +215,10 @@ int32_t gsa_value_gate(const gsa_shape* shape, const void* V, const void* g2_log
  *                a larger workspace lets the call use larger slabs (fewer launches).
  * gsa_forward_workspace_bytes(.., slab_rows, ..): bytes that let every slab hold at least that many
  * query rows (rounded up to a multiple of 128); slab_rows = 0 gives the minimum.
- * Lk above GSA_SELECT_MAX_LK: GSA_ERR_UNSUPPORTED. */
+ * Lk above GSA_SELECT_MAX_LK: GSA_ERR_UNSUPPORTED.
+ * Dense fallback (ctl->dense_below > Lk, bf16 only): the call is gsa_dense_gated_attn over all rows; it
+ * produces `out` alone, so idx_out, n_sel_out, k_out and row_var_out must be NULL (GSA_ERR_SHAPE otherwise),
+ * and the workspace must hold gsa_dense_attn_workspace_bytes(shape, g2 != NULL) bytes. */
 int32_t gsa_forward(const gsa_shape* shape, const gsa_adaptive* ctl, const void* Q, const void* K,
                     const void* V, const void* g1_logits, const void* g2_logits, const void* qI,
                     const void* kI, const float* w, const float* bI, float softmax_scale, void* out,

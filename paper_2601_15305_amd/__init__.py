@@ -34,7 +34,7 @@ class GsaShape(ctypes.Structure):
 
 
 class GsaAdaptive(ctypes.Structure):
-    _fields_ = [("vbar", ctypes.c_float)] + [(n, ctypes.c_int32) for n in ("k_base", "k_min", "k_max", "k_fixed", "mode")]
+    _fields_ = [("vbar", ctypes.c_float)] + [(n, ctypes.c_int32) for n in ("k_base", "k_min", "k_max", "k_fixed", "mode", "dense_below")]
 
 
 class GsaTuning(ctypes.Structure):
@@ -133,8 +133,8 @@ def shape_of(wl):
     return make_shape(wl.B, wl.Lq, wl.Lk, wl.q_offset, wl.H, wl.H_kv, wl.d_h, wl.HI, wl.dI, wl.dtype, wl.indexer_act)
 
 
-def make_adaptive(vbar, k_base, k_min, k_max, k_fixed=0, mode=0):
-    return GsaAdaptive(float(vbar), k_base, k_min, k_max, k_fixed, mode)
+def make_adaptive(vbar, k_base, k_min, k_max, k_fixed=0, mode=0, dense_below=0):
+    return GsaAdaptive(float(vbar), k_base, k_min, k_max, k_fixed, mode, dense_below)
 
 
 def make_tuning(attn_window=0, attn_kv_per_wg=0, select_exact_only=0, forward_fp32_scores=0, attn_rows_per_wave=0):

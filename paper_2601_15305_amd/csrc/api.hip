@@ -66,7 +66,7 @@ static int32_t check_rows(const gsa_shape* s, int32_t row_begin, int32_t row_end
 
 static int32_t check_ctl(const gsa_adaptive* c) {
     if (!c) return GSA_ERR_NULL;
-    if (c->k_fixed < 0) return GSA_ERR_SHAPE;
+    if (c->k_fixed < 0 || c->dense_below < 0) return GSA_ERR_SHAPE;
     if (c->k_fixed > 0) return GSA_OK;
     if (c->k_min < 1 || c->k_min > c->k_max || c->k_base < 1) return GSA_ERR_SHAPE;
     if (c->mode != 0 && c->mode != 1) return GSA_ERR_UNSUPPORTED;
@@ -498,6 +498,11 @@ int32_t gsa_forward(const gsa_shape* shape, const gsa_adaptive* ctl, const void*
                     const gsa_tuning* tuning, void* stream) {
     int32_t rc = check_forward_args(shape, ctl, Q, K, V, g1_logits, g2_logits, qI, kI, w, softmax_scale, out, k_cap);
     if (rc != GSA_OK) return rc;
+    if (ctl->dense_below > shape->Lk) {  // short context: dense attention over every visible key (Sec. 8)
+        if (idx_out || n_sel_out || k_out || row_var_out) return GSA_ERR_SHAPE;
+        return gsa_dense_gated_attn(shape, 0, shape->Lq, Q, K, V, g2_logits, g1_logits, softmax_scale, out, workspace,
+                                    workspace_bytes, stream);
+    }
     if (!workspace || !aligned(workspace, 256)) return GSA_ERR_WORKSPACE;
     const gsa_shape& s = *shape;
     const gsa_tuning& tn = tuning_or_default(tuning);
@@ -518,6 +523,18 @@ int32_t gsa_forward_noalloc(const gsa_shape* shape, const gsa_adaptive* ctl, con
     if (rc != GSA_OK) return rc;
     const gsa_shape& s = *shape;
     const gsa_tuning& tn = tuning_or_default(tuning);
+    if (ctl->dense_below > s.Lk) {  // short context: dense attention over every visible key (Sec. 8)
+        if (idx_out || n_sel_out || k_out || row_var_out) return GSA_ERR_SHAPE;
+        if (gsa_dense_attn_workspace_bytes(shape, g2_logits != nullptr) > kStaticScratchBytes) {
+            g_last_error = "gsa_forward_noalloc: the gated values of this problem exceed the library's static scratch";
+            return GSA_ERR_WORKSPACE;
+        }
+        unsigned char* dws = nullptr;
+        rc = static_scratch(&dws);
+        if (rc != GSA_OK) return rc;
+        return gsa_dense_gated_attn(shape, 0, s.Lq, Q, K, V, g2_logits, g1_logits, softmax_scale, out, dws, kStaticScratchBytes,
+                                    stream);
+    }
     const size_t fixed = plan_fixed(s, k_cap, g2_logits != nullptr).total;
     if (fixed > kStaticScratchBytes ||
         !slabs_fit(s, k_cap, idx_out == nullptr, forward_keys(s, tn), kStaticScratchBytes - fixed, tn)) {

@@ -420,6 +420,40 @@ def test_sparse_path_with_full_budget_equals_dense_kernel():
     assert (out.float() - res["out"].float()).abs().max().item() <= 1e-2
 
 
+def test_forward_dense_fallback_below_a_context_length():
+    """Sec. 8: below a few thousand tokens the indexer costs more than it saves; gsa_adaptive.dense_below makes
+    gsa_forward attend every visible key for such contexts (the dense kernel), and changes nothing above it."""
+    wl = wl_("fallback", 2, 900, 900, 0, 16, 4, 128, 4, 64, "bf16", kmin=32, kmax=128, seed=17)
+    t = S.make_inputs(wl, "cpu")
+    d = T.to_device(t)
+    sh = G.shape_of(wl)
+    ws = G.workspace(G.gsa_forward_workspace_bytes(sh, 128, True, 900))
+
+    def fwd(ctl, want_aux):
+        out = torch.full_like(d["Q"], float("nan"))
+        aux = [torch.empty((2, 900), dtype=torch.int32, device="cuda") for _ in range(2)] if want_aux else [None, None]
+        G.gsa_forward(sh, ctl, d["Q"], d["K"], d["V"], d["g1"], d["g2"], d["qI"], d["kI"], d["w"], None, 0.0, out, None, aux[0],
+                      aux[1], None, 128, ws)
+        torch.cuda.synchronize()
+        return out
+
+    sparse = fwd(G.make_adaptive(0.3, 64, 32, 128), True)
+    assert torch.equal(fwd(G.make_adaptive(0.3, 64, 32, 128, dense_below=900), True), sparse), "Lk == dense_below: still sparse"
+    dense = fwd(G.make_adaptive(0.3, 64, 32, 128, dense_below=901), False)
+    ref = torch.empty_like(d["Q"])
+    G.gsa_dense_gated_attn(sh, 0, 900, d["Q"], d["K"], d["V"], d["g2"], d["g1"], 0.0, ref, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dense, ref)
+    assert (dense.float() - sparse.float()).abs().max().item() > 1e-2, "the two paths really differ at this budget"
+    o = T.oracle_inputs(t)
+    for (b, i) in [(0, 0), (1, 899), (0, 450)]:
+        want, _ = O.sparse_gated_attn_row(o["Q"][b, i], o["K"][b], o["V"][b], o["g2"][b], o["g1"][b, i], np.arange(i + 1))
+        T.check_out(dense[b, i], want, "bf16")
+    with pytest.raises(G.GsaError) as ei:      # the fallback produces no index sets
+        fwd(G.make_adaptive(0.3, 64, 32, 128, dense_below=901), True)
+    assert ei.value.status == G.GSA_ERR_SHAPE
+
+
 def test_attention_gate_limits_on_gpu():
     """Saturated gate logits: +40 makes both sigmoids 1 in fp32 (plain SDPA on the set), -40 kills the output."""
     wl = wl_("attlim", 1, 64, 64, 0, 8, 2, 128, 4, 32, "bf16", seed=9)
