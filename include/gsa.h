@@ -228,6 +228,33 @@ int32_t gsa_forward(const gsa_shape* shape, const gsa_adaptive* ctl, const void*
 size_t gsa_forward_workspace_bytes(const gsa_shape* shape, int32_t k_cap, int32_t has_g2, int32_t slab_rows,
                                    const gsa_tuning* tuning);
 
+/* ---- decode-serving state (the "Decode" column of Table 9) -----------------------------------------
+ * Per-sequence append-only caches with a capacity of Lk tokens each:
+ *   kI_cache [B, Lk, dI]   K_cache, Vg_cache [B, Lk, H_kv, d_h]   seq_lens [B] int32 (device)
+ * Vg_cache holds the gated values V * sigmoid(g2) (Sec. 3.5), rounded to dtype exactly as gsa_value_gate
+ * does, so a decode step gathers two rows per selected key and never reads the gate logits of old tokens.
+ * The sequences of a batch may have different lengths (ragged): seq_lens[b] tokens of sequence b are valid.
+ *
+ * gsa_cache_append: shape->Lq = T new tokens per sequence.  Token j of sequence b is written at position
+ * seq_lens[b] + j (dropped if that is beyond the capacity); seq_lens_out[b] = min(seq_lens[b] + T, Lk)
+ * (may be NULL; must not alias seq_lens).  kI_new [B,T,dI]; K_new, V_new, g2_new [B,T,H_kv,d_h].
+ *
+ * gsa_decode_step: gsa_forward for the last Lq tokens of every sequence against its own context: query row
+ * i of sequence b has position seq_lens[b] - Lq + i (seq_lens counts the new tokens, which must already be in
+ * the caches) and sees keys 0 .. that position; keys at or beyond seq_lens[b] are never read.  Values outside
+ * [Lq, Lk] are clamped.  Everything else (controller, selection, outputs, k_cap, tuning) as in gsa_forward;
+ * key windows and the dense fallback do not apply.  workspace: gsa_decode_workspace_bytes(shape, k_cap, tuning). */
+int32_t gsa_cache_append(const gsa_shape* shape, const void* kI_new, const void* K_new, const void* V_new,
+                         const void* g2_new, const int32_t* seq_lens, void* kI_cache, void* K_cache,
+                         void* Vg_cache, int32_t* seq_lens_out, void* stream);
+int32_t gsa_decode_step(const gsa_shape* shape, const gsa_adaptive* ctl, const void* Q, const void* g1_logits,
+                        const void* qI, const float* w, const float* bI, const void* kI_cache,
+                        const void* K_cache, const void* Vg_cache, const int32_t* seq_lens, float softmax_scale,
+                        void* out, int32_t* idx_out, int32_t* n_sel_out, int32_t* k_out, float* row_var_out,
+                        int32_t k_cap, void* workspace, size_t workspace_bytes, const gsa_tuning* tuning,
+                        void* stream);
+size_t gsa_decode_workspace_bytes(const gsa_shape* shape, int32_t k_cap, const gsa_tuning* tuning);
+
 /* ---- comparison variants: dense causal attention, Sec. 2.1 Eq. 2 ------------------------------------
  * Every visible key, no indexer and no selection: with g2 and g1 given this is the "gated only" variant of
  * Sec. 7.1 (Eq. 2 with V' = V * sigmoid(g2) and the result multiplied by sigmoid(g1)), with both NULL the

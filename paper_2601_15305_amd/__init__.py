@@ -25,6 +25,7 @@ ENTRY_POINTS = (
     "gsa_indexer_scores", "gsa_indexer_keys", "gsa_indexer_workspace_bytes", "gsa_adaptive_k", "gsa_topk_select",
     "gsa_topk_select_keys", "gsa_sparse_gated_attn", "gsa_attn_workspace_bytes", "gsa_value_gate", "gsa_forward",
     "gsa_forward_workspace_bytes", "gsa_forward_noalloc", "gsa_dense_gated_attn", "gsa_dense_attn_workspace_bytes",
+    "gsa_cache_append", "gsa_decode_step", "gsa_decode_workspace_bytes",
     "gsa_probe_gather", "gsa_status_string", "gsa_last_error", "gsa_version",
 )
 
@@ -88,6 +89,12 @@ def load():
     lib.gsa_forward.restype = i32
     lib.gsa_forward_noalloc.argtypes = [shp, ctl, vp, vp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, i32, tun, vp]
     lib.gsa_forward_noalloc.restype = i32
+    lib.gsa_cache_append.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.gsa_cache_append.restype = i32
+    lib.gsa_decode_step.argtypes = [shp, ctl, vp, vp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, i32, vp, sz, tun, vp]
+    lib.gsa_decode_step.restype = i32
+    lib.gsa_decode_workspace_bytes.argtypes = [shp, i32, tun]
+    lib.gsa_decode_workspace_bytes.restype = sz
     lib.gsa_dense_gated_attn.argtypes = [shp, i32, i32, vp, vp, vp, vp, vp, f32, vp, vp, sz, vp]
     lib.gsa_dense_gated_attn.restype = i32
     lib.gsa_dense_attn_workspace_bytes.argtypes = [shp, i32]
@@ -251,6 +258,27 @@ def gsa_forward_noalloc(shape, ctl, Q, K, V, g1_logits, g2_logits, qI, kI, w, bI
     if rc == GSA_ERR_WORKSPACE:
         raise GsaError(rc, "gsa_forward_noalloc: " + load().gsa_last_error().decode())
     _check(rc, "gsa_forward_noalloc")
+
+
+def gsa_cache_append(shape, kI_new, K_new, V_new, g2_new, seq_lens, kI_cache, K_cache, Vg_cache, seq_lens_out=None, stream=None):
+    rc = load().gsa_cache_append(ctypes.byref(shape), _ptr(kI_new), _ptr(K_new), _ptr(V_new), _ptr(g2_new), _ptr(seq_lens),
+                                 _ptr(kI_cache), _ptr(K_cache), _ptr(Vg_cache), _ptr(seq_lens_out), _stream(stream))
+    _check(rc, "gsa_cache_append")
+
+
+def gsa_decode_workspace_bytes(shape, k_cap, tuning=None):
+    return load().gsa_decode_workspace_bytes(ctypes.byref(shape), k_cap, _tun(tuning))
+
+
+def gsa_decode_step(shape, ctl, Q, g1_logits, qI, w, bI, kI_cache, K_cache, Vg_cache, seq_lens, softmax_scale, out, idx_out,
+                    n_sel_out, k_out, row_var_out, k_cap, workspace, workspace_bytes=None, tuning=None, stream=None):
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load().gsa_decode_step(ctypes.byref(shape), ctypes.byref(ctl) if ctl is not None else None, _ptr(Q), _ptr(g1_logits),
+                                _ptr(qI), _ptr(w), _ptr(bI), _ptr(kI_cache), _ptr(K_cache), _ptr(Vg_cache), _ptr(seq_lens),
+                                float(softmax_scale), _ptr(out), _ptr(idx_out), _ptr(n_sel_out), _ptr(k_out), _ptr(row_var_out),
+                                k_cap, _ptr(workspace), workspace_bytes, _tun(tuning), _stream(stream))
+    _check(rc, "gsa_decode_step")
 
 
 def gsa_dense_attn_workspace_bytes(shape, has_g2):

@@ -9,19 +9,18 @@
 
 namespace gsa {
 // defined in indexer.hip / select.hip / attention.hip
-void indexer_plan(const gsa_shape& sh, int row_begin, int row_end, int* kc_out, int* nsplit_out, int* ntiles_out);
-size_t indexer_workspace_bytes(const gsa_shape& sh, int row_begin, int row_end);
+size_t indexer_workspace_bytes(const gsa_shape& sh, int row_begin, int row_end, bool ragged);
 hipError_t launch_indexer(const gsa_shape& sh, const void* qI, const void* kI, const float* w, const float* bI,
                           int row_begin, int row_end, float* scores, uint16_t* keys, int64_t ld, float* row_mean,
-                          float* row_var, void* workspace, hipStream_t st);
+                          float* row_var, void* workspace, const int32_t* seq_lens, hipStream_t st);
 hipError_t launch_select(const gsa_shape& sh, int row_begin, int row_end, const float* scores, int64_t ld,
                          const int32_t* n_sel, int k_cap, int32_t* idx_out, int idx_rows, int idx_row0, bool exact_only,
-                         hipStream_t st);
+                         const int32_t* seq_lens, hipStream_t st);
 hipError_t launch_select16(const gsa_shape& sh, int row_begin, int row_end, const uint16_t* keys, int64_t ld,
                            const int32_t* n_sel, int k_cap, int32_t* idx_out, int idx_rows, int idx_row0, const void* qI,
-                           const void* kI, const float* w, const float* bI, hipStream_t st);
+                           const void* kI, const float* w, const float* bI, const int32_t* seq_lens, hipStream_t st);
 hipError_t launch_adaptive_k(const gsa_shape& sh, const gsa_adaptive& c, int row_begin, int row_end,
-                             const float* row_var, int32_t* k_out, int32_t* n_sel_out, hipStream_t st);
+                             const float* row_var, int32_t* k_out, int32_t* n_sel_out, const int32_t* seq_lens, hipStream_t st);
 hipError_t launch_value_gate(const gsa_shape& sh, const void* V, const void* g2, void* Vg, hipStream_t st);
 hipError_t launch_attention(const gsa_shape& sh, int row_begin, int row_end, const void* Q, const void* K, const void* V,
                             const void* g2, const void* g1, const int32_t* idx, int idx_rows, int idx_row0,
@@ -30,6 +29,9 @@ hipError_t launch_attention(const gsa_shape& sh, int row_begin, int row_end, con
 size_t attn_workspace_bytes(const gsa_shape& sh, int row_begin, int row_end, int k_cap, const gsa_tuning& tn);
 hipError_t launch_dense_attention(const gsa_shape& sh, int row_begin, int row_end, const void* Q, const void* K, const void* Vg,
                                   const void* g1, float scale, void* out, hipStream_t st);
+hipError_t launch_cache_append(const gsa_shape& sh, const void* kI_new, const void* K_new, const void* V_new, const void* g2_new,
+                               const int32_t* seq_lens, void* kI_cache, void* K_cache, void* Vg_cache, int32_t* seq_lens_out,
+                               hipStream_t st);
 hipError_t launch_probe_gather(const void* table, const int32_t* idx, int64_t n_idx, int waves, uint32_t* sink, hipStream_t st);
 
 static thread_local std::string g_last_error;
@@ -123,11 +125,12 @@ static FixedPlan plan_fixed(const gsa_shape& s, int k_cap, bool has_g2) {
     return p;
 }
 
-static SlabPlan plan_slab(const gsa_shape& s, int k_cap, bool own_idx, bool use_keys, int r0, int r1, const gsa_tuning& tn) {
+static SlabPlan plan_slab(const gsa_shape& s, int k_cap, bool own_idx, bool use_keys, bool ragged, int r0, int r1, const gsa_tuning& tn) {
     SlabPlan p;
     p.r0 = r0;
     p.r1 = r1;
-    const int64_t last = (int64_t)s.q_offset + r1 - 1 < s.Lk - 1 ? (int64_t)s.q_offset + r1 - 1 : s.Lk - 1;
+    // (with per-sequence lengths a row may see up to the whole capacity)
+    const int64_t last = ragged ? s.Lk - 1 : ((int64_t)s.q_offset + r1 - 1 < s.Lk - 1 ? (int64_t)s.q_offset + r1 - 1 : s.Lk - 1);
     p.ld = (last + 1 + 31) & ~(int64_t)31;
     const size_t rows = (size_t)s.B * (r1 - r0);
     size_t off = 0;
@@ -136,7 +139,7 @@ static SlabPlan plan_slab(const gsa_shape& s, int k_cap, bool own_idx, bool use_
     p.off_scores = off;
     off += up256(rows * (size_t)p.ld * (use_keys ? 2 : 4));
     p.off_partial = off;
-    off += up256(indexer_workspace_bytes(s, r0, r1));
+    off += up256(indexer_workspace_bytes(s, r0, r1, ragged));
     p.off_attn = off;
     off += up256(attn_workspace_bytes(s, r0, r1, k_cap, tn));
     p.total = off;
@@ -156,17 +159,17 @@ static bool forward_keys(const gsa_shape& s, const gsa_tuning& tn) {
 
 // The slab that starts at row r0: as many rows as fit into `avail` bytes of per-slab workspace.  Returns
 // false if not even 128 rows (or the rest of the rows) fit.
-static bool next_slab(const gsa_shape& s, int k_cap, bool own_idx, bool use_keys, size_t avail, const gsa_tuning& tn, int r0,
+static bool next_slab(const gsa_shape& s, int k_cap, bool own_idx, bool use_keys, bool ragged, size_t avail, const gsa_tuning& tn, int r0,
                       SlabPlan* out) {
     const int64_t max_blocks = cdiv(s.Lq - r0, 128);
-    SlabPlan best = plan_slab(s, k_cap, own_idx, use_keys, r0, slab_end(s, r0, max_blocks), tn);
+    SlabPlan best = plan_slab(s, k_cap, own_idx, use_keys, ragged, r0, slab_end(s, r0, max_blocks), tn);
     if (best.total > avail) {
         int64_t lo = 1, hi = max_blocks;  // invariant: `lo` blocks fit (checked first), `hi` blocks do not
-        best = plan_slab(s, k_cap, own_idx, use_keys, r0, slab_end(s, r0, lo), tn);
+        best = plan_slab(s, k_cap, own_idx, use_keys, ragged, r0, slab_end(s, r0, lo), tn);
         if (best.total > avail) return false;
         while (hi - lo > 1) {
             const int64_t mid = (lo + hi) / 2;
-            const SlabPlan p = plan_slab(s, k_cap, own_idx, use_keys, r0, slab_end(s, r0, mid), tn);
+            const SlabPlan p = plan_slab(s, k_cap, own_idx, use_keys, ragged, r0, slab_end(s, r0, mid), tn);
             if (p.total <= avail) {
                 lo = mid;
                 best = p;
@@ -180,10 +183,10 @@ static bool next_slab(const gsa_shape& s, int k_cap, bool own_idx, bool use_keys
 }
 
 // Can [0, Lq) be cut into slabs that fit?  (The same walk the launches make, without launching.)
-static bool slabs_fit(const gsa_shape& s, int k_cap, bool own_idx, bool use_keys, size_t avail, const gsa_tuning& tn) {
+static bool slabs_fit(const gsa_shape& s, int k_cap, bool own_idx, bool use_keys, bool ragged, size_t avail, const gsa_tuning& tn) {
     SlabPlan p;
     for (int r0 = 0; r0 < s.Lq; r0 = p.r1)
-        if (!next_slab(s, k_cap, own_idx, use_keys, avail, tn, r0, &p)) return false;
+        if (!next_slab(s, k_cap, own_idx, use_keys, ragged, avail, tn, r0, &p)) return false;
     return true;
 }
 
@@ -192,7 +195,7 @@ static int32_t forward_launches(const gsa_shape& s, const gsa_adaptive& ctl, con
                                 const void* g1_logits, const void* g2_logits, const void* qI, const void* kI, const float* w,
                                 const float* bI, float softmax_scale, void* out, int32_t* idx_out, int32_t* n_sel_out,
                                 int32_t* k_out, float* row_var_out, int32_t k_cap, unsigned char* ws, size_t ws_bytes,
-                                const gsa_tuning& tn, hipStream_t st) {
+                                const int32_t* seq_lens, const gsa_tuning& tn, hipStream_t st) {
     const FixedPlan fx = plan_fixed(s, k_cap, g2_logits != nullptr);
     const bool has_g2 = g2_logits != nullptr;
     const bool prepass = has_g2 && gate_as_prepass(s, k_cap);
@@ -214,20 +217,21 @@ static int32_t forward_launches(const gsa_shape& s, const gsa_adaptive& ctl, con
     unsigned char* sw = ws + fx.total;  // per-slab part
     SlabPlan p;
     for (int r0 = 0; r0 < s.Lq; r0 = p.r1) {
-        if (!next_slab(s, k_cap, own_idx, use_keys, ws_bytes - fx.total, tn, r0, &p)) return GSA_ERR_WORKSPACE;
+        if (!next_slab(s, k_cap, own_idx, use_keys, seq_lens != nullptr, ws_bytes - fx.total, tn, r0, &p)) return GSA_ERR_WORKSPACE;
         const int r1 = p.r1;
         float* scores = reinterpret_cast<float*>(sw + p.off_scores);
         uint16_t* keys = reinterpret_cast<uint16_t*>(sw + p.off_scores);
         e = launch_indexer(s, qI, kI, w, bI, r0, r1, use_keys ? nullptr : scores, use_keys ? keys : nullptr, p.ld, nullptr,
-                           var, sw + p.off_partial, st);
+                           var, sw + p.off_partial, seq_lens, st);
         if (e != hipSuccess) return hip_fail(e, "gsa_forward/indexer");
-        e = launch_adaptive_k(s, ctl, r0, r1, var, kbuf, nsel, st);
+        e = launch_adaptive_k(s, ctl, r0, r1, var, kbuf, nsel, seq_lens, st);
         if (e != hipSuccess) return hip_fail(e, "gsa_forward/adaptive_k");
         int32_t* idx = own_idx ? reinterpret_cast<int32_t*>(sw + p.off_idx) : idx_out;
         const int idx_rows = own_idx ? (r1 - r0) : s.Lq;
         const int idx_row0 = own_idx ? r0 : 0;
-        e = use_keys ? launch_select16(s, r0, r1, keys, p.ld, nsel, k_cap, idx, idx_rows, idx_row0, qI, kI, w, bI, st)
-                     : launch_select(s, r0, r1, scores, p.ld, nsel, k_cap, idx, idx_rows, idx_row0, tn.select_exact_only != 0, st);
+        e = use_keys ? launch_select16(s, r0, r1, keys, p.ld, nsel, k_cap, idx, idx_rows, idx_row0, qI, kI, w, bI, seq_lens, st)
+                     : launch_select(s, r0, r1, scores, p.ld, nsel, k_cap, idx, idx_rows, idx_row0, tn.select_exact_only != 0,
+                                     seq_lens, st);
         if (e != hipSuccess) return hip_fail(e, "gsa_forward/select");
         e = launch_attention(s, r0, r1, Q, K, Vuse, g2use, g1_logits, idx, idx_rows, idx_row0, nsel, k_cap, scale, out,
                              sw + p.off_attn, tn, st);
@@ -256,11 +260,11 @@ static int32_t check_forward_args(const gsa_shape* shape, const gsa_adaptive* ct
 }
 
 // Bytes of the whole forward workspace when every slab holds `blocks` * 128 rows.
-static size_t forward_bytes_uniform(const gsa_shape& s, int k_cap, bool has_g2, int64_t blocks, const gsa_tuning& tn) {
+static size_t forward_bytes_uniform(const gsa_shape& s, int k_cap, bool has_g2, int64_t blocks, const gsa_tuning& tn, bool ragged = false) {
     const bool use_keys = forward_keys(s, tn);
     size_t slab = 0;
     for (int r0 = 0; r0 < s.Lq;) {
-        const SlabPlan p = plan_slab(s, k_cap, true, use_keys, r0, slab_end(s, r0, blocks), tn);
+        const SlabPlan p = plan_slab(s, k_cap, true, use_keys, ragged, r0, slab_end(s, r0, blocks), tn);
         if (p.total > slab) slab = p.total;
         r0 = p.r1;
     }
@@ -321,7 +325,7 @@ int32_t gsa_version(void) { return 100; }
 
 size_t gsa_indexer_workspace_bytes(const gsa_shape* shape, int32_t row_begin, int32_t row_end) {
     if (check_shape(shape) != GSA_OK || check_rows(shape, row_begin, row_end) != GSA_OK) return 0;
-    return up256(indexer_workspace_bytes(*shape, row_begin, row_end));
+    return up256(indexer_workspace_bytes(*shape, row_begin, row_end, false));
 }
 
 int32_t gsa_indexer_scores(const gsa_shape* shape, const void* qI, const void* kI, const float* w, const float* bI,
@@ -334,10 +338,10 @@ int32_t gsa_indexer_scores(const gsa_shape* shape, const void* qI, const void* k
     if (rc != GSA_OK) return rc;
     if (scores && (ld_scores < shape->Lk || (ld_scores & 3) != 0)) return GSA_ERR_SHAPE;
     if (!aligned(qI, 16) || !aligned(kI, 16) || (scores && !aligned(scores, 16))) return GSA_ERR_SHAPE;
-    if (!workspace || !aligned(workspace, 256) || workspace_bytes < indexer_workspace_bytes(*shape, row_begin, row_end))
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < indexer_workspace_bytes(*shape, row_begin, row_end, false))
         return GSA_ERR_WORKSPACE;
     hipError_t e = launch_indexer(*shape, qI, kI, w, bI, row_begin, row_end, scores, nullptr, ld_scores, row_mean, row_var,
-                                  workspace, static_cast<hipStream_t>(stream));
+                                  workspace, nullptr, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_indexer_scores");
 }
 
@@ -352,10 +356,10 @@ int32_t gsa_indexer_keys(const gsa_shape* shape, const void* qI, const void* kI,
     if (rc != GSA_OK) return rc;
     if (ld_keys < shape->Lk || (ld_keys & 7) != 0) return GSA_ERR_SHAPE;
     if (!aligned(qI, 16) || !aligned(kI, 16) || !aligned(keys, 16)) return GSA_ERR_SHAPE;
-    if (!workspace || !aligned(workspace, 256) || workspace_bytes < indexer_workspace_bytes(*shape, row_begin, row_end))
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < indexer_workspace_bytes(*shape, row_begin, row_end, false))
         return GSA_ERR_WORKSPACE;
     hipError_t e = launch_indexer(*shape, qI, kI, w, bI, row_begin, row_end, nullptr, keys, ld_keys, row_mean, row_var,
-                                  workspace, static_cast<hipStream_t>(stream));
+                                  workspace, nullptr, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_indexer_keys");
 }
 
@@ -366,7 +370,7 @@ int32_t gsa_adaptive_k(const gsa_shape* shape, const gsa_adaptive* ctl, const fl
     rc = check_ctl(ctl);
     if (rc != GSA_OK) return rc;
     if (!n_sel_out || (ctl->k_fixed == 0 && !row_var)) return GSA_ERR_NULL;
-    hipError_t e = launch_adaptive_k(*shape, *ctl, 0, shape->Lq, row_var, k_out, n_sel_out, static_cast<hipStream_t>(stream));
+    hipError_t e = launch_adaptive_k(*shape, *ctl, 0, shape->Lq, row_var, k_out, n_sel_out, nullptr, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_adaptive_k");
 }
 
@@ -383,7 +387,7 @@ int32_t gsa_topk_select(const gsa_shape* shape, int32_t row_begin, int32_t row_e
     if (ld_scores < shape->Lk || (ld_scores & 3) != 0 || !aligned(scores, 16)) return GSA_ERR_SHAPE;
     if (k_cap < 1 || k_cap > 8192) return GSA_ERR_SHAPE;
     hipError_t e = launch_select(*shape, row_begin, row_end, scores, ld_scores, n_sel, k_cap, idx_out, shape->Lq, 0,
-                                 tuning_or_default(tuning).select_exact_only != 0, static_cast<hipStream_t>(stream));
+                                 tuning_or_default(tuning).select_exact_only != 0, nullptr, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_topk_select");
 }
 
@@ -401,7 +405,7 @@ int32_t gsa_topk_select_keys(const gsa_shape* shape, int32_t row_begin, int32_t 
     if (ld_keys < shape->Lk || (ld_keys & 7) != 0 || !aligned(keys, 16) || !aligned(qI, 16) || !aligned(kI, 16)) return GSA_ERR_SHAPE;
     if (k_cap < 1 || k_cap > 8192) return GSA_ERR_SHAPE;
     hipError_t e = launch_select16(*shape, row_begin, row_end, keys, ld_keys, n_sel, k_cap, idx_out, shape->Lq, 0, qI, kI, w,
-                                   bI, static_cast<hipStream_t>(stream));
+                                   bI, nullptr, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_topk_select_keys");
 }
 
@@ -508,11 +512,54 @@ int32_t gsa_forward(const gsa_shape* shape, const gsa_adaptive* ctl, const void*
     const gsa_tuning& tn = tuning_or_default(tuning);
     const size_t fixed = plan_fixed(s, k_cap, g2_logits != nullptr).total;
     if (fixed > workspace_bytes ||
-        !slabs_fit(s, k_cap, idx_out == nullptr, forward_keys(s, tn), workspace_bytes - fixed, tn))
+        !slabs_fit(s, k_cap, idx_out == nullptr, forward_keys(s, tn), false, workspace_bytes - fixed, tn))
         return GSA_ERR_WORKSPACE;
     return forward_launches(s, *ctl, Q, K, V, g1_logits, g2_logits, qI, kI, w, bI, softmax_scale, out, idx_out, n_sel_out,
-                            k_out, row_var_out, k_cap, static_cast<unsigned char*>(workspace), workspace_bytes, tn,
+                            k_out, row_var_out, k_cap, static_cast<unsigned char*>(workspace), workspace_bytes, nullptr, tn,
                             static_cast<hipStream_t>(stream));
+}
+
+size_t gsa_decode_workspace_bytes(const gsa_shape* shape, int32_t k_cap, const gsa_tuning* tuning) {
+    if (check_shape(shape) != GSA_OK || check_select_len(shape) != GSA_OK || k_cap < 1 || k_cap > 8192) return 0;
+    gsa_tuning tn = tuning_or_default(tuning);
+    tn.attn_window = -1;
+    return forward_bytes_uniform(*shape, k_cap, false, cdiv(shape->Lq, 128), tn, true);
+}
+
+int32_t gsa_decode_step(const gsa_shape* shape, const gsa_adaptive* ctl, const void* Q, const void* g1_logits, const void* qI,
+                        const float* w, const float* bI, const void* kI_cache, const void* K_cache, const void* Vg_cache,
+                        const int32_t* seq_lens, float softmax_scale, void* out, int32_t* idx_out, int32_t* n_sel_out,
+                        int32_t* k_out, float* row_var_out, int32_t k_cap, void* workspace, size_t workspace_bytes,
+                        const gsa_tuning* tuning, void* stream) {
+    int32_t rc = check_forward_args(shape, ctl, Q, K_cache, Vg_cache, g1_logits, nullptr, qI, kI_cache, w, softmax_scale, out, k_cap);
+    if (rc != GSA_OK) return rc;
+    if (!seq_lens) return GSA_ERR_NULL;
+    if (ctl->dense_below > 0) return GSA_ERR_UNSUPPORTED;  // the dense kernel takes one context length for the whole batch
+    if (!workspace || !aligned(workspace, 256)) return GSA_ERR_WORKSPACE;
+    const gsa_shape& s = *shape;
+    gsa_tuning tn = tuning_or_default(tuning);
+    tn.attn_window = -1;  // which rows see which key window is only known on the device: no windows
+    const size_t fixed = plan_fixed(s, k_cap, false).total;
+    if (fixed > workspace_bytes || !slabs_fit(s, k_cap, idx_out == nullptr, forward_keys(s, tn), true, workspace_bytes - fixed, tn))
+        return GSA_ERR_WORKSPACE;
+    return forward_launches(s, *ctl, Q, K_cache, Vg_cache, g1_logits, nullptr, qI, kI_cache, w, bI, softmax_scale, out, idx_out,
+                            n_sel_out, k_out, row_var_out, k_cap, static_cast<unsigned char*>(workspace), workspace_bytes,
+                            seq_lens, tn, static_cast<hipStream_t>(stream));
+}
+
+int32_t gsa_cache_append(const gsa_shape* shape, const void* kI_new, const void* K_new, const void* V_new, const void* g2_new,
+                         const int32_t* seq_lens, void* kI_cache, void* K_cache, void* Vg_cache, int32_t* seq_lens_out,
+                         void* stream) {
+    int32_t rc = check_shape(shape);
+    if (rc != GSA_OK) return rc;
+    if (!kI_new || !K_new || !V_new || !g2_new || !seq_lens || !kI_cache || !K_cache || !Vg_cache) return GSA_ERR_NULL;
+    if (seq_lens_out == seq_lens) return GSA_ERR_SHAPE;  // lengths are read by every thread while they would be rewritten
+    if (!aligned(kI_new, 16) || !aligned(K_new, 16) || !aligned(V_new, 16) || !aligned(g2_new, 16) || !aligned(kI_cache, 16) ||
+        !aligned(K_cache, 16) || !aligned(Vg_cache, 16))
+        return GSA_ERR_SHAPE;
+    hipError_t e = launch_cache_append(*shape, kI_new, K_new, V_new, g2_new, seq_lens, kI_cache, K_cache, Vg_cache, seq_lens_out,
+                                       static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_cache_append");
 }
 
 int32_t gsa_forward_noalloc(const gsa_shape* shape, const gsa_adaptive* ctl, const void* Q, const void* K, const void* V,
@@ -537,7 +584,7 @@ int32_t gsa_forward_noalloc(const gsa_shape* shape, const gsa_adaptive* ctl, con
     }
     const size_t fixed = plan_fixed(s, k_cap, g2_logits != nullptr).total;
     if (fixed > kStaticScratchBytes ||
-        !slabs_fit(s, k_cap, idx_out == nullptr, forward_keys(s, tn), kStaticScratchBytes - fixed, tn)) {
+        !slabs_fit(s, k_cap, idx_out == nullptr, forward_keys(s, tn), false, kStaticScratchBytes - fixed, tn)) {
         g_last_error = "gsa_forward_noalloc: this problem needs " +
                        std::to_string(forward_bytes_uniform(s, k_cap, g2_logits != nullptr, 1, tn)) +
                        " bytes of scratch, the library's static scratch holds " + std::to_string(kStaticScratchBytes) +
@@ -549,7 +596,7 @@ int32_t gsa_forward_noalloc(const gsa_shape* shape, const gsa_adaptive* ctl, con
     if (rc != GSA_OK) return rc;
     // nothing in the scratch has to start at zero: every kernel writes what it later reads
     return forward_launches(s, *ctl, Q, K, V, g1_logits, g2_logits, qI, kI, w, bI, softmax_scale, out, idx_out, n_sel_out,
-                            k_out, row_var_out, k_cap, ws, kStaticScratchBytes, tn, static_cast<hipStream_t>(stream));
+                            k_out, row_var_out, k_cap, ws, kStaticScratchBytes, nullptr, tn, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

@@ -44,6 +44,12 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+// Position offset of batch element b: query row i has absolute position offset + i.  With per-sequence lengths
+// (ragged decode batches) the Lq rows are the last Lq tokens of a sequence that holds seq_lens[b] tokens.
+__device__ __forceinline__ int batch_q_offset(const int32_t* seq_lens, int b, int q_offset, int Lq, int Lk) {
+    return seq_lens ? max(0, min(seq_lens[b] - Lq, Lk - Lq)) : q_offset;
+}
+
 // Exact host/device ceil-div.
 __host__ __device__ constexpr int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 

@@ -39,6 +39,7 @@ struct IndexerArgs {
     int32_t kc;      // keys per split (multiple of 128)
     int32_t nsplit;
     int32_t ntiles;  // query tiles in the slab
+    const int32_t* seq_lens;  // per-sequence lengths (ragged decode) or null
     int32_t hi;      // indexer heads in memory (the kernels work on the next power of two, the extra heads weigh zero)
 };
 
@@ -98,7 +99,8 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
     const bool narrow = (a.row_end - t_wg0) <= QW;
     const int t_w0 = narrow ? t_wg0 : t_wg0 + wv * QW;
     const int t_wg_last = min(t_wg0 + QT, a.row_end) - 1;
-    const int kmax_wg = min(a.q_offset + t_wg_last, a.Lk - 1);  // last key any row of the workgroup sees
+    const int qoff = batch_q_offset(a.seq_lens, b, a.q_offset, a.Lq, a.Lk);
+    const int kmax_wg = min(qoff + t_wg_last, a.Lk - 1);  // last key any row of the workgroup sees
     const int key_lo = split * a.kc;
     const int key_hi = min(key_lo + a.kc, kmax_wg + 1);         // exclusive
 
@@ -117,7 +119,7 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
     // it is needed: the masked tiles at the diagonal and the final reduction)
     auto lim_of = [&](int s) {
         const int t = t_w0 + slot_row(s) + kHalfRows * h;
-        return t < a.row_end ? min(a.q_offset + t, a.Lk - 1) : -1;
+        return t < a.row_end ? min(qoff + t, a.Lk - 1) : -1;
     };
     // element offset of a slot's score row from the wave's base: lane part here, uniform part at the use
     const uint32_t half_off = (uint32_t)(kHalfRows * h) * (uint32_t)a.ld;
@@ -185,8 +187,8 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
         const int t_w_last = min(t_w0 + QW, a.row_end) - 1;
         const bool wave_has_rows = t_w0 < a.row_end;
         const bool wave_rows_full = (t_w0 + QW) <= a.row_end;
-        const int lim_first = min(a.q_offset + t_w0, a.Lk - 1);
-        const int lim_last = wave_has_rows ? min(a.q_offset + t_w_last, a.Lk - 1) : -1;
+        const int lim_first = min(qoff + t_w0, a.Lk - 1);
+        const int lim_last = wave_has_rows ? min(qoff + t_w_last, a.Lk - 1) : -1;
 
         const unsigned char* kbase = static_cast<const unsigned char*>(a.kI) + (int64_t)b * a.Lk * ROWB;
         u32x4 stage[NCH];
@@ -313,7 +315,7 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
         // (vmcnt(#stores)) instead of draining every outstanding store at each tile boundary.
         int nlead = 0;
         if (!ROW1 && t_wg0 + QT <= a.row_end) {
-            const int lim_wg_first = min(a.q_offset + t_wg0, a.Lk - 1);
+            const int lim_wg_first = min(qoff + t_wg0, a.Lk - 1);
             nlead = (lim_wg_first + 1 - key_lo) / kBN;
             nlead = min(nlead, min(ntile - 1, (a.Lk - key_lo) / kBN - 1));
             nlead = max(nlead, 0);
@@ -326,7 +328,7 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
         // key stream, not by arithmetic: their leading tiles keep two tiles of loads in flight and do the
         // arithmetic of the one live slot only, again without branches.
         if constexpr (ROW1 && HI <= 4) {
-            const int lim_row = min(a.q_offset + t_wg0, a.Lk - 1);
+            const int lim_row = min(qoff + t_wg0, a.Lk - 1);
             int nlead1 = (lim_row + 1 - key_lo) / kBN;  // wholly visible tiles
             nlead1 = max(min(nlead1, ntile - 1), 0);
             u32x4 stage2[NCH];
@@ -424,7 +426,7 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
 //   mean = c + S1/n,  var = S2/n - (S1/n)^2   with d = I - c.
 __global__ void indexer_finalize_kernel(const float2* partial, const float* w, float* row_mean, float* row_var,
                                         int B, int Lq, int Lk, int q_offset, int row_begin, int row_end, int nsplit,
-                                        int HI, int hi, int relu) {
+                                        int HI, int hi, int relu, const int32_t* seq_lens) {
     const int R = row_end - row_begin;
     const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= (int64_t)B * R) return;
@@ -448,7 +450,7 @@ __global__ void indexer_finalize_kernel(const float2* partial, const float* w, f
     } else {
         for (int j = 0; j < hi; ++j) c += 0.5f * wr[j];
     }
-    const double nvis = (double)(min(q_offset + t, Lk - 1) + 1);
+    const double nvis = (double)(min(batch_q_offset(seq_lens, b, q_offset, Lq, Lk) + t, Lk - 1) + 1);
     const double m = S1 / nvis;
     double var = S2 / nvis - m * m;
     if (var < 0.0) var = 0.0;
@@ -461,10 +463,12 @@ static int kernel_heads(int hi) { return hi <= 1 ? 1 : (hi <= 2 ? 2 : (hi <= 4 ?
 static int queries_per_wg(int hi) { return 4 * (32 / kernel_heads(hi)); }
 
 // Keys per split: enough splits that the launch fills the chip, never less than four key tiles.
-void indexer_plan(const gsa_shape& sh, int row_begin, int row_end, int* kc_out, int* nsplit_out, int* ntiles_out) {
+// (With per-sequence lengths the visible range of a row is only known on the device; the plan is always made
+// for the whole capacity, which bounds every sequence.)
+void indexer_plan(const gsa_shape& sh, int row_begin, int row_end, int* kc_out, int* nsplit_out, int* ntiles_out, bool ragged) {
     const int QT = queries_per_wg(sh.HI);
     const int ntiles = (int)cdiv(row_end - row_begin, QT);
-    const int maxvis = (sh.q_offset + row_end - 1 < sh.Lk - 1 ? sh.q_offset + row_end - 1 : sh.Lk - 1) + 1;
+    const int maxvis = ragged ? sh.Lk : (sh.q_offset + row_end - 1 < sh.Lk - 1 ? sh.q_offset + row_end - 1 : sh.Lk - 1) + 1;
     const int64_t want_wgs = 2048;  // measured flat between 1500 and 2300 on 256 CUs
     int64_t nsplit = cdiv(want_wgs, (int64_t)ntiles * sh.B);
     if (nsplit < 1) nsplit = 1;
@@ -476,9 +480,9 @@ void indexer_plan(const gsa_shape& sh, int row_begin, int row_end, int* kc_out, 
     *ntiles_out = ntiles;
 }
 
-size_t indexer_workspace_bytes(const gsa_shape& sh, int row_begin, int row_end) {
+size_t indexer_workspace_bytes(const gsa_shape& sh, int row_begin, int row_end, bool ragged) {
     int kc, nsplit, ntiles;
-    indexer_plan(sh, row_begin, row_end, &kc, &nsplit, &ntiles);
+    indexer_plan(sh, row_begin, row_end, &kc, &nsplit, &ntiles, ragged);
     return (size_t)sh.B * (size_t)(row_end - row_begin) * (size_t)nsplit * 4 * sizeof(float2);
 }
 
@@ -524,8 +528,9 @@ static hipError_t launch_di(const IndexerArgs& a, int DI, int HI, bool relu, hip
 
 hipError_t launch_indexer(const gsa_shape& sh, const void* qI, const void* kI, const float* w, const float* bI,
                           int row_begin, int row_end, float* scores, uint16_t* keys, int64_t ld, float* row_mean,
-                          float* row_var, void* workspace, hipStream_t st) {
+                          float* row_var, void* workspace, const int32_t* seq_lens, hipStream_t st) {
     IndexerArgs a;
+    a.seq_lens = seq_lens;
     a.keys = keys;
     a.qI = qI;
     a.kI = kI;
@@ -540,7 +545,7 @@ hipError_t launch_indexer(const gsa_shape& sh, const void* qI, const void* kI, c
     a.q_offset = sh.q_offset;
     a.row_begin = row_begin;
     a.row_end = row_end;
-    indexer_plan(sh, row_begin, row_end, &a.kc, &a.nsplit, &a.ntiles);
+    indexer_plan(sh, row_begin, row_end, &a.kc, &a.nsplit, &a.ntiles, seq_lens != nullptr);
     a.hi = sh.HI;
     const int HIK = kernel_heads(sh.HI);
     const bool relu = sh.indexer_act == GSA_ACT_RELU;
@@ -549,7 +554,7 @@ hipError_t launch_indexer(const gsa_shape& sh, const void* qI, const void* kI, c
     if (e != hipSuccess) return e;
     const int64_t rows = (int64_t)sh.B * (row_end - row_begin);
     hipLaunchKernelGGL(indexer_finalize_kernel, dim3((unsigned)cdiv(rows, 256)), dim3(256), 0, st, a.partial, w, row_mean,
-                       row_var, sh.B, sh.Lq, sh.Lk, sh.q_offset, row_begin, row_end, a.nsplit, HIK, sh.HI, relu ? 1 : 0);
+                       row_var, sh.B, sh.Lq, sh.Lk, sh.q_offset, row_begin, row_end, a.nsplit, HIK, sh.HI, relu ? 1 : 0, seq_lens);
     return hipGetLastError();
 }
 

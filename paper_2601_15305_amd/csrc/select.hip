@@ -31,6 +31,7 @@ struct SelectArgs {
     int32_t nw;  // bitmap words reserved per bitmap
     int32_t idx_rows, idx_row0;  // idx_out holds rows [idx_row0, idx_row0+idx_rows) of every batch element
     int32_t sampled;             // allow the sampled one-pass path
+    const int32_t* seq_lens;     // per-sequence lengths (ragged decode) or null
 };
 
 // One-pass path for long rows with a small budget.  A strided sample of the row (16 consecutive scores
@@ -158,7 +159,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_select_kernel(SelectArgs a) 
     const int64_t rid = (int64_t)gridDim.x - 1 - blockIdx.x;  // longest rows of the slab first
     const int b = (int)(rid / R);
     const int t = a.row_begin + (int)(rid % R);
-    const int n = min(a.q_offset + t, a.Lk - 1) + 1;
+    const int n = min(batch_q_offset(a.seq_lens, b, a.q_offset, a.Lq, a.Lk) + t, a.Lk - 1) + 1;
     int m = a.n_sel[(int64_t)b * a.Lq + t];
     m = max(0, min(m, min(n, a.k_cap)));
     int32_t* out = a.idx_out + ((int64_t)b * a.idx_rows + (t - a.idx_row0)) * a.k_cap;
@@ -189,8 +190,9 @@ size_t select_lds_bytes(int Lk) {
 
 hipError_t launch_select(const gsa_shape& sh, int row_begin, int row_end, const float* scores, int64_t ld,
                          const int32_t* n_sel, int k_cap, int32_t* idx_out, int idx_rows, int idx_row0, bool exact_only,
-                         hipStream_t st) {
+                         const int32_t* seq_lens, hipStream_t st) {
     SelectArgs a;
+    a.seq_lens = seq_lens;
     a.scores = scores;
     a.ld = ld;
     a.n_sel = n_sel;
@@ -222,7 +224,7 @@ hipError_t launch_select(const gsa_shape& sh, int row_begin, int row_end, const 
 // double precision from the fp32 variance; floor before clamp, clamp before the integer conversion.
 __global__ void adaptive_k_kernel(const float* row_var, int32_t* k_out, int32_t* n_sel_out, int B, int Lq, int Lk,
                                   int q_offset, int row_begin, int row_end, double vbar, int k_base, int k_min,
-                                  int k_max, int k_fixed, int mode) {
+                                  int k_max, int k_fixed, int mode, const int32_t* seq_lens) {
     const int R = row_end - row_begin;
     const int64_t lid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (lid >= (int64_t)B * R) return;
@@ -243,16 +245,16 @@ __global__ void adaptive_k_kernel(const float* row_var, int32_t* k_out, int32_t*
         if (r > (double)k_max) r = (double)k_max;
         k = (int)r;
     }
-    const int nvis = min(q_offset + t, Lk - 1) + 1;
+    const int nvis = min(batch_q_offset(seq_lens, (int)(lid / R), q_offset, Lq, Lk) + t, Lk - 1) + 1;
     if (k_out) k_out[gid] = k;
     n_sel_out[gid] = min(k, nvis);
 }
 
 hipError_t launch_adaptive_k(const gsa_shape& sh, const gsa_adaptive& c, int row_begin, int row_end,
-                             const float* row_var, int32_t* k_out, int32_t* n_sel_out, hipStream_t st) {
+                             const float* row_var, int32_t* k_out, int32_t* n_sel_out, const int32_t* seq_lens, hipStream_t st) {
     const int64_t rows = (int64_t)sh.B * (row_end - row_begin);
     hipLaunchKernelGGL(adaptive_k_kernel, dim3((unsigned)cdiv(rows, 256)), dim3(256), 0, st, row_var, k_out, n_sel_out,
-                       sh.B, sh.Lq, sh.Lk, sh.q_offset, row_begin, row_end, (double)c.vbar, c.k_base, c.k_min, c.k_max, c.k_fixed, c.mode);
+                       sh.B, sh.Lq, sh.Lk, sh.q_offset, row_begin, row_end, (double)c.vbar, c.k_base, c.k_min, c.k_max, c.k_fixed, c.mode, seq_lens);
     return hipGetLastError();
 }
 

@@ -32,6 +32,7 @@ struct Select16Args {
     int32_t nw;
     int32_t idx_rows, idx_row0;
     int32_t hi;  // indexer heads in memory; the kernel is built for the next power of two, the extra heads weigh zero
+    const int32_t* seq_lens;  // per-sequence lengths (ragged decode) or null
 };
 
 constexpr int kKeysPerVec = 8;                                      // one 16-byte load
@@ -141,7 +142,7 @@ __global__ __launch_bounds__(kSelThreads, 4) void topk_select16_kernel(Select16A
     const int64_t rid = (int64_t)gridDim.x - 1 - blockIdx.x;  // longest rows of the slab first
     const int b = (int)(rid / R);
     const int t = a.row_begin + (int)(rid % R);
-    const int n = min(a.q_offset + t, a.Lk - 1) + 1;
+    const int n = min(batch_q_offset(a.seq_lens, b, a.q_offset, a.Lq, a.Lk) + t, a.Lk - 1) + 1;
     int m = a.n_sel[(int64_t)b * a.Lq + t];
     m = max(0, min(m, min(n, a.k_cap)));
     int32_t* out = a.idx_out + ((int64_t)b * a.idx_rows + (t - a.idx_row0)) * a.k_cap;
@@ -494,8 +495,9 @@ static hipError_t launch16_di(const Select16Args& a, int DI, int HI, size_t smem
 
 hipError_t launch_select16(const gsa_shape& sh, int row_begin, int row_end, const uint16_t* keys, int64_t ld,
                            const int32_t* n_sel, int k_cap, int32_t* idx_out, int idx_rows, int idx_row0, const void* qI,
-                           const void* kI, const float* w, const float* bI, hipStream_t st) {
+                           const void* kI, const float* w, const float* bI, const int32_t* seq_lens, hipStream_t st) {
     Select16Args a;
+    a.seq_lens = seq_lens;
     a.keys = keys;
     a.ld = ld;
     a.n_sel = n_sel;

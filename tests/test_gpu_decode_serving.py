@@ -1,0 +1,106 @@
+"""Decode-serving state: append-only caches with gated values, and decode steps over a batch of sequences of
+different lengths (the "Decode" column of Table 9 is the only place the paper touches it), against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2601_15305_amd as G
+from paper_2601_15305_amd import synthetic as S
+from oracle import gsa_oracle as O
+
+import gsa_testlib as T
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("dtype,Hkv,dh,dI", [("bf16", 4, 128, 64), ("f32", 2, 64, 32), ("bf16", 1, 64, 128)])
+def test_cache_append_writes_gated_values_at_each_sequences_end(dtype, Hkv, dh, dI):
+    B, T_, cap = 4, 3, 50
+    wl = S.Workload("append", B, T_, cap, 0, 4 * Hkv, Hkv, dh, 4, dI, dtype, 8, 4, 16, seed=5)
+    t = S.make_inputs(wl.with_(Lk=T_), "cuda")           # K, V, g2, kI of the T new tokens
+    sh = G.shape_of(wl)
+    dt = S.torch_dtype(dtype)
+    lens = torch.tensor([0, 17, cap - 1, cap - 3], dtype=torch.int32, device="cuda")
+    caches = [torch.full((B, cap, dI), 7.0, dtype=dt, device="cuda"), torch.full((B, cap, Hkv, dh), 7.0, dtype=dt, device="cuda"),
+              torch.full((B, cap, Hkv, dh), 7.0, dtype=dt, device="cuda")]
+    lens_out = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+    G.gsa_cache_append(sh, t["kI"], t["K"], t["V"], t["g2"], lens, caches[0], caches[1], caches[2], lens_out)
+    torch.cuda.synchronize()
+    assert lens_out.tolist() == [3, 20, cap, cap]
+    Vg = torch.empty_like(t["V"])
+    G.gsa_value_gate(G.shape_of(wl.with_(Lk=T_)), t["V"], t["g2"], Vg)      # the same rounding as the pre-pass
+    ref = T.to64(t["V"]) * O.sigmoid(T.to64(t["g2"]))
+    assert np.abs(T.to64(Vg) - ref).max() <= (2e-2 if dtype == "bf16" else 1e-6)
+    for b, l0 in enumerate(lens.tolist()):
+        fit = min(T_, cap - l0)
+        assert torch.equal(caches[0][b, l0:l0 + fit], t["kI"][b, :fit])
+        assert torch.equal(caches[1][b, l0:l0 + fit], t["K"][b, :fit])
+        assert torch.equal(caches[2][b, l0:l0 + fit], Vg[b, :fit])
+        for c in caches:      # everything else is untouched
+            assert (c[b, :l0] == 7.0).all() and (c[b, l0 + fit:] == 7.0).all()
+    with pytest.raises(G.GsaError):
+        G.gsa_cache_append(sh, t["kI"], t["K"], t["V"], t["g2"], lens, caches[0], caches[1], caches[2], lens)
+
+
+@pytest.mark.parametrize("Lq", [1, 3])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_decode_step_over_ragged_batch(dtype, Lq):
+    """Sequences of different lengths in one batch; the cache beyond a sequence's length holds NaN and must never
+    reach a result."""
+    B, cap = 6, 2600
+    lens = [Lq, 37, 300, 2600, 1024, 2599]
+    wl = S.Workload("ragged", B, Lq, cap, 0, 16 if dtype == "bf16" else 4, 4 if dtype == "bf16" else 2, 128 if dtype == "bf16" else 64,
+                    4, 64, dtype, 45, 16, 128, seed=23)
+    t = S.make_inputs(wl, "cuda")
+    sh = G.shape_of(wl)
+    Vg = torch.empty_like(t["V"])
+    G.gsa_value_gate(sh, t["V"], t["g2"], Vg)
+    kI_c, K_c, Vg_c = t["kI"].clone(), t["K"].clone(), Vg
+    for b, l in enumerate(lens):
+        kI_c[b, l:] = float("nan")
+        K_c[b, l:] = float("nan")
+        Vg_c[b, l:] = float("nan")
+    seq_lens = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    ctl_kw = dict(vbar=0.3, k_base=45, k_min=16, k_max=128, k_fixed=0, mode=0)
+    ctl = G.make_adaptive(0.3, 45, 16, 128)
+    out = torch.full_like(t["Q"], float("nan"))
+    idx = torch.full((B, Lq, 128), -7, dtype=torch.int32, device="cuda")
+    n_sel = torch.empty((B, Lq), dtype=torch.int32, device="cuda")
+    k = torch.empty_like(n_sel)
+    var = torch.empty((B, Lq), dtype=torch.float32, device="cuda")
+    ws = G.workspace(G.gsa_decode_workspace_bytes(sh, 128))
+    ws.fill_(0xFF)
+    G.gsa_decode_step(sh, ctl, t["Q"], t["g1"], t["qI"], t["w"], None, kI_c, K_c, Vg_c, seq_lens, 0.0, out, idx, n_sel, k, var, 128, ws)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all(), "nothing beyond a sequence's length may be read"
+    o = {name: T.to64(v) for name, v in t.items()}
+    idx_h, n_h, k_h, var_h, out_h = idx.cpu().numpy(), n_sel.cpu().numpy(), k.cpu().numpy(), var.cpu().numpy(), T.to64(out)
+    excused = 0
+    for b, l in enumerate(lens):
+        for i in range(Lq):
+            n = l - Lq + i + 1
+            I = O.indexer_scores_row(o["qI"][b, i], o["kI"][b, :n], o["w"][b, i], None)
+            _, v64 = O.row_stats(I)
+            assert abs(var_h[b, i] - v64) <= 2e-5 * v64 + 5e-8
+            T.k_band_ok(k_h[b, i:i + 1], np.array([v64]), ctl_kw)
+            assert n_h[b, i] == min(k_h[b, i], n)
+            T.check_index_row_wellformed(idx_h[b, i], n_h[b, i], n, 128)
+            excused += T.check_selection_vs_fp64(idx_h[b, i], int(n_h[b, i]), I)
+            ref, _ = O.sparse_gated_attn_row(o["Q"][b, i], o["K"][b], o["V"][b], o["g2"][b], o["g1"][b, i], idx_h[b, i, :n_h[b, i]])
+            T.check_out(out_h[b, i], ref, dtype)
+    assert excused <= 3
+    # a batch whose sequences all have the same length is the plain forward with that offset
+    same = torch.full((B,), 1500, dtype=torch.int32, device="cuda")
+    out2 = torch.empty_like(out)
+    Vg_full = torch.empty_like(t["V"])
+    G.gsa_value_gate(sh, t["V"], t["g2"], Vg_full)
+    G.gsa_decode_step(sh, ctl, t["Q"], t["g1"], t["qI"], t["w"], None, t["kI"], t["K"], Vg_full, same, 0.0, out2, None, None, None,
+                      None, 128, ws)
+    wl2 = wl.with_(Lk=1500, q_offset=1500 - Lq)
+    t2 = dict(t)
+    for name in ("K", "V", "g2", "kI"):
+        t2[name] = t[name][:, :1500].contiguous()
+    res = T.gpu_forward(wl2, t2, ctl, k_cap=128)
+    torch.cuda.synchronize()
+    assert torch.equal(out2, res["out"])
+
