@@ -50,6 +50,24 @@ def n_visible(i, q_offset, Lk):
     return min(q_offset + i, Lk - 1) + 1
 
 
+# --------------------------------------------------------------------------- projections around the path
+def linear(x, W):
+    """y = x W^T for W stored [out_features, in_features]: the form of every projection of the layer --
+    Q, K, V (Sec. 2.1 Eq. 1), q^I and k^I (Sec. 3.3), the gate logits h W^g_V and h W^g_O (Sec. 3.5), and the
+    output projection W_O applied to the gated heads (App. B).  x [..., in] -> [..., out]."""
+    x = np.asarray(x, np.float64)
+    W = np.asarray(W, np.float64)
+    out = np.zeros(x.shape[:-1] + (W.shape[0],), np.float64)
+    for o in range(W.shape[0]):
+        out[..., o] = np.sum(x * W[o], axis=-1)
+    return out
+
+
+def indexer_head_weights(h, W_Iw):
+    """w_{t,j} = sigma(h_t W^{Iw}_j) (Sec. 3.3): the per-head weights of the indexer, in (0, 1)."""
+    return sigmoid(linear(h, W_Iw))
+
+
 # --------------------------------------------------------------------------- Sec. 3.3
 def indexer_scores_row(qI_t, kI_vis, w_t, bI=None, act="sigmoid"):
     """Eq. "indexer" (Sec. 3.3) for one query: I_{t,s} = sum_j w_{t,j} sigma(q^I_{t,j}.k^I_s + b^I_j).

@@ -24,6 +24,39 @@ def _tiny(seed=0, B=2, Lq=7, Lk=7, q_offset=0, H=4, Hkv=2, dh=8, HI=3, dI=5):
         bI=r.standard_normal(HI), q_offset=q_offset)
 
 
+# ---------------------------------------------------------------- projections (Sec. 2.1 Eq. 1, Sec. 3.3, Sec. 3.5, App. B)
+def test_linear_projection_against_library_and_loops():
+    """y = x W^T: the library routine torch.nn.functional.linear in fp64, an entry-by-entry loop, and unit-vector
+    weights that must pick single input features (a transposed weight matrix fails every one of them)."""
+    r = rng(3)
+    x = r.standard_normal((2, 5, 7))
+    W = r.standard_normal((4, 7))
+    y = O.linear(x, W)
+    assert y.shape == (2, 5, 4)
+    lib = torch.nn.functional.linear(torch.from_numpy(x), torch.from_numpy(W)).numpy()
+    assert np.allclose(y, lib, rtol=1e-13, atol=1e-14)
+    for (b, t, o) in [(0, 0, 0), (1, 4, 3), (0, 2, 1)]:
+        acc = 0.0
+        for c in range(7):
+            acc += x[b, t, c] * W[o, c]
+        assert abs(y[b, t, o] - acc) < 1e-13
+    pick = np.zeros((3, 7)); pick[0, 6] = 1.0; pick[1, 0] = -2.0; pick[2, 3] = 0.5
+    yp = O.linear(x, pick)
+    assert np.array_equal(yp[..., 0], x[..., 6]) and np.array_equal(yp[..., 1], -2.0 * x[..., 0]) and np.array_equal(yp[..., 2], 0.5 * x[..., 3])
+
+
+def test_indexer_head_weights_are_sigmoids_of_a_projection():
+    """Sec. 3.3: w = sigma(h W^Iw) lies in (0,1); zero weights give exactly 1/2; the tanh identity pins the sigmoid."""
+    r = rng(4)
+    h = r.standard_normal((3, 6, 9))
+    W = r.standard_normal((4, 9))
+    w = O.indexer_head_weights(h, W)
+    assert w.shape == (3, 6, 4) and np.all(w > 0) and np.all(w < 1)
+    assert np.all(O.indexer_head_weights(h, np.zeros((4, 9))) == 0.5)
+    z = np.einsum("btc,jc->btj", h, W)
+    assert np.allclose(w, 0.5 * (1.0 + np.tanh(0.5 * z)), rtol=1e-13)
+
+
 # ---------------------------------------------------------------- Sec. 3.3 indexer
 def test_indexer_range_open_interval():
     """Sec. 3.3: every sigmoid factor is in (0,1) so I in (0, H^I); more sharply I < sum_j w_j."""
