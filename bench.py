@@ -14,6 +14,7 @@ Inputs are resident in HBM before the timed region.  Prints one JSON line:
   stages                per-stage times and rates (both forms of indexer and selection)
   one_slab              the same call with the whole problem in one slab (large workspace), for comparison
   decode_c5, c4_h_kv16  the decode configuration and the 16-kv-head reading of the 128K prefill
+  projections           the layer's input and output projections at the same token count (d_model 2048)
   cpu_baseline          the CPU oracle timed on a bounded sample of the same workload on this machine's host cores
 """
 import argparse
@@ -279,6 +280,30 @@ def comparison_variants(G, S, CM, wl, t, run, gsa_ms):
     return res
 
 
+def projections_leg(G, wl, d_model, dev):
+    """The layer's linear projections at the workload's token count (Sec. 2.1 Eq. 1, Sec. 3.3, Sec. 3.5, App. B):
+    the fused input GEMM (all eight segments) and the output projection, against the dense bf16 MFMA peak."""
+    import torch
+    sh = G.shape_of(wl.with_(Lk=wl.Lq, q_offset=0))
+    tokens = wl.B * wl.Lq
+    g = torch.Generator(device=dev).manual_seed(7)
+    h = torch.randn((wl.B, wl.Lq, d_model), generator=g, device=dev).to(torch.bfloat16)
+    widths = [wl.H * wl.d_h, wl.H_kv * wl.d_h, wl.H_kv * wl.d_h, wl.H * wl.d_h, wl.H_kv * wl.d_h, wl.HI * wl.dI, wl.dI, wl.HI]
+    W = [(torch.randn((n, d_model), generator=g, device=dev) * d_model ** -0.5).to(torch.bfloat16) for n in widths]
+    outs = [torch.empty((wl.B, wl.Lq, n), dtype=torch.float32 if i == 7 else torch.bfloat16, device=dev) for i, n in enumerate(widths)]
+    ims = timed(lambda: G.gsa_input_projections(sh, d_model, h, *W, *outs), 5)
+    W_O = (torch.randn((d_model, wl.H * wl.d_h), generator=g, device=dev) * (wl.H * wl.d_h) ** -0.5).to(torch.bfloat16)
+    y = torch.empty((wl.B, wl.Lq, d_model), dtype=torch.bfloat16, device=dev)
+    oms = timed(lambda: G.gsa_output_projection(sh, d_model, outs[0], W_O, y), 5)
+    fi = 2.0 * tokens * d_model * sum(widths)
+    fo = 2.0 * tokens * d_model * wl.H * wl.d_h
+    return {"d_model": d_model, "tokens": tokens, "input_features": sum(widths),
+            "input_ms": round(ims, 3), "input_tflops": round(fi / (ims * 1e-3) / 1e12, 1),
+            "input_frac_mfma_peak": round(fi / (ims * 1e-3) / 1e12 / PEAK_MFMA_BF16_TFLOPS, 4),
+            "output_ms": round(oms, 3), "output_tflops": round(fo / (oms * 1e-3) / 1e12, 1),
+            "output_frac_mfma_peak": round(fo / (oms * 1e-3) / 1e12 / PEAK_MFMA_BF16_TFLOPS, 4)}
+
+
 def small_leg(G, S, CM, wl, steps, warmup, workspace_gib):
     """queries/s of another configuration (fresh inputs), with the indexer's key-scan rate for decode shapes."""
     import torch
@@ -460,7 +485,9 @@ def main():
     if not args.no_extras and wl.name == "C4-128k-prefill" and not args.h_kv:
         del t, run, fused
         torch.cuda.empty_cache()
-        print("[bench] decode and 16-kv-head legs ...", file=sys.stderr, flush=True)
+        print("[bench] projections, decode and 16-kv-head legs ...", file=sys.stderr, flush=True)
+        result["projections"] = projections_leg(G, S.C4, 2048, dev)
+        torch.cuda.empty_cache()
         result["decode_c5"] = small_leg(G, S, CM, S.C5, 20, 3, args.workspace_gib)
         result["c4_h_kv16"] = small_leg(G, S, CM, S.C4.with_(H_kv=16), 3, 1, args.workspace_gib)
     print(json.dumps(result))

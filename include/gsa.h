@@ -255,6 +255,33 @@ int32_t gsa_decode_step(const gsa_shape* shape, const gsa_adaptive* ctl, const v
                         void* stream);
 size_t gsa_decode_workspace_bytes(const gsa_shape* shape, int32_t k_cap, const gsa_tuning* tuning);
 
+/* ---- the linear projections around the path (Sec. 2.1 Eq. 1, Sec. 3.3, Sec. 3.5, App. B) ------------
+ * Every projection is y = x W^T with W stored row-major [out_features, in_features], bf16 in, fp32
+ * accumulation, bf16 out (GSA_BF16 shapes only; GSA_ERR_UNSUPPORTED otherwise).  All pointers are device
+ * pointers owned by the caller; weights and inputs 16-byte aligned.
+ *
+ * gsa_input_projections: one fused GEMM over the hidden states h [B, Lq, d_model] (d_model a multiple of
+ * 64) that writes, for the B*Lq tokens of h, every input of the path in the layouts gsa_forward reads:
+ *   Q = h W_Q^T          [B, Lq, H, d_h]        W_Q  [H*d_h, d_model]       (Sec. 2.1 Eq. 1)
+ *   K, V                 [B, Lq, H_kv, d_h]     W_K, W_V [H_kv*d_h, d_model]
+ *   g1_logits = h W_g1^T [B, Lq, H, d_h]        W_g1 [H*d_h, d_model]       (output gate G1, Sec. 3.5)
+ *   g2_logits = h W_g2^T [B, Lq, H_kv, d_h]     W_g2 [H_kv*d_h, d_model]    (value gate G2, Sec. 3.5)
+ *   qI = h W_qI^T        [B, Lq, HI, dI]        W_qI [HI*dI, d_model]       (Sec. 3.3)
+ *   kI = h W_kI^T        [B, Lq, dI]            W_kI [dI, d_model]
+ *   w  = sigmoid(h W_Iw^T) [B, Lq, HI] fp32     W_Iw [HI, d_model]          (indexer head weights, Sec. 3.3)
+ * A projection is skipped when both its weight and its destination are NULL (one of the two alone:
+ * GSA_ERR_NULL).  In a prefill Lq = Lk and K, V, g2_logits, kI are the whole context; in a decode step they
+ * are the rows gsa_cache_append takes.
+ *
+ * gsa_output_projection: y = attn_out W_O^T with attn_out [B, Lq, H*d_h] (the gated heads, concatenated;
+ * H*d_h a multiple of 64), W_O [d_model, H*d_h], y [B, Lq, d_model] (App. B). */
+int32_t gsa_input_projections(const gsa_shape* shape, int32_t d_model, const void* h, const void* W_Q,
+                              const void* W_K, const void* W_V, const void* W_g1, const void* W_g2,
+                              const void* W_qI, const void* W_kI, const void* W_Iw, void* Q, void* K, void* V,
+                              void* g1_logits, void* g2_logits, void* qI, void* kI, float* w, void* stream);
+int32_t gsa_output_projection(const gsa_shape* shape, int32_t d_model, const void* attn_out, const void* W_O,
+                              void* y, void* stream);
+
 /* ---- comparison variants: dense causal attention, Sec. 2.1 Eq. 2 ------------------------------------
  * Every visible key, no indexer and no selection: with g2 and g1 given this is the "gated only" variant of
  * Sec. 7.1 (Eq. 2 with V' = V * sigmoid(g2) and the result multiplied by sigmoid(g1)), with both NULL the

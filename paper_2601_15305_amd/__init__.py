@@ -25,7 +25,7 @@ ENTRY_POINTS = (
     "gsa_indexer_scores", "gsa_indexer_keys", "gsa_indexer_workspace_bytes", "gsa_adaptive_k", "gsa_topk_select",
     "gsa_topk_select_keys", "gsa_sparse_gated_attn", "gsa_attn_workspace_bytes", "gsa_value_gate", "gsa_forward",
     "gsa_forward_workspace_bytes", "gsa_forward_noalloc", "gsa_dense_gated_attn", "gsa_dense_attn_workspace_bytes",
-    "gsa_cache_append", "gsa_decode_step", "gsa_decode_workspace_bytes",
+    "gsa_cache_append", "gsa_decode_step", "gsa_decode_workspace_bytes", "gsa_input_projections", "gsa_output_projection",
     "gsa_probe_gather", "gsa_status_string", "gsa_last_error", "gsa_version",
 )
 
@@ -91,6 +91,10 @@ def load():
     lib.gsa_forward_noalloc.restype = i32
     lib.gsa_cache_append.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.gsa_cache_append.restype = i32
+    lib.gsa_input_projections.argtypes = [shp, i32] + [vp] * 18
+    lib.gsa_input_projections.restype = i32
+    lib.gsa_output_projection.argtypes = [shp, i32, vp, vp, vp, vp]
+    lib.gsa_output_projection.restype = i32
     lib.gsa_decode_step.argtypes = [shp, ctl, vp, vp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, i32, vp, sz, tun, vp]
     lib.gsa_decode_step.restype = i32
     lib.gsa_decode_workspace_bytes.argtypes = [shp, i32, tun]
@@ -264,6 +268,19 @@ def gsa_cache_append(shape, kI_new, K_new, V_new, g2_new, seq_lens, kI_cache, K_
     rc = load().gsa_cache_append(ctypes.byref(shape), _ptr(kI_new), _ptr(K_new), _ptr(V_new), _ptr(g2_new), _ptr(seq_lens),
                                  _ptr(kI_cache), _ptr(K_cache), _ptr(Vg_cache), _ptr(seq_lens_out), _stream(stream))
     _check(rc, "gsa_cache_append")
+
+
+def gsa_input_projections(shape, d_model, h, W_Q, W_K, W_V, W_g1, W_g2, W_qI, W_kI, W_Iw, Q, K, V, g1_logits, g2_logits, qI, kI, w,
+                          stream=None):
+    rc = load().gsa_input_projections(ctypes.byref(shape), int(d_model), _ptr(h), _ptr(W_Q), _ptr(W_K), _ptr(W_V), _ptr(W_g1),
+                                      _ptr(W_g2), _ptr(W_qI), _ptr(W_kI), _ptr(W_Iw), _ptr(Q), _ptr(K), _ptr(V), _ptr(g1_logits),
+                                      _ptr(g2_logits), _ptr(qI), _ptr(kI), _ptr(w), _stream(stream))
+    _check(rc, "gsa_input_projections")
+
+
+def gsa_output_projection(shape, d_model, attn_out, W_O, y, stream=None):
+    rc = load().gsa_output_projection(ctypes.byref(shape), int(d_model), _ptr(attn_out), _ptr(W_O), _ptr(y), _stream(stream))
+    _check(rc, "gsa_output_projection")
 
 
 def gsa_decode_workspace_bytes(shape, k_cap, tuning=None):

@@ -32,6 +32,8 @@ hipError_t launch_dense_attention(const gsa_shape& sh, int row_begin, int row_en
 hipError_t launch_cache_append(const gsa_shape& sh, const void* kI_new, const void* K_new, const void* V_new, const void* g2_new,
                                const int32_t* seq_lens, void* kI_cache, void* K_cache, void* Vg_cache, int32_t* seq_lens_out,
                                hipStream_t st);
+hipError_t launch_projection(const void* x, int64_t tokens, int K, int nseg, const void* const* W, void* const* out,
+                             const int32_t* width, const int32_t* kind, hipStream_t st);
 hipError_t launch_probe_gather(const void* table, const int32_t* idx, int64_t n_idx, int waves, uint32_t* sink, hipStream_t st);
 
 static thread_local std::string g_last_error;
@@ -560,6 +562,63 @@ int32_t gsa_cache_append(const gsa_shape* shape, const void* kI_new, const void*
     hipError_t e = launch_cache_append(*shape, kI_new, K_new, V_new, g2_new, seq_lens, kI_cache, K_cache, Vg_cache, seq_lens_out,
                                        static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_cache_append");
+}
+
+// Shared by both projection entry points: d_model is the contraction length of every weight matrix.
+static int32_t check_projection(const gsa_shape* shape, int32_t d_model, const void* x) {
+    int32_t rc = check_shape(shape);
+    if (rc != GSA_OK) return rc;
+    if (!x) return GSA_ERR_NULL;
+    if (shape->dtype != GSA_BF16) return GSA_ERR_UNSUPPORTED;
+    if (d_model < 64 || d_model % 64 != 0) return GSA_ERR_UNSUPPORTED;
+    if (!aligned(x, 16)) return GSA_ERR_SHAPE;
+    return GSA_OK;
+}
+
+int32_t gsa_input_projections(const gsa_shape* shape, int32_t d_model, const void* h, const void* W_Q, const void* W_K,
+                              const void* W_V, const void* W_g1, const void* W_g2, const void* W_qI, const void* W_kI,
+                              const void* W_Iw, void* Q, void* K, void* V, void* g1_logits, void* g2_logits, void* qI, void* kI,
+                              float* w, void* stream) {
+    int32_t rc = check_projection(shape, d_model, h);
+    if (rc != GSA_OK) return rc;
+    const gsa_shape& s = *shape;
+    const void* Wm[8] = {W_Q, W_K, W_V, W_g1, W_g2, W_qI, W_kI, W_Iw};
+    void* dst[8] = {Q, K, V, g1_logits, g2_logits, qI, kI, w};
+    const int32_t feat[8] = {s.H * s.d_h, s.H_kv * s.d_h, s.H_kv * s.d_h, s.H * s.d_h, s.H_kv * s.d_h, s.HI * s.dI, s.dI, s.HI};
+    const void* Wu[8];
+    void* du[8];
+    int32_t width[8], kind[8];
+    int n = 0;
+    for (int i = 0; i < 8; ++i) {
+        if (!Wm[i] && !dst[i]) continue;              // a projection that is not asked for
+        if (!Wm[i] || !dst[i]) return GSA_ERR_NULL;   // weights without a destination, or the reverse
+        if (!aligned(Wm[i], 16) || !aligned(dst[i], 8)) return GSA_ERR_SHAPE;
+        Wu[n] = Wm[i];
+        du[n] = dst[i];
+        width[n] = feat[i];
+        kind[n] = i == 7 ? 1 : 0;
+        ++n;
+    }
+    if (n == 0) return GSA_ERR_NULL;
+    hipError_t e = launch_projection(h, (int64_t)s.B * s.Lq, d_model, n, Wu, du, width, kind, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_input_projections");
+}
+
+int32_t gsa_output_projection(const gsa_shape* shape, int32_t d_model, const void* attn_out, const void* W_O, void* y,
+                              void* stream) {
+    int32_t rc = check_shape(shape);
+    if (rc != GSA_OK) return rc;
+    if (!attn_out || !W_O || !y) return GSA_ERR_NULL;
+    if (shape->dtype != GSA_BF16) return GSA_ERR_UNSUPPORTED;
+    const int32_t Kc = shape->H * shape->d_h;         // contraction over the concatenated heads
+    if (d_model < 1 || Kc % 64 != 0) return GSA_ERR_UNSUPPORTED;
+    if (!aligned(attn_out, 16) || !aligned(W_O, 16) || !aligned(y, 8)) return GSA_ERR_SHAPE;
+    const void* Wu[1] = {W_O};
+    void* du[1] = {y};
+    const int32_t width[1] = {d_model}, kind[1] = {0};
+    hipError_t e = launch_projection(attn_out, (int64_t)shape->B * shape->Lq, Kc, 1, Wu, du, width, kind,
+                                     static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_output_projection");
 }
 
 int32_t gsa_forward_noalloc(const gsa_shape* shape, const gsa_adaptive* ctl, const void* Q, const void* K, const void* V,
