@@ -15,6 +15,8 @@
 //      constant rows) the exact multi-pass radix select runs over the recomputed scores instead.
 // Two recomputed scores can differ from the indexer's own by fp32 rounding only, i.e. only keys within
 // about 1e-7 (relative) of a bin edge or of each other can be ordered differently.
+#include <algorithm>
+
 #include "select_common.hpp"
 
 namespace gsa {
@@ -33,7 +35,13 @@ struct Select16Args {
     int32_t idx_rows, idx_row0;
     int32_t hi;  // indexer heads in memory; the kernel is built for the next power of two, the extra heads weigh zero
     const int32_t* seq_lens;  // per-sequence lengths (ragged decode) or null
+    int32_t cap;          // wave-per-row kernel: records a row can hold in LDS
+    int32_t only_marked;  // workgroup-per-row kernel: take only the rows the wave-per-row kernel left marked
 };
+
+// First entry of an output row that the wave-per-row kernel could not finish (never a valid index, and not the
+// -1 of an unused entry): the workgroup-per-row kernel, launched afterwards, takes exactly these rows.
+constexpr int32_t kRowDeferred = -2;
 
 constexpr int kKeysPerVec = 8;                                      // one 16-byte load
 constexpr int kBatch16 = kSelThreads * kKeysPerVec * kVecPerBatch;  // keys per batch of a workgroup
@@ -146,6 +154,7 @@ __global__ __launch_bounds__(kSelThreads, 4) void topk_select16_kernel(Select16A
     int m = a.n_sel[(int64_t)b * a.Lq + t];
     m = max(0, min(m, min(n, a.k_cap)));
     int32_t* out = a.idx_out + ((int64_t)b * a.idx_rows + (t - a.idx_row0)) * a.k_cap;
+    if (a.only_marked && out[0] != kRowDeferred) return;  // finished by the wave-per-row kernel (same for all threads)
     if (m == n || m == 0) {
         for (int j = tid; j < a.k_cap; j += kSelThreads) out[j] = j < m ? j : -1;
         return;
@@ -454,6 +463,401 @@ __global__ __launch_bounds__(kSelThreads, 4) void topk_select16_kernel(Select16A
     emit_selection(out, a.k_cap, m, n, bm_sel, with_ties ? L.region2 : nullptr, m_eq, scan64);
 }
 
+
+// ------------------------------------------------------------------------------------------------------------
+// Wave-per-row form of the same selection: one 64-lane workgroup per query row and no barriers between waves,
+// so that several rows per compute unit are in flight and the latency-bound steps of one row overlap the
+// streaming of the others.  Steps (all wave-synchronous):
+//   1. a strided sample of at most 8192 keys (quads of lanes read 32 consecutive keys out of every P; the whole
+//      row when it has at most 8192 keys) is counted into a 4096-bin histogram of the top 12 key bits (16-bit
+//      counters, two per LDS word); the bin holding the r-th largest sample key, r a 3-sigma upper estimate of
+//      the rank the m-th largest key of the row has in the sample, gives a conservative threshold thr;
+//   2. one stream over the row.  Stage A, per 16-byte vector: lanes whose vector holds a key >= thr push the
+//      vector and its first index into a ring in LDS, behind those of the lower lanes (ballot prefix).  Stage B,
+//      whenever 64 vectors wait: one lane per vector expands it into 32-bit records
+//      {min(key - thr + 1, 8191) << 19 | index}, placed after the records of the lower lanes.  The wave walks
+//      the row in order, so the record list is sorted by index;
+//   3. the exact threshold among the records: a 2048-bin histogram of the top 11 bits of the 13-bit relative
+//      key, then the last two bits; keys above it are taken, keys equal to it are ordered by their recomputed
+//      fp32 scores (as in the workgroup-per-row kernel) when only some of them fit;
+//   4. the taken records are written out in list order, which is ascending index order: no bitmap, no sort.
+// A row the estimate fails on (too many or too few candidates, thr = 0, a threshold inside the saturated
+// relative keys, more than kWaveTieCap keys at the threshold) is marked kRowDeferred and left to the
+// workgroup-per-row kernel, which is exact for every input.
+constexpr int kWaveSampleVec = 16;   // 16-byte vectors of the sample a lane holds: 8192 sampled keys at most
+constexpr int kWaveSampleKeys = 64 * kWaveSampleVec * kKeysPerVec;
+constexpr int kWaveStreamVec = 16;   // 16-byte vectors per lane in one batch of the stream (two batches in flight)
+constexpr int kWaveBatch = 64 * kWaveStreamVec * kKeysPerVec;
+constexpr int kWaveQueue = 128;      // ring of vectors waiting for stage B (a power of two, at least 2 * 64)
+constexpr uint32_t kRelMax = 8191;   // relative keys saturate here (13 bits); index field: 19 bits
+constexpr int kWaveTieCap = 256;
+constexpr int kWaveHistWords = 1024; // the record histogram: 2048 bins of 16 bits; during the stream, the ring
+static_assert(GSA_SELECT_MAX_LK <= (1 << 19), "record index field");
+static_assert(kWaveQueue * 5 <= kWaveHistWords, "the ring lives where the record histogram will be");
+
+__device__ __forceinline__ uint32_t pk_min_u16(uint32_t x, uint32_t y) {
+    uint32_t d;
+    asm("v_pk_min_u16 %0, %1, %2" : "=v"(d) : "v"(x), "v"(y));
+    return d;
+}
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t x, uint32_t y) {
+    uint32_t d;
+    asm("v_pk_max_u16 %0, %1, %2" : "=v"(d) : "v"(x), "v"(y));
+    return d;
+}
+// number of set bits of a wave mask in the lanes below this one
+__device__ __forceinline__ uint32_t lanes_below(unsigned long long mask) {
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+// inclusive sum over this lane and all higher lanes
+__device__ __forceinline__ uint32_t wave_suffix_sum(uint32_t x, int lane) {
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t v = __shfl_down(x, o, 64);
+        if (lane + o < 64) x += v;
+    }
+    return x;
+}
+// Exclusive prefix sum over the lanes of a small per-lane count (< 2^BITS), and the wave total, from ballots of
+// the count's bit planes (planes nobody has set cost one branch).
+template <int BITS>
+__device__ __forceinline__ uint32_t wave_prefix_small(uint32_t cnt, uint32_t* total_out) {
+    uint32_t below = 0, total = 0;
+#pragma unroll
+    for (int bit = 0; bit < BITS; ++bit) {
+        const unsigned long long plane = __ballot((cnt >> bit) & 1u);
+        if (plane != 0ull) {
+            below += lanes_below(plane) << bit;
+            total += (uint32_t)__popcll(plane) << bit;
+        }
+    }
+    *total_out = total;
+    return below;
+}
+
+// Wave-wide search in a histogram of NBINS 16-bit counters (two per word, bin b in half b & 1 of word b >> 1):
+// the largest bin b with sum_{b' >= b} count[b'] >= need, and above = sum_{b' > b} count[b'].  Returns -1 when
+// the histogram holds fewer than `need` elements.  The same result in every lane.
+template <int NBINS>
+__device__ __forceinline__ int wave_find_bin(const uint32_t* hist, uint32_t need, int lane, uint32_t* above_out) {
+    constexpr int BPL = NBINS / 64;  // bins per lane
+    constexpr int WPL = BPL / 2;     // words per lane
+    uint32_t own = 0;
+#pragma unroll
+    for (int i = 0; i < WPL / 4; ++i) {
+        const u32x4 v = *reinterpret_cast<const u32x4*>(hist + lane * WPL + 4 * i);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) own = __builtin_amdgcn_sad_u16(v[e], 0u, own);
+    }
+    const uint32_t suf = wave_suffix_sum(own, lane);  // decreasing with the lane
+    const unsigned long long ok = __ballot(suf >= need);
+    if (ok == 0ull) return -1;
+    const int owner = 63 - __clzll(ok);
+    const uint32_t above_owner = __shfl(suf - own, owner, 64);
+    uint32_t c = 0;
+    if (lane < BPL) {
+        const int bin = owner * BPL + lane;
+        c = (hist[bin >> 1] >> ((bin & 1) * 16)) & 0xffffu;
+    }
+    const uint32_t suf2 = wave_suffix_sum(c, lane) + above_owner;
+    const unsigned long long ok2 = __ballot(lane < BPL && suf2 >= need);
+    const int j = 63 - __clzll(ok2);  // ok2 != 0: the owner's first bin reaches suf >= need
+    *above_out = __shfl(suf2 - c, j, 64);
+    return owner * BPL + j;
+}
+
+template <typename T, int DI, int HI>
+__global__ __launch_bounds__(64) void topk_select16_wave_kernel(Select16Args a) {
+    extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+    uint32_t* rec = lds;            // a.cap records; before the stream, the sample histogram (2048 words)
+    uint32_t* aux = lds + a.cap;    // the ring, then the record histogram, then the query, tie list and tie scores
+    const int aux_words = max(kWaveHistWords, HI * DI + 2 * HI + 2 * kWaveTieCap);
+    uint32_t* sub = aux + aux_words;  // 8 words: counters of the last two key bits
+
+    const int lane = threadIdx.x;
+    const int R = a.row_end - a.row_begin;
+    const int64_t rid = (int64_t)gridDim.x - 1 - blockIdx.x;  // longest rows of the slab first
+    const int b = (int)(rid / R);
+    const int t = a.row_begin + (int)(rid % R);
+    const int n = min(batch_q_offset(a.seq_lens, b, a.q_offset, a.Lq, a.Lk) + t, a.Lk - 1) + 1;
+    int m = a.n_sel[(int64_t)b * a.Lq + t];
+    m = max(0, min(m, min(n, a.k_cap)));
+    int32_t* out = a.idx_out + ((int64_t)b * a.idx_rows + (t - a.idx_row0)) * a.k_cap;
+    if (m == n || m == 0) {
+        for (int j = lane; j < a.k_cap; j += 64) out[j] = j < m ? j : -1;
+        return;
+    }
+    const uint16_t* krow = a.keys + ((int64_t)b * R + (t - a.row_begin)) * a.ld;
+    const uint32_t cap = (uint32_t)a.cap;
+    auto defer = [&]() {
+        if (lane == 0) out[0] = kRowDeferred;
+    };
+
+    // The query's indexer heads, needed when keys tie at the threshold (most rows): requested now, parked in LDS
+    // only if that happens.
+    constexpr int QPL = (HI * DI + 63) / 64;
+    float qreg[QPL];
+    float wreg = 0.f, nbreg = 0.f;
+#pragma unroll
+    for (int i = 0; i < QPL; ++i) {
+        const int c = lane + i * 64;
+        qreg[i] = c < a.hi * DI ? (float)static_cast<const T*>(a.qI)[((int64_t)b * a.Lq + t) * a.hi * DI + c] : 0.f;
+    }
+    if (lane < a.hi) {
+        wreg = a.w[((int64_t)b * a.Lq + t) * a.hi + lane];
+        nbreg = a.bI ? -kLog2e * a.bI[lane] : 0.f;
+    }
+
+    // ---- 1. sample histogram and conservative threshold ------------------------------------------------------
+    const int P = 32 * ((n + kWaveSampleKeys - 1) / kWaveSampleKeys);  // keys from one sampled quad to the next
+    {
+        u32x4 sv[kWaveSampleVec];
+        const int sb0 = (lane >> 2) * P + (lane & 3) * 8;  // rows are padded to a multiple of 32 keys
+#pragma unroll
+        for (int u = 0; u < kWaveSampleVec; ++u) {
+            const int sb = sb0 + u * 16 * P;
+            sv[u] = sb < n ? *reinterpret_cast<const u32x4*>(krow + sb) : u32x4{0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) reinterpret_cast<u32x4*>(rec)[i * 64 + lane] = u32x4{0, 0, 0, 0};  // 2048 words
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < kWaveSampleVec; ++u) {
+            const int sb = sb0 + u * 16 * P;
+            if (sb < n) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const uint32_t key = (sv[u][e >> 1] >> ((e & 1) * 16)) & 0xffffu;
+                    const uint32_t one = (key & 16u) ? 0x10000u : 1u;
+                    atomicAdd(&rec[key >> 5], sb + e < n ? one : 0u);
+                }
+            }
+        }
+        __syncthreads();
+    }
+    const int ms = (n / P) * 32 + min(32, n % P);  // sampled keys
+    uint32_t r = (uint32_t)m;
+    if (P > 32) {
+        const float lam = (float)m * (float)ms / (float)n;
+        r = (uint32_t)ceilf(lam + 3.0f * sqrtf(lam) + 2.0f);
+    }
+    uint32_t above;
+    const int b_lo = (int)r <= ms ? wave_find_bin<4096>(rec, r, lane, &above) : -1;
+    if (b_lo <= 0) {  // thr = 0 would make every key a candidate
+        defer();
+        return;
+    }
+    const uint32_t thr = (uint32_t)b_lo << 4;
+    __syncthreads();  // the histogram has been read; the records take its place
+
+    // ---- 2. stream: the records of all keys >= thr, in index order ----------------------------------------------
+    // key >= thr  <=>  the saturating 16-bit difference key - (thr - 1) is not zero (it is the relative key)
+    const uint32_t thr2 = (thr - 1) * 0x00010001u;
+    u32x4* qv = reinterpret_cast<u32x4*>(aux);  // ring: the waiting vectors ...
+    uint32_t* qk = aux + 4 * kWaveQueue;        // ... and the index of their first key
+    uint32_t nrec = 0, qhead = 0, qtail = 0;    // wave-uniform
+
+    // Stage B: the first `count` vectors of the ring, one lane each.
+    auto expand = [&](uint32_t count) {
+        __syncthreads();  // the ring entries written by other lanes
+        u32x4 v = u32x4{0, 0, 0, 0};
+        uint32_t kb = 0;
+        if ((uint32_t)lane < count) {
+            const uint32_t slot = (qhead + (uint32_t)lane) & (kWaveQueue - 1);
+            v = qv[slot];
+            kb = qk[slot];
+        }
+        uint32_t d[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) d[i] = pk_sub_sat_u16(v[i], thr2);
+        // bit 2i of mm: the low key of word i is a candidate; bit 16 + 2i: its high key
+        const uint32_t mm = pk_min_u16(d[0], 0x00010001u) | (pk_min_u16(d[1], 0x00010001u) << 2) |
+                            (pk_min_u16(d[2], 0x00010001u) << 4) | (pk_min_u16(d[3], 0x00010001u) << 6);
+        uint32_t mask8 = (mm | (mm >> 15)) & 0xffu;  // bit e: key kb + e is a candidate
+        uint32_t total;
+        uint32_t pos = nrec + wave_prefix_small<4>(__popc(mask8), &total);
+        while (__ballot(mask8 != 0u) != 0ull) {
+            if (mask8 != 0u) {
+                const uint32_t e = (uint32_t)__ffs(mask8) - 1u;
+                const uint32_t dw = (e & 4u) ? ((e & 2u) ? d[3] : d[2]) : ((e & 2u) ? d[1] : d[0]);
+                const uint32_t rel = min((dw >> ((e & 1u) * 16)) & 0xffffu, kRelMax);
+                if (pos < cap) rec[pos] = (rel << 19) | (kb + e);
+                ++pos;
+                mask8 &= mask8 - 1u;
+            }
+        }
+        nrec += total;
+        qhead += count;
+    };
+    // Stage A over one batch held in registers.
+    auto consume = [&](const u32x4* buf, int b0) {
+#pragma unroll
+        for (int u = 0; u < kWaveStreamVec; ++u) {
+            const int w0 = b0 + u * 64 * kKeysPerVec;  // first key of this wave-wide vector
+            if (w0 >= n) break;
+            const int kb = w0 + lane * kKeysPerVec;
+            u32x4 v = buf[u];
+            if (w0 + 64 * kKeysPerVec > n) {  // the vector holding the end of the row: keys beyond it count as zero
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int k0 = kb + 2 * i;
+                    if (k0 + 1 >= n) v[i] = k0 >= n ? 0u : (v[i] & 0xffffu);
+                }
+            }
+            const uint32_t mx = pk_max_u16(pk_max_u16(v[0], v[1]), pk_max_u16(v[2], v[3]));
+            const bool hit = pk_sub_sat_u16(mx, thr2) != 0u;
+            const unsigned long long H = __ballot(hit);
+            if (H == 0ull) continue;
+            if (hit) {
+                const uint32_t slot = (qtail + lanes_below(H)) & (kWaveQueue - 1);
+                qv[slot] = v;
+                qk[slot] = (uint32_t)kb;
+            }
+            qtail += (uint32_t)__popcll(H);
+            if (qtail - qhead >= 64u) expand(64u);  // at most 127 entries were waiting: the ring never overflows
+        }
+    };
+    // Loads of a batch; a vector beyond the row reads the row's last vector instead (and is never looked at).
+    const int last_vec = ((n - 1) / kKeysPerVec) * kKeysPerVec;
+    auto load = [&](int b0, u32x4* v) {
+#pragma unroll
+        for (int u = 0; u < kWaveStreamVec; ++u) {
+            const int base = min(b0 + (u * 64 + lane) * kKeysPerVec, last_vec);
+            v[u] = *reinterpret_cast<const u32x4*>(krow + base);
+        }
+    };
+    {
+        u32x4 bufA[kWaveStreamVec], bufB[kWaveStreamVec];
+        load(0, bufA);
+        for (int b0 = 0; b0 < n; b0 += 2 * kWaveBatch) {
+            if (b0 + kWaveBatch < n) load(b0 + kWaveBatch, bufB);
+            consume(bufA, b0);
+            if (b0 + kWaveBatch >= n) break;
+            if (b0 + 2 * kWaveBatch < n) load(b0 + 2 * kWaveBatch, bufA);
+            consume(bufB, b0 + kWaveBatch);
+        }
+    }
+    if (qtail != qhead) expand(qtail - qhead);
+    if (nrec > cap || nrec < (uint32_t)m) {  // the estimate failed (either way)
+        defer();
+        return;
+    }
+    __syncthreads();  // records complete; the ring is dead
+
+    // ---- 3. exact threshold among the records ---------------------------------------------------------------------
+#pragma unroll
+    for (int i = 0; i < kWaveHistWords / 256; ++i) reinterpret_cast<u32x4*>(aux)[i * 64 + lane] = u32x4{0, 0, 0, 0};
+    if (lane < 8) sub[lane] = 0;
+    __syncthreads();
+    for (uint32_t c0 = lane * 4; c0 < nrec; c0 += 256) {  // cap is a multiple of 4: the read stays inside rec
+        const u32x4 rv = *reinterpret_cast<const u32x4*>(rec + c0);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t bin = rv[e] >> 21;  // top 11 bits of the relative key
+            if (c0 + e < nrec) atomicAdd(&aux[bin >> 1], (bin & 1u) ? 0x10000u : 1u);
+        }
+    }
+    __syncthreads();
+    const int b1 = wave_find_bin<2048>(aux, (uint32_t)m, lane, &above);  // >= 0: nrec >= m
+    uint32_t need = (uint32_t)m - above;  // to take among the records of bin b1
+    for (uint32_t c0 = lane * 4; c0 < nrec; c0 += 256) {
+        const u32x4 rv = *reinterpret_cast<const u32x4*>(rec + c0);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t rel = rv[e] >> 19;
+            if (c0 + e < nrec && (rel >> 2) == (uint32_t)b1) atomicAdd(&sub[rel & 3u], 1u);
+        }
+    }
+    __syncthreads();
+    uint32_t Tq = 0, ne = 0;  // relative key of the threshold, records that carry it
+    for (int s = 3; s >= 0; --s) {
+        ne = sub[s];
+        if (need <= ne) {
+            Tq = ((uint32_t)b1 << 2) | (uint32_t)s;
+            break;
+        }
+        need -= ne;
+    }
+    if (Tq >= kRelMax || (need < ne && ne > (uint32_t)kWaveTieCap)) {  // saturated keys cannot be ordered here
+        defer();
+        return;
+    }
+    __syncthreads();  // aux is reused
+
+    // ---- 3b. only some of the keys at the threshold fit: order them by their recomputed fp32 scores ------------------
+    uint32_t take_from = Tq;  // records with a relative key >= take_from are taken
+    if (need < ne) {
+        float* q_lds = reinterpret_cast<float*>(aux);  // HI*DI query values, then HI weights, HI biases
+        float* w_lds = q_lds + HI * DI;
+        float* nb_lds = w_lds + HI;
+        uint32_t* tie_pos = aux + HI * DI + 2 * HI;
+        float* tie_score = reinterpret_cast<float*>(tie_pos + kWaveTieCap);
+#pragma unroll
+        for (int i = 0; i < QPL; ++i) {
+            const int c = lane + i * 64;
+            if (c < HI * DI) q_lds[c] = qreg[i];
+        }
+        if (lane < HI) {
+            w_lds[lane] = wreg;
+            nb_lds[lane] = nbreg;
+        }
+        uint32_t tn = 0;
+        for (uint32_t c0 = 0; c0 < nrec; c0 += 256) {  // list order = index order (a lane holds 4 consecutive records)
+            const uint32_t c = c0 + lane * 4;
+            u32x4 rv = u32x4{0, 0, 0, 0};
+            if (c < nrec) rv = *reinterpret_cast<const u32x4*>(rec + c);
+            uint32_t tm = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) tm |= (c + e < nrec && (rv[e] >> 19) == Tq) ? (1u << e) : 0u;
+            uint32_t total;
+            uint32_t o = tn + wave_prefix_small<3>(__popc(tm), &total);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (tm & (1u << e)) tie_pos[o++] = c + e;
+            tn += total;
+        }
+        __syncthreads();
+        const T* kbase = static_cast<const T*>(a.kI) + (int64_t)b * a.Lk * DI;
+        for (uint32_t i = lane; i < ne; i += 64) {
+            const uint32_t si = rec[tie_pos[i]] & 0x7ffffu;
+            tie_score[i] = recompute_score<T, DI, HI>(kbase + (int64_t)si * DI, q_lds, w_lds, nb_lds);
+        }
+        __syncthreads();
+        for (uint32_t i = lane; i < ne; i += 64) {
+            const float si = tie_score[i];
+            uint32_t rank = 0;
+            for (uint32_t j = 0; j < ne; ++j) {
+                const float sj = tie_score[j];
+                rank += (sj > si || (sj == si && j < i)) ? 1u : 0u;  // equal scores: lowest index first
+            }
+            if (rank < need) rec[tie_pos[i]] |= kRelMax << 19;  // now above the threshold (Tq < kRelMax)
+        }
+        __syncthreads();
+        take_from = Tq + 1;
+    }
+
+    // ---- 4. the taken records, in list order ----------------------------------------------------------------------
+    uint32_t wpos = 0;
+    for (uint32_t c0 = 0; c0 < nrec; c0 += 256) {
+        const uint32_t c = c0 + lane * 4;
+        u32x4 rv = u32x4{0, 0, 0, 0};
+        if (c < nrec) rv = *reinterpret_cast<const u32x4*>(rec + c);
+        uint32_t sm = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) sm |= (c + e < nrec && (rv[e] >> 19) >= take_from) ? (1u << e) : 0u;
+        uint32_t total;
+        uint32_t o = wpos + wave_prefix_small<3>(__popc(sm), &total);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (sm & (1u << e)) {
+                if (o < (uint32_t)a.k_cap) out[o] = (int32_t)(rv[e] & 0x7ffffu);
+                ++o;
+            }
+        wpos += total;
+    }
+    for (int j = m + lane; j < a.k_cap; j += 64) out[j] = -1;
+}
+
 static int kernel_heads16(int hi) { return hi <= 1 ? 1 : (hi <= 2 ? 2 : (hi <= 4 ? 4 : 8)); }
 
 size_t select16_lds_bytes(const gsa_shape& sh) {
@@ -463,13 +867,37 @@ size_t select16_lds_bytes(const gsa_shape& sh) {
     return (size_t)(kRegion0_16 + nw + r2 + 32 + HIK * sh.dI + 2 * HIK) * sizeof(uint32_t);
 }
 
+// Records a row can hold in the wave-per-row kernel.  The candidates of a row with budget m number about
+// 1.2 m +- 0.07 m (sampled one key in 16); 11/8 of the largest budget leaves 2.6 sigma.  Budgets up to 2048:
+// eight workgroups of 20 KB per compute unit; 4096: six.
+static int wave_record_cap(int k_cap) { return k_cap <= 2048 ? 4088 : std::min((k_cap * 11 / 8 + 3) & ~3, 14336); }
+static size_t wave_lds_bytes(int k_cap, int HIK, int DI) {
+    const int aux_words = std::max(kWaveHistWords, HIK * DI + 2 * HIK + 2 * kWaveTieCap);
+    return (size_t)(wave_record_cap(k_cap) + aux_words + 8) * sizeof(uint32_t);
+}
+
+// Both kernels, one after the other on the stream: the wave-per-row kernel finishes nearly every row, the
+// workgroup-per-row kernel then takes the rows left marked (its other workgroups leave at once).
 template <typename T, int DI, int HI>
-static hipError_t launch16_one(const Select16Args& a, size_t smem, int64_t rows, hipStream_t st) {
-    auto kern = topk_select16_kernel<T, DI, HI>;
-    if (smem > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+static hipError_t launch16_one(const Select16Args& a0, size_t smem, int64_t rows, hipStream_t st) {
+    Select16Args a = a0;
+    auto wave = topk_select16_wave_kernel<T, DI, HI>;
+    const size_t wsmem = wave_lds_bytes(a.k_cap, HI, DI);
+    if (wsmem > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(wave), hipFuncAttributeMaxDynamicSharedMemorySize, (int)wsmem);
         if (e != hipSuccess) return e;
     }
+    a.cap = wave_record_cap(a.k_cap);
+    a.only_marked = 0;
+    hipLaunchKernelGGL(wave, dim3((unsigned)rows), dim3(64), wsmem, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    auto kern = topk_select16_kernel<T, DI, HI>;
+    if (smem > 48 * 1024) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+    }
+    a.only_marked = 1;
     hipLaunchKernelGGL(kern, dim3((unsigned)rows), dim3(kSelThreads), smem, st, a);
     return hipGetLastError();
 }
