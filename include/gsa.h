@@ -99,6 +99,9 @@ typedef struct gsa_tuning {
     int32_t select_exact_only;   /* 1 = gsa_topk_select never takes its sampled one-pass variant */
     int32_t forward_fp32_scores; /* 1 = gsa_forward keeps fp32 scores between indexer and selection, not 16-bit keys */
     int32_t attn_rows_per_wave;  /* query rows one wave of the bf16 attention streams through: 0 = chosen by the library, else 1..64 */
+    int32_t select_wave_min_rows; /* selection on 16-bit keys: calls with at least this many rows (B * rows in range) run
+                                    one wave per row (rows the estimate fails on fall back), smaller calls one workgroup
+                                    per row: 0 = chosen by the library (2048), 1 = always a wave per row, -1 = never */
 } gsa_tuning;
 
 /* ---- stage 1: gated lightning indexer, Sec. 3.3, Eq. "indexer" ----------------------
@@ -162,7 +165,8 @@ int32_t gsa_topk_select(const gsa_shape* shape, int32_t row_begin, int32_t row_e
  * fp32 scores except between scores that agree to within fp32 rounding (about 1e-7 relative). */
 int32_t gsa_topk_select_keys(const gsa_shape* shape, int32_t row_begin, int32_t row_end, const uint16_t* keys,
                              int64_t ld_keys, const int32_t* n_sel, int32_t k_cap, int32_t* idx_out,
-                             const void* qI, const void* kI, const float* w, const float* bI, void* stream);
+                             const void* qI, const void* kI, const float* w, const float* bI,
+                             const gsa_tuning* tuning, void* stream);
 
 /* ---- stage 4: sparse attention with value gate G2 and output gate G1, Sec. 3.5-3.6 --
  * For query head h (kv head g = h / (H/H_kv)) over S_t = idx[b,t,0:n_sel[b,t]]:

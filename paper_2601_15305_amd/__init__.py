@@ -40,7 +40,7 @@ class GsaAdaptive(ctypes.Structure):
 
 class GsaTuning(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("attn_window", "attn_kv_per_wg", "select_exact_only", "forward_fp32_scores",
-                                                  "attn_rows_per_wave")]
+                                                  "attn_rows_per_wave", "select_wave_min_rows")]
 
 
 class GsaError(RuntimeError):
@@ -69,7 +69,7 @@ def load():
     lib.gsa_indexer_scores.restype = i32
     lib.gsa_indexer_keys.argtypes = [shp, vp, vp, vp, vp, i32, i32, vp, i64, vp, vp, vp, sz, vp]
     lib.gsa_indexer_keys.restype = i32
-    lib.gsa_topk_select_keys.argtypes = [shp, i32, i32, vp, i64, vp, i32, vp, vp, vp, vp, vp, vp]
+    lib.gsa_topk_select_keys.argtypes = [shp, i32, i32, vp, i64, vp, i32, vp, vp, vp, vp, vp, tun, vp]
     lib.gsa_topk_select_keys.restype = i32
     lib.gsa_probe_gather.argtypes = [vp, i64, vp, i64, i32, vp, vp]
     lib.gsa_probe_gather.restype = i32
@@ -148,9 +148,11 @@ def make_adaptive(vbar, k_base, k_min, k_max, k_fixed=0, mode=0, dense_below=0):
     return GsaAdaptive(float(vbar), k_base, k_min, k_max, k_fixed, mode, dense_below)
 
 
-def make_tuning(attn_window=0, attn_kv_per_wg=0, select_exact_only=0, forward_fp32_scores=0, attn_rows_per_wave=0):
+def make_tuning(attn_window=0, attn_kv_per_wg=0, select_exact_only=0, forward_fp32_scores=0, attn_rows_per_wave=0,
+                select_wave_min_rows=0):
     """gsa_tuning: launch-shape switches (0 = the library decides).  Pass None for all defaults."""
-    return GsaTuning(attn_window, attn_kv_per_wg, select_exact_only, forward_fp32_scores, attn_rows_per_wave)
+    return GsaTuning(attn_window, attn_kv_per_wg, select_exact_only, forward_fp32_scores, attn_rows_per_wave,
+                     select_wave_min_rows)
 
 
 def _tun(tuning):
@@ -190,9 +192,9 @@ def gsa_indexer_keys(shape, qI, kI, w, bI, row_begin, row_end, keys, ld_keys, ro
     _check(rc, "gsa_indexer_keys")
 
 
-def gsa_topk_select_keys(shape, row_begin, row_end, keys, ld_keys, n_sel, k_cap, idx_out, qI, kI, w, bI, stream=None):
+def gsa_topk_select_keys(shape, row_begin, row_end, keys, ld_keys, n_sel, k_cap, idx_out, qI, kI, w, bI, tuning=None, stream=None):
     rc = load().gsa_topk_select_keys(ctypes.byref(shape), row_begin, row_end, _ptr(keys), ld_keys, _ptr(n_sel), k_cap,
-                                     _ptr(idx_out), _ptr(qI), _ptr(kI), _ptr(w), _ptr(bI), _stream(stream))
+                                     _ptr(idx_out), _ptr(qI), _ptr(kI), _ptr(w), _ptr(bI), _tun(tuning), _stream(stream))
     _check(rc, "gsa_topk_select_keys")
 
 

@@ -18,7 +18,8 @@ hipError_t launch_select(const gsa_shape& sh, int row_begin, int row_end, const 
                          const int32_t* seq_lens, hipStream_t st);
 hipError_t launch_select16(const gsa_shape& sh, int row_begin, int row_end, const uint16_t* keys, int64_t ld,
                            const int32_t* n_sel, int k_cap, int32_t* idx_out, int idx_rows, int idx_row0, const void* qI,
-                           const void* kI, const float* w, const float* bI, const int32_t* seq_lens, hipStream_t st);
+                           const void* kI, const float* w, const float* bI, const int32_t* seq_lens, int wave_min_rows,
+                           hipStream_t st);
 hipError_t launch_adaptive_k(const gsa_shape& sh, const gsa_adaptive& c, int row_begin, int row_end,
                              const float* row_var, int32_t* k_out, int32_t* n_sel_out, const int32_t* seq_lens, hipStream_t st);
 hipError_t launch_value_gate(const gsa_shape& sh, const void* V, const void* g2, void* Vg, hipStream_t st);
@@ -81,7 +82,7 @@ static int32_t check_ctl(const gsa_adaptive* c) {
 // The selection kernels keep two bitmaps of a row in LDS: beyond this context length they do not fit.
 static int32_t check_select_len(const gsa_shape* s) { return s->Lk > GSA_SELECT_MAX_LK ? GSA_ERR_UNSUPPORTED : GSA_OK; }
 
-static const gsa_tuning kDefaultTuning = {0, 0, 0, 0, 0};
+static const gsa_tuning kDefaultTuning = {0, 0, 0, 0, 0, 0};
 static const gsa_tuning& tuning_or_default(const gsa_tuning* t) { return t ? *t : kDefaultTuning; }
 
 static bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -231,7 +232,8 @@ static int32_t forward_launches(const gsa_shape& s, const gsa_adaptive& ctl, con
         int32_t* idx = own_idx ? reinterpret_cast<int32_t*>(sw + p.off_idx) : idx_out;
         const int idx_rows = own_idx ? (r1 - r0) : s.Lq;
         const int idx_row0 = own_idx ? r0 : 0;
-        e = use_keys ? launch_select16(s, r0, r1, keys, p.ld, nsel, k_cap, idx, idx_rows, idx_row0, qI, kI, w, bI, seq_lens, st)
+        e = use_keys ? launch_select16(s, r0, r1, keys, p.ld, nsel, k_cap, idx, idx_rows, idx_row0, qI, kI, w, bI, seq_lens,
+                                       tn.select_wave_min_rows, st)
                      : launch_select(s, r0, r1, scores, p.ld, nsel, k_cap, idx, idx_rows, idx_row0, tn.select_exact_only != 0,
                                      seq_lens, st);
         if (e != hipSuccess) return hip_fail(e, "gsa_forward/select");
@@ -395,7 +397,7 @@ int32_t gsa_topk_select(const gsa_shape* shape, int32_t row_begin, int32_t row_e
 
 int32_t gsa_topk_select_keys(const gsa_shape* shape, int32_t row_begin, int32_t row_end, const uint16_t* keys,
                              int64_t ld_keys, const int32_t* n_sel, int32_t k_cap, int32_t* idx_out, const void* qI,
-                             const void* kI, const float* w, const float* bI, void* stream) {
+                             const void* kI, const float* w, const float* bI, const gsa_tuning* tuning, void* stream) {
     int32_t rc = check_shape(shape);
     if (rc != GSA_OK) return rc;
     rc = check_select_len(shape);
@@ -407,7 +409,7 @@ int32_t gsa_topk_select_keys(const gsa_shape* shape, int32_t row_begin, int32_t 
     if (ld_keys < shape->Lk || (ld_keys & 7) != 0 || !aligned(keys, 16) || !aligned(qI, 16) || !aligned(kI, 16)) return GSA_ERR_SHAPE;
     if (k_cap < 1 || k_cap > 8192) return GSA_ERR_SHAPE;
     hipError_t e = launch_select16(*shape, row_begin, row_end, keys, ld_keys, n_sel, k_cap, idx_out, shape->Lq, 0, qI, kI, w,
-                                   bI, nullptr, static_cast<hipStream_t>(stream));
+                                   bI, nullptr, tuning_or_default(tuning).select_wave_min_rows, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_topk_select_keys");
 }
 

@@ -35,12 +35,13 @@ struct Select16Args {
     int32_t idx_rows, idx_row0;
     int32_t hi;  // indexer heads in memory; the kernel is built for the next power of two, the extra heads weigh zero
     const int32_t* seq_lens;  // per-sequence lengths (ragged decode) or null
-    int32_t cap;          // wave-per-row kernel: records a row can hold in LDS
-    int32_t only_marked;  // workgroup-per-row kernel: take only the rows the wave-per-row kernel left marked
+    int32_t cap;         // wave-per-row kernel: records a row can hold in LDS
+    int32_t m_lo, m_hi;  // wave-per-row kernel: this launch takes the rows with m_lo < budget <= m_hi
+    int32_t group;       // workgroup-per-row kernel: rows a workgroup looks at; 0: one row, taken unconditionally
 };
 
 // First entry of an output row that the wave-per-row kernel could not finish (never a valid index, and not the
-// -1 of an unused entry): the workgroup-per-row kernel, launched afterwards, takes exactly these rows.
+// -1 of an unused entry): the workgroup-per-row code, launched afterwards, takes exactly these rows.
 constexpr int32_t kRowDeferred = -2;
 
 constexpr int kKeysPerVec = 8;                                      // one 16-byte load
@@ -130,9 +131,9 @@ __device__ __forceinline__ float recompute_score(const T* __restrict__ krow, con
     return sc;
 }
 
+// One row by one workgroup of kSelThreads threads: exact for every input.
 template <typename T, int DI, int HI>
-__global__ __launch_bounds__(kSelThreads, 4) void topk_select16_kernel(Select16Args a) {
-    extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+__device__ __forceinline__ void select16_row(const Select16Args& a, int64_t rid, uint32_t* lds) {
     SelLds L;
     L.region0 = lds;
     L.bm_sel = lds + kRegion0_16;
@@ -147,14 +148,12 @@ __global__ __launch_bounds__(kSelThreads, 4) void topk_select16_kernel(Select16A
 
     const int tid = threadIdx.x;
     const int R = a.row_end - a.row_begin;
-    const int64_t rid = (int64_t)gridDim.x - 1 - blockIdx.x;  // longest rows of the slab first
     const int b = (int)(rid / R);
     const int t = a.row_begin + (int)(rid % R);
     const int n = min(batch_q_offset(a.seq_lens, b, a.q_offset, a.Lq, a.Lk) + t, a.Lk - 1) + 1;
     int m = a.n_sel[(int64_t)b * a.Lq + t];
     m = max(0, min(m, min(n, a.k_cap)));
     int32_t* out = a.idx_out + ((int64_t)b * a.idx_rows + (t - a.idx_row0)) * a.k_cap;
-    if (a.only_marked && out[0] != kRowDeferred) return;  // finished by the wave-per-row kernel (same for all threads)
     if (m == n || m == 0) {
         for (int j = tid; j < a.k_cap; j += kSelThreads) out[j] = j < m ? j : -1;
         return;
@@ -463,6 +462,37 @@ __global__ __launch_bounds__(kSelThreads, 4) void topk_select16_kernel(Select16A
     emit_selection(out, a.k_cap, m, n, bm_sel, with_ties ? L.region2 : nullptr, m_eq, scan64);
 }
 
+// The rows the wave-per-row kernel left marked (kRowDeferred in the first entry of their output row): every
+// workgroup looks at a.group (at most kDeferGroup) consecutive rows and takes the marked ones, one after the
+// other.  With a.group = 0 a workgroup takes one row unconditionally (few rows: a workgroup per row from the start).
+constexpr int kDeferGroup = 16;
+template <typename T, int DI, int HI>
+__global__ __launch_bounds__(kSelThreads, 4) void topk_select16_deferred_kernel(Select16Args a) {
+    extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+    const int R = a.row_end - a.row_begin;
+    const int64_t rows = (int64_t)a.B * R;
+    if (a.group == 0) {
+        select16_row<T, DI, HI>(a, rows - 1 - (int64_t)blockIdx.x, lds);  // longest rows first
+        return;
+    }
+    const int64_t r0 = (int64_t)blockIdx.x * a.group;
+    uint32_t marked = 0;  // the same in every thread
+#pragma unroll
+    for (int i = 0; i < kDeferGroup; ++i) {
+        const int64_t rid = r0 + i;
+        if (i < a.group && rid < rows) {
+            const int b = (int)(rid / R);
+            const int t = a.row_begin + (int)(rid % R);
+            marked |= a.idx_out[((int64_t)b * a.idx_rows + (t - a.idx_row0)) * a.k_cap] == kRowDeferred ? (1u << i) : 0u;
+        }
+    }
+    while (marked) {
+        const int i = __ffs(marked) - 1;
+        marked &= marked - 1u;
+        select16_row<T, DI, HI>(a, r0 + i, lds);
+        __syncthreads();  // LDS is reused by the next row
+    }
+}
 
 // ------------------------------------------------------------------------------------------------------------
 // Wave-per-row form of the same selection: one 64-lane workgroup per query row and no barriers between waves,
@@ -580,14 +610,38 @@ __global__ __launch_bounds__(64) void topk_select16_wave_kernel(Select16Args a) 
     const int b = (int)(rid / R);
     const int t = a.row_begin + (int)(rid % R);
     const int n = min(batch_q_offset(a.seq_lens, b, a.q_offset, a.Lq, a.Lk) + t, a.Lk - 1) + 1;
+    const uint16_t* krow = a.keys + ((int64_t)b * R + (t - a.row_begin)) * a.ld;
     int m = a.n_sel[(int64_t)b * a.Lq + t];
     m = max(0, min(m, min(n, a.k_cap)));
+    if (m <= a.m_lo || m > a.m_hi) return;  // a row of the other launch
     int32_t* out = a.idx_out + ((int64_t)b * a.idx_rows + (t - a.idx_row0)) * a.k_cap;
     if (m == n || m == 0) {
         for (int j = lane; j < a.k_cap; j += 64) out[j] = j < m ? j : -1;
         return;
     }
-    const uint16_t* krow = a.keys + ((int64_t)b * R + (t - a.row_begin)) * a.ld;
+    // The sample (step 1) and the first batch of the stream (step 2) are requested right away: their addresses
+    // depend on the row alone.
+    const int P = 32 * ((n + kWaveSampleKeys - 1) / kWaveSampleKeys);  // keys from one sampled quad to the next
+    const int ms = (n / P) * 32 + min(32, n % P);                      // sampled keys
+    const int sb0 = (lane >> 2) * P + (lane & 3) * 8;                  // (rows are padded to a multiple of 8 keys)
+    u32x4 sv[kWaveSampleVec];
+#pragma unroll
+    for (int u = 0; u < kWaveSampleVec; ++u) {
+        const int sb = sb0 + u * 16 * P;
+        sv[u] = sb < n ? *reinterpret_cast<const u32x4*>(krow + sb) : u32x4{0, 0, 0, 0};
+    }
+    // Loads of a batch of the stream; a vector beyond the row reads the row's last vector instead (and is never
+    // looked at).  One batch is in flight while the other is worked on.
+    const int last_vec = ((n - 1) / kKeysPerVec) * kKeysPerVec;
+    auto load = [&](int b0, u32x4* v) {
+#pragma unroll
+        for (int u = 0; u < kWaveStreamVec; ++u) {
+            const int base = min(b0 + (u * 64 + lane) * kKeysPerVec, last_vec);
+            v[u] = *reinterpret_cast<const u32x4*>(krow + base);
+        }
+    };
+    u32x4 bufA[kWaveStreamVec], bufB[kWaveStreamVec];
+    load(0, bufA);  // on its way while the sample is counted
     const uint32_t cap = (uint32_t)a.cap;
     auto defer = [&]() {
         if (lane == 0) out[0] = kRowDeferred;
@@ -608,51 +662,9 @@ __global__ __launch_bounds__(64) void topk_select16_wave_kernel(Select16Args a) 
         nbreg = a.bI ? -kLog2e * a.bI[lane] : 0.f;
     }
 
-    // ---- 1. sample histogram and conservative threshold ------------------------------------------------------
-    const int P = 32 * ((n + kWaveSampleKeys - 1) / kWaveSampleKeys);  // keys from one sampled quad to the next
-    {
-        u32x4 sv[kWaveSampleVec];
-        const int sb0 = (lane >> 2) * P + (lane & 3) * 8;  // rows are padded to a multiple of 32 keys
-#pragma unroll
-        for (int u = 0; u < kWaveSampleVec; ++u) {
-            const int sb = sb0 + u * 16 * P;
-            sv[u] = sb < n ? *reinterpret_cast<const u32x4*>(krow + sb) : u32x4{0, 0, 0, 0};
-        }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) reinterpret_cast<u32x4*>(rec)[i * 64 + lane] = u32x4{0, 0, 0, 0};  // 2048 words
-        __syncthreads();
-#pragma unroll
-        for (int u = 0; u < kWaveSampleVec; ++u) {
-            const int sb = sb0 + u * 16 * P;
-            if (sb < n) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const uint32_t key = (sv[u][e >> 1] >> ((e & 1) * 16)) & 0xffffu;
-                    const uint32_t one = (key & 16u) ? 0x10000u : 1u;
-                    atomicAdd(&rec[key >> 5], sb + e < n ? one : 0u);
-                }
-            }
-        }
-        __syncthreads();
-    }
-    const int ms = (n / P) * 32 + min(32, n % P);  // sampled keys
-    uint32_t r = (uint32_t)m;
-    if (P > 32) {
-        const float lam = (float)m * (float)ms / (float)n;
-        r = (uint32_t)ceilf(lam + 3.0f * sqrtf(lam) + 2.0f);
-    }
-    uint32_t above;
-    const int b_lo = (int)r <= ms ? wave_find_bin<4096>(rec, r, lane, &above) : -1;
-    if (b_lo <= 0) {  // thr = 0 would make every key a candidate
-        defer();
-        return;
-    }
-    const uint32_t thr = (uint32_t)b_lo << 4;
-    __syncthreads();  // the histogram has been read; the records take its place
-
-    // ---- 2. stream: the records of all keys >= thr, in index order ----------------------------------------------
-    // key >= thr  <=>  the saturating 16-bit difference key - (thr - 1) is not zero (it is the relative key)
-    const uint32_t thr2 = (thr - 1) * 0x00010001u;
+    // ---- 1 + 2. threshold from a sample, then the stream --------------------------------------------------------------
+    for (int j = m + lane; j < a.k_cap; j += 64) out[j] = -1;          // the unused tail of the output row
+    uint32_t thr2 = 0;                        // (thr - 1) in both halves
     u32x4* qv = reinterpret_cast<u32x4*>(aux);  // ring: the waiting vectors ...
     uint32_t* qk = aux + 4 * kWaveQueue;        // ... and the index of their first key
     uint32_t nrec = 0, qhead = 0, qtail = 0;    // wave-uniform
@@ -717,30 +729,58 @@ __global__ __launch_bounds__(64) void topk_select16_wave_kernel(Select16Args a) 
             if (qtail - qhead >= 64u) expand(64u);  // at most 127 entries were waiting: the ring never overflows
         }
     };
-    // Loads of a batch; a vector beyond the row reads the row's last vector instead (and is never looked at).
-    const int last_vec = ((n - 1) / kKeysPerVec) * kKeysPerVec;
-    auto load = [&](int b0, u32x4* v) {
-#pragma unroll
-        for (int u = 0; u < kWaveStreamVec; ++u) {
-            const int base = min(b0 + (u * 64 + lane) * kKeysPerVec, last_vec);
-            v[u] = *reinterpret_cast<const u32x4*>(krow + base);
-        }
-    };
+    float rank = (float)m;  // rank in the sample whose key becomes the threshold
+    if (P > 32) {
+        const float lam = (float)m * (float)ms / (float)n;
+        rank = ceilf(lam + 3.0f * sqrtf(lam) + 2.0f);
+    }
     {
-        u32x4 bufA[kWaveStreamVec], bufB[kWaveStreamVec];
-        load(0, bufA);
+        // -- sample histogram
+        {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) reinterpret_cast<u32x4*>(rec)[i * 64 + lane] = u32x4{0, 0, 0, 0};  // 2048 words
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < kWaveSampleVec; ++u) {
+                const int sb = sb0 + u * 16 * P;
+                if (sb < n) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const uint32_t key = (sv[u][e >> 1] >> ((e & 1) * 16)) & 0xffffu;
+                        const uint32_t one = (key & 16u) ? 0x10000u : 1u;
+                        atomicAdd(&rec[key >> 5], sb + e < n ? one : 0u);
+                    }
+                }
+            }
+            __syncthreads();
+        }
+        if (kWaveBatch < n) load(kWaveBatch, bufB);  // the second batch, while the threshold is looked up
+        // -- conservative threshold: the bin of the sample key with that rank
+        uint32_t above;
+        const uint32_t r = (uint32_t)fminf(fmaxf(rank, 1.0f), 1.0e9f);
+        const int b_lo = r <= (uint32_t)ms ? wave_find_bin<4096>(rec, r, lane, &above) : -1;
+        if (b_lo <= 0) {  // thr = 0 would make every key a candidate
+            defer();
+            return;
+        }
+        thr2 = (((uint32_t)b_lo << 4) - 1u) * 0x00010001u;
+        __syncthreads();  // the histogram has been read; the records take its place
+
+        // -- stream: the records of all keys >= thr, in index order
+        // (key >= thr  <=>  the saturating 16-bit difference key - (thr - 1) is not zero; it is the relative key)
+        nrec = qhead = qtail = 0;
         for (int b0 = 0; b0 < n; b0 += 2 * kWaveBatch) {
-            if (b0 + kWaveBatch < n) load(b0 + kWaveBatch, bufB);
             consume(bufA, b0);
             if (b0 + kWaveBatch >= n) break;
             if (b0 + 2 * kWaveBatch < n) load(b0 + 2 * kWaveBatch, bufA);
             consume(bufB, b0 + kWaveBatch);
+            if (b0 + 3 * kWaveBatch < n) load(b0 + 3 * kWaveBatch, bufB);
         }
-    }
-    if (qtail != qhead) expand(qtail - qhead);
-    if (nrec > cap || nrec < (uint32_t)m) {  // the estimate failed (either way)
-        defer();
-        return;
+        if (qtail != qhead) expand(qtail - qhead);
+        if (nrec > cap || nrec < (uint32_t)m) {  // the estimate failed (either way)
+            defer();
+            return;
+        }
     }
     __syncthreads();  // records complete; the ring is dead
 
@@ -758,6 +798,7 @@ __global__ __launch_bounds__(64) void topk_select16_wave_kernel(Select16Args a) 
         }
     }
     __syncthreads();
+    uint32_t above;
     const int b1 = wave_find_bin<2048>(aux, (uint32_t)m, lane, &above);  // >= 0: nrec >= m
     uint32_t need = (uint32_t)m - above;  // to take among the records of bin b1
     for (uint32_t c0 = lane * 4; c0 < nrec; c0 += 256) {
@@ -855,7 +896,6 @@ __global__ __launch_bounds__(64) void topk_select16_wave_kernel(Select16Args a) 
             }
         wpos += total;
     }
-    for (int j = m + lane; j < a.k_cap; j += 64) out[j] = -1;
 }
 
 static int kernel_heads16(int hi) { return hi <= 1 ? 1 : (hi <= 2 ? 2 : (hi <= 4 ? 4 : 8)); }
@@ -868,62 +908,80 @@ size_t select16_lds_bytes(const gsa_shape& sh) {
 }
 
 // Records a row can hold in the wave-per-row kernel.  The candidates of a row with budget m number about
-// 1.2 m +- 0.07 m (sampled one key in 16); 11/8 of the largest budget leaves 2.6 sigma.  Budgets up to 2048:
-// eight workgroups of 20 KB per compute unit; 4096: six.
-static int wave_record_cap(int k_cap) { return k_cap <= 2048 ? 4088 : std::min((k_cap * 11 / 8 + 3) & ~3, 14336); }
+// 1.2 m +- 0.07 m (sampled one key in 16).  Budgets up to kWaveSplit get 4088 records (2.6 sigma at the split):
+// eight workgroups of 20 KB per compute unit.  Rows with larger budgets run in a launch of their own with
+// 11/8 of the largest budget (2.6 sigma again; six workgroups per compute unit at 4096).
+constexpr int kWaveSplit = 2816;
+static int wave_record_cap(int k_cap) { return k_cap <= kWaveSplit ? 4088 : std::min((k_cap * 11 / 8 + 3) & ~3, 14336); }
 static size_t wave_lds_bytes(int k_cap, int HIK, int DI) {
     const int aux_words = std::max(kWaveHistWords, HIK * DI + 2 * HIK + 2 * kWaveTieCap);
     return (size_t)(wave_record_cap(k_cap) + aux_words + 8) * sizeof(uint32_t);
 }
 
 // Both kernels, one after the other on the stream: the wave-per-row kernel finishes nearly every row, the
-// workgroup-per-row kernel then takes the rows left marked (its other workgroups leave at once).
+// workgroup-per-row kernel then takes the rows left marked.  With few rows (decode) a wave per row would leave
+// most of the chip idle and every row slow: the workgroup-per-row kernel takes them all.
+constexpr int64_t kWaveMinRows = 2048;
 template <typename T, int DI, int HI>
-static hipError_t launch16_one(const Select16Args& a0, size_t smem, int64_t rows, hipStream_t st) {
+static hipError_t launch16_one(const Select16Args& a0, size_t smem, int64_t rows, int wave_min_rows, hipStream_t st) {
     Select16Args a = a0;
-    auto wave = topk_select16_wave_kernel<T, DI, HI>;
-    const size_t wsmem = wave_lds_bytes(a.k_cap, HI, DI);
-    if (wsmem > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(wave), hipFuncAttributeMaxDynamicSharedMemorySize, (int)wsmem);
-        if (e != hipSuccess) return e;
-    }
-    a.cap = wave_record_cap(a.k_cap);
-    a.only_marked = 0;
-    hipLaunchKernelGGL(wave, dim3((unsigned)rows), dim3(64), wsmem, st, a);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    auto kern = topk_select16_kernel<T, DI, HI>;
+    hipError_t e;
+    auto kern = topk_select16_deferred_kernel<T, DI, HI>;
     if (smem > 48 * 1024) {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
     }
-    a.only_marked = 1;
-    hipLaunchKernelGGL(kern, dim3((unsigned)rows), dim3(kSelThreads), smem, st, a);
+    if (wave_min_rows < 0 || rows < (wave_min_rows > 0 ? (int64_t)wave_min_rows : kWaveMinRows)) {
+        a.group = 0;
+        hipLaunchKernelGGL(kern, dim3((unsigned)rows), dim3(kSelThreads), smem, st, a);
+        return hipGetLastError();
+    }
+    auto wave = topk_select16_wave_kernel<T, DI, HI>;
+    const size_t wsmem = wave_lds_bytes(a.k_cap, HI, DI);
+    if (wsmem > 48 * 1024) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(wave), hipFuncAttributeMaxDynamicSharedMemorySize, (int)wsmem);
+        if (e != hipSuccess) return e;
+    }
+    if (a.k_cap > kWaveSplit) {  // the rows with large budgets first, with the larger record lists
+        a.cap = wave_record_cap(a.k_cap);
+        a.m_lo = kWaveSplit;
+        a.m_hi = a.k_cap;
+        hipLaunchKernelGGL(wave, dim3((unsigned)rows), dim3(64), wsmem, st, a);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    a.m_lo = -1;
+    a.m_hi = std::min(a.k_cap, kWaveSplit);
+    a.cap = wave_record_cap(a.m_hi);
+    hipLaunchKernelGGL(wave, dim3((unsigned)rows), dim3(64), wave_lds_bytes(a.m_hi, HI, DI), st, a);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    a.group = kDeferGroup;
+    hipLaunchKernelGGL(kern, dim3((unsigned)cdiv(rows, kDeferGroup)), dim3(kSelThreads), smem, st, a);
     return hipGetLastError();
 }
 template <typename T, int DI>
-static hipError_t launch16_hi(const Select16Args& a, int HI, size_t smem, int64_t rows, hipStream_t st) {
+static hipError_t launch16_hi(const Select16Args& a, int HI, size_t smem, int64_t rows, int wmr, hipStream_t st) {
     switch (HI) {
-        case 1: return launch16_one<T, DI, 1>(a, smem, rows, st);
-        case 2: return launch16_one<T, DI, 2>(a, smem, rows, st);
-        case 4: return launch16_one<T, DI, 4>(a, smem, rows, st);
-        case 8: return launch16_one<T, DI, 8>(a, smem, rows, st);
+        case 1: return launch16_one<T, DI, 1>(a, smem, rows, wmr, st);
+        case 2: return launch16_one<T, DI, 2>(a, smem, rows, wmr, st);
+        case 4: return launch16_one<T, DI, 4>(a, smem, rows, wmr, st);
+        case 8: return launch16_one<T, DI, 8>(a, smem, rows, wmr, st);
     }
     return hipErrorInvalidValue;
 }
 template <typename T>
-static hipError_t launch16_di(const Select16Args& a, int DI, int HI, size_t smem, int64_t rows, hipStream_t st) {
+static hipError_t launch16_di(const Select16Args& a, int DI, int HI, size_t smem, int64_t rows, int wmr, hipStream_t st) {
     switch (DI) {
-        case 32: return launch16_hi<T, 32>(a, HI, smem, rows, st);
-        case 64: return launch16_hi<T, 64>(a, HI, smem, rows, st);
-        case 128: return launch16_hi<T, 128>(a, HI, smem, rows, st);
+        case 32: return launch16_hi<T, 32>(a, HI, smem, rows, wmr, st);
+        case 64: return launch16_hi<T, 64>(a, HI, smem, rows, wmr, st);
+        case 128: return launch16_hi<T, 128>(a, HI, smem, rows, wmr, st);
     }
     return hipErrorInvalidValue;
 }
 
 hipError_t launch_select16(const gsa_shape& sh, int row_begin, int row_end, const uint16_t* keys, int64_t ld,
                            const int32_t* n_sel, int k_cap, int32_t* idx_out, int idx_rows, int idx_row0, const void* qI,
-                           const void* kI, const float* w, const float* bI, const int32_t* seq_lens, hipStream_t st) {
+                           const void* kI, const float* w, const float* bI, const int32_t* seq_lens, int wave_min_rows,
+                           hipStream_t st) {
     Select16Args a;
     a.seq_lens = seq_lens;
     a.keys = keys;
@@ -948,8 +1006,8 @@ hipError_t launch_select16(const gsa_shape& sh, int row_begin, int row_end, cons
     const size_t smem = select16_lds_bytes(sh);
     const int64_t rows = (int64_t)sh.B * (row_end - row_begin);
     const int HIK = kernel_heads16(sh.HI);
-    return sh.dtype == GSA_BF16 ? launch16_di<__bf16>(a, sh.dI, HIK, smem, rows, st)
-                                : launch16_di<float>(a, sh.dI, HIK, smem, rows, st);
+    return sh.dtype == GSA_BF16 ? launch16_di<__bf16>(a, sh.dI, HIK, smem, rows, wave_min_rows, st)
+                                : launch16_di<float>(a, sh.dI, HIK, smem, rows, wave_min_rows, st);
 }
 
 }  // namespace gsa

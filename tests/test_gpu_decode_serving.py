@@ -42,11 +42,13 @@ def test_cache_append_writes_gated_values_at_each_sequences_end(dtype, Hkv, dh, 
         G.gsa_cache_append(sh, t["kI"], t["K"], t["V"], t["g2"], lens, caches[0], caches[1], caches[2], lens)
 
 
+@pytest.mark.parametrize("wave", [0, 1])
 @pytest.mark.parametrize("Lq", [1, 3])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-def test_decode_step_over_ragged_batch(dtype, Lq):
+def test_decode_step_over_ragged_batch(dtype, Lq, wave):
     """Sequences of different lengths in one batch; the cache beyond a sequence's length holds NaN and must never
-    reach a result."""
+    reach a result.  wave = 1: the selection runs its wave-per-row kernel even on this small batch."""
+    tn = G.make_tuning(select_wave_min_rows=wave)
     B, cap = 6, 2600
     lens = [Lq, 37, 300, 2600, 1024, 2599]
     wl = S.Workload("ragged", B, Lq, cap, 0, 16 if dtype == "bf16" else 4, 4 if dtype == "bf16" else 2, 128 if dtype == "bf16" else 64,
@@ -70,7 +72,8 @@ def test_decode_step_over_ragged_batch(dtype, Lq):
     var = torch.empty((B, Lq), dtype=torch.float32, device="cuda")
     ws = G.workspace(G.gsa_decode_workspace_bytes(sh, 128))
     ws.fill_(0xFF)
-    G.gsa_decode_step(sh, ctl, t["Q"], t["g1"], t["qI"], t["w"], None, kI_c, K_c, Vg_c, seq_lens, 0.0, out, idx, n_sel, k, var, 128, ws)
+    G.gsa_decode_step(sh, ctl, t["Q"], t["g1"], t["qI"], t["w"], None, kI_c, K_c, Vg_c, seq_lens, 0.0, out, idx, n_sel, k, var, 128, ws,
+                      tuning=tn)
     torch.cuda.synchronize()
     assert torch.isfinite(out.float()).all(), "nothing beyond a sequence's length may be read"
     o = {name: T.to64(v) for name, v in t.items()}
@@ -95,12 +98,12 @@ def test_decode_step_over_ragged_batch(dtype, Lq):
     Vg_full = torch.empty_like(t["V"])
     G.gsa_value_gate(sh, t["V"], t["g2"], Vg_full)
     G.gsa_decode_step(sh, ctl, t["Q"], t["g1"], t["qI"], t["w"], None, t["kI"], t["K"], Vg_full, same, 0.0, out2, None, None, None,
-                      None, 128, ws)
+                      None, 128, ws, tuning=tn)
     wl2 = wl.with_(Lk=1500, q_offset=1500 - Lq)
     t2 = dict(t)
     for name in ("K", "V", "g2", "kI"):
         t2[name] = t[name][:, :1500].contiguous()
-    res = T.gpu_forward(wl2, t2, ctl, k_cap=128)
+    res = T.gpu_forward(wl2, t2, ctl, k_cap=128, tuning=tn)
     torch.cuda.synchronize()
     assert torch.equal(out2, res["out"])
 

@@ -77,10 +77,12 @@ KEY_CASES = [
 ]
 
 
+@pytest.mark.parametrize("wave", [1, -1])
 @pytest.mark.parametrize("dtype,HI,dI,B,Lq,Lk,off,bias,k_cap", KEY_CASES)
-def test_indexer_keys_and_selection_on_keys(dtype, HI, dI, B, Lq, Lk, off, bias, k_cap):
+def test_indexer_keys_and_selection_on_keys(dtype, HI, dI, B, Lq, Lk, off, bias, k_cap, wave):
     """The two stage calls in the form the fused forward uses: 16-bit fixed-point keys of the scores
-    (Sec. 3.3) and the top-k_t selection on them (Eq. 4), against the fp64 oracle."""
+    (Sec. 3.3) and the top-k_t selection on them (Eq. 4), against the fp64 oracle.  Both selection kernels:
+    one wave per row (wave = 1; rows its estimate fails on fall back) and one workgroup per row (wave = -1)."""
     wl = wl_("keys", B, Lq, Lk, off, 4, 2, 64, HI, dI, dtype, seed=300 + HI + dI)
     t = S.make_inputs(wl, "cpu", with_bias=bias)
     d = T.to_device(t)
@@ -96,7 +98,8 @@ def test_indexer_keys_and_selection_on_keys(dtype, HI, dI, B, Lq, Lk, off, bias,
     r = np.random.default_rng(HI)
     n_sel = torch.from_numpy(r.integers(1, k_cap + 1, (B, Lq)).astype(np.int32)).cuda()
     idx = torch.full((B, Lq, k_cap), -7, dtype=torch.int32, device="cuda")
-    G.gsa_topk_select_keys(sh, 0, Lq, keys, ld, n_sel, k_cap, idx, d["qI"], d["kI"], d["w"], d["bI"])
+    G.gsa_topk_select_keys(sh, 0, Lq, keys, ld, n_sel, k_cap, idx, d["qI"], d["kI"], d["w"], d["bI"],
+                           tuning=G.make_tuning(select_wave_min_rows=wave))
     torch.cuda.synchronize()
     HIK = 1 << (HI - 1).bit_length()
     kh = keys.cpu().numpy().view(np.uint16).astype(np.int64)
@@ -747,7 +750,8 @@ def test_forward_random_shapes(case):
     t = S.make_inputs(wl, "cpu", with_bias=bias)
     d = T.to_device(t)
     ctl, kw = _ctl_for(wl, _vbar_from_gpu(wl, d) + 1e-6)
-    res = T.gpu_forward(wl, d, ctl, slab_rows=slab, tuning=None)
+    # odd cases: the selection on keys runs one wave per row however few rows there are
+    res = T.gpu_forward(wl, d, ctl, slab_rows=slab, tuning=G.make_tuning(select_wave_min_rows=case % 2))
     rows = {(int(b), int(i)) for b, i in zip(r.integers(0, B, 12), r.integers(0, Lq, 12))} | {(0, 0), (B - 1, Lq - 1)}
     _check_forward(wl, t, res, kw, sorted(rows))
 
@@ -758,7 +762,7 @@ def test_forward_random_shapes_key_windows(case):
     r = np.random.default_rng(5000 + case)
     _, HI, dI, H, Hkv, dh, B, Lq, Lk, off, bias, slab, kmin, kmax = _random_case(r)
     window = int(r.integers(8, 300))
-    tn = G.make_tuning(attn_window=window, attn_rows_per_wave=int(r.integers(1, 10)))
+    tn = G.make_tuning(attn_window=window, attn_rows_per_wave=int(r.integers(1, 10)), select_wave_min_rows=(case + 1) % 2)
     wl = wl_("rndw", B, Lq, Lk, off, H, Hkv, dh, HI, dI, "bf16", kmin=kmin, kmax=kmax, seed=6000 + case)
     t = S.make_inputs(wl, "cpu", with_bias=bias)
     d = T.to_device(t)
