@@ -13,7 +13,8 @@ Inputs are resident in HBM before the timed region.  Prints one JSON line:
                         (rocprofv3 counters collected by two child runs of this script)
   stages                per-stage times and rates (both forms of indexer and selection)
   one_slab              the same call with the whole problem in one slab (large workspace), for comparison
-  decode_c5, c4_h_kv16  the decode configuration and the 16-kv-head reading of the 128K prefill
+  decode_c5, c4_h_kv16  the decode configuration (eager calls, and one call captured in a HIP graph and replayed)
+                        and the 16-kv-head reading of the 128K prefill
   projections           the layer's input and output projections at the same token count (d_model 2048)
   cpu_baseline          the CPU oracle timed on a bounded sample of the same workload on this machine's host cores
 """
@@ -324,6 +325,19 @@ def small_leg(G, S, CM, wl, steps, warmup, workspace_gib):
         res["indexer_ms"] = round(ims, 4)
         res["indexer_key_scan_gbs"] = round(scan / (ims * 1e-3) / 1e9, 1)
         res["indexer_frac_hbm_peak"] = round(scan / (ims * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)
+        # the same step captured once in a HIP graph and replayed (the call launches kernels only)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            run.step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            run.step()
+        gms = timed(graph.replay, max(steps, 20))
+        res["graph_replay_ms_per_step"] = round(gms, 4)
+        res["graph_replay_queries_per_s"] = round(wl.B * wl.Lq / (gms * 1e-3), 1)
     else:
         sh, k_cap = run.sh, run.k_cap
         ws_a = G.workspace(G.gsa_attn_workspace_bytes(sh, 0, wl.Lq, k_cap), dev)

@@ -107,3 +107,49 @@ def test_decode_step_over_ragged_batch(dtype, Lq, wave):
     torch.cuda.synchronize()
     assert torch.equal(out2, res["out"])
 
+
+
+def test_decode_step_replays_from_a_hip_graph():
+    """gsa_decode_step launches kernels only (no allocation, no memset, no synchronisation), so a serving loop can
+    capture it once and replay it.  Every replay, with fresh inputs written by eager work in between, must give the
+    bits of the eager call on the same inputs."""
+    B, cap, Lq, k_cap = 8, 3000, 1, 128
+    wl = S.Workload("graph", B, Lq, cap, 0, 16, 4, 128, 4, 64, "bf16", 45, 16, 128, seed=29)
+    t = S.make_inputs(wl, "cuda")
+    sh = G.shape_of(wl)
+    Vg = torch.empty_like(t["V"])
+    G.gsa_value_gate(sh, t["V"], t["g2"], Vg)
+    seq_lens = torch.tensor([3000, 17, 2999, 1500, 64, 2048, 1, 777], dtype=torch.int32, device="cuda")
+    ctl = G.make_adaptive(0.3, 45, 16, 128)
+    Q, qI, w = t["Q"].clone(), t["qI"].clone(), t["w"].clone()
+    bufs = [dict(out=torch.empty_like(Q), idx=torch.empty((B, Lq, k_cap), dtype=torch.int32, device="cuda"),
+                 n=torch.empty((B, Lq), dtype=torch.int32, device="cuda"), k=torch.empty((B, Lq), dtype=torch.int32, device="cuda"),
+                 var=torch.empty((B, Lq), dtype=torch.float32, device="cuda")) for _ in range(2)]
+    ws = G.workspace(G.gsa_decode_workspace_bytes(sh, k_cap))
+
+    def step(o):
+        G.gsa_decode_step(sh, ctl, Q, t["g1"], qI, w, None, t["kI"], t["K"], Vg, seq_lens, 0.0, o["out"], o["idx"], o["n"], o["k"],
+                          o["var"], k_cap, ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(bufs[0])                       # warm-up outside the capture (kernel attributes, lazy module load)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(bufs[0])
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    for rep in range(4):
+        # eager work between the replays: new queries, new indexer queries, new lengths
+        Q.copy_(torch.randn(Q.shape, generator=gen, device="cuda").to(Q.dtype))
+        qI.copy_(torch.randn(qI.shape, generator=gen, device="cuda").to(qI.dtype))
+        seq_lens.copy_(torch.randint(1, cap + 1, (B,), generator=gen, device="cuda").to(torch.int32))
+        ws.fill_(0xFF)
+        graph.replay()
+        torch.cuda.synchronize()
+        step(bufs[1])
+        torch.cuda.synchronize()
+        for name in ("out", "idx", "n", "k", "var"):
+            assert torch.equal(bufs[0][name], bufs[1][name]), "replay %d differs from the eager call in %s" % (rep, name)
