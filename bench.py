@@ -338,6 +338,33 @@ def small_leg(G, S, CM, wl, steps, warmup, workspace_gib):
         gms = timed(graph.replay, max(steps, 20))
         res["graph_replay_ms_per_step"] = round(gms, 4)
         res["graph_replay_queries_per_s"] = round(wl.B * wl.Lq / (gms * 1e-3), 1)
+        # the same step on paged caches: the rows of every sequence behind a shuffled block table (pages of 256 tokens)
+        page = 256
+        max_pages = wl.Lk // page
+        pool_pages = wl.B * max_pages
+        gen = torch.Generator(device=dev).manual_seed(11)
+        table = torch.randperm(pool_pages, generator=gen, device=dev).to(torch.int32).reshape(wl.B, max_pages)
+        Vg = torch.empty_like(t["V"])
+        G.gsa_value_gate(run.sh, t["V"], t["g2"], Vg)
+
+        def to_pool(x):   # [B, Lk, ...] -> [pool_pages, page, ...] with page table[b, p] holding tokens p*page.. of sequence b
+            pool = torch.empty((pool_pages, page) + tuple(x.shape[2:]), dtype=x.dtype, device=dev)
+            pool[table.reshape(-1).long()] = x.reshape((pool_pages, page) + tuple(x.shape[2:]))
+            return pool
+        kI_p, K_p = to_pool(t["kI"]), to_pool(t["K"])
+        Vg_p = to_pool(Vg)
+        del Vg
+        seq_lens = torch.full((wl.B,), wl.Lk, dtype=torch.int32, device=dev)
+        out_p = torch.empty_like(run.out)
+        ws_p = G.workspace(G.gsa_paged_decode_workspace_bytes(run.sh, run.k_cap), dev)
+        pms = timed(lambda: G.gsa_paged_decode_step(run.sh, run.ctl, page, table, pool_pages, t["Q"], t["g1"], t["qI"], t["w"], None, kI_p,
+                                                    K_p, Vg_p, seq_lens, 0.0, out_p, None, None, None, None, run.k_cap, ws_p), max(steps, 20))
+        run.step()
+        torch.cuda.synchronize()
+        res["paged_ms_per_step"] = round(pms, 4)
+        res["paged_queries_per_s"] = round(wl.B * wl.Lq / (pms * 1e-3), 1)
+        res["paged_equals_contiguous"] = bool(torch.equal(out_p, run.out))
+        del kI_p, K_p, Vg_p
     else:
         sh, k_cap = run.sh, run.k_cap
         ws_a = G.workspace(G.gsa_attn_workspace_bytes(sh, 0, wl.Lq, k_cap), dev)

@@ -259,6 +259,29 @@ int32_t gsa_decode_step(const gsa_shape* shape, const gsa_adaptive* ctl, const v
                         void* stream);
 size_t gsa_decode_workspace_bytes(const gsa_shape* shape, int32_t k_cap, const gsa_tuning* tuning);
 
+/* The same two calls on paged (block-table) caches, as serving engines keep them: the tokens of a sequence sit in
+ * pages of page_size tokens scattered over pools shared by all sequences,
+ *   kI_pool [pool_pages, page_size, dI]   K_pool, Vg_pool [pool_pages, page_size, H_kv, d_h]
+ *   block_table [B, Lk / page_size] int32 (device): block_table[b][p] = pool page holding tokens p*page_size .. of
+ *   sequence b.  Only the entries up to a sequence's last token are read; page numbers are clamped to the pool.
+ * shape->Lk is the capacity of one sequence (a multiple of page_size); page_size is a power of two >= 128 (an
+ * indexer key tile never straddles two pages); pool_pages * page_size < 2^31; one pool may exceed 4 GiB.
+ * Everything else as in gsa_cache_append / gsa_decode_step (same results bit for bit for the same cached rows);
+ * idx_out holds token positions inside the sequence, not pool rows.
+ * Errors: GSA_ERR_SHAPE for a bad page_size / capacity / pool size, GSA_ERR_NULL for a missing table. */
+int32_t gsa_paged_cache_append(const gsa_shape* shape, int32_t page_size, const int32_t* block_table, int32_t pool_pages,
+                               const void* kI_new, const void* K_new, const void* V_new, const void* g2_new,
+                               const int32_t* seq_lens, void* kI_pool, void* K_pool, void* Vg_pool,
+                               int32_t* seq_lens_out, void* stream);
+int32_t gsa_paged_decode_step(const gsa_shape* shape, const gsa_adaptive* ctl, int32_t page_size,
+                              const int32_t* block_table, int32_t pool_pages, const void* Q, const void* g1_logits,
+                              const void* qI, const float* w, const float* bI, const void* kI_pool,
+                              const void* K_pool, const void* Vg_pool, const int32_t* seq_lens, float softmax_scale,
+                              void* out, int32_t* idx_out, int32_t* n_sel_out, int32_t* k_out, float* row_var_out,
+                              int32_t k_cap, void* workspace, size_t workspace_bytes, const gsa_tuning* tuning,
+                              void* stream);
+size_t gsa_paged_decode_workspace_bytes(const gsa_shape* shape, int32_t k_cap, const gsa_tuning* tuning);
+
 /* ---- the linear projections around the path (Sec. 2.1 Eq. 1, Sec. 3.3, Sec. 3.5, App. B) ------------
  * Every projection is y = x W^T with W stored row-major [out_features, in_features], bf16 in, fp32
  * accumulation, bf16 out (GSA_BF16 shapes only; GSA_ERR_UNSUPPORTED otherwise).  All pointers are device

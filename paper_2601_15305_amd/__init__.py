@@ -25,7 +25,8 @@ ENTRY_POINTS = (
     "gsa_indexer_scores", "gsa_indexer_keys", "gsa_indexer_workspace_bytes", "gsa_adaptive_k", "gsa_topk_select",
     "gsa_topk_select_keys", "gsa_sparse_gated_attn", "gsa_attn_workspace_bytes", "gsa_value_gate", "gsa_forward",
     "gsa_forward_workspace_bytes", "gsa_forward_noalloc", "gsa_dense_gated_attn", "gsa_dense_attn_workspace_bytes",
-    "gsa_cache_append", "gsa_decode_step", "gsa_decode_workspace_bytes", "gsa_input_projections", "gsa_output_projection",
+    "gsa_cache_append", "gsa_decode_step", "gsa_decode_workspace_bytes", "gsa_paged_cache_append", "gsa_paged_decode_step",
+    "gsa_paged_decode_workspace_bytes", "gsa_input_projections", "gsa_output_projection",
     "gsa_probe_gather", "gsa_status_string", "gsa_last_error", "gsa_version",
 )
 
@@ -99,6 +100,13 @@ def load():
     lib.gsa_decode_step.restype = i32
     lib.gsa_decode_workspace_bytes.argtypes = [shp, i32, tun]
     lib.gsa_decode_workspace_bytes.restype = sz
+    lib.gsa_paged_cache_append.argtypes = [shp, i32, vp, i32] + [vp] * 10
+    lib.gsa_paged_cache_append.restype = i32
+    lib.gsa_paged_decode_step.argtypes = [shp, ctl, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, i32, vp, sz,
+                                          tun, vp]
+    lib.gsa_paged_decode_step.restype = i32
+    lib.gsa_paged_decode_workspace_bytes.argtypes = [shp, i32, tun]
+    lib.gsa_paged_decode_workspace_bytes.restype = sz
     lib.gsa_dense_gated_attn.argtypes = [shp, i32, i32, vp, vp, vp, vp, vp, f32, vp, vp, sz, vp]
     lib.gsa_dense_gated_attn.restype = i32
     lib.gsa_dense_attn_workspace_bytes.argtypes = [shp, i32]
@@ -298,6 +306,31 @@ def gsa_decode_step(shape, ctl, Q, g1_logits, qI, w, bI, kI_cache, K_cache, Vg_c
                                 float(softmax_scale), _ptr(out), _ptr(idx_out), _ptr(n_sel_out), _ptr(k_out), _ptr(row_var_out),
                                 k_cap, _ptr(workspace), workspace_bytes, _tun(tuning), _stream(stream))
     _check(rc, "gsa_decode_step")
+
+
+def gsa_paged_cache_append(shape, page_size, block_table, pool_pages, kI_new, K_new, V_new, g2_new, seq_lens, kI_pool, K_pool, Vg_pool,
+                           seq_lens_out=None, stream=None):
+    rc = load().gsa_paged_cache_append(ctypes.byref(shape), page_size, _ptr(block_table), pool_pages, _ptr(kI_new), _ptr(K_new),
+                                       _ptr(V_new), _ptr(g2_new), _ptr(seq_lens), _ptr(kI_pool), _ptr(K_pool), _ptr(Vg_pool),
+                                       _ptr(seq_lens_out), _stream(stream))
+    _check(rc, "gsa_paged_cache_append")
+
+
+def gsa_paged_decode_workspace_bytes(shape, k_cap, tuning=None):
+    return load().gsa_paged_decode_workspace_bytes(ctypes.byref(shape), k_cap, _tun(tuning))
+
+
+def gsa_paged_decode_step(shape, ctl, page_size, block_table, pool_pages, Q, g1_logits, qI, w, bI, kI_pool, K_pool, Vg_pool, seq_lens,
+                          softmax_scale, out, idx_out, n_sel_out, k_out, row_var_out, k_cap, workspace, workspace_bytes=None,
+                          tuning=None, stream=None):
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load().gsa_paged_decode_step(ctypes.byref(shape), ctypes.byref(ctl) if ctl is not None else None, page_size,
+                                      _ptr(block_table), pool_pages, _ptr(Q), _ptr(g1_logits), _ptr(qI), _ptr(w), _ptr(bI),
+                                      _ptr(kI_pool), _ptr(K_pool), _ptr(Vg_pool), _ptr(seq_lens), float(softmax_scale), _ptr(out),
+                                      _ptr(idx_out), _ptr(n_sel_out), _ptr(k_out), _ptr(row_var_out), k_cap, _ptr(workspace),
+                                      workspace_bytes, _tun(tuning), _stream(stream))
+    _check(rc, "gsa_paged_decode_step")
 
 
 def gsa_dense_attn_workspace_bytes(shape, has_g2):

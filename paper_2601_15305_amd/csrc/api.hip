@@ -12,27 +12,29 @@ namespace gsa {
 size_t indexer_workspace_bytes(const gsa_shape& sh, int row_begin, int row_end, bool ragged);
 hipError_t launch_indexer(const gsa_shape& sh, const void* qI, const void* kI, const float* w, const float* bI,
                           int row_begin, int row_end, float* scores, uint16_t* keys, int64_t ld, float* row_mean,
-                          float* row_var, void* workspace, const int32_t* seq_lens, hipStream_t st);
+                          float* row_var, void* workspace, const int32_t* seq_lens, const PageMap& pm, hipStream_t st);
 hipError_t launch_select(const gsa_shape& sh, int row_begin, int row_end, const float* scores, int64_t ld,
                          const int32_t* n_sel, int k_cap, int32_t* idx_out, int idx_rows, int idx_row0, bool exact_only,
                          const int32_t* seq_lens, hipStream_t st);
 hipError_t launch_select16(const gsa_shape& sh, int row_begin, int row_end, const uint16_t* keys, int64_t ld,
                            const int32_t* n_sel, int k_cap, int32_t* idx_out, int idx_rows, int idx_row0, const void* qI,
                            const void* kI, const float* w, const float* bI, const int32_t* seq_lens, int wave_min_rows,
-                           hipStream_t st);
+                           const PageMap& pm, hipStream_t st);
 hipError_t launch_adaptive_k(const gsa_shape& sh, const gsa_adaptive& c, int row_begin, int row_end,
                              const float* row_var, int32_t* k_out, int32_t* n_sel_out, const int32_t* seq_lens, hipStream_t st);
 hipError_t launch_value_gate(const gsa_shape& sh, const void* V, const void* g2, void* Vg, hipStream_t st);
 hipError_t launch_attention(const gsa_shape& sh, int row_begin, int row_end, const void* Q, const void* K, const void* V,
                             const void* g2, const void* g1, const int32_t* idx, int idx_rows, int idx_row0,
                             const int32_t* n_sel, int k_cap, float scale, void* out, void* workspace, const gsa_tuning& tn,
-                            hipStream_t st);
+                            int64_t pool_rows, hipStream_t st);
 size_t attn_workspace_bytes(const gsa_shape& sh, int row_begin, int row_end, int k_cap, const gsa_tuning& tn);
 hipError_t launch_dense_attention(const gsa_shape& sh, int row_begin, int row_end, const void* Q, const void* K, const void* Vg,
                                   const void* g1, float scale, void* out, hipStream_t st);
 hipError_t launch_cache_append(const gsa_shape& sh, const void* kI_new, const void* K_new, const void* V_new, const void* g2_new,
                                const int32_t* seq_lens, void* kI_cache, void* K_cache, void* Vg_cache, int32_t* seq_lens_out,
-                               hipStream_t st);
+                               const PageMap& pm, hipStream_t st);
+hipError_t launch_translate_indices(const gsa_shape& sh, const PageMap& pm, int row_begin, int row_end, const int32_t* idx,
+                                    int idx_rows, int idx_row0, const int32_t* n_sel, int k_cap, int32_t* phys, hipStream_t st);
 hipError_t launch_projection(const void* x, int64_t tokens, int K, int nseg, const void* const* W, void* const* out,
                              const int32_t* width, const int32_t* kind, hipStream_t st);
 hipError_t launch_probe_gather(const void* table, const int32_t* idx, int64_t n_idx, int waves, uint32_t* sink, hipStream_t st);
@@ -101,8 +103,12 @@ struct FixedPlan {
 struct SlabPlan {
     int r0, r1;
     int64_t ld;
-    size_t off_idx, off_scores, off_partial, off_attn, total;  // offsets from the start of the per-slab part
+    size_t off_idx, off_phys, off_scores, off_partial, off_attn, total;  // offsets from the start of the per-slab part
 };
+// `ragged` arguments below: 0 = one position offset for the whole batch, 1 = per-sequence lengths (decode-serving
+// caches), 2 = per-sequence lengths with paged caches (the slab also holds the selected rows as pool rows).
+constexpr int kRagged = 1, kPaged = 2;
+static const PageMap kNoPages = {nullptr, 0, 0, 0};
 
 // The value gate runs as a dense pre-pass (once per key token) when the queries together gather
 // clearly more rows than there are tokens; otherwise (decode: one query against a long cache) it
@@ -128,7 +134,7 @@ static FixedPlan plan_fixed(const gsa_shape& s, int k_cap, bool has_g2) {
     return p;
 }
 
-static SlabPlan plan_slab(const gsa_shape& s, int k_cap, bool own_idx, bool use_keys, bool ragged, int r0, int r1, const gsa_tuning& tn) {
+static SlabPlan plan_slab(const gsa_shape& s, int k_cap, bool own_idx, bool use_keys, int ragged, int r0, int r1, const gsa_tuning& tn) {
     SlabPlan p;
     p.r0 = r0;
     p.r1 = r1;
@@ -139,10 +145,12 @@ static SlabPlan plan_slab(const gsa_shape& s, int k_cap, bool own_idx, bool use_
     size_t off = 0;
     p.off_idx = off;
     if (own_idx) off += up256(rows * (size_t)k_cap * 4);
+    p.off_phys = off;
+    if (ragged == kPaged) off += up256(rows * (size_t)k_cap * 4);
     p.off_scores = off;
     off += up256(rows * (size_t)p.ld * (use_keys ? 2 : 4));
     p.off_partial = off;
-    off += up256(indexer_workspace_bytes(s, r0, r1, ragged));
+    off += up256(indexer_workspace_bytes(s, r0, r1, ragged != 0));
     p.off_attn = off;
     off += up256(attn_workspace_bytes(s, r0, r1, k_cap, tn));
     p.total = off;
@@ -162,7 +170,7 @@ static bool forward_keys(const gsa_shape& s, const gsa_tuning& tn) {
 
 // The slab that starts at row r0: as many rows as fit into `avail` bytes of per-slab workspace.  Returns
 // false if not even 128 rows (or the rest of the rows) fit.
-static bool next_slab(const gsa_shape& s, int k_cap, bool own_idx, bool use_keys, bool ragged, size_t avail, const gsa_tuning& tn, int r0,
+static bool next_slab(const gsa_shape& s, int k_cap, bool own_idx, bool use_keys, int ragged, size_t avail, const gsa_tuning& tn, int r0,
                       SlabPlan* out) {
     const int64_t max_blocks = cdiv(s.Lq - r0, 128);
     SlabPlan best = plan_slab(s, k_cap, own_idx, use_keys, ragged, r0, slab_end(s, r0, max_blocks), tn);
@@ -186,7 +194,7 @@ static bool next_slab(const gsa_shape& s, int k_cap, bool own_idx, bool use_keys
 }
 
 // Can [0, Lq) be cut into slabs that fit?  (The same walk the launches make, without launching.)
-static bool slabs_fit(const gsa_shape& s, int k_cap, bool own_idx, bool use_keys, bool ragged, size_t avail, const gsa_tuning& tn) {
+static bool slabs_fit(const gsa_shape& s, int k_cap, bool own_idx, bool use_keys, int ragged, size_t avail, const gsa_tuning& tn) {
     SlabPlan p;
     for (int r0 = 0; r0 < s.Lq; r0 = p.r1)
         if (!next_slab(s, k_cap, own_idx, use_keys, ragged, avail, tn, r0, &p)) return false;
@@ -198,8 +206,10 @@ static int32_t forward_launches(const gsa_shape& s, const gsa_adaptive& ctl, con
                                 const void* g1_logits, const void* g2_logits, const void* qI, const void* kI, const float* w,
                                 const float* bI, float softmax_scale, void* out, int32_t* idx_out, int32_t* n_sel_out,
                                 int32_t* k_out, float* row_var_out, int32_t k_cap, unsigned char* ws, size_t ws_bytes,
-                                const int32_t* seq_lens, const gsa_tuning& tn, hipStream_t st) {
+                                const int32_t* seq_lens, const PageMap& pm, const gsa_tuning& tn, hipStream_t st) {
     const FixedPlan fx = plan_fixed(s, k_cap, g2_logits != nullptr);
+    const int ragged = pm.table ? kPaged : (seq_lens ? kRagged : 0);
+    const int64_t pool_rows = pm.table ? ((int64_t)pm.pool_pages << pm.page_shift) : 0;
     const bool has_g2 = g2_logits != nullptr;
     const bool prepass = has_g2 && gate_as_prepass(s, k_cap);
     const bool own_idx = idx_out == nullptr;
@@ -220,12 +230,12 @@ static int32_t forward_launches(const gsa_shape& s, const gsa_adaptive& ctl, con
     unsigned char* sw = ws + fx.total;  // per-slab part
     SlabPlan p;
     for (int r0 = 0; r0 < s.Lq; r0 = p.r1) {
-        if (!next_slab(s, k_cap, own_idx, use_keys, seq_lens != nullptr, ws_bytes - fx.total, tn, r0, &p)) return GSA_ERR_WORKSPACE;
+        if (!next_slab(s, k_cap, own_idx, use_keys, ragged, ws_bytes - fx.total, tn, r0, &p)) return GSA_ERR_WORKSPACE;
         const int r1 = p.r1;
         float* scores = reinterpret_cast<float*>(sw + p.off_scores);
         uint16_t* keys = reinterpret_cast<uint16_t*>(sw + p.off_scores);
         e = launch_indexer(s, qI, kI, w, bI, r0, r1, use_keys ? nullptr : scores, use_keys ? keys : nullptr, p.ld, nullptr,
-                           var, sw + p.off_partial, seq_lens, st);
+                           var, sw + p.off_partial, seq_lens, pm, st);
         if (e != hipSuccess) return hip_fail(e, "gsa_forward/indexer");
         e = launch_adaptive_k(s, ctl, r0, r1, var, kbuf, nsel, seq_lens, st);
         if (e != hipSuccess) return hip_fail(e, "gsa_forward/adaptive_k");
@@ -233,12 +243,22 @@ static int32_t forward_launches(const gsa_shape& s, const gsa_adaptive& ctl, con
         const int idx_rows = own_idx ? (r1 - r0) : s.Lq;
         const int idx_row0 = own_idx ? r0 : 0;
         e = use_keys ? launch_select16(s, r0, r1, keys, p.ld, nsel, k_cap, idx, idx_rows, idx_row0, qI, kI, w, bI, seq_lens,
-                                       tn.select_wave_min_rows, st)
+                                       tn.select_wave_min_rows, pm, st)
                      : launch_select(s, r0, r1, scores, p.ld, nsel, k_cap, idx, idx_rows, idx_row0, tn.select_exact_only != 0,
                                      seq_lens, st);
         if (e != hipSuccess) return hip_fail(e, "gsa_forward/select");
-        e = launch_attention(s, r0, r1, Q, K, Vuse, g2use, g1_logits, idx, idx_rows, idx_row0, nsel, k_cap, scale, out,
-                             sw + p.off_attn, tn, st);
+        const int32_t* gather = idx;
+        int gather_rows = idx_rows, gather_row0 = idx_row0;
+        if (pm.table) {  // the attention gathers rows of the pool: translate the selected positions
+            int32_t* phys = reinterpret_cast<int32_t*>(sw + p.off_phys);
+            e = launch_translate_indices(s, pm, r0, r1, idx, idx_rows, idx_row0, nsel, k_cap, phys, st);
+            if (e != hipSuccess) return hip_fail(e, "gsa_forward/translate");
+            gather = phys;
+            gather_rows = r1 - r0;
+            gather_row0 = r0;
+        }
+        e = launch_attention(s, r0, r1, Q, K, Vuse, g2use, g1_logits, gather, gather_rows, gather_row0, nsel, k_cap, scale, out,
+                             sw + p.off_attn, tn, pool_rows, st);
         if (e != hipSuccess) return hip_fail(e, "gsa_forward/attention");
     }
     return GSA_OK;
@@ -264,7 +284,7 @@ static int32_t check_forward_args(const gsa_shape* shape, const gsa_adaptive* ct
 }
 
 // Bytes of the whole forward workspace when every slab holds `blocks` * 128 rows.
-static size_t forward_bytes_uniform(const gsa_shape& s, int k_cap, bool has_g2, int64_t blocks, const gsa_tuning& tn, bool ragged = false) {
+static size_t forward_bytes_uniform(const gsa_shape& s, int k_cap, bool has_g2, int64_t blocks, const gsa_tuning& tn, int ragged = 0) {
     const bool use_keys = forward_keys(s, tn);
     size_t slab = 0;
     for (int r0 = 0; r0 < s.Lq;) {
@@ -345,7 +365,7 @@ int32_t gsa_indexer_scores(const gsa_shape* shape, const void* qI, const void* k
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < indexer_workspace_bytes(*shape, row_begin, row_end, false))
         return GSA_ERR_WORKSPACE;
     hipError_t e = launch_indexer(*shape, qI, kI, w, bI, row_begin, row_end, scores, nullptr, ld_scores, row_mean, row_var,
-                                  workspace, nullptr, static_cast<hipStream_t>(stream));
+                                  workspace, nullptr, kNoPages, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_indexer_scores");
 }
 
@@ -363,7 +383,7 @@ int32_t gsa_indexer_keys(const gsa_shape* shape, const void* qI, const void* kI,
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < indexer_workspace_bytes(*shape, row_begin, row_end, false))
         return GSA_ERR_WORKSPACE;
     hipError_t e = launch_indexer(*shape, qI, kI, w, bI, row_begin, row_end, nullptr, keys, ld_keys, row_mean, row_var,
-                                  workspace, nullptr, static_cast<hipStream_t>(stream));
+                                  workspace, nullptr, kNoPages, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_indexer_keys");
 }
 
@@ -409,7 +429,8 @@ int32_t gsa_topk_select_keys(const gsa_shape* shape, int32_t row_begin, int32_t 
     if (ld_keys < shape->Lk || (ld_keys & 7) != 0 || !aligned(keys, 16) || !aligned(qI, 16) || !aligned(kI, 16)) return GSA_ERR_SHAPE;
     if (k_cap < 1 || k_cap > 8192) return GSA_ERR_SHAPE;
     hipError_t e = launch_select16(*shape, row_begin, row_end, keys, ld_keys, n_sel, k_cap, idx_out, shape->Lq, 0, qI, kI, w,
-                                   bI, nullptr, tuning_or_default(tuning).select_wave_min_rows, static_cast<hipStream_t>(stream));
+                                   bI, nullptr, tuning_or_default(tuning).select_wave_min_rows, kNoPages,
+                                   static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_topk_select_keys");
 }
 
@@ -438,7 +459,7 @@ int32_t gsa_sparse_gated_attn(const gsa_shape* shape, int32_t row_begin, int32_t
     if (need > 0 && (!workspace || !aligned(workspace, 256) || workspace_bytes < need)) return GSA_ERR_WORKSPACE;
     const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt((float)shape->d_h);
     hipError_t e = launch_attention(*shape, row_begin, row_end, Q, K, V, g2_logits, g1_logits, idx, shape->Lq, 0, n_sel,
-                                    k_cap, scale, out, workspace, tn, static_cast<hipStream_t>(stream));
+                                    k_cap, scale, out, workspace, tn, 0, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_sparse_gated_attn");
 }
 
@@ -519,7 +540,7 @@ int32_t gsa_forward(const gsa_shape* shape, const gsa_adaptive* ctl, const void*
         !slabs_fit(s, k_cap, idx_out == nullptr, forward_keys(s, tn), false, workspace_bytes - fixed, tn))
         return GSA_ERR_WORKSPACE;
     return forward_launches(s, *ctl, Q, K, V, g1_logits, g2_logits, qI, kI, w, bI, softmax_scale, out, idx_out, n_sel_out,
-                            k_out, row_var_out, k_cap, static_cast<unsigned char*>(workspace), workspace_bytes, nullptr, tn,
+                            k_out, row_var_out, k_cap, static_cast<unsigned char*>(workspace), workspace_bytes, nullptr, kNoPages, tn,
                             static_cast<hipStream_t>(stream));
 }
 
@@ -527,7 +548,7 @@ size_t gsa_decode_workspace_bytes(const gsa_shape* shape, int32_t k_cap, const g
     if (check_shape(shape) != GSA_OK || check_select_len(shape) != GSA_OK || k_cap < 1 || k_cap > 8192) return 0;
     gsa_tuning tn = tuning_or_default(tuning);
     tn.attn_window = -1;
-    return forward_bytes_uniform(*shape, k_cap, false, cdiv(shape->Lq, 128), tn, true);
+    return forward_bytes_uniform(*shape, k_cap, false, cdiv(shape->Lq, 128), tn, kRagged);
 }
 
 int32_t gsa_decode_step(const gsa_shape* shape, const gsa_adaptive* ctl, const void* Q, const void* g1_logits, const void* qI,
@@ -544,11 +565,75 @@ int32_t gsa_decode_step(const gsa_shape* shape, const gsa_adaptive* ctl, const v
     gsa_tuning tn = tuning_or_default(tuning);
     tn.attn_window = -1;  // which rows see which key window is only known on the device: no windows
     const size_t fixed = plan_fixed(s, k_cap, false).total;
-    if (fixed > workspace_bytes || !slabs_fit(s, k_cap, idx_out == nullptr, forward_keys(s, tn), true, workspace_bytes - fixed, tn))
+    if (fixed > workspace_bytes || !slabs_fit(s, k_cap, idx_out == nullptr, forward_keys(s, tn), kRagged, workspace_bytes - fixed, tn))
         return GSA_ERR_WORKSPACE;
     return forward_launches(s, *ctl, Q, K_cache, Vg_cache, g1_logits, nullptr, qI, kI_cache, w, bI, softmax_scale, out, idx_out,
                             n_sel_out, k_out, row_var_out, k_cap, static_cast<unsigned char*>(workspace), workspace_bytes,
-                            seq_lens, tn, static_cast<hipStream_t>(stream));
+                            seq_lens, kNoPages, tn, static_cast<hipStream_t>(stream));
+}
+
+// ---- paged caches ------------------------------------------------------------------------------------
+// page_size: a power of two, at least 128 tokens (an indexer key tile must not straddle two pages); Lk (the capacity of
+// a sequence) a multiple of it; the pool below 2^31 rows.
+static int32_t make_page_map(const gsa_shape& s, int32_t page_size, const int32_t* block_table, int32_t pool_pages, PageMap* pm) {
+    if (!block_table) return GSA_ERR_NULL;
+    if (page_size < 128 || (page_size & (page_size - 1)) != 0 || s.Lk % page_size != 0 || pool_pages < 1) return GSA_ERR_SHAPE;
+    if ((int64_t)pool_pages * page_size > 0x7fffffffLL) return GSA_ERR_UNSUPPORTED;
+    int shift = 0;
+    while ((1 << shift) < page_size) ++shift;
+    *pm = PageMap{block_table, shift, s.Lk / page_size, pool_pages};
+    return GSA_OK;
+}
+
+size_t gsa_paged_decode_workspace_bytes(const gsa_shape* shape, int32_t k_cap, const gsa_tuning* tuning) {
+    if (check_shape(shape) != GSA_OK || k_cap < 1 || k_cap > 8192) return 0;
+    gsa_tuning tn = tuning_or_default(tuning);
+    tn.attn_window = -1;
+    return forward_bytes_uniform(*shape, k_cap, false, cdiv(shape->Lq, 128), tn, kPaged);
+}
+
+int32_t gsa_paged_decode_step(const gsa_shape* shape, const gsa_adaptive* ctl, int32_t page_size, const int32_t* block_table,
+                              int32_t pool_pages, const void* Q, const void* g1_logits, const void* qI, const float* w,
+                              const float* bI, const void* kI_pool, const void* K_pool, const void* Vg_pool,
+                              const int32_t* seq_lens, float softmax_scale, void* out, int32_t* idx_out, int32_t* n_sel_out,
+                              int32_t* k_out, float* row_var_out, int32_t k_cap, void* workspace, size_t workspace_bytes,
+                              const gsa_tuning* tuning, void* stream) {
+    int32_t rc = check_forward_args(shape, ctl, Q, K_pool, Vg_pool, g1_logits, nullptr, qI, kI_pool, w, softmax_scale, out, k_cap);
+    if (rc != GSA_OK) return rc;
+    if (!seq_lens) return GSA_ERR_NULL;
+    if (ctl->dense_below > 0) return GSA_ERR_UNSUPPORTED;
+    PageMap pm;
+    rc = make_page_map(*shape, page_size, block_table, pool_pages, &pm);
+    if (rc != GSA_OK) return rc;
+    if (!workspace || !aligned(workspace, 256)) return GSA_ERR_WORKSPACE;
+    const gsa_shape& s = *shape;
+    gsa_tuning tn = tuning_or_default(tuning);
+    tn.attn_window = -1;
+    const size_t fixed = plan_fixed(s, k_cap, false).total;
+    if (fixed > workspace_bytes || !slabs_fit(s, k_cap, idx_out == nullptr, forward_keys(s, tn), kPaged, workspace_bytes - fixed, tn))
+        return GSA_ERR_WORKSPACE;
+    return forward_launches(s, *ctl, Q, K_pool, Vg_pool, g1_logits, nullptr, qI, kI_pool, w, bI, softmax_scale, out, idx_out,
+                            n_sel_out, k_out, row_var_out, k_cap, static_cast<unsigned char*>(workspace), workspace_bytes,
+                            seq_lens, pm, tn, static_cast<hipStream_t>(stream));
+}
+
+int32_t gsa_paged_cache_append(const gsa_shape* shape, int32_t page_size, const int32_t* block_table, int32_t pool_pages,
+                               const void* kI_new, const void* K_new, const void* V_new, const void* g2_new,
+                               const int32_t* seq_lens, void* kI_pool, void* K_pool, void* Vg_pool, int32_t* seq_lens_out,
+                               void* stream) {
+    int32_t rc = check_shape(shape);
+    if (rc != GSA_OK) return rc;
+    if (!kI_new || !K_new || !V_new || !g2_new || !seq_lens || !kI_pool || !K_pool || !Vg_pool) return GSA_ERR_NULL;
+    if (seq_lens_out == seq_lens) return GSA_ERR_SHAPE;
+    if (!aligned(kI_new, 16) || !aligned(K_new, 16) || !aligned(V_new, 16) || !aligned(g2_new, 16) || !aligned(kI_pool, 16) ||
+        !aligned(K_pool, 16) || !aligned(Vg_pool, 16))
+        return GSA_ERR_SHAPE;
+    PageMap pm;
+    rc = make_page_map(*shape, page_size, block_table, pool_pages, &pm);
+    if (rc != GSA_OK) return rc;
+    hipError_t e = launch_cache_append(*shape, kI_new, K_new, V_new, g2_new, seq_lens, kI_pool, K_pool, Vg_pool, seq_lens_out, pm,
+                                       static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_paged_cache_append");
 }
 
 int32_t gsa_cache_append(const gsa_shape* shape, const void* kI_new, const void* K_new, const void* V_new, const void* g2_new,
@@ -562,7 +647,7 @@ int32_t gsa_cache_append(const gsa_shape* shape, const void* kI_new, const void*
         !aligned(K_cache, 16) || !aligned(Vg_cache, 16))
         return GSA_ERR_SHAPE;
     hipError_t e = launch_cache_append(*shape, kI_new, K_new, V_new, g2_new, seq_lens, kI_cache, K_cache, Vg_cache, seq_lens_out,
-                                       static_cast<hipStream_t>(stream));
+                                       kNoPages, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_cache_append");
 }
 
@@ -657,7 +742,8 @@ int32_t gsa_forward_noalloc(const gsa_shape* shape, const gsa_adaptive* ctl, con
     if (rc != GSA_OK) return rc;
     // nothing in the scratch has to start at zero: every kernel writes what it later reads
     return forward_launches(s, *ctl, Q, K, V, g1_logits, g2_logits, qI, kI, w, bI, softmax_scale, out, idx_out, n_sel_out,
-                            k_out, row_var_out, k_cap, ws, kStaticScratchBytes, nullptr, tn, static_cast<hipStream_t>(stream));
+                            k_out, row_var_out, k_cap, ws, kStaticScratchBytes, nullptr, kNoPages, tn,
+                            static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

@@ -46,6 +46,9 @@ struct AttnArgs {
     int32_t q_offset;
     int32_t part_row0, part_rows;  // rows of the slab that `part` and `winoff` are laid out for
     int32_t rpw;                   // query rows a wave of the bf16 kernel works through (1 .. 64)
+    // Pool mode (paged caches): idx holds rows of one pool [pool_rows, H_kv, d_h] shared by all batch elements
+    // (already translated through the block table); 0: idx holds token positions inside [B, Lk, H_kv, d_h].
+    int64_t pool_rows;
 };
 
 constexpr float kNegBig = -1.0e30f;
@@ -72,7 +75,8 @@ __device__ __forceinline__ float quad_row_sum(float x) {
 // bounds of all rows of the wave are fetched once, up front (lane i keeps those of row i).  A row therefore
 // costs no start-up chain of dependent loads (bounds -> indices -> rows), which is what a short piece -- a
 // row's share of one key window -- would otherwise spend most of its time on.
-template <int DH, bool HAS_G2>
+// POOL: the lists hold rows of a pool that may exceed 4 GiB: row addresses are 64-bit per lane.
+template <int DH, bool HAS_G2, bool POOL = false>
 __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     constexpr int KK = DH / 32;        // MFMA k-steps of the score product
     constexpr int MB = DH / 16;        // 16-feature blocks of the value product
@@ -149,9 +153,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
         if (j0 >= je) ri = seek(ri + 1, j0, je);
     };
 
-    const unsigned char* Kb = static_cast<const unsigned char*>(a.K) + ((int64_t)b * a.Lk * a.H_kv + g) * ROWB;
-    const unsigned char* Vb = static_cast<const unsigned char*>(a.V) + ((int64_t)b * a.Lk * a.H_kv + g) * ROWB;
-    const unsigned char* Gb = HAS_G2 ? static_cast<const unsigned char*>(a.g2) + ((int64_t)b * a.Lk * a.H_kv + g) * ROWB : nullptr;
+    const int64_t row0 = POOL ? 0 : (int64_t)b * a.Lk;  // first row of this batch element's K / V'
+    const unsigned char* Kb = static_cast<const unsigned char*>(a.K) + (row0 * a.H_kv + g) * ROWB;
+    const unsigned char* Vb = static_cast<const unsigned char*>(a.V) + (row0 * a.H_kv + g) * ROWB;
+    const unsigned char* Gb = HAS_G2 ? static_cast<const unsigned char*>(a.g2) + (row0 * a.H_kv + g) * ROWB : nullptr;
     const int32_t* idx0 = a.idx + ((int64_t)b * a.idx_rows + (t0 - a.idx_row0)) * a.k_cap;  // index list of row t0
 
     bf16x8 qf[KK], qf_next[KK];
@@ -184,11 +189,19 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
     auto issue = [&](const int (&tokv)[NVL]) {
 #pragma unroll
         for (int r = 0; r < NVL; ++r) {  // whole rows, 16 bytes per lane: K and V' of a token at the same offset
-            const int tk = max(0, min(tokv[r], a.Lk - 1));
-            const uint32_t off = __umul24((uint32_t)tk, tokstride) + (uint32_t)(lane % VCH) * 16u;  // token < 2^24, stride < 2^24
-            kr[r] = *reinterpret_cast<const u32x4*>(Kb + off);
-            vf[r] = *reinterpret_cast<const u32x4*>(Vb + off);
-            if constexpr (HAS_G2) gf[r] = *reinterpret_cast<const u32x4*>(Gb + off);
+            if constexpr (POOL) {
+                const int64_t row = max((int64_t)0, min((int64_t)tokv[r], a.pool_rows - 1));
+                const int64_t off = row * tokstride + (lane % VCH) * 16;
+                kr[r] = *reinterpret_cast<const u32x4*>(Kb + off);
+                vf[r] = *reinterpret_cast<const u32x4*>(Vb + off);
+                if constexpr (HAS_G2) gf[r] = *reinterpret_cast<const u32x4*>(Gb + off);
+            } else {
+                const int tk = max(0, min(tokv[r], a.Lk - 1));
+                const uint32_t off = __umul24((uint32_t)tk, tokstride) + (uint32_t)(lane % VCH) * 16u;  // token < 2^24, stride < 2^24
+                kr[r] = *reinterpret_cast<const u32x4*>(Kb + off);
+                vf[r] = *reinterpret_cast<const u32x4*>(Vb + off);
+                if constexpr (HAS_G2) gf[r] = *reinterpret_cast<const u32x4*>(Gb + off);
+            }
         }
     };
     // K and V' rows -> LDS (natural layout: row = token slot, 16 B per lane)
@@ -500,6 +513,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a) {
     const int t = a.row_begin + (int)(rid % R);
     const int64_t qrow = (int64_t)b * a.Lq + t;
     const int nsel = max(0, min(a.n_sel[qrow], a.k_cap));
+    const int64_t row0 = a.pool_rows ? 0 : (int64_t)b * a.Lk;  // first row of this batch element's K / V
     const int32_t* idxrow = a.idx + ((int64_t)b * a.idx_rows + (t - a.idx_row0)) * a.k_cap;
     const int G = a.H / a.H_kv;
     const float* Q = static_cast<const float*>(a.Q);
@@ -519,8 +533,8 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a) {
         for (int j0 = 0; j0 < nsel; j0 += 64) {
             const int j = j0 + lane;
             int tok = idxrow[min(j, nsel - 1)];
-            tok = max(0, min(tok, a.Lk - 1));
-            const int64_t krow = (((int64_t)b * a.Lk + tok) * a.H_kv + g) * DH;
+            tok = (int)max((int64_t)0, min((int64_t)tok, (a.pool_rows ? a.pool_rows : (int64_t)a.Lk) - 1));
+            const int64_t krow = ((row0 + tok) * a.H_kv + g) * DH;
             float acc = 0.f;
             for (int c = 0; c < DH; c += 4) {
                 const float4 kv = *reinterpret_cast<const float4*>(K + krow + c);
@@ -545,7 +559,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a) {
             for (int u = 0; u < cnt; ++u) {
                 const float pu = __shfl(p, u, 64);
                 const int tu = __shfl(tok, u, 64);
-                const int64_t vrow = (((int64_t)b * a.Lk + tu) * a.H_kv + g) * DH;
+                const int64_t vrow = ((row0 + tu) * a.H_kv + g) * DH;
 #pragma unroll
                 for (int e = 0; e < DPL; ++e) {
                     float v = V[vrow + lane + 64 * e];
@@ -682,8 +696,9 @@ size_t attn_workspace_bytes(const gsa_shape& sh, int row_begin, int row_end, int
 hipError_t launch_attention(const gsa_shape& sh, int row_begin, int row_end, const void* Q, const void* K, const void* V,
                             const void* g2, const void* g1, const int32_t* idx, int idx_rows, int idx_row0,
                             const int32_t* n_sel, int k_cap, float scale, void* out, void* workspace, const gsa_tuning& tn,
-                            hipStream_t st) {
+                            int64_t pool_rows, hipStream_t st) {
     AttnArgs a;
+    a.pool_rows = pool_rows;
     a.Q = Q;
     a.K = K;
     a.V = V;
@@ -739,6 +754,8 @@ hipError_t launch_attention(const gsa_shape& sh, int row_begin, int row_end, con
             const dim3 grid((unsigned)(sh.B * cdiv(lrows, a.rpw)), (unsigned)(sh.H_kv / gpb), (unsigned)(a.window ? 1 : a.nsplit));
             void (*kern)(AttnArgs) = sh.d_h == 128 ? (g2 ? attn_bf16_kernel<128, true> : attn_bf16_kernel<128, false>)
                                                    : (g2 ? attn_bf16_kernel<64, true> : attn_bf16_kernel<64, false>);
+            if (pool_rows)  // (paged caches hold gated values: no g2 here, checked by the caller)
+                kern = sh.d_h == 128 ? attn_bf16_kernel<128, false, true> : attn_bf16_kernel<64, false, true>;
             if (z == 0 && smem > 48 * 1024) {
                 hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
                 if (e != hipSuccess) return e;

@@ -18,6 +18,7 @@ struct AppendArgs {
     int32_t B, T, Lk;
     int32_t kv_chunks;  // 16-byte chunks of one token's K (or V) row: H_kv * d_h * element size / 16
     int32_t ki_chunks;  // 16-byte chunks of one token's indexer key
+    PageMap pm;         // contiguous caches [B, Lk, ...] or pages of a pool
 };
 
 // One thread per 16-byte chunk of a new token's K row (and the matching V chunk), the first ki_chunks threads
@@ -35,12 +36,12 @@ __global__ void cache_append_kernel(AppendArgs a) {
     if (c == 0 && j == 0 && a.seq_lens_out) a.seq_lens_out[b] = min(len + a.T, a.Lk);
     const int pos = len + j;
     if (pos >= a.Lk) return;
+    const int64_t row = cache_row(a.pm, b, pos, a.Lk);
     if (c < a.ki_chunks)
-        static_cast<u32x4*>(a.kI_cache)[((int64_t)b * a.Lk + pos) * a.ki_chunks + c] =
-            static_cast<const u32x4*>(a.kI_new)[bt * a.ki_chunks + c];
+        static_cast<u32x4*>(a.kI_cache)[row * a.ki_chunks + c] = static_cast<const u32x4*>(a.kI_new)[bt * a.ki_chunks + c];
     if (c >= a.kv_chunks) return;
     const int64_t src = bt * a.kv_chunks + c;
-    const int64_t dst = ((int64_t)b * a.Lk + pos) * a.kv_chunks + c;
+    const int64_t dst = row * a.kv_chunks + c;
     static_cast<u32x4*>(a.K_cache)[dst] = static_cast<const u32x4*>(a.K_new)[src];
     u32x4 v = static_cast<const u32x4*>(a.V_new)[src];
     const u32x4 g = static_cast<const u32x4*>(a.g2_new)[src];
@@ -60,9 +61,10 @@ __global__ void cache_append_kernel(AppendArgs a) {
 
 hipError_t launch_cache_append(const gsa_shape& sh, const void* kI_new, const void* K_new, const void* V_new, const void* g2_new,
                                const int32_t* seq_lens, void* kI_cache, void* K_cache, void* Vg_cache, int32_t* seq_lens_out,
-                               hipStream_t st) {
+                               const PageMap& pm, hipStream_t st) {
     const int eb = sh.dtype == GSA_BF16 ? 2 : 4;
     AppendArgs a;
+    a.pm = pm;
     a.kI_new = kI_new;
     a.K_new = K_new;
     a.V_new = V_new;
@@ -82,6 +84,30 @@ hipError_t launch_cache_append(const gsa_shape& sh, const void* kI_new, const vo
         hipLaunchKernelGGL(cache_append_kernel<true>, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st, a);
     else
         hipLaunchKernelGGL(cache_append_kernel<false>, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
+// Paged caches: the selected token positions of every row, rewritten as rows of the pool (what the attention
+// kernels gather in pool mode).  phys [B, row_end - row_begin, k_cap]; entries beyond n_sel are left alone.
+__global__ void translate_indices_kernel(PageMap pm, const int32_t* idx, int idx_rows, int idx_row0, const int32_t* n_sel,
+                                         int32_t* phys, int B, int Lq, int Lk, int row_begin, int row_end, int k_cap) {
+    const int R = row_end - row_begin;
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= (int64_t)B * R * k_cap) return;
+    const int j = (int)(gid % k_cap);
+    const int64_t rid = gid / k_cap;
+    const int b = (int)(rid / R);
+    const int t = row_begin + (int)(rid % R);
+    if (j >= n_sel[(int64_t)b * Lq + t]) return;
+    const int tok = idx[((int64_t)b * idx_rows + (t - idx_row0)) * k_cap + j];
+    phys[gid] = (int32_t)cache_row(pm, b, max(0, min(tok, Lk - 1)), Lk);
+}
+
+hipError_t launch_translate_indices(const gsa_shape& sh, const PageMap& pm, int row_begin, int row_end, const int32_t* idx,
+                                    int idx_rows, int idx_row0, const int32_t* n_sel, int k_cap, int32_t* phys, hipStream_t st) {
+    const int64_t n = (int64_t)sh.B * (row_end - row_begin) * k_cap;
+    hipLaunchKernelGGL(translate_indices_kernel, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st, pm, idx, idx_rows, idx_row0, n_sel,
+                       phys, sh.B, sh.Lq, sh.Lk, row_begin, row_end, k_cap);
     return hipGetLastError();
 }
 

@@ -50,6 +50,23 @@ __device__ __forceinline__ int batch_q_offset(const int32_t* seq_lens, int b, in
     return seq_lens ? max(0, min(seq_lens[b] - Lq, Lk - Lq)) : q_offset;
 }
 
+// Where the cached rows of a sequence live.  Contiguous caches (table == nullptr): row s of sequence b is row
+// b * Lk + s of a [B, Lk, ...] tensor.  Paged caches: a sequence's tokens sit in pages of 2^page_shift tokens
+// scattered over a pool of pool_pages pages; table[b * max_pages + p] is the pool page that holds tokens
+// p * 2^page_shift .. of sequence b (page numbers are clamped to the pool, so a bad table reads wrong rows,
+// never memory outside the pool).
+struct PageMap {
+    const int32_t* table;
+    int32_t page_shift;
+    int32_t max_pages;
+    int32_t pool_pages;
+};
+__device__ __forceinline__ int64_t cache_row(const PageMap& pm, int b, int s, int Lk) {
+    if (!pm.table) return (int64_t)b * Lk + s;
+    const int pg = max(0, min(pm.table[(int64_t)b * pm.max_pages + (s >> pm.page_shift)], pm.pool_pages - 1));
+    return ((int64_t)pg << pm.page_shift) + (s & ((1 << pm.page_shift) - 1));
+}
+
 // Exact host/device ceil-div.
 __host__ __device__ constexpr int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 

@@ -41,6 +41,7 @@ struct IndexerArgs {
     int32_t ntiles;  // query tiles in the slab
     const int32_t* seq_lens;  // per-sequence lengths (ragged decode) or null
     int32_t hi;      // indexer heads in memory (the kernels work on the next power of two, the extra heads weigh zero)
+    PageMap pm;      // where the rows of kI live (contiguous tensor or pages of a pool)
 };
 
 constexpr int kBN = 128;  // keys per LDS tile
@@ -190,17 +191,24 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
         const int lim_first = min(qoff + t_w0, a.Lk - 1);
         const int lim_last = wave_has_rows ? min(qoff + t_w_last, a.Lk - 1) : -1;
 
-        const unsigned char* kbase = static_cast<const unsigned char*>(a.kI) + (int64_t)b * a.Lk * ROWB;
+        // First row of the key tile that starts at token s0 (a multiple of kBN; pages hold a multiple of kBN tokens,
+        // so a tile never straddles two).  Tiles beyond the last one any row of the workgroup sees are only ever
+        // requested by prefetches that run ahead: they read that last tile instead (with paged caches the pages
+        // beyond a sequence's end need not exist).
+        const int last_tile = kmax_wg & ~(kBN - 1);
+        auto tile_ptr = [&](int s0) {
+            return static_cast<const unsigned char*>(a.kI) + cache_row(a.pm, b, min(s0, last_tile), a.Lk) * ROWB;
+        };
         u32x4 stage[NCH];
         auto load_tile = [&](int s0) {
+            const unsigned char* tp = tile_ptr(s0);
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
                 const int ch = tid + c * 256;
                 const int r = ch / CHPR;
                 const int col = ch % CHPR;
                 const int s = s0 + r;
-                stage[c] = (s < a.Lk) ? *reinterpret_cast<const u32x4*>(kbase + (int64_t)s * ROWB + col * 16)
-                                      : u32x4{0, 0, 0, 0};
+                stage[c] = (s < a.Lk) ? *reinterpret_cast<const u32x4*>(tp + r * ROWB + col * 16) : u32x4{0, 0, 0, 0};
             }
         };
         auto store_tile = [&](int buf) {
@@ -333,11 +341,12 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
             nlead1 = max(min(nlead1, ntile - 1), 0);
             u32x4 stage2[NCH];
             auto load_clamped = [&](int s0, u32x4* st) {  // rows beyond the range repeat the last key: never used unmasked
+                const unsigned char* tp = tile_ptr(s0);
+                const int rmax = a.Lk - 1 - min(s0, last_tile);
 #pragma unroll
                 for (int c = 0; c < NCH; ++c) {
                     const int ch = tid + c * 256;
-                    const int sidx = min(s0 + ch / CHPR, a.Lk - 1);
-                    st[c] = *reinterpret_cast<const u32x4*>(kbase + (int64_t)sidx * ROWB + (ch % CHPR) * 16);
+                    st[c] = *reinterpret_cast<const u32x4*>(tp + min(ch / CHPR, rmax) * ROWB + (ch % CHPR) * 16);
                 }
             };
             if (nlead1 > 0) load_clamped(key_lo + kBN, stage);  // tile 1
@@ -365,10 +374,11 @@ __global__ __launch_bounds__(256, STORE == 0 ? 3 : 2) void indexer_kernel(Indexe
         }
         for (; !ROW1 && it < nlead; ++it) {
             const int s0 = key_lo + it * kBN;
+            const unsigned char* tp = tile_ptr(s0 + kBN);
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {  // prefetch of the next tile, no bounds checks needed
                 const int ch = tid + c * 256;
-                stage[c] = *reinterpret_cast<const u32x4*>(kbase + (int64_t)(s0 + kBN + ch / CHPR) * ROWB + (ch % CHPR) * 16);
+                stage[c] = *reinterpret_cast<const u32x4*>(tp + (ch / CHPR) * ROWB + (ch % CHPR) * 16);
             }
             full_tile(smem + (it & 1) * (kBN * LDSROW), s0);
             store_tile((it + 1) & 1);
@@ -528,8 +538,9 @@ static hipError_t launch_di(const IndexerArgs& a, int DI, int HI, bool relu, hip
 
 hipError_t launch_indexer(const gsa_shape& sh, const void* qI, const void* kI, const float* w, const float* bI,
                           int row_begin, int row_end, float* scores, uint16_t* keys, int64_t ld, float* row_mean,
-                          float* row_var, void* workspace, const int32_t* seq_lens, hipStream_t st) {
+                          float* row_var, void* workspace, const int32_t* seq_lens, const PageMap& pm, hipStream_t st) {
     IndexerArgs a;
+    a.pm = pm;
     a.seq_lens = seq_lens;
     a.keys = keys;
     a.qI = qI;

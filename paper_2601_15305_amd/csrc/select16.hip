@@ -38,6 +38,7 @@ struct Select16Args {
     int32_t cap;         // wave-per-row kernel: records a row can hold in LDS
     int32_t m_lo, m_hi;  // wave-per-row kernel: this launch takes the rows with m_lo < budget <= m_hi
     int32_t group;       // workgroup-per-row kernel: rows a workgroup looks at; 0: one row, taken unconditionally
+    PageMap pm;          // where the rows of kI live (contiguous tensor or pages of a pool)
 };
 
 // First entry of an output row that the wave-per-row kernel could not finish (never a valid index, and not the
@@ -386,7 +387,7 @@ __device__ __forceinline__ void select16_row(const Select16Args& a, int64_t rid,
     uint32_t m_eq = 0;
     bool with_ties = false;
     if (need < ne) {
-        const T* kbase = static_cast<const T*>(a.kI) + (int64_t)b * a.Lk * DI;
+        const T* kpool = static_cast<const T*>(a.kI);  // rows found through cache_row (contiguous or paged)
         if (ne <= (uint32_t)kTieCap) {
             // DI/8 lanes per element, eight channels each: one round trip to memory per pass
             constexpr int LPT = DI / 8;
@@ -397,7 +398,7 @@ __device__ __forceinline__ void select16_row(const Select16Args& a, int64_t rid,
 #pragma unroll
                 for (int j = 0; j < HI; ++j) z[j] = 0.f;
                 if (i < ne) {
-                    const T* kr = kbase + (int64_t)tie_list[i] * DI + 8 * g;
+                    const T* kr = kpool + cache_row(a.pm, b, (int)tie_list[i], a.Lk) * DI + 8 * g;
                     float kv[8];
                     if constexpr (sizeof(T) == 2) {
                         const u32x4 v = *reinterpret_cast<const u32x4*>(kr);
@@ -446,7 +447,7 @@ __device__ __forceinline__ void select16_row(const Select16Args& a, int64_t rid,
             select_exact(
                 [&](auto&& f) {
                     stream_keys(krow, n, [&](int si, uint32_t key) {
-                        if (key == Tq) f(si, recompute_score<T, DI, HI>(kbase + (int64_t)si * DI, q_lds, w_lds, nb_lds));
+                        if (key == Tq) f(si, recompute_score<T, DI, HI>(kpool + cache_row(a.pm, b, si, a.Lk) * DI, q_lds, w_lds, nb_lds));
                     });
                 },
                 n, (int)need, L, &m_eq, true);
@@ -858,10 +859,10 @@ __global__ __launch_bounds__(64) void topk_select16_wave_kernel(Select16Args a) 
             tn += total;
         }
         __syncthreads();
-        const T* kbase = static_cast<const T*>(a.kI) + (int64_t)b * a.Lk * DI;
+        const T* kpool = static_cast<const T*>(a.kI);
         for (uint32_t i = lane; i < ne; i += 64) {
             const uint32_t si = rec[tie_pos[i]] & 0x7ffffu;
-            tie_score[i] = recompute_score<T, DI, HI>(kbase + (int64_t)si * DI, q_lds, w_lds, nb_lds);
+            tie_score[i] = recompute_score<T, DI, HI>(kpool + cache_row(a.pm, b, (int)si, a.Lk) * DI, q_lds, w_lds, nb_lds);
         }
         __syncthreads();
         for (uint32_t i = lane; i < ne; i += 64) {
@@ -981,8 +982,9 @@ static hipError_t launch16_di(const Select16Args& a, int DI, int HI, size_t smem
 hipError_t launch_select16(const gsa_shape& sh, int row_begin, int row_end, const uint16_t* keys, int64_t ld,
                            const int32_t* n_sel, int k_cap, int32_t* idx_out, int idx_rows, int idx_row0, const void* qI,
                            const void* kI, const float* w, const float* bI, const int32_t* seq_lens, int wave_min_rows,
-                           hipStream_t st) {
+                           const PageMap& pm, hipStream_t st) {
     Select16Args a;
+    a.pm = pm;
     a.seq_lens = seq_lens;
     a.keys = keys;
     a.ld = ld;

@@ -153,3 +153,116 @@ def test_decode_step_replays_from_a_hip_graph():
         torch.cuda.synchronize()
         for name in ("out", "idx", "n", "k", "var"):
             assert torch.equal(bufs[0][name], bufs[1][name]), "replay %d differs from the eager call in %s" % (rep, name)
+
+
+def _paged_copy(lens, cap, page, tensors, seed):
+    """Scatter contiguous caches [B, cap, ...] into pools of shuffled pages.  Only the pages a sequence needs exist;
+    the other table entries point far outside the pool (they must never be used), unused pool pages hold NaN."""
+    B = len(lens)
+    max_pages = cap // page
+    need = [(l + page - 1) // page for l in lens]
+    pool_pages = sum(need) + 5
+    g = torch.Generator().manual_seed(seed)
+    perm = torch.randperm(pool_pages, generator=g).tolist()
+    table = torch.full((B, max_pages), 2 ** 30, dtype=torch.int32)
+    pools = [torch.full((pool_pages, page) + tuple(t.shape[2:]), float("nan"), dtype=t.dtype, device=t.device) for t in tensors]
+    nxt = 0
+    for b in range(B):
+        for p in range(need[b]):
+            pg = perm[nxt]
+            nxt += 1
+            table[b, p] = pg
+            n = min(page, lens[b] - p * page)
+            for pool, t in zip(pools, tensors):
+                pool[pg, :n] = t[b, p * page:p * page + n]
+    return table.cuda(), pool_pages, pools
+
+
+@pytest.mark.parametrize("wave", [0, 1])
+@pytest.mark.parametrize("dtype,Lq,page", [("bf16", 1, 256), ("bf16", 3, 128), ("f32", 2, 512)])
+def test_paged_decode_step_equals_the_contiguous_one(dtype, Lq, page, wave):
+    """The same cached rows behind a shuffled block table: every output of the paged call equals the contiguous
+    call's bit for bit; pages a sequence does not own hold NaN and the table entries beyond its length point
+    outside the pool."""
+    B, cap, k_cap = 6, 2560, 128
+    lens = [Lq, 37, 300, 2560, 1024, 2559]
+    wl = S.Workload("paged", B, Lq, cap, 0, 16 if dtype == "bf16" else 4, 4 if dtype == "bf16" else 2, 128 if dtype == "bf16" else 64,
+                    4, 64, dtype, 45, 16, 128, seed=31)
+    t = S.make_inputs(wl, "cuda")
+    sh = G.shape_of(wl)
+    Vg = torch.empty_like(t["V"])
+    G.gsa_value_gate(sh, t["V"], t["g2"], Vg)
+    seq_lens = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    ctl = G.make_adaptive(0.3, 45, 16, 128)
+    tn = G.make_tuning(select_wave_min_rows=wave)
+
+    def outputs():
+        return dict(out=torch.full_like(t["Q"], float("nan")), idx=torch.full((B, Lq, k_cap), -7, dtype=torch.int32, device="cuda"),
+                    n=torch.empty((B, Lq), dtype=torch.int32, device="cuda"), k=torch.empty((B, Lq), dtype=torch.int32, device="cuda"),
+                    var=torch.empty((B, Lq), dtype=torch.float32, device="cuda"))
+    ref = outputs()
+    ws = G.workspace(G.gsa_decode_workspace_bytes(sh, k_cap))
+    G.gsa_decode_step(sh, ctl, t["Q"], t["g1"], t["qI"], t["w"], None, t["kI"], t["K"], Vg, seq_lens, 0.0, ref["out"], ref["idx"], ref["n"],
+                      ref["k"], ref["var"], k_cap, ws, tuning=tn)
+    table, pool_pages, (kI_p, K_p, Vg_p) = _paged_copy(lens, cap, page, [t["kI"], t["K"], Vg], seed=page + Lq)
+    got = outputs()
+    ws2 = G.workspace(G.gsa_paged_decode_workspace_bytes(sh, k_cap))
+    ws2.fill_(0xFF)
+    G.gsa_paged_decode_step(sh, ctl, page, table, pool_pages, t["Q"], t["g1"], t["qI"], t["w"], None, kI_p, K_p, Vg_p, seq_lens, 0.0,
+                            got["out"], got["idx"], got["n"], got["k"], got["var"], k_cap, ws2, tuning=tn)
+    torch.cuda.synchronize()
+    assert torch.isfinite(got["out"].float()).all(), "a page outside a sequence was read"
+    for name in ("n", "k", "var", "out"):
+        assert torch.equal(got[name], ref[name]), name
+    valid = torch.arange(k_cap, device="cuda")[None, None, :] < ref["n"][..., None]
+    assert torch.equal(got["idx"][valid], ref["idx"][valid])
+    # argument errors are decided on the host
+    for bad_page in (100, 64, 384):
+        with pytest.raises(G.GsaError) as e:
+            G.gsa_paged_decode_step(sh, ctl, bad_page, table, pool_pages, t["Q"], t["g1"], t["qI"], t["w"], None, kI_p, K_p, Vg_p, seq_lens,
+                                    0.0, got["out"], None, None, None, None, k_cap, ws2)
+        assert e.value.status == G.GSA_ERR_SHAPE
+    with pytest.raises(G.GsaError) as e:
+        G.gsa_paged_decode_step(sh, ctl, page, None, pool_pages, t["Q"], t["g1"], t["qI"], t["w"], None, kI_p, K_p, Vg_p, seq_lens, 0.0,
+                                got["out"], None, None, None, None, k_cap, ws2)
+    assert e.value.status == G.GSA_ERR_NULL
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_paged_cache_append_fills_the_pages_of_each_sequence(dtype):
+    """T new tokens per sequence land at each sequence's own end, in the page the block table names; the pools hold
+    exactly what the contiguous caches hold at the same positions."""
+    B, cap, page, T_new = 4, 1024, 128, 5
+    Hkv, dh, dI = 2, 64, 32
+    lens = [0, 126, 500, 1021]        # crossing a page boundary; running into the capacity
+    wl = S.Workload("pappend", B, T_new, cap, 0, 4, Hkv, dh, 2, dI, dtype, 8, 4, 16, seed=37)
+    t = S.make_inputs(wl, "cuda")
+    sh = G.shape_of(wl)
+    new = {n: t[n][:, :T_new].contiguous() for n in ("kI", "K", "V", "g2")}
+    seq_lens = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    dt = t["K"].dtype
+    kI_c = torch.zeros((B, cap, dI), dtype=dt, device="cuda")
+    K_c = torch.zeros((B, cap, Hkv, dh), dtype=dt, device="cuda")
+    Vg_c = torch.zeros_like(K_c)
+    out_c = torch.empty_like(seq_lens)
+    G.gsa_cache_append(sh, new["kI"], new["K"], new["V"], new["g2"], seq_lens, kI_c, K_c, Vg_c, out_c)
+    max_pages = cap // page
+    pool_pages = B * max_pages + 3
+    perm = torch.randperm(pool_pages, generator=torch.Generator().manual_seed(3))[:B * max_pages].reshape(B, max_pages).to(torch.int32).cuda()
+    kI_p = torch.zeros((pool_pages, page, dI), dtype=dt, device="cuda")
+    K_p = torch.zeros((pool_pages, page, Hkv, dh), dtype=dt, device="cuda")
+    Vg_p = torch.zeros_like(K_p)
+    out_p = torch.empty_like(seq_lens)
+    G.gsa_paged_cache_append(sh, page, perm, pool_pages, new["kI"], new["K"], new["V"], new["g2"], seq_lens, kI_p, K_p, Vg_p, out_p)
+    torch.cuda.synchronize()
+    assert torch.equal(out_p, out_c) and out_c.tolist() == [5, 131, 505, 1024]
+    for b in range(B):
+        for p in range(max_pages):
+            pg = int(perm[b, p])
+            assert torch.equal(kI_p[pg], kI_c[b, p * page:(p + 1) * page])
+            assert torch.equal(K_p[pg], K_c[b, p * page:(p + 1) * page])
+            assert torch.equal(Vg_p[pg], Vg_c[b, p * page:(p + 1) * page])
+    used = set(perm.flatten().tolist())
+    for pg in range(pool_pages):
+        if pg not in used:
+            assert not K_p[pg].any() and not kI_p[pg].any(), "a page outside the table was written"

@@ -67,6 +67,8 @@ def _check(h, W, out, tokens):
     (1, 1, 64, 2, 1, 64, 1, 32),       # one token, one k-step
     (3, 128, 320, 16, 4, 128, 4, 64),  # the layer shape of Table 9 at a small width; 5636 features, 3 token blocks
     (1, 1000, 128, 2, 2, 64, 7, 128),  # seven indexer heads: the sigmoid segment straddles a group of four features
+    (1, 2100, 128, 4, 2, 64, 3, 32),   # large-call shape (256 x 256 tiles): 9 ragged token blocks, 1027 features = 4 blocks + 3
+    (2, 1300, 192, 16, 4, 128, 4, 64), # large-call shape, 5636 features: 23 feature blocks in groups of four (last group: 3)
 ])
 def test_input_projections_match_oracle(B, Lq, d_model, H, H_kv, d_h, HI, dI):
     sh = G.make_shape(B, Lq, Lq, 0, H, H_kv, d_h, HI, dI, "bf16")
@@ -74,7 +76,7 @@ def test_input_projections_match_oracle(B, Lq, d_model, H, H_kv, d_h, HI, dI):
     out = _run(sh, d_model, h, W)
     n_tok = B * Lq
     tokens = np.arange(n_tok) if n_tok <= 160 else np.unique(np.concatenate(
-        [np.arange(0, 8), np.arange(n_tok - 8, n_tok), np.arange(120, 136), np.random.default_rng(5).integers(0, n_tok, 64)]))
+        [np.arange(0, 8), np.arange(n_tok - 8, n_tok), np.arange(120, 136), np.arange(250, 262), np.random.default_rng(5).integers(0, n_tok, 64)]))
     _check(h, W, out, torch.from_numpy(tokens).cuda())
 
 
@@ -100,7 +102,7 @@ def test_skipped_projections_and_pairing():
     assert e.value.status == G.GSA_ERR_UNSUPPORTED
 
 
-@pytest.mark.parametrize("B,Lq,H,d_h,d_model", [(2, 77, 4, 64, 192), (1, 300, 16, 128, 130), (4, 1, 2, 64, 2048)])
+@pytest.mark.parametrize("B,Lq,H,d_h,d_model", [(2, 77, 4, 64, 192), (1, 300, 16, 128, 130), (4, 1, 2, 64, 2048), (1, 2500, 8, 64, 770)])
 def test_output_projection_matches_oracle(B, Lq, H, d_h, d_model):
     sh = G.make_shape(B, Lq, Lq, 0, H, H, d_h, 1, 32, "bf16")
     g = torch.Generator().manual_seed(Lq)
@@ -109,7 +111,11 @@ def test_output_projection_matches_oracle(B, Lq, H, d_h, d_model):
     y = torch.full((B, Lq, d_model), float("nan"), dtype=torch.bfloat16, device="cuda")
     G.gsa_output_projection(sh, d_model, u, W_O, y)
     torch.cuda.synchronize()
-    _check(u, {"O": W_O}, {"O": y}, torch.arange(B * Lq, device="cuda"))
+    n_tok = B * Lq
+    tokens = torch.arange(n_tok, device="cuda") if n_tok <= 400 else torch.cat(
+        [torch.arange(0, 8, device="cuda"), torch.arange(n_tok - 8, n_tok, device="cuda"), torch.arange(250, 262, device="cuda"),
+         torch.randint(0, n_tok, (48,), generator=torch.Generator().manual_seed(1)).cuda()])
+    _check(u, {"O": W_O}, {"O": y}, tokens)
 
 
 def test_projections_feed_the_forward_path():
