@@ -194,6 +194,96 @@ def sparse_gated_attn_row(Q_t, K, V, g2, g1_t, idx, scale=None):
     return out, A_all
 
 
+# --------------------------------------------------------------------------- training side (Sec. 6.1)
+def sparse_gated_attn_bwd_row(Q_t, K, V, g2, g1_t, idx, dout_t, scale=None):
+    """Gradients of one query row of Sec. 3.5 / 3.6 (the selection S_t = idx is held fixed: top-k has no
+    gradient), for the upstream gradient dout_t [H, dh] of the gated output.  With s_j = scale * q.k_j,
+    P = softmax(s), V'_j = V_j * sigma(g2_j), O = sum_j P_j V'_j, out = O * sigma(g1):
+        dO   = dout * sigma(g1)                 dg1  = dout * O * sigma(g1) (1 - sigma(g1))
+        dP_j = dO . V'_j                        ds_j = P_j (dP_j - sum_i P_i dP_i)
+        dq   = scale * sum_j ds_j k_j           dk_j = scale * ds_j q          dV'_j = P_j dO
+        dV_j = dV'_j * sigma(g2_j)              dg2_j = dV'_j * V_j * sigma(g2_j) (1 - sigma(g2_j))
+    Returns dQ_t [H, dh], dg1_t [H, dh], and dK, dV, dg2 [|S|, Hkv, dh]: the contributions of this row to
+    the selected keys (heads of one kv group summed), in the order of idx."""
+    Q_t = np.asarray(Q_t, np.float64)
+    dout_t = np.asarray(dout_t, np.float64)
+    H, dh = Q_t.shape
+    Hkv = K.shape[1]
+    group = H // Hkv
+    if scale is None:
+        scale = 1.0 / math.sqrt(dh)
+    idx = np.asarray(idx, np.int64)
+    n = idx.shape[0]
+    dQ = np.zeros((H, dh), np.float64)
+    dg1 = np.zeros((H, dh), np.float64)
+    dK = np.zeros((n, Hkv, dh), np.float64)
+    dV = np.zeros((n, Hkv, dh), np.float64)
+    dg2 = np.zeros((n, Hkv, dh), np.float64)
+    if n == 0:
+        return dQ, dg1, dK, dV, dg2
+    for h in range(H):
+        g = h // group
+        Ks = np.asarray(K[idx, g], np.float64)
+        Vs = np.asarray(V[idx, g], np.float64)
+        s2 = sigmoid(np.asarray(g2[idx, g], np.float64)) if g2 is not None else np.ones_like(Vs)
+        Vp = Vs * s2
+        logit = (Ks @ Q_t[h]) * scale
+        e = np.exp(logit - np.max(logit))
+        P = e / np.sum(e)
+        O = P @ Vp
+        s1 = sigmoid(np.asarray(g1_t[h], np.float64)) if g1_t is not None else np.ones(dh)
+        dO = dout_t[h] * s1
+        if g1_t is not None:
+            dg1[h] = dout_t[h] * O * s1 * (1.0 - s1)
+        dP = Vp @ dO
+        ds = P * (dP - np.sum(P * dP))
+        dQ[h] = scale * (ds @ Ks)
+        dK[:, g] += scale * ds[:, None] * Q_t[h][None, :]
+        dVp = P[:, None] * dO[None, :]
+        dV[:, g] += dVp * s2
+        if g2 is not None:
+            dg2[:, g] += dVp * Vs * s2 * (1.0 - s2)
+    return dQ, dg1, dK, dV, dg2
+
+
+def indexer_sparse_kl_row(A, I_sel):
+    """Sparse-phase indexer loss of one query (Sec. 6.1, second equation):
+        L_t = KL(p_{t,S_t} || softmax(I_{t,S_t})),
+    with the target p the attention distribution over S_t, averaged over the query heads (the score has no head
+    index) and treated as a constant, and the softmax of the indexer scores taken over S_t.  A [H, |S|] attention
+    weights (rows sum to 1), I_sel [|S|] the scores of the selected keys.  Returns the loss and its gradient with
+    respect to I_sel, softmax(I_sel) - p.  Terms with p = 0 contribute nothing."""
+    A = np.asarray(A, np.float64)
+    I_sel = np.asarray(I_sel, np.float64)
+    if I_sel.shape[0] == 0:
+        return 0.0, np.zeros(0)
+    p = A.mean(axis=0)
+    z = I_sel - np.max(I_sel)
+    logq = z - math.log(np.sum(np.exp(z)))
+    pos = p > 0
+    loss = float(np.sum(p[pos] * (np.log(p[pos]) - logq[pos])))
+    return loss, np.exp(logq) - p
+
+
+def indexer_scores_bwd_row(qI_t, kI_sel, w_t, bI, dI_sel):
+    """Gradients of Eq. "indexer" (Sec. 3.3) for one query, given dL/dI_{t,s} for the keys in kI_sel [|S|, dI]:
+        z_{j,s} = q_j . k_s + b_j,   I_s = sum_j w_j sigma(z_{j,s})
+        dw_j = sum_s dI_s sigma(z_{j,s})                    dz_{j,s} = dI_s w_j sigma (1 - sigma)
+        dq_j = sum_s dz_{j,s} k_s      dk_s = sum_j dz_{j,s} q_j      db_j = sum_s dz_{j,s}
+    Returns dqI [HI, dI], dkI [|S|, dI] (this row's contribution), dw [HI], dbI [HI]."""
+    q = np.asarray(qI_t, np.float64)
+    k = np.asarray(kI_sel, np.float64)
+    w = np.asarray(w_t, np.float64)
+    d = np.asarray(dI_sel, np.float64)
+    z = k @ q.T                                   # [|S|, HI]
+    if bI is not None:
+        z = z + np.asarray(bI, np.float64)[None, :]
+    sg = sigmoid(z)
+    dw = d @ sg
+    dz = d[:, None] * w[None, :] * sg * (1.0 - sg)
+    return dz.T @ k, dz @ q, dw, dz.sum(axis=0)
+
+
 # --------------------------------------------------------------------------- whole path
 def gsa_forward_row(b, i, Q, K, V, g1, g2, qI, kI, w, bI, q_offset, ctl, scale=None, act="sigmoid"):
     """The four stages for one query row (b, i).  ctl: dict(vbar, k_base, k_min, k_max,

@@ -376,3 +376,116 @@ def test_cost_model_reproduces_printed_speedup():
         assert C.causal_pairs(B, Lq, Lk, off) == brute
     assert C.indexer_flops(10, 4, 64) == 5120 and C.attention_flops(3, 16, 128) == 3 * 8192
     assert C.gathered_bytes(5, 4, 128, 2) == 5 * 2048 and C.gathered_bytes(5, 4, 128, 2, True) == 5 * 3072
+
+
+# ---------------------------------------------------------------- training side (Sec. 6.1; gradients of Sec. 3.3, 3.5, 3.6)
+def _bwd_case(seed, H=4, Hkv=2, dh=8, Lk=23, n=9, gates=True):
+    r = rng(seed)
+    Q = r.standard_normal((H, dh)); K = r.standard_normal((Lk, Hkv, dh)); V = r.standard_normal((Lk, Hkv, dh))
+    g2 = r.standard_normal((Lk, Hkv, dh)) if gates else None
+    g1 = r.standard_normal((H, dh)) if gates else None
+    idx = np.sort(r.choice(Lk, n, replace=False))
+    dout = r.standard_normal((H, dh))
+    return Q, K, V, g2, g1, idx, dout
+
+
+@pytest.mark.parametrize("gates", [True, False])
+def test_attention_backward_against_autograd(gates):
+    """The closed-form gradients of the sparse gated attention against torch.autograd on an independent formulation:
+    dense masked softmax over all keys (-inf outside S_t), GQA by repeating kv heads, gates as torch.sigmoid."""
+    Q, K, V, g2, g1, idx, dout = _bwd_case(5, gates=gates)
+    H, dh = Q.shape
+    Lk, Hkv, _ = K.shape
+    t = lambda a: torch.tensor(a, dtype=torch.float64, requires_grad=True)
+    Qt, Kt, Vt = t(Q), t(K), t(V)
+    g2t = t(g2) if gates else None
+    g1t = t(g1) if gates else None
+    mask = torch.full((Lk,), float("-inf"), dtype=torch.float64)
+    mask[torch.from_numpy(idx)] = 0.0
+    Vp = Vt * torch.sigmoid(g2t) if gates else Vt
+    Kr = Kt.repeat_interleave(H // Hkv, dim=1)             # [Lk, H, dh]
+    Vr = Vp.repeat_interleave(H // Hkv, dim=1)
+    logits = torch.einsum("hd,shd->hs", Qt, Kr) / math.sqrt(dh) + mask[None, :]
+    out = torch.einsum("hs,shd->hd", torch.softmax(logits, dim=-1), Vr)
+    if gates:
+        out = out * torch.sigmoid(g1t)
+    out.backward(torch.from_numpy(dout))
+    dQ, dg1, dK, dV, dg2 = O.sparse_gated_attn_bwd_row(Q, K, V, g2, g1, idx, dout)
+    assert np.allclose(dQ, Qt.grad.numpy(), rtol=1e-10, atol=1e-12)
+    full = lambda part: (lambda z: (z.__setitem__(idx, part), z)[1])(np.zeros((Lk, Hkv, dh)))
+    assert np.allclose(full(dK), Kt.grad.numpy(), rtol=1e-10, atol=1e-12)
+    assert np.allclose(full(dV), Vt.grad.numpy(), rtol=1e-10, atol=1e-12)
+    if gates:
+        assert np.allclose(dg1, g1t.grad.numpy(), rtol=1e-10, atol=1e-12)
+        assert np.allclose(full(dg2), g2t.grad.numpy(), rtol=1e-10, atol=1e-12)
+        off = np.setdiff1d(np.arange(Lk), idx)
+        assert not Kt.grad.numpy()[off].any() and not g2t.grad.numpy()[off].any(), "keys outside S_t get no gradient"
+    else:
+        assert not dg1.any() and not dg2.any()
+
+
+def test_attention_backward_against_finite_differences():
+    """Central differences of the forward oracle itself, one entry of every input."""
+    Q, K, V, g2, g1, idx, dout = _bwd_case(8)
+    dQ, dg1, dK, dV, dg2 = O.sparse_gated_attn_bwd_row(Q, K, V, g2, g1, idx, dout)
+    f = lambda Q_, K_, V_, g2_, g1_: float(np.sum(O.sparse_gated_attn_row(Q_, K_, V_, g2_, g1_, idx)[0] * dout))
+    eps = 1e-6
+    def fd(arrs, which, pos):
+        a = [x.copy() for x in arrs]; b = [x.copy() for x in arrs]
+        a[which][pos] += eps; b[which][pos] -= eps
+        return (f(*a) - f(*b)) / (2 * eps)
+    base = [Q, K, V, g2, g1]
+    j = 3                                   # list position of a selected key
+    s = int(idx[j])
+    assert abs(fd(base, 0, (2, 5)) - dQ[2, 5]) < 1e-7
+    assert abs(fd(base, 1, (s, 1, 3)) - dK[j, 1, 3]) < 1e-7
+    assert abs(fd(base, 2, (s, 0, 7)) - dV[j, 0, 7]) < 1e-7
+    assert abs(fd(base, 3, (s, 1, 2)) - dg2[j, 1, 2]) < 1e-7
+    assert abs(fd(base, 4, (1, 4)) - dg1[1, 4]) < 1e-7
+    # invariants: the gradient of the logits sums to zero (softmax), so dq is orthogonal to nothing in particular but
+    # a key-independent shift of all selected keys by u changes nothing: sum_j dk_j . u = -(dq-term) ... check directly
+    u = rng(1).standard_normal(Q.shape[1])
+    K2 = K.copy(); K2[idx] += 1e-6 * u
+    shift = (f(Q, K2, V, g2, g1) - f(Q, K, V, g2, g1)) / 1e-6
+    assert abs(shift - float(np.sum(dK * u))) < 1e-5
+
+
+def test_sparse_kl_loss_and_gradient():
+    """Sec. 6.1: zero when softmax(I) equals the head-averaged attention; otherwise equal to scipy's relative
+    entropy; gradient softmax(I) - p (finite differences; sums to zero)."""
+    from scipy.special import rel_entr, softmax, logsumexp
+    r = rng(12)
+    A = softmax(r.standard_normal((4, 11)), axis=-1)
+    p = A.mean(0)
+    loss0, grad0 = O.indexer_sparse_kl_row(A, np.log(p) + 3.7)      # softmax(log p + c) = p
+    assert abs(loss0) < 1e-14 and np.allclose(grad0, 0, atol=1e-14)
+    I = r.uniform(0, 4, 11)
+    loss, grad = O.indexer_sparse_kl_row(A, I)
+    assert abs(loss - float(np.sum(rel_entr(p, softmax(I))))) < 1e-13 and loss > 0
+    assert abs(np.sum(grad)) < 1e-14
+    for s in (0, 5, 10):
+        Ip = I.copy(); Im = I.copy(); Ip[s] += 1e-6; Im[s] -= 1e-6
+        assert abs((O.indexer_sparse_kl_row(A, Ip)[0] - O.indexer_sparse_kl_row(A, Im)[0]) / 2e-6 - grad[s]) < 1e-8
+    A0 = A.copy(); A0[:, 2] = 0; A0 /= A0.sum(-1, keepdims=True)   # a key no head attends to: contributes nothing
+    l0, g0 = O.indexer_sparse_kl_row(A0, I)
+    assert np.isfinite(l0) and abs(g0[2] - softmax(I)[2]) < 1e-15
+    assert O.indexer_sparse_kl_row(np.zeros((4, 0)), np.zeros(0))[0] == 0.0
+
+
+def test_indexer_backward_against_autograd():
+    """Gradients of Eq. "indexer" against torch.autograd on the scores written with torch ops."""
+    r = rng(14)
+    HI, dI, n = 3, 6, 7
+    q = r.standard_normal((HI, dI)); k = r.standard_normal((n, dI)); w = r.uniform(0.1, 0.9, HI); b = r.standard_normal(HI)
+    d = r.standard_normal(n)
+    t = lambda a: torch.tensor(a, dtype=torch.float64, requires_grad=True)
+    qt, kt, wt, bt = t(q), t(k), t(w), t(b)
+    I = (torch.sigmoid(kt @ qt.T + bt[None, :]) * wt[None, :]).sum(-1)
+    assert np.allclose(I.detach().numpy(), O.indexer_scores_row(q, k, w, b), rtol=1e-13)
+    I.backward(torch.from_numpy(d))
+    dq, dk, dw, db = O.indexer_scores_bwd_row(q, k, w, b, d)
+    for mine, ref in ((dq, qt.grad), (dk, kt.grad), (dw, wt.grad), (db, bt.grad)):
+        assert np.allclose(mine, ref.numpy(), rtol=1e-11, atol=1e-13)
+    dq0, dk0, dw0, db0 = O.indexer_scores_bwd_row(q, k, w, None, d)
+    I0 = (torch.sigmoid(kt.detach() @ qt.detach().T) * wt.detach()[None, :]).sum(-1)
+    assert np.allclose(dw0, (torch.sigmoid(kt.detach() @ qt.detach().T) * torch.from_numpy(d)[:, None]).sum(0).numpy())
