@@ -16,6 +16,7 @@ Inputs are resident in HBM before the timed region.  Prints one JSON line:
   decode_c5, c4_h_kv16  the decode configuration (eager calls, and one call captured in a HIP graph and replayed)
                         and the 16-kv-head reading of the 128K prefill
   projections           the layer's input and output projections at the same token count (d_model 2048)
+  training_c2           backward of the sparse gated attention and the sparse-phase indexer loss at the 8K configuration
   cpu_baseline          the CPU oracle timed on a bounded sample of the same workload on this machine's host cores
 """
 import argparse
@@ -305,6 +306,38 @@ def projections_leg(G, wl, d_model, dev):
             "output_frac_mfma_peak": round(fo / (oms * 1e-3) / 1e12 / PEAK_MFMA_BF16_TFLOPS, 4)}
 
 
+def training_leg(G, S, wl, dev):
+    """Training side (Sec. 6.1) at a training-length context: the backward of the sparse gated attention (selection
+    held fixed) and the sparse-phase indexer loss with its gradients, after one forward call that fixes the selection."""
+    import torch
+    t = S.make_inputs(wl, dev)
+    run = ForwardRun(G, wl, t, 8)
+    run.step()
+    torch.cuda.synchronize()
+    sh, k_cap = run.sh, run.k_cap
+    f32 = dict(dtype=torch.float32, device=dev)
+    dout = torch.randn(t["Q"].shape, generator=torch.Generator(device=dev).manual_seed(3), device=dev).to(t["Q"].dtype)
+    dQ, dg1 = torch.empty(t["Q"].shape, **f32), torch.empty(t["Q"].shape, **f32)
+    dK, dV, dg2 = (torch.empty(t["K"].shape, **f32) for _ in range(3))
+    p_mean = torch.empty((wl.B, wl.Lq, k_cap), **f32)
+    bms = timed(lambda: G.gsa_sparse_gated_attn_bwd(sh, t["Q"], t["K"], t["V"], t["g2"], t["g1"], run.idx, run.n_sel, k_cap, 0.0, dout,
+                                                    dQ, dK, dV, dg1, dg2, p_mean), 2)
+    loss = torch.empty((wl.B, wl.Lq), **f32)
+    dqI, dkI, dw = torch.empty(t["qI"].shape, **f32), torch.empty(t["kI"].shape, **f32), torch.empty(t["w"].shape, **f32)
+    kms = timed(lambda: G.gsa_indexer_sparse_kl(sh, t["qI"], t["kI"], t["w"], None, run.idx, run.n_sel, k_cap, p_mean, loss, dqI, dkI, dw),
+                2)
+    fms, _ = run.time(3, 1)
+    pairs = int(run.n_sel.sum().item())
+    # fp32 atomic adds of the backward: one dK and one dV' row per (query, selected key, chunk of up to four query
+    # heads of a kv group)
+    G_ = wl.H // wl.H_kv
+    hc = 4 if G_ % 4 == 0 else (2 if G_ % 2 == 0 else 1)
+    atomic_bytes = pairs * (wl.H // hc) * wl.d_h * 4 * 2
+    return {"workload": wl.name, "forward_ms": round(fms, 3), "attn_backward_ms": round(bms, 3), "indexer_kl_ms": round(kms, 3),
+            "selected_pairs": pairs, "attn_backward_atomic_gbs": round(atomic_bytes / (bms * 1e-3) / 1e9, 1),
+            "mean_kl_per_row": round(float(loss.double().mean().item()), 5)}
+
+
 def small_leg(G, S, CM, wl, steps, warmup, workspace_gib):
     """queries/s of another configuration (fresh inputs), with the indexer's key-scan rate for decode shapes."""
     import torch
@@ -528,6 +561,8 @@ def main():
         torch.cuda.empty_cache()
         print("[bench] projections, decode and 16-kv-head legs ...", file=sys.stderr, flush=True)
         result["projections"] = projections_leg(G, S.C4, 2048, dev)
+        torch.cuda.empty_cache()
+        result["training_c2"] = training_leg(G, S, S.C2, dev)
         torch.cuda.empty_cache()
         result["decode_c5"] = small_leg(G, S, CM, S.C5, 20, 3, args.workspace_gib)
         result["c4_h_kv16"] = small_leg(G, S, CM, S.C4.with_(H_kv=16), 3, 1, args.workspace_gib)

@@ -309,6 +309,35 @@ int32_t gsa_input_projections(const gsa_shape* shape, int32_t d_model, const voi
 int32_t gsa_output_projection(const gsa_shape* shape, int32_t d_model, const void* attn_out, const void* W_O,
                               void* y, void* stream);
 
+/* ---- training side, Sec. 6.1 ------------------------------------------------------------------------
+ * gsa_sparse_gated_attn_bwd: gradients of stage 4 (Sec. 3.5, 3.6) for the upstream gradient dout
+ * [B, Lq, H, d_h] (dtype elements) of its output, with the selection idx / n_sel held fixed (top-k has no
+ * gradient) and Lq = the rows idx covers (row range = all rows).  With s_j = scale * q.k_j, P = softmax(s),
+ * V'_j = V_j * sigmoid(g2_j), O = sum_j P_j V'_j, out = O * sigmoid(g1):
+ *   dO = dout * sigmoid(g1)         dg1 = dout * O * sigmoid(g1) (1 - sigmoid(g1))
+ *   ds_j = P_j (dO.V'_j - dO.O)     dq = scale * sum_j ds_j k_j     dk_j += scale * ds_j q     dV'_j += P_j dO
+ *   dV = dV' * sigmoid(g2)          dg2 = dV' * V * sigmoid(g2) (1 - sigmoid(g2))
+ * All gradients are fp32: dQ, dg1 [B, Lq, H, d_h]; dK, dV, dg2 [B, Lk, H_kv, d_h] (written entirely: rows no
+ * query selected are zero; sums over the queries use fp32 atomics, so their last bits vary between runs).
+ * g1_logits and dg1 are given together or both NULL, likewise g2_logits and dg2.
+ *   p_mean  device, out, fp32 [B, Lq, k_cap] or NULL: the attention weights of every row over its selected keys,
+ *           averaged over the H heads -- the target p_{t,S_t} of the sparse-phase indexer loss.
+ *
+ * gsa_indexer_sparse_kl: the sparse-phase indexer loss of Sec. 6.1, per query row,
+ *   loss_rows[b,t] = KL(p_{t,S_t} || softmax_{s in S_t} I_{t,s}),   p taken as a constant (the frozen target),
+ * and the gradients it sends into the indexer of Sec. 3.3 (dI_s = softmax(I)_s - p_s):
+ *   dqI [B, Lq, HI, dI]   dkI [B, Lk, dI] (atomics)   dw [B, Lq, HI] (w.r.t. the post-sigmoid head weights)
+ *   dbI [HI] (atomics; given together with bI or both NULL), all fp32.  Sigmoid indexer only. */
+int32_t gsa_sparse_gated_attn_bwd(const gsa_shape* shape, const void* Q, const void* K, const void* V,
+                                  const void* g2_logits, const void* g1_logits, const int32_t* idx,
+                                  const int32_t* n_sel, int32_t k_cap, float softmax_scale, const void* dout,
+                                  float* dQ, float* dK, float* dV, float* dg1, float* dg2, float* p_mean,
+                                  void* stream);
+int32_t gsa_indexer_sparse_kl(const gsa_shape* shape, const void* qI, const void* kI, const float* w,
+                              const float* bI, const int32_t* idx, const int32_t* n_sel, int32_t k_cap,
+                              const float* p, float* loss_rows, float* dqI, float* dkI, float* dw, float* dbI,
+                              void* stream);
+
 /* ---- comparison variants: dense causal attention, Sec. 2.1 Eq. 2 ------------------------------------
  * Every visible key, no indexer and no selection: with g2 and g1 given this is the "gated only" variant of
  * Sec. 7.1 (Eq. 2 with V' = V * sigmoid(g2) and the result multiplied by sigmoid(g1)), with both NULL the

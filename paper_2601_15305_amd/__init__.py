@@ -26,7 +26,8 @@ ENTRY_POINTS = (
     "gsa_topk_select_keys", "gsa_sparse_gated_attn", "gsa_attn_workspace_bytes", "gsa_value_gate", "gsa_forward",
     "gsa_forward_workspace_bytes", "gsa_forward_noalloc", "gsa_dense_gated_attn", "gsa_dense_attn_workspace_bytes",
     "gsa_cache_append", "gsa_decode_step", "gsa_decode_workspace_bytes", "gsa_paged_cache_append", "gsa_paged_decode_step",
-    "gsa_paged_decode_workspace_bytes", "gsa_input_projections", "gsa_output_projection",
+    "gsa_paged_decode_workspace_bytes", "gsa_input_projections", "gsa_output_projection", "gsa_sparse_gated_attn_bwd",
+    "gsa_indexer_sparse_kl",
     "gsa_probe_gather", "gsa_status_string", "gsa_last_error", "gsa_version",
 )
 
@@ -100,6 +101,10 @@ def load():
     lib.gsa_decode_step.restype = i32
     lib.gsa_decode_workspace_bytes.argtypes = [shp, i32, tun]
     lib.gsa_decode_workspace_bytes.restype = sz
+    lib.gsa_sparse_gated_attn_bwd.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, i32, f32] + [vp] * 8
+    lib.gsa_sparse_gated_attn_bwd.restype = i32
+    lib.gsa_indexer_sparse_kl.argtypes = [shp, vp, vp, vp, vp, vp, vp, i32] + [vp] * 7
+    lib.gsa_indexer_sparse_kl.restype = i32
     lib.gsa_paged_cache_append.argtypes = [shp, i32, vp, i32] + [vp] * 10
     lib.gsa_paged_cache_append.restype = i32
     lib.gsa_paged_decode_step.argtypes = [shp, ctl, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, i32, vp, sz,
@@ -331,6 +336,20 @@ def gsa_paged_decode_step(shape, ctl, page_size, block_table, pool_pages, Q, g1_
                                       _ptr(idx_out), _ptr(n_sel_out), _ptr(k_out), _ptr(row_var_out), k_cap, _ptr(workspace),
                                       workspace_bytes, _tun(tuning), _stream(stream))
     _check(rc, "gsa_paged_decode_step")
+
+
+def gsa_sparse_gated_attn_bwd(shape, Q, K, V, g2_logits, g1_logits, idx, n_sel, k_cap, softmax_scale, dout, dQ, dK, dV, dg1, dg2,
+                              p_mean=None, stream=None):
+    rc = load().gsa_sparse_gated_attn_bwd(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(g2_logits), _ptr(g1_logits), _ptr(idx),
+                                          _ptr(n_sel), k_cap, float(softmax_scale), _ptr(dout), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dg1),
+                                          _ptr(dg2), _ptr(p_mean), _stream(stream))
+    _check(rc, "gsa_sparse_gated_attn_bwd")
+
+
+def gsa_indexer_sparse_kl(shape, qI, kI, w, bI, idx, n_sel, k_cap, p, loss_rows, dqI, dkI, dw, dbI=None, stream=None):
+    rc = load().gsa_indexer_sparse_kl(ctypes.byref(shape), _ptr(qI), _ptr(kI), _ptr(w), _ptr(bI), _ptr(idx), _ptr(n_sel), k_cap, _ptr(p),
+                                      _ptr(loss_rows), _ptr(dqI), _ptr(dkI), _ptr(dw), _ptr(dbI), _stream(stream))
+    _check(rc, "gsa_indexer_sparse_kl")
 
 
 def gsa_dense_attn_workspace_bytes(shape, has_g2):

@@ -7,7 +7,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgsa.so")
-SOURCES = ("api.hip", "indexer.hip", "select.hip", "select16.hip", "attention.hip", "dense.hip", "cache.hip", "proj.hip", "probe.hip")
+SOURCES = ("api.hip", "indexer.hip", "select.hip", "select16.hip", "attention.hip", "dense.hip", "cache.hip", "proj.hip", "train.hip", "probe.hip")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc", "-Wall", "-Wno-unused-function",

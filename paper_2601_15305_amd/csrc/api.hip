@@ -37,6 +37,12 @@ hipError_t launch_translate_indices(const gsa_shape& sh, const PageMap& pm, int 
                                     int idx_rows, int idx_row0, const int32_t* n_sel, int k_cap, int32_t* phys, hipStream_t st);
 hipError_t launch_projection(const void* x, int64_t tokens, int K, int nseg, const void* const* W, void* const* out,
                              const int32_t* width, const int32_t* kind, hipStream_t st);
+hipError_t launch_attention_bwd(const gsa_shape& sh, const void* Q, const void* K, const void* V, const void* g2, const void* g1,
+                                const int32_t* idx, const int32_t* n_sel, int k_cap, float scale, const void* dout, float* dQ,
+                                float* dK, float* dV, float* dg1, float* dg2, float* p_sum, hipStream_t st);
+hipError_t launch_indexer_kl(const gsa_shape& sh, const void* qI, const void* kI, const float* w, const float* bI, const int32_t* idx,
+                             const int32_t* n_sel, int k_cap, const float* p, float* loss, float* dqI, float* dkI, float* dw,
+                             float* dbI, hipStream_t st);
 hipError_t launch_probe_gather(const void* table, const int32_t* idx, int64_t n_idx, int waves, uint32_t* sink, hipStream_t st);
 
 static thread_local std::string g_last_error;
@@ -706,6 +712,36 @@ int32_t gsa_output_projection(const gsa_shape* shape, int32_t d_model, const voi
     hipError_t e = launch_projection(attn_out, (int64_t)shape->B * shape->Lq, Kc, 1, Wu, du, width, kind,
                                      static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_output_projection");
+}
+
+int32_t gsa_sparse_gated_attn_bwd(const gsa_shape* shape, const void* Q, const void* K, const void* V, const void* g2_logits,
+                                  const void* g1_logits, const int32_t* idx, const int32_t* n_sel, int32_t k_cap,
+                                  float softmax_scale, const void* dout, float* dQ, float* dK, float* dV, float* dg1, float* dg2,
+                                  float* p_mean, void* stream) {
+    int32_t rc = check_shape(shape);
+    if (rc != GSA_OK) return rc;
+    if (!Q || !K || !V || !idx || !n_sel || !dout || !dQ || !dK || !dV) return GSA_ERR_NULL;
+    if ((g1_logits == nullptr) != (dg1 == nullptr) || (g2_logits == nullptr) != (dg2 == nullptr)) return GSA_ERR_NULL;
+    if (k_cap < 1 || k_cap > 8192) return GSA_ERR_SHAPE;
+    if (!(softmax_scale >= 0.0f) || !std::isfinite(softmax_scale)) return GSA_ERR_SHAPE;
+    const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt((float)shape->d_h);
+    hipError_t e = launch_attention_bwd(*shape, Q, K, V, g2_logits, g1_logits, idx, n_sel, k_cap, scale, dout, dQ, dK, dV, dg1, dg2,
+                                        p_mean, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_sparse_gated_attn_bwd");
+}
+
+int32_t gsa_indexer_sparse_kl(const gsa_shape* shape, const void* qI, const void* kI, const float* w, const float* bI,
+                              const int32_t* idx, const int32_t* n_sel, int32_t k_cap, const float* p, float* loss_rows,
+                              float* dqI, float* dkI, float* dw, float* dbI, void* stream) {
+    int32_t rc = check_shape(shape);
+    if (rc != GSA_OK) return rc;
+    if (shape->indexer_act != GSA_ACT_SIGMOID) return GSA_ERR_UNSUPPORTED;
+    if (!qI || !kI || !w || !idx || !n_sel || !p || !loss_rows || !dqI || !dkI || !dw) return GSA_ERR_NULL;
+    if ((bI == nullptr) != (dbI == nullptr)) return GSA_ERR_NULL;
+    if (k_cap < 1 || k_cap > 8192) return GSA_ERR_SHAPE;
+    hipError_t e = launch_indexer_kl(*shape, qI, kI, w, bI, idx, n_sel, k_cap, p, loss_rows, dqI, dkI, dw, dbI,
+                                     static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_indexer_sparse_kl");
 }
 
 int32_t gsa_forward_noalloc(const gsa_shape* shape, const gsa_adaptive* ctl, const void* Q, const void* K, const void* V,

@@ -1,0 +1,522 @@
+// Training side (Sec. 6.1): gradients of the sparse gated attention of Sec. 3.5 / 3.6 with the selection S_t held
+// fixed (top-k has no gradient), the sparse-phase loss of the indexer, KL(p_{t,S_t} || softmax(I_{t,S_t})), and
+// the gradients of the indexer scores of Sec. 3.3 that this loss sends back.
+//
+// All kernels use plain vector arithmetic in fp32 (inputs bf16 or fp32, gradients fp32).  One wave handles one
+// query and up to four query heads of one kv group: a lane computes the logits of one selected token from the whole
+// K row (chunks of 64 tokens), then every lane owns d_h / 64 features for the sums over tokens.  Contributions to
+// keys that several queries select are added with fp32 atomics (their order, and so the last bits of dK, dV, dg2,
+// dkI, dbI, varies from run to run).
+#include "common.hpp"
+
+namespace gsa {
+
+constexpr float kTrainNegBig = -1.0e30f;
+
+template <typename T>
+__device__ __forceinline__ float ldf(const T* p, int64_t i);
+template <>
+__device__ __forceinline__ float ldf<float>(const float* p, int64_t i) {
+    return p[i];
+}
+template <>
+__device__ __forceinline__ float ldf<__bf16>(const __bf16* p, int64_t i) {
+    return bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(p)[i]);
+}
+__device__ __forceinline__ float precise_sigmoid(float z) { return 1.0f / (1.0f + expf(-z)); }
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+struct AttnBwdArgs {
+    const void* Q;
+    const void* K;
+    const void* V;
+    const void* g2;
+    const void* g1;
+    const void* dout;
+    const int32_t* idx;    // [B, Lq, k_cap]
+    const int32_t* n_sel;  // [B, Lq]
+    float* dQ;             // [B, Lq, H, d_h]
+    float* dK;             // [B, Lk, H_kv, d_h], zeroed before the launch
+    float* dVp;            // [B, Lk, H_kv, d_h], zeroed before the launch: gradient of the gated values V'
+    float* dg1;            // [B, Lq, H, d_h] or null
+    float* p_sum;          // [B, Lq, k_cap] or null, zeroed before the launch: attention weights averaged over the heads
+    int32_t B, Lq, Lk, H, H_kv, k_cap;
+    float scale;
+};
+
+// Eight consecutive elements of a row as floats (one or two 16-byte loads).
+__device__ __forceinline__ void load8(const float* p, float (&x)[8]) {
+    const float4 a = *reinterpret_cast<const float4*>(p);
+    const float4 b = *reinterpret_cast<const float4*>(p + 4);
+    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
+    x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+}
+__device__ __forceinline__ void load8(const __bf16* p, float (&x)[8]) {
+    const u32x4 v = *reinterpret_cast<const u32x4*>(p);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        x[2 * e] = bf16_bits_to_f32(v[e] & 0xffffu);
+        x[2 * e + 1] = bf16_bits_to_f32(v[e] >> 16);
+    }
+}
+
+// One wave per (query, chunk of HC query heads of one kv group): dQ, dg1 of those heads and their contributions to
+// dK and dV' of the selected keys.  The heads of a chunk share every K / V / g2 row the wave reads, and their
+// contributions to a key are summed in registers before the one atomic add per feature.
+template <typename T, int DH, int HC>
+__global__ __launch_bounds__(256) void attn_bwd_kernel(AttnBwdArgs a) {
+    constexpr int DPL = DH / 64;  // features per lane
+    __shared__ __attribute__((aligned(16))) float lds[4][2 * HC * DH];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    float* qs = lds[wv];              // the queries of the chunk's heads [HC][DH]
+    float* dos = lds[wv] + HC * DH;   // gradients of their ungated outputs [HC][DH]
+    const int64_t qrow = blockIdx.x;  // (b, t)
+    const int b = (int)(qrow / a.Lq);
+    const int nsel = max(0, min(a.n_sel[qrow], a.k_cap));
+    const int32_t* idxrow = a.idx + qrow * a.k_cap;
+    const int G = a.H / a.H_kv;       // a multiple of HC (chosen by the host)
+    const int nchunk = a.H / HC;
+    const T* Q = static_cast<const T*>(a.Q);
+    const T* K = static_cast<const T*>(a.K);
+    const T* V = static_cast<const T*>(a.V);
+    const T* G2 = static_cast<const T*>(a.g2);
+    const T* G1 = static_cast<const T*>(a.g1);
+    const T* DO = static_cast<const T*>(a.dout);
+    const float inv_heads = 1.0f / (float)a.H;
+
+    for (int ch = wv; ch < nchunk; ch += 4) {
+        const int h0 = ch * HC;
+        const int g = h0 / G;
+        const int64_t qbase = (qrow * a.H + h0) * DH;  // head hh of the chunk: + hh * DH
+        float q[HC][DPL];
+#pragma unroll
+        for (int hh = 0; hh < HC; ++hh)
+#pragma unroll
+            for (int e = 0; e < DPL; ++e) {
+                q[hh][e] = ldf(Q, qbase + hh * DH + lane + 64 * e);
+                qs[hh * DH + lane + 64 * e] = q[hh][e];
+            }
+        __builtin_amdgcn_s_waitcnt(0);  // (one wave per LDS region: its own writes, then its own reads)
+        __builtin_amdgcn_wave_barrier();
+        auto key_row = [&](int tok) { return (((int64_t)b * a.Lk + tok) * a.H_kv + g) * DH; };
+        auto logits_of = [&](int64_t krow, float (&x)[HC]) {
+#pragma unroll
+            for (int hh = 0; hh < HC; ++hh) x[hh] = 0.f;
+            for (int c = 0; c < DH; c += 8) {
+                float kv[8];
+                load8(K + krow + c, kv);
+#pragma unroll
+                for (int hh = 0; hh < HC; ++hh) {
+                    const float4 q0 = *reinterpret_cast<const float4*>(qs + hh * DH + c);
+                    const float4 q1 = *reinterpret_cast<const float4*>(qs + hh * DH + c + 4);
+                    x[hh] = fmaf(q0.x, kv[0], x[hh]); x[hh] = fmaf(q0.y, kv[1], x[hh]);
+                    x[hh] = fmaf(q0.z, kv[2], x[hh]); x[hh] = fmaf(q0.w, kv[3], x[hh]);
+                    x[hh] = fmaf(q1.x, kv[4], x[hh]); x[hh] = fmaf(q1.y, kv[5], x[hh]);
+                    x[hh] = fmaf(q1.z, kv[6], x[hh]); x[hh] = fmaf(q1.w, kv[7], x[hh]);
+                }
+            }
+#pragma unroll
+            for (int hh = 0; hh < HC; ++hh) x[hh] *= a.scale;
+        };
+        // ---- pass 1: running maximum m, sum l and the unnormalised output o of every head ------------------------
+        float m[HC], l[HC], o[HC][DPL];
+#pragma unroll
+        for (int hh = 0; hh < HC; ++hh) {
+            m[hh] = kTrainNegBig;
+            l[hh] = 0.f;
+#pragma unroll
+            for (int e = 0; e < DPL; ++e) o[hh][e] = 0.f;
+        }
+        for (int j0 = 0; j0 < nsel; j0 += 64) {
+            const int j = j0 + lane;
+            const int tok = max(0, min(idxrow[min(j, nsel - 1)], a.Lk - 1));
+            float x[HC], p[HC];
+            logits_of(key_row(tok), x);
+#pragma unroll
+            for (int hh = 0; hh < HC; ++hh) {
+                if (j >= nsel) x[hh] = kTrainNegBig;
+                const float mnew = fmaxf(m[hh], wave_max(x[hh]));
+                const float alpha = expf(m[hh] - mnew);
+                p[hh] = j < nsel ? expf(x[hh] - mnew) : 0.f;
+                l[hh] = l[hh] * alpha + wave_sum(p[hh]);
+                m[hh] = mnew;
+#pragma unroll
+                for (int e = 0; e < DPL; ++e) o[hh][e] *= alpha;
+            }
+            const int cnt = min(64, nsel - j0);
+            for (int u = 0; u < cnt; ++u) {
+                const int64_t vrow = key_row(__shfl(tok, u, 64));
+                float v[DPL];
+#pragma unroll
+                for (int e = 0; e < DPL; ++e) {
+                    v[e] = ldf(V, vrow + lane + 64 * e);
+                    if (G2) v[e] *= precise_sigmoid(ldf(G2, vrow + lane + 64 * e));
+                }
+#pragma unroll
+                for (int hh = 0; hh < HC; ++hh) {
+                    const float pu = __shfl(p[hh], u, 64);
+#pragma unroll
+                    for (int e = 0; e < DPL; ++e) o[hh][e] = fmaf(pu, v[e], o[hh][e]);
+                }
+            }
+        }
+        // ---- gradient of the ungated outputs, of the output gate; D = dO . O -----------------------------------
+        float inv_l[HC], D[HC], dO[HC][DPL];
+#pragma unroll
+        for (int hh = 0; hh < HC; ++hh) {
+            inv_l[hh] = l[hh] > 0.f ? 1.0f / l[hh] : 0.f;
+            float dpart = 0.f;
+#pragma unroll
+            for (int e = 0; e < DPL; ++e) {
+                const int64_t i = qbase + hh * DH + lane + 64 * e;
+                const float Oe = o[hh][e] * inv_l[hh];
+                const float dy = ldf(DO, i);
+                float s1 = 1.0f;
+                if (G1) {
+                    s1 = precise_sigmoid(ldf(G1, i));
+                    if (a.dg1) a.dg1[i] = dy * Oe * s1 * (1.0f - s1);
+                }
+                dO[hh][e] = dy * s1;
+                dos[hh * DH + lane + 64 * e] = dO[hh][e];
+                dpart = fmaf(dO[hh][e], Oe, dpart);
+            }
+            D[hh] = wave_sum(dpart);
+        }
+        __builtin_amdgcn_s_waitcnt(0);
+        __builtin_amdgcn_wave_barrier();
+        // ---- pass 2: ds_j = P_j (dO . V'_j - D); dq, and the contributions to dK and dV' ------------------------
+        float dq[HC][DPL];
+#pragma unroll
+        for (int hh = 0; hh < HC; ++hh)
+#pragma unroll
+            for (int e = 0; e < DPL; ++e) dq[hh][e] = 0.f;
+        for (int j0 = 0; j0 < nsel; j0 += 64) {
+            const int j = j0 + lane;
+            const int tok = max(0, min(idxrow[min(j, nsel - 1)], a.Lk - 1));
+            float P[HC], ds[HC];
+#pragma unroll
+            for (int hh = 0; hh < HC; ++hh) P[hh] = ds[hh] = 0.f;
+            if (j < nsel) {
+                const int64_t krow = key_row(tok);
+                float x[HC], dP[HC];
+                logits_of(krow, x);
+#pragma unroll
+                for (int hh = 0; hh < HC; ++hh) dP[hh] = 0.f;
+                for (int c = 0; c < DH; c += 8) {
+                    float v[8];
+                    load8(V + krow + c, v);
+                    if (G2) {
+                        float gg[8];
+                        load8(G2 + krow + c, gg);
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[e] *= precise_sigmoid(gg[e]);
+                    }
+#pragma unroll
+                    for (int hh = 0; hh < HC; ++hh)
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) dP[hh] = fmaf(dos[hh * DH + c + e], v[e], dP[hh]);
+                }
+                float psum = 0.f;
+#pragma unroll
+                for (int hh = 0; hh < HC; ++hh) {
+                    P[hh] = expf(x[hh] - m[hh]) * inv_l[hh];
+                    ds[hh] = P[hh] * (dP[hh] - D[hh]) * a.scale;
+                    psum += P[hh];
+                }
+                if (a.p_sum) atomicAdd(&a.p_sum[qrow * a.k_cap + j], psum * inv_heads);
+            }
+            const int cnt = min(64, nsel - j0);
+            for (int u = 0; u < cnt; ++u) {
+                const int64_t krow = key_row(__shfl(tok, u, 64));
+                float kel[DPL], dk[DPL], dv[DPL];
+#pragma unroll
+                for (int e = 0; e < DPL; ++e) {
+                    kel[e] = ldf(K, krow + lane + 64 * e);
+                    dk[e] = dv[e] = 0.f;
+                }
+#pragma unroll
+                for (int hh = 0; hh < HC; ++hh) {
+                    const float dsu = __shfl(ds[hh], u, 64);
+                    const float pu = __shfl(P[hh], u, 64);
+#pragma unroll
+                    for (int e = 0; e < DPL; ++e) {
+                        dq[hh][e] = fmaf(dsu, kel[e], dq[hh][e]);
+                        dk[e] = fmaf(dsu, q[hh][e], dk[e]);
+                        dv[e] = fmaf(pu, dO[hh][e], dv[e]);
+                    }
+                }
+#pragma unroll
+                for (int e = 0; e < DPL; ++e) {
+                    atomicAdd(&a.dK[krow + lane + 64 * e], dk[e]);
+                    atomicAdd(&a.dVp[krow + lane + 64 * e], dv[e]);
+                }
+            }
+        }
+#pragma unroll
+        for (int hh = 0; hh < HC; ++hh)
+#pragma unroll
+            for (int e = 0; e < DPL; ++e) a.dQ[qbase + hh * DH + lane + 64 * e] = dq[hh][e];
+        __builtin_amdgcn_wave_barrier();  // the next chunk rewrites qs and dos
+    }
+}
+
+// dV = dV' * sigmoid(g2) (in place), dg2 = dV' * V * sigmoid(g2) (1 - sigmoid(g2)); without g2, dV = dV' and dg2 = 0.
+template <typename T>
+__global__ void value_gate_bwd_kernel(const T* V, const T* g2, float* dV, float* dg2, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const float d = dV[i];
+    if (g2) {
+        const float s = precise_sigmoid(ldf(g2, i));
+        dV[i] = d * s;
+        if (dg2) dg2[i] = d * ldf(V, i) * s * (1.0f - s);
+    } else if (dg2) {
+        dg2[i] = 0.f;
+    }
+}
+
+__global__ void fill_zero_kernel(float* p, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0.f;
+}
+static void zero_fill(float* p, int64_t n, hipStream_t st) {
+    if (p && n > 0) hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st, p, n);
+}
+
+hipError_t launch_attention_bwd(const gsa_shape& sh, const void* Q, const void* K, const void* V, const void* g2, const void* g1,
+                                const int32_t* idx, const int32_t* n_sel, int k_cap, float scale, const void* dout, float* dQ,
+                                float* dK, float* dV, float* dg1, float* dg2, float* p_sum, hipStream_t st) {
+    AttnBwdArgs a;
+    a.Q = Q;
+    a.K = K;
+    a.V = V;
+    a.g2 = g2;
+    a.g1 = g1;
+    a.dout = dout;
+    a.idx = idx;
+    a.n_sel = n_sel;
+    a.dQ = dQ;
+    a.dK = dK;
+    a.dVp = dV;
+    a.dg1 = dg1;
+    a.p_sum = p_sum;
+    a.B = sh.B;
+    a.Lq = sh.Lq;
+    a.Lk = sh.Lk;
+    a.H = sh.H;
+    a.H_kv = sh.H_kv;
+    a.k_cap = k_cap;
+    a.scale = scale;
+    const int64_t kv_elems = (int64_t)sh.B * sh.Lk * sh.H_kv * sh.d_h;
+    zero_fill(dK, kv_elems, st);
+    zero_fill(dV, kv_elems, st);
+    zero_fill(p_sum, (int64_t)sh.B * sh.Lq * k_cap, st);
+    const dim3 grid((unsigned)((int64_t)sh.B * sh.Lq));
+    const int G = sh.H / sh.H_kv;
+    const int hc = G % 4 == 0 ? 4 : (G % 2 == 0 ? 2 : 1);  // query heads of one kv group a wave takes together
+    void (*kern)(AttnBwdArgs) = nullptr;
+    if (sh.dtype == GSA_BF16) {
+        if (sh.d_h == 128)
+            kern = hc == 4 ? attn_bwd_kernel<__bf16, 128, 4> : (hc == 2 ? attn_bwd_kernel<__bf16, 128, 2> : attn_bwd_kernel<__bf16, 128, 1>);
+        else
+            kern = hc == 4 ? attn_bwd_kernel<__bf16, 64, 4> : (hc == 2 ? attn_bwd_kernel<__bf16, 64, 2> : attn_bwd_kernel<__bf16, 64, 1>);
+    } else {
+        if (sh.d_h == 128)
+            kern = hc == 4 ? attn_bwd_kernel<float, 128, 4> : (hc == 2 ? attn_bwd_kernel<float, 128, 2> : attn_bwd_kernel<float, 128, 1>);
+        else
+            kern = hc == 4 ? attn_bwd_kernel<float, 64, 4> : (hc == 2 ? attn_bwd_kernel<float, 64, 2> : attn_bwd_kernel<float, 64, 1>);
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(256), 0, st, a);
+    if (sh.dtype == GSA_BF16)
+        hipLaunchKernelGGL(value_gate_bwd_kernel<__bf16>, dim3((unsigned)cdiv(kv_elems, 256)), dim3(256), 0, st,
+                           static_cast<const __bf16*>(V), static_cast<const __bf16*>(g2), dV, dg2, kv_elems);
+    else
+        hipLaunchKernelGGL(value_gate_bwd_kernel<float>, dim3((unsigned)cdiv(kv_elems, 256)), dim3(256), 0, st,
+                           static_cast<const float*>(V), static_cast<const float*>(g2), dV, dg2, kv_elems);
+    return hipGetLastError();
+}
+
+// ---- sparse-phase indexer loss and the gradients it sends into the indexer (Sec. 6.1, Sec. 3.3) -----------------
+struct IndexerKlArgs {
+    const void* qI;        // [B, Lq, HI, dI]
+    const void* kI;        // [B, Lk, dI]
+    const float* w;        // [B, Lq, HI]
+    const float* bI;       // [HI] or null
+    const int32_t* idx;    // [B, Lq, k_cap]
+    const int32_t* n_sel;  // [B, Lq]
+    const float* p;        // [B, Lq, k_cap]: target distribution over the selected keys
+    float* loss;           // [B, Lq]
+    float* dqI;            // [B, Lq, HI, dI]
+    float* dkI;            // [B, Lk, dI], zeroed before the launch
+    float* dw;             // [B, Lq, HI]
+    float* dbI;            // [HI] or null, zeroed before the launch
+    int32_t B, Lq, Lk, HI, dI, k_cap;
+};
+
+// One wave per query.  A lane computes the logits z_{j,s} and the score I_s of one selected key (chunks of 64);
+// the softmax over S_t takes two passes over the (recomputed) scores; then every lane owns dI / 64 features of
+// dq (lanes beyond dI idle) for the sums over keys.  HI <= 8.
+template <typename T>
+__global__ __launch_bounds__(256) void indexer_kl_kernel(IndexerKlArgs a) {
+    extern __shared__ float klds[];  // per wave: the query's heads [HI * dI]
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int64_t row = (int64_t)blockIdx.x * 4 + wv;
+    if (row >= (int64_t)a.B * a.Lq) return;  // (the waves of a workgroup never synchronise with each other)
+    const int b = (int)(row / a.Lq);
+    const int HI = a.HI, DI = a.dI;
+    float* qs = klds + wv * (8 * 128);
+    const T* qI = static_cast<const T*>(a.qI) + row * HI * DI;
+    const T* kI = static_cast<const T*>(a.kI) + (int64_t)b * a.Lk * DI;
+    for (int c = lane; c < HI * DI; c += 64) qs[c] = ldf(qI, c);
+    __builtin_amdgcn_s_waitcnt(0);
+    __builtin_amdgcn_wave_barrier();
+    const int nsel = max(0, min(a.n_sel[row], a.k_cap));
+    const int32_t* idxrow = a.idx + row * a.k_cap;
+    const float* prow = a.p + row * a.k_cap;
+    float wj[8], bj[8];
+#pragma unroll
+    for (int h = 0; h < 8; ++h) {
+        wj[h] = h < HI ? a.w[row * HI + h] : 0.f;
+        bj[h] = (h < HI && a.bI) ? a.bI[h] : 0.f;
+    }
+    // sigma(z_{h,s}) of the lane's key for every head; returns the score
+    auto score_of = [&](int tok, float (&sg)[8]) {
+        const T* kr = kI + (int64_t)tok * DI;
+        float z[8];
+#pragma unroll
+        for (int h = 0; h < 8; ++h) z[h] = 0.f;
+        for (int c = 0; c < DI; ++c) {
+            const float kc = ldf(kr, c);
+#pragma unroll
+            for (int h = 0; h < 8; ++h)
+                if (h < HI) z[h] = fmaf(qs[h * DI + c], kc, z[h]);
+        }
+        float sc = 0.f;
+#pragma unroll
+        for (int h = 0; h < 8; ++h) {
+            sg[h] = h < HI ? precise_sigmoid(z[h] + bj[h]) : 0.f;
+            sc = fmaf(wj[h], sg[h], sc);
+        }
+        return sc;
+    };
+    // ---- softmax statistics of the scores over S_t ----------------------------------------------------------------
+    float m = kTrainNegBig, l = 0.f;
+    for (int j0 = 0; j0 < nsel; j0 += 64) {
+        const int j = j0 + lane;
+        const int tok = max(0, min(idxrow[min(j, nsel - 1)], a.Lk - 1));
+        float sg[8];
+        const float x = j < nsel ? score_of(tok, sg) : kTrainNegBig;
+        const float mnew = fmaxf(m, wave_max(x));
+        l = l * expf(m - mnew) + wave_sum(j < nsel ? expf(x - mnew) : 0.f);
+        m = mnew;
+    }
+    const float logl = nsel > 0 ? logf(l) : 0.f;
+    // ---- loss, dI = softmax(I) - p, and the gradients of Eq. "indexer" -------------------------------------------
+    float loss = 0.f;
+    float dwacc[8], dbacc[8];
+#pragma unroll
+    for (int h = 0; h < 8; ++h) dwacc[h] = dbacc[h] = 0.f;
+    float dq[8][2];  // features lane and lane + 64 of every head
+#pragma unroll
+    for (int h = 0; h < 8; ++h) dq[h][0] = dq[h][1] = 0.f;
+    for (int j0 = 0; j0 < nsel; j0 += 64) {
+        const int j = j0 + lane;
+        const int tok = max(0, min(idxrow[min(j, nsel - 1)], a.Lk - 1));
+        float dz[8];
+#pragma unroll
+        for (int h = 0; h < 8; ++h) dz[h] = 0.f;
+        if (j < nsel) {
+            float sg[8];
+            const float x = score_of(tok, sg);
+            const float logq = x - m - logl;
+            const float p = prow[j];
+            if (p > 0.f) loss += p * (logf(p) - logq);
+            const float dI = expf(logq) - p;
+#pragma unroll
+            for (int h = 0; h < 8; ++h) {
+                dwacc[h] = fmaf(dI, sg[h], dwacc[h]);
+                dz[h] = dI * wj[h] * sg[h] * (1.0f - sg[h]);
+                dbacc[h] += dz[h];
+            }
+        }
+        const int cnt = min(64, nsel - j0);
+        for (int u = 0; u < cnt; ++u) {
+            const int tu = __shfl(tok, u, 64);
+            float dzu[8];
+#pragma unroll
+            for (int h = 0; h < 8; ++h) dzu[h] = h < HI ? __shfl(dz[h], u, 64) : 0.f;
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int c = lane + 64 * e;
+                if (c < DI) {
+                    const float kc = ldf(kI, (int64_t)tu * DI + c);
+                    float dk = 0.f;
+#pragma unroll
+                    for (int h = 0; h < 8; ++h)
+                        if (h < HI) {
+                            dq[h][e] = fmaf(dzu[h], kc, dq[h][e]);
+                            dk = fmaf(dzu[h], qs[h * DI + c], dk);
+                        }
+                    atomicAdd(&a.dkI[((int64_t)b * a.Lk + tu) * DI + c], dk);
+                }
+            }
+        }
+    }
+    loss = wave_sum(loss);
+    if (lane == 0) a.loss[row] = loss;
+#pragma unroll
+    for (int h = 0; h < 8; ++h) {
+        if (h < HI) {
+            const float dw = wave_sum(dwacc[h]);
+            const float db = wave_sum(dbacc[h]);
+            if (lane == 0) {
+                a.dw[row * HI + h] = dw;
+                if (a.dbI) atomicAdd(&a.dbI[h], db);
+            }
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int c = lane + 64 * e;
+                if (c < DI) a.dqI[(row * HI + h) * DI + c] = dq[h][e];
+            }
+        }
+    }
+}
+
+hipError_t launch_indexer_kl(const gsa_shape& sh, const void* qI, const void* kI, const float* w, const float* bI, const int32_t* idx,
+                             const int32_t* n_sel, int k_cap, const float* p, float* loss, float* dqI, float* dkI, float* dw,
+                             float* dbI, hipStream_t st) {
+    IndexerKlArgs a;
+    a.qI = qI;
+    a.kI = kI;
+    a.w = w;
+    a.bI = bI;
+    a.idx = idx;
+    a.n_sel = n_sel;
+    a.p = p;
+    a.loss = loss;
+    a.dqI = dqI;
+    a.dkI = dkI;
+    a.dw = dw;
+    a.dbI = dbI;
+    a.B = sh.B;
+    a.Lq = sh.Lq;
+    a.Lk = sh.Lk;
+    a.HI = sh.HI;
+    a.dI = sh.dI;
+    a.k_cap = k_cap;
+    zero_fill(dkI, (int64_t)sh.B * sh.Lk * sh.dI, st);
+    zero_fill(dbI, sh.HI, st);
+    const size_t smem = 4 * 8 * 128 * sizeof(float);
+    const dim3 grid((unsigned)cdiv((int64_t)sh.B * sh.Lq, 4));
+    if (sh.dtype == GSA_BF16)
+        hipLaunchKernelGGL(indexer_kl_kernel<__bf16>, grid, dim3(256), smem, st, a);
+    else
+        hipLaunchKernelGGL(indexer_kl_kernel<float>, grid, dim3(256), smem, st, a);
+    return hipGetLastError();
+}
+
+}  // namespace gsa
