@@ -39,6 +39,7 @@ CASES = [
     ("bf16", 1, 200, 16, 4, 128, 4, 64, 70, True, False),
     ("f32", 1, 130, 4, 4, 64, 3, 64, 33, False, True),
     ("f32", 2, 90, 8, 2, 128, 8, 128, 90, True, False),     # budget covers every visible key of every row
+    ("bf16", 1, 140, 16, 1, 64, 5, 32, 130, True, True),    # sixteen query heads on one kv head: four chunks of four heads
 ]
 
 
