@@ -199,6 +199,10 @@ def gather_ceilings(G, dev):
         idx = torch.randint(0, rows, (n_idx,), dtype=torch.int32, device=dev, generator=g)
         ms = timed(lambda: G.gsa_probe_gather(table, rows, idx, n_idx, waves, sink), 5)
         res[name] = round(n_idx * 256 / (ms * 1e-3) / 1e9, 1)
+        if table_bytes == 2 << 20:
+            # the same rows, each staged through LDS (write + read back) as an MFMA operand has to be: eight waves per CU
+            ms = timed(lambda: G.gsa_probe_gather_staged(table, rows, idx, n_idx, 256 * 8, sink), 5)
+            res[name + "_staged_through_lds"] = round(n_idx * 256 / (ms * 1e-3) / 1e9, 1)
         del table, idx
     return res
 
@@ -510,6 +514,10 @@ def main():
         "hbm": {"compulsory_bytes": compulsory, "achieved": round(compulsory / att_s / 1e9, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": round(compulsory / att_s / 1e9 / PEAK_HBM_GBS, 4)},
         "hbm_gather_ceiling_gbs": ceil["hbm_resident_4GiB_table"],
+        "staged_gather_ceiling_gbs": ceil["l2_resident_2MiB_table_staged_through_lds"],
+        "frac_of_staged_gather_ceiling": round(att_gbs / ceil["l2_resident_2MiB_table_staged_through_lds"], 4),
+        "staged_gather_ceiling_source": "the same gather with every row written to and read back from LDS once (gsa_probe_gather_staged, "
+                                        "eight waves per CU): load return, LDS write and LDS read share a CU's data path",
         "traffic": None,
     }
     if isinstance(traffic, dict):

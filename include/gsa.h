@@ -377,6 +377,12 @@ int32_t gsa_forward_noalloc(const gsa_shape* shape, const gsa_adaptive* ctl, con
  *   [0, table_rows), n_idx a multiple of 64;  sink device, out, uint32 [waves];  waves a multiple of 4. */
 int32_t gsa_probe_gather(const void* table, int64_t table_rows, const int32_t* idx, int64_t n_idx, int32_t waves,
                          uint32_t* sink, void* stream);
+/* The same gather with every row staged through LDS (registers -> a wave-private 16 KB tile -> registers, the
+ * least an MFMA operand built from gathered rows needs; 64 KB of LDS per 256-thread workgroup, so eight waves
+ * per CU).  Same arguments and sink values as gsa_probe_gather.  The register return of the loads and the LDS
+ * writes and reads share a CU's data path: this rate is the ceiling for the attention kernel's dataflow. */
+int32_t gsa_probe_gather_staged(const void* table, int64_t table_rows, const int32_t* idx, int64_t n_idx, int32_t waves,
+                                uint32_t* sink, void* stream);
 
 /* ---- misc ---------------------------------------------------------------------------- */
 const char* gsa_status_string(int32_t status); /* static string */

@@ -28,7 +28,7 @@ ENTRY_POINTS = (
     "gsa_cache_append", "gsa_decode_step", "gsa_decode_workspace_bytes", "gsa_paged_cache_append", "gsa_paged_decode_step",
     "gsa_paged_decode_workspace_bytes", "gsa_input_projections", "gsa_output_projection", "gsa_sparse_gated_attn_bwd",
     "gsa_indexer_sparse_kl",
-    "gsa_probe_gather", "gsa_status_string", "gsa_last_error", "gsa_version",
+    "gsa_probe_gather", "gsa_probe_gather_staged", "gsa_status_string", "gsa_last_error", "gsa_version",
 )
 
 
@@ -75,6 +75,8 @@ def load():
     lib.gsa_topk_select_keys.restype = i32
     lib.gsa_probe_gather.argtypes = [vp, i64, vp, i64, i32, vp, vp]
     lib.gsa_probe_gather.restype = i32
+    lib.gsa_probe_gather_staged.argtypes = [vp, i64, vp, i64, i32, vp, vp]
+    lib.gsa_probe_gather_staged.restype = i32
     lib.gsa_indexer_workspace_bytes.argtypes = [shp, i32, i32]
     lib.gsa_indexer_workspace_bytes.restype = sz
     lib.gsa_adaptive_k.argtypes = [shp, ctl, vp, vp, vp, vp]
@@ -214,6 +216,11 @@ def gsa_topk_select_keys(shape, row_begin, row_end, keys, ld_keys, n_sel, k_cap,
 def gsa_probe_gather(table, table_rows, idx, n_idx, waves, sink, stream=None):
     rc = load().gsa_probe_gather(_ptr(table), table_rows, _ptr(idx), n_idx, waves, _ptr(sink), _stream(stream))
     _check(rc, "gsa_probe_gather")
+
+
+def gsa_probe_gather_staged(table, table_rows, idx, n_idx, waves, sink, stream=None):
+    rc = load().gsa_probe_gather_staged(_ptr(table), table_rows, _ptr(idx), n_idx, waves, _ptr(sink), _stream(stream))
+    _check(rc, "gsa_probe_gather_staged")
 
 
 def gsa_adaptive_k(shape, ctl, row_var, k_out, n_sel_out, stream=None):

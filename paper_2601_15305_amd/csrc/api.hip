@@ -44,6 +44,7 @@ hipError_t launch_indexer_kl(const gsa_shape& sh, const void* qI, const void* kI
                              const int32_t* n_sel, int k_cap, const float* p, float* loss, float* dqI, float* dkI, float* dw,
                              float* dbI, hipStream_t st);
 hipError_t launch_probe_gather(const void* table, const int32_t* idx, int64_t n_idx, int waves, uint32_t* sink, hipStream_t st);
+hipError_t launch_probe_gather_staged(const void* table, const int32_t* idx, int64_t n_idx, int waves, uint32_t* sink, hipStream_t st);
 
 static thread_local std::string g_last_error;
 
@@ -518,6 +519,16 @@ int32_t gsa_probe_gather(const void* table, int64_t table_rows, const int32_t* i
     if (!aligned(table, 16)) return GSA_ERR_SHAPE;
     hipError_t e = launch_probe_gather(table, idx, n_idx, waves, sink, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_probe_gather");
+}
+
+int32_t gsa_probe_gather_staged(const void* table, int64_t table_rows, const int32_t* idx, int64_t n_idx, int32_t waves,
+                                uint32_t* sink, void* stream) {
+    if (!table || !idx || !sink) return GSA_ERR_NULL;
+    if (table_rows < 1 || table_rows > 0x7fffffffLL || n_idx < 64 || (n_idx & 63) != 0 || waves < 4 || (waves & 3) != 0)
+        return GSA_ERR_SHAPE;
+    if (!aligned(table, 16)) return GSA_ERR_SHAPE;
+    hipError_t e = launch_probe_gather_staged(table, idx, n_idx, waves, sink, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_probe_gather_staged");
 }
 
 size_t gsa_forward_workspace_bytes(const gsa_shape* shape, int32_t k_cap, int32_t has_g2, int32_t slab_rows,

@@ -53,6 +53,10 @@ struct AttnArgs {
 
 constexpr float kNegBig = -1.0e30f;
 
+#ifndef GSA_ATTN_DIRECT
+#define GSA_ATTN_DIRECT 1
+#endif
+
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 // max over lanes {l, l^16, l^32, l^48} without a trip through LDS (row swaps of gfx950)
@@ -69,6 +73,58 @@ __device__ __forceinline__ float quad_row_sum(float x) {
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// ---- pieces of the direct-to-LDS variant ------------------------------------------------------------------------
+// Rows go from global memory straight into LDS (global_load_lds_dwordx4: lane l's 16 bytes land at the LDS address
+// in M0 + 16 l), without passing through registers.  The compiler would wait for EVERY outstanding vector-memory
+// operation before any LDS read that could see such data, which would serialise the two streams (K rows, V' rows)
+// this variant keeps in flight; so the LDS reads of these tiles are written as instructions the compiler does not
+// look into, each followed (in straight-line code) by a hand-placed wait that names the registers read.  The list
+// entries take the same road (one 4-byte-per-lane transfer per tile into a small LDS buffer): a register whose
+// load the compiler cannot see must not stay pending across a branch, where it may be copied before it has arrived.
+typedef __attribute__((address_space(1))) const void gmem_cv;
+typedef __attribute__((address_space(3))) void lds_v;
+__device__ __forceinline__ void row_chunk_to_lds(const void* src, unsigned char* lds_dst) {
+    __builtin_amdgcn_global_load_lds((gmem_cv*)src, (lds_v*)lds_dst, 16, 0, 0);
+}
+__device__ __forceinline__ uint32_t lds_addr(const unsigned char* p) { return (uint32_t)(uintptr_t)(lds_v*)p; }
+template <int OFF>
+__device__ __forceinline__ u32x4 lds_read128_raw(uint32_t addr) {
+    u32x4 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+template <int OFF>
+__device__ __forceinline__ s16x4 lds_read_tr16_raw(uint32_t addr) {
+    s16x4 v;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+template <int OFF>
+__device__ __forceinline__ int lds_read32_raw(uint32_t addr) {
+    int v;
+    asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+// "at most N LDS operations outstanding"; the registers named are results of raw reads that are complete afterwards
+template <int N>
+__device__ __forceinline__ void wait_lds(u32x4& a, u32x4& b, u32x4& c, u32x4& d) {
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_lds(s16x4& a, s16x4& b, s16x4& c, s16x4& d) {
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N) : "memory");
+}
+__device__ __forceinline__ void wait_lds_all(int (&t)[8]) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(t[0]), "+v"(t[1]), "+v"(t[2]), "+v"(t[3]), "+v"(t[4]), "+v"(t[5]), "+v"(t[6]), "+v"(t[7]));
+}
+// "at most N vector-memory operations outstanding" (they complete in order).  This wait is one the compiler sees,
+// so that it knows what has completed and adds no wait of its own for registers that older loads wrote.
+template <int N>
+__device__ __forceinline__ void wait_vmem() {
+    __builtin_amdgcn_s_waitcnt(((N >> 4) << 14) | (0xF << 8) | (0x7 << 4) | (N & 15));  // vmcnt(N), other counters open
+    asm volatile("" ::: "memory");
+}
+
 // A wave works through the pieces of `a.rpw` consecutive query rows (same batch element, same kv head) as ONE
 // stream of 32-token tiles: while a tile is being multiplied, the K/V' rows of the next tile and the indices of
 // the one after it are already on their way, also when those tiles belong to the next query row.  The list
@@ -76,8 +132,10 @@ __device__ __forceinline__ float quad_row_sum(float x) {
 // costs no start-up chain of dependent loads (bounds -> indices -> rows), which is what a short piece -- a
 // row's share of one key window -- would otherwise spend most of its time on.
 // POOL: the lists hold rows of a pool that may exceed 4 GiB: row addresses are 64-bit per lane.
-template <int DH, bool HAS_G2, bool POOL = false>
+// DIRECT (d_h = 128, gated values given): K and V' rows go straight into LDS, see attn_direct_stream below.
+template <int DH, bool HAS_G2, bool POOL = false, bool DIRECT = false>
 __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
+    static_assert(!DIRECT || (DH == 128 && !HAS_G2), "the direct-to-LDS variant is written for 256-byte rows of gated values");
     constexpr int KK = DH / 32;        // MFMA k-steps of the score product
     constexpr int MB = DH / 16;        // 16-feature blocks of the value product
     constexpr int ROWB = DH * 2;       // bytes of one head row
@@ -89,11 +147,12 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wv = tid >> 6;
+    const int lane = tid & 63, wv = DIRECT ? __builtin_amdgcn_readfirstlane(tid >> 6) : tid >> 6;
     const int n = lane & 15;   // head within the group / token within a 16-token sub-tile
     const int q = lane >> 4;   // k-chunk selector
-    unsigned char* vlds = smem + wv * (32 * (VROW + KROW));
-    unsigned char* klds = vlds + 32 * VROW;
+    // (DIRECT: two unpadded 32 x 256-byte tiles, chunks XOR-swizzled inside every row)
+    unsigned char* vlds = smem + wv * (DIRECT ? 16640 + 1024 * ((a.H / a.H_kv + 3) >> 2) : 32 * (VROW + KROW));
+    unsigned char* klds = vlds + (DIRECT ? 8192 : 32 * VROW);
 
     // blockDim.x / 64 kv heads per workgroup; blockIdx.y selects which ones.  Blocks are dispatched
     // x-fastest, so all queries work on one slice of kv heads before the next slice starts: the K/V'
@@ -356,57 +415,350 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnArgs a) {
         }
     };
 
-    // ---- the tile stream: c = tile being worked on, nx = tile whose rows are requested next, p = tile whose
-    // indices are requested next ------------------------------------------------------------------------------
-    int c_ri, c_j0 = 0, c_je = 0;
-    c_ri = seek(0, c_j0, c_je);
-    int n_ri = c_ri, n_j0 = c_j0, n_je = c_je;
-    int p_ri = nrows, p_j0 = 0, p_je = 0;
-    int tok_pref[NVL];
+    if constexpr (DIRECT) {
+        // ---- direct-to-LDS stream --------------------------------------------------------------------------------
+        // One K tile and one V' tile per wave.  The K rows of the next tile are requested as soon as the score
+        // product has read the current ones, its V' rows as soon as the value product has read the current ones:
+        // each of the two streams is in flight while the other half of the arithmetic runs.  Tile slot s = 4 r + g
+        // (load instruction r, lane group g = lane / 16) holds list entry j0 + s; lane p = lane % 16 of the group
+        // fetches the 16-byte chunk p ^ (s & 15) of the K row and p ^ 2 (s & 7) of the V' row, which makes both the
+        // 16-byte operand reads of K and the transposing reads of V' conflict-free on unpadded 256-byte rows.
+        const int g4 = lane >> 4, p16 = lane & 15;
+        uint32_t kcol[4], vcol[2];  // byte offset of this lane's chunk in the rows of load r: kcol[r & 3], vcol[r & 1]
 #pragma unroll
-    for (int r = 0; r < NVL; ++r) tok_pref[r] = 0;
-    if (c_ri < nrows) {
-        load_idx(c_ri, c_j0, c_je, tok_pref);
-        issue(tok_pref);  // the one start-up chain of the wave: indices, then rows
-        load_q(c_ri);
-        advance(n_ri, n_j0, n_je);
-        p_ri = n_ri, p_j0 = n_j0, p_je = n_je;
-        if (n_ri < nrows) {
-            load_idx(n_ri, n_j0, n_je, tok_pref);
-            advance(p_ri, p_j0, p_je);
+        for (int r = 0; r < 4; ++r) kcol[r] = (uint32_t)(p16 ^ ((4 * r + g4) & 15)) * 16u;
+#pragma unroll
+        for (int r = 0; r < 2; ++r) vcol[r] = (uint32_t)(p16 ^ (2 * ((4 * r + g4) & 7))) * 16u;
+        uint32_t kread[KK], vread[MB];  // LDS addresses of this lane's operand reads (sub-tile 1: + 4096)
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) kread[kk] = lds_addr(klds) + n * 256 + (((4 * kk + q) ^ n) << 4);
+        {
+            const int row = 4 * q + ((lane & 15) >> 2), c4 = lane & 3;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+                vread[mb] = lds_addr(vlds) + row * 256 + ((2 * (mb ^ (row & 7)) + (c4 >> 1)) << 4) + (c4 & 1) * 8;
         }
-    }
-    int rows_done = 0;  // rows [0, rows_done) have been finished
-    int cur_row = -1;   // row whose accumulators are live
-    while (c_ri < nrows) {
-        if (c_ri != cur_row) {  // first tile of a row
-            for (; rows_done < c_ri; ++rows_done) {  // rows without a tile in this piece: only their state moves on
-                reset_acc();
-                finish_row(rows_done);
+        unsigned char* ilds = klds + 8192;  // list entries of the tile to request next: 64 x 4 bytes, the first 32 used
+        // The query heads of a row take the same road: one transfer per four heads into a [heads][256 B] tile with the
+        // K tile's chunk swizzle, read back as the B operand when the row starts.
+        unsigned char* qlds = ilds + 256;
+        const int qinstr = (G + 3) >> 2;
+        uint32_t qread[KK];
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) qread[kk] = lds_addr(qlds) + n * 256 + (((4 * kk + q) ^ n) << 4);
+        auto request_q = [&](int ri) {
+            const unsigned char* qrow = static_cast<const unsigned char*>(a.Q) + (((int64_t)b * a.Lq + t0 + ri) * a.H + g * G) * ROWB;
+            for (int i = 0; i < qinstr; ++i) {
+                const int hh = min(4 * i + g4, G - 1);  // (heads past the group: a copy of the last one, never used)
+                row_chunk_to_lds(qrow + hh * ROWB + ((p16 ^ ((4 * i + g4) & 15)) << 4), qlds + i * 1024);
             }
-            reset_acc();
+        };
+        auto read_q = [&]() {
+            u32x4 v[KK];
 #pragma unroll
-            for (int kk = 0; kk < KK; ++kk) qf[kk] = qf_next[kk];  // (before the next row's heads may be requested)
-            cur_row = c_ri;
+            for (int kk = 0; kk < KK; ++kk) v[kk] = lds_read128_raw<0>(qread[kk]);
+            wait_lds<0>(v[0], v[1], v[2], v[3]);
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) qf[kk] = __builtin_bit_cast(bf16x8, head_ok ? v[kk] : u32x4{0, 0, 0, 0});
+        };
+        const uint32_t iread = lds_addr(ilds) + g4 * 4;
+        auto request_idx = [&](int ri, int j0, int je) {  // entries j0 .. of row ri (clamped to the piece) -> ilds[lane]
+            const int32_t* row = idx0 + (int64_t)ri * a.k_cap;
+            __builtin_amdgcn_global_load_lds((gmem_cv*)(row + min(j0 + lane, je - 1)), (lds_v*)ilds, 4, 0, 0);
+        };
+        auto read_idx = [&](int (&tk)[8]) {  // this lane's entries: slot 4 r + g4 for load instruction r
+            tk[0] = lds_read32_raw<0>(iread);
+            tk[1] = lds_read32_raw<16>(iread);
+            tk[2] = lds_read32_raw<32>(iread);
+            tk[3] = lds_read32_raw<48>(iread);
+            tk[4] = lds_read32_raw<64>(iread);
+            tk[5] = lds_read32_raw<80>(iread);
+            tk[6] = lds_read32_raw<96>(iread);
+            tk[7] = lds_read32_raw<112>(iread);
+            wait_lds_all(tk);
+            // clamped once for both tiles: a bad list reads wrong rows, never memory outside K / V'
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                if constexpr (POOL)
+                    tk[r] = (int)max((int64_t)0, min((int64_t)tk[r], a.pool_rows - 1));
+                else
+                    tk[r] = (int)__umul24((uint32_t)max(0, min(tk[r], a.Lk - 1)), tokstride);
+            }
+        };
+        // (rows of one batch element span less than 4 GiB: 32-bit lane offsets on a wave-uniform base; pool: 64-bit)
+        // (tk: what read_idx left: byte offsets of the rows, or clamped pool rows)
+        auto request_rows = [&](const unsigned char* base, unsigned char* tile, const int (&tk)[8], const uint32_t* col, int colmask) {
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                if constexpr (POOL)
+                    row_chunk_to_lds(base + ((int64_t)tk[r] * tokstride + col[r & colmask]), tile + r * 1024);
+                else
+                    row_chunk_to_lds(base + ((uint32_t)tk[r] + col[r & colmask]), tile + r * 1024);
+            }
+        };
+        auto request_k = [&](const int (&tk)[8]) { request_rows(Kb, klds, tk, kcol, 3); };
+        auto request_v = [&](const int (&tk)[8]) { request_rows(Vb, vlds, tk, vcol, 1); };
+
+        // The end of a row's piece (what finish_row does) in two steps,
+        // so that what has to be read for it (the state the previous windows left, the output-gate logits) can be
+        // requested while the row's last tile is still being multiplied.
+        f32x4 st_o[MB];
+        float st_m = 0.f, st_l = 0.f;
+        u32x2 st_g1[MB];
+        auto row_end_loads = [&](int ri) {
+            const int flags = __builtin_amdgcn_readlane(m_flags, ri);
+            const int t = t0 + ri;
+            if (!head_ok) return;
+            if (flags & 1) {
+                const int64_t prow = (int64_t)b * a.part_rows + (t - a.part_row0);
+                const float* const state = a.part + (((prow * a.H) + head) * rec_per_head + rec) * (DH + 4);
+    #pragma unroll
+                for (int mb = 0; mb < MB; ++mb) st_o[mb] = *reinterpret_cast<const f32x4*>(state + mb * 16 + 4 * q);
+                st_m = state[DH];
+                st_l = state[DH + 1];
+            }
+            if (!(flags & 2) && a.g1) {  // all output-gate logits of this lane together, so that the loads overlap
+                const int64_t obase = (((int64_t)b * a.Lq + t) * a.H + head) * DH;
+    #pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+                    st_g1[mb] = *reinterpret_cast<const u32x2*>(static_cast<const __bf16*>(a.g1) + obase + mb * 16 + 4 * q);
+            }
+        };
+        auto row_end_finish = [&](int ri) {
+            const int flags = __builtin_amdgcn_readlane(m_flags, ri);
+            const int t = t0 + ri;
+            const int64_t qrow = (int64_t)b * a.Lq + t;
+            const int64_t prow = (int64_t)b * a.part_rows + (t - a.part_row0);
+            float ltot = quad_row_sum(lrun);
+            float* const state = a.part + (((prow * a.H) + (head_ok ? head : 0)) * rec_per_head + rec) * (DH + 4);
+            if ((flags & 1) && head_ok) {  // merge with the state of the previous key windows
+                const float M = fmaxf(mrun, st_m);
+                const float wa = fast_exp2(mrun - M), wb = fast_exp2(st_m - M);
+    #pragma unroll
+                for (int mb = 0; mb < MB; ++mb) o[mb] = o[mb] * wa + st_o[mb] * wb;
+                ltot = ltot * wa + st_l * wb;
+                mrun = M;
+            }
+            if (flags & 2) {
+                if (head_ok) {
+    #pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) *reinterpret_cast<f32x4*>(state + mb * 16 + 4 * q) = o[mb];
+                    if (q == 0) {
+                        state[DH] = mrun;
+                        state[DH + 1] = ltot;
+                    }
+                }
+                return;
+            }
+            if (head_ok) {
+                const float inv = ltot > 0.f ? 1.0f / ltot : 0.f;
+                const int64_t obase = (qrow * a.H + head) * DH;
+    #pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    const int d0 = mb * 16 + 4 * q;
+                    float y[4];
+    #pragma unroll
+                    for (int i = 0; i < 4; ++i) y[i] = o[mb][i] * inv;
+                    if (a.g1) {
+                        const u32x2 gw = st_g1[mb];
+                        y[0] *= sigmoid_f32(bf16_bits_to_f32(gw[0] & 0xffffu));
+                        y[1] *= sigmoid_f32(bf16_bits_to_f32(gw[0] >> 16));
+                        y[2] *= sigmoid_f32(bf16_bits_to_f32(gw[1] & 0xffffu));
+                        y[3] *= sigmoid_f32(bf16_bits_to_f32(gw[1] >> 16));
+                    }
+                    u32x2 ow = {pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
+                    *reinterpret_cast<u32x2*>(static_cast<__bf16*>(a.out) + obase + d0) = ow;
+                }
+            }
+        };
+        auto finish_row_now = [&](int ri) {
+            row_end_loads(ri);
+            row_end_finish(ri);
+        };
+
+        int c_ri, c_j0 = 0, c_je = 0;
+        c_ri = seek(0, c_j0, c_je);
+        int n_ri = c_ri, n_j0 = c_j0, n_je = c_je;
+        int p_ri = nrows, p_j0 = 0, p_je = 0;
+        int tok_n[8];  // list entries (token numbers) of the tile whose rows are requested next
+#pragma unroll
+        for (int r = 0; r < 8; ++r) tok_n[r] = 0;
+        if (c_ri < nrows) {
+            // vector-memory order, here and in every pass of the loop: K rows, (query heads), list entries, V' rows
+            request_idx(c_ri, c_j0, c_je);
+            wait_vmem<0>();
+            read_idx(tok_n);
+            request_k(tok_n);
+            request_q(c_ri);
+            advance(n_ri, n_j0, n_je);
+            p_ri = n_ri, p_j0 = n_j0, p_je = n_je;
+            if (n_ri < nrows) {
+                request_idx(n_ri, n_j0, n_je);
+                advance(p_ri, p_j0, p_je);
+            }
+            request_v(tok_n);
         }
-        stage();
-        if (n_ri < nrows) {  // the row registers are free again
-            issue(tok_pref);
-            if (n_ri != c_ri) load_q(n_ri);  // first tile of another row: its query heads come along
-            if (p_ri < nrows) load_idx(p_ri, p_j0, p_je, tok_pref);
+        int rows_done = 0, cur_row = -1;
+        while (c_ri < nrows) {
+            const bool has_n = n_ri < nrows, has_p = p_ri < nrows;
+            const bool row_ends = c_j0 + 32 >= c_je;
+            // K rows of this tile (and everything older: query heads, the next tile's list entries) have landed; its V'
+            // rows may still fly
+            wait_vmem<8>();
+            if (c_ri != cur_row) {
+                for (; rows_done < c_ri; ++rows_done) {
+                    reset_acc();
+                    finish_row_now(rows_done);
+                }
+                reset_acc();
+                read_q();
+                cur_row = c_ri;
+            }
+            u32x4 ka[KK], kb[KK];
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) ka[kk] = lds_read128_raw<0>(kread[kk]);
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) kb[kk] = lds_read128_raw<4096>(kread[kk]);
+            f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+            wait_lds<4>(ka[0], ka[1], ka[2], ka[3]);
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[kk]), qf[kk], s0, 0, 0, 0);
+            wait_lds<0>(kb[0], kb[1], kb[2], kb[3]);
+            if (has_n) {  // the K tile is free: next tile's K rows, then the list entries of the tile after it
+                read_idx(tok_n);
+                request_k(tok_n);
+                if (n_ri != c_ri) request_q(n_ri);
+                if (has_p) request_idx(p_ri, p_j0, p_je);
+            }
+            if (row_ends) row_end_loads(c_ri);  // (used after the value product)
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kb[kk]), qf[kk], s1, 0, 0, 0);
+            // ---- online softmax of the 32 slots (as in the staged variant) ------------------------------------------
+            const int j0 = c_j0, je = c_je;
+            float x[8];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                x[i] = s0[i] * sl2;
+                x[4 + i] = s1[i] * sl2;
+            }
+            if (j0 + 32 > je) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (j0 + 4 * q + i >= je) x[i] = kNegBig;
+                    if (j0 + 16 + 4 * q + i >= je) x[4 + i] = kNegBig;
+                }
+            }
+            float tmax = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+            tmax = quad_row_max(tmax);
+            const float mnew = fmaxf(mrun, tmax);
+            const float alpha = fast_exp2(mrun - mnew);
+            float psum = 0.f;
+            float pr[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                pr[i] = fast_exp2(x[i] - mnew);
+                psum += pr[i];
+            }
+            lrun = lrun * alpha + psum;
+            mrun = mnew;
+            if (__any(alpha != 1.0f)) {
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) o[mb] *= alpha;
+            }
+            u32x4 pw = {pack_bf16x2(pr[0], pr[1]), pack_bf16x2(pr[2], pr[3]), pack_bf16x2(pr[4], pr[5]), pack_bf16x2(pr[6], pr[7])};
+            const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
+            // ---- the V' rows of this tile have landed (the requests made above may still fly) -----------------------
+            if (has_n && has_p)
+                wait_vmem<9>();
+            else if (has_n)
+                wait_vmem<8>();
+            else
+                wait_vmem<0>();
+            s16x4 va[MB], vb[MB];
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                va[mb] = lds_read_tr16_raw<0>(vread[mb]);
+                vb[mb] = lds_read_tr16_raw<4096>(vread[mb]);
+            }
+            typedef __attribute__((ext_vector_type(8))) short s16x8;
+#pragma unroll
+            for (int h = 0; h < MB / 2; ++h) {
+                if (h == 0) wait_lds<12>(va[0], vb[0], va[1], vb[1]);
+                if (h == 1) wait_lds<8>(va[2], vb[2], va[3], vb[3]);
+                if (h == 2) wait_lds<4>(va[4], vb[4], va[5], vb[5]);
+                if (h == 3) wait_lds<0>(va[6], vb[6], va[7], vb[7]);
+#pragma unroll
+                for (int mb = 2 * h; mb < 2 * h + 2; ++mb) {
+                    s16x8 av = {va[mb][0], va[mb][1], va[mb][2], va[mb][3], vb[mb][0], vb[mb][1], vb[mb][2], vb[mb][3]};
+                    o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av), pf, o[mb], 0, 0, 0);
+                }
+            }
+            if (row_ends) {
+                row_end_finish(c_ri);
+                rows_done = c_ri + 1;
+            }
+            if (has_n) request_v(tok_n);  // the V' tile is free
+            c_ri = n_ri, c_j0 = n_j0, c_je = n_je;
+            n_ri = p_ri, n_j0 = p_j0, n_je = p_je;
+            if (p_ri < nrows) advance(p_ri, p_j0, p_je);
         }
-        compute(c_j0, c_je);
-        if (c_j0 + 32 >= c_je) {
-            finish_row(c_ri);
-            rows_done = c_ri + 1;
+        for (; rows_done < nrows; ++rows_done) {
+            reset_acc();
+            finish_row_now(rows_done);
         }
-        c_ri = n_ri, c_j0 = n_j0, c_je = n_je;
-        n_ri = p_ri, n_j0 = p_j0, n_je = p_je;
-        if (p_ri < nrows) advance(p_ri, p_j0, p_je);
-    }
-    for (; rows_done < nrows; ++rows_done) {
-        reset_acc();
-        finish_row(rows_done);
+    } else {
+        // ---- the tile stream: c = tile being worked on, nx = tile whose rows are requested next, p = tile whose
+        // indices are requested next ------------------------------------------------------------------------------
+        int c_ri, c_j0 = 0, c_je = 0;
+        c_ri = seek(0, c_j0, c_je);
+        int n_ri = c_ri, n_j0 = c_j0, n_je = c_je;
+        int p_ri = nrows, p_j0 = 0, p_je = 0;
+        int tok_pref[NVL];
+    #pragma unroll
+        for (int r = 0; r < NVL; ++r) tok_pref[r] = 0;
+        if (c_ri < nrows) {
+            load_idx(c_ri, c_j0, c_je, tok_pref);
+            issue(tok_pref);  // the one start-up chain of the wave: indices, then rows
+            load_q(c_ri);
+            advance(n_ri, n_j0, n_je);
+            p_ri = n_ri, p_j0 = n_j0, p_je = n_je;
+            if (n_ri < nrows) {
+                load_idx(n_ri, n_j0, n_je, tok_pref);
+                advance(p_ri, p_j0, p_je);
+            }
+        }
+        int rows_done = 0;  // rows [0, rows_done) have been finished
+        int cur_row = -1;   // row whose accumulators are live
+        while (c_ri < nrows) {
+            if (c_ri != cur_row) {  // first tile of a row
+                for (; rows_done < c_ri; ++rows_done) {  // rows without a tile in this piece: only their state moves on
+                    reset_acc();
+                    finish_row(rows_done);
+                }
+                reset_acc();
+    #pragma unroll
+                for (int kk = 0; kk < KK; ++kk) qf[kk] = qf_next[kk];  // (before the next row's heads may be requested)
+                cur_row = c_ri;
+            }
+            stage();
+            if (n_ri < nrows) {  // the row registers are free again
+                issue(tok_pref);
+                if (n_ri != c_ri) load_q(n_ri);  // first tile of another row: its query heads come along
+                if (p_ri < nrows) load_idx(p_ri, p_j0, p_je, tok_pref);
+            }
+            compute(c_j0, c_je);
+            if (c_j0 + 32 >= c_je) {
+                finish_row(c_ri);
+                rows_done = c_ri + 1;
+            }
+            c_ri = n_ri, c_j0 = n_j0, c_je = n_je;
+            n_ri = p_ri, n_j0 = p_j0, n_je = p_je;
+            if (p_ri < nrows) advance(p_ri, p_j0, p_je);
+        }
+        for (; rows_done < nrows; ++rows_done) {
+            reset_acc();
+            finish_row(rows_done);
+        }
     }
 }
 
@@ -648,19 +1000,23 @@ static int attn_splits(const gsa_shape& sh, int64_t rows, int k_cap, const gsa_t
 }
 
 // Query rows a wave of the bf16 kernel streams through: as many as still leave about four thousand workgroups.
-static int attn_rows_per_wave(int64_t lrows, int slices, const gsa_tuning& tn) {
+static int attn_rows_per_wave(int64_t lrows, int slices, bool direct, const gsa_tuning& tn) {
     if (tn.attn_rows_per_wave > 0) return tn.attn_rows_per_wave < 64 ? tn.attn_rows_per_wave : 64;
-    const int64_t r = lrows * slices / 4096;
-    return (int)(r < 1 ? 1 : (r > 8 ? 8 : r));
+    const int64_t r = lrows * slices / 4096, cap = direct ? 4 : 8;  // (measured: C4, 30.6 ms with 4, 30.8 with 8)
+    return (int)(r < 1 ? 1 : (r > cap ? cap : r));
 }
+
+// The direct-to-LDS variant of the bf16 kernel: gated values given, 256-byte rows.
+static bool attn_direct(const gsa_shape& sh, const void* g2) { return GSA_ATTN_DIRECT && sh.dtype == GSA_BF16 && sh.d_h == 128 && !g2; }
 
 // Key-window mode (bf16, many rows, long context): keys per window, 0 = off.  The K/V' rows of one window
 // and kv-head slice (window * kv heads per workgroup * d_h * 4 bytes) then stay largely resident in the
 // 4 MB L2 of every XCD while all rows gather from them, instead of every gather going out to the
 // memory-side cache.  Two forces set the size.  A row needs enough selected keys per window to amortise
-// the start of a workgroup: 384 * Lk / k_cap keys per window leave the longest rows about k_cap/10 keys
-// (a dozen 32-key tiles) per window.  The footprint has to stay near the L2 size: it is kept between
-// 2 MiB and 8 MiB whatever the head dimension.
+// the start of a row's piece: 256 * Lk / k_cap keys per window leave the longest rows about k_cap/16 keys
+// (eight 32-key tiles) per window.  The footprint has to stay near the L2 size: it is kept between
+// 2 MiB and 8 MiB whatever the head dimension.  (Measured at 128K context, k_cap 4096, direct-to-LDS kernel:
+// 8192 keys 30.6 ms, 10240 30.9, 12288 32.2, 6144 33.0, 16384 38.3.)
 static int attn_window(const gsa_shape& sh, int64_t rows, int k_cap, const gsa_tuning& tn) {
     if (tn.attn_window < 0 || sh.dtype != GSA_BF16) return 0;
     int w;
@@ -670,7 +1026,7 @@ static int attn_window(const gsa_shape& sh, int64_t rows, int k_cap, const gsa_t
     } else {
         const int gpb = attn_groups_per_block(sh, rows, tn);
         const int64_t key_bytes = (int64_t)gpb * sh.d_h * 4;  // K row + V' row of the kv heads a workgroup works on
-        int64_t w64 = 384 * (int64_t)sh.Lk / (k_cap > 0 ? k_cap : 1);
+        int64_t w64 = 256 * (int64_t)sh.Lk / (k_cap > 0 ? k_cap : 1);
         const int64_t w_lo = (2 << 20) / key_bytes, w_hi = (8 << 20) / key_bytes;
         w64 = w64 < w_lo ? w_lo : (w64 > w_hi ? w_hi : w64);
         w = (int)((w64 + 512) / 1024 * 1024);
@@ -740,7 +1096,10 @@ hipError_t launch_attention(const gsa_shape& sh, int row_begin, int row_end, con
     if (sh.dtype == GSA_BF16) {
         const int gpb = attn_groups_per_block(sh, rows, tn);
         const dim3 block(64 * gpb);
-        const size_t smem = (size_t)gpb * 32 * ((sh.d_h * 2 + 32) + (sh.d_h * 2 + 16));  // V' tile + K tile per wave
+        // gated values given, 256-byte rows: K and V' rows go straight into LDS (per wave two unpadded 8 KB tiles, 256 bytes of list entries, 1 KB per four query heads)
+        const bool direct = attn_direct(sh, g2);
+        const size_t smem = direct ? (size_t)gpb * (16640 + 1024 * ((sh.H / sh.H_kv + 3) / 4))
+                                   : (size_t)gpb * 32 * ((sh.d_h * 2 + 32) + (sh.d_h * 2 + 16));  // V' tile + K tile per wave
         // one launch, or in key-window mode one launch per window over the rows that can see it
         const int nlaunch = a.window ? a.nsplit : 1;
         for (int z = 0; z < nlaunch; ++z) {
@@ -750,12 +1109,13 @@ hipError_t launch_attention(const gsa_shape& sh, int row_begin, int row_end, con
                 if (a.row_begin >= row_end) break;
             }
             const int lrows = row_end - a.row_begin;  // per batch element
-            a.rpw = attn_rows_per_wave((int64_t)sh.B * lrows, sh.H_kv / gpb, tn);
+            a.rpw = attn_rows_per_wave((int64_t)sh.B * lrows, sh.H_kv / gpb, direct, tn);
             const dim3 grid((unsigned)(sh.B * cdiv(lrows, a.rpw)), (unsigned)(sh.H_kv / gpb), (unsigned)(a.window ? 1 : a.nsplit));
             void (*kern)(AttnArgs) = sh.d_h == 128 ? (g2 ? attn_bf16_kernel<128, true> : attn_bf16_kernel<128, false>)
                                                    : (g2 ? attn_bf16_kernel<64, true> : attn_bf16_kernel<64, false>);
             if (pool_rows)  // (paged caches hold gated values: no g2 here, checked by the caller)
                 kern = sh.d_h == 128 ? attn_bf16_kernel<128, false, true> : attn_bf16_kernel<64, false, true>;
+            if (direct) kern = pool_rows ? attn_bf16_kernel<128, false, true, true> : attn_bf16_kernel<128, false, false, true>;
             if (z == 0 && smem > 48 * 1024) {
                 hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
                 if (e != hipSuccess) return e;

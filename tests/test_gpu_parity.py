@@ -770,3 +770,22 @@ def test_forward_random_shapes_key_windows(case):
     res = T.gpu_forward(wl, d, ctl, slab_rows=slab, tuning=tn)
     rows = {(int(b), int(i)) for b, i in zip(r.integers(0, B, 12), r.integers(0, Lq, 12))} | {(0, 0), (B - 1, Lq - 1)}
     _check_forward(wl, t, res, kw, sorted(rows))
+
+
+def test_gather_probes_return_the_xor_of_the_rows_they_read():
+    """The two measurement helpers (plain whole-row gather, and the same rows staged through LDS) against the plain
+    definition of what they leave in `sink`: wave v XORs every 32-bit word of the rows idx[c*64 .. c*64+64), c = v, v + waves, ..."""
+    rows, n_idx, waves = 4096, 64 * 300, 64
+    g = torch.Generator().manual_seed(5)
+    table = torch.randint(-2**31, 2**31 - 1, (rows, 64), dtype=torch.int32, generator=g)
+    idx = torch.randint(0, rows, (n_idx,), dtype=torch.int32, generator=g)
+    row_x = np.bitwise_xor.reduce(table.numpy().view(np.uint32), axis=1)
+    per_chunk = np.bitwise_xor.reduce(row_x[idx.numpy().reshape(-1, 64)], axis=1)
+    want = np.zeros(waves, np.uint32)
+    for c, x in enumerate(per_chunk):
+        want[c % waves] ^= x
+    for fn in (G.gsa_probe_gather, G.gsa_probe_gather_staged):
+        sink = torch.zeros(waves, dtype=torch.int32, device="cuda")
+        fn(table.cuda(), rows, idx.cuda(), n_idx, waves, sink)
+        torch.cuda.synchronize()
+        assert np.array_equal(sink.cpu().numpy().view(np.uint32), want), fn.__name__
