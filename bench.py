@@ -514,10 +514,11 @@ def main():
         "hbm": {"compulsory_bytes": compulsory, "achieved": round(compulsory / att_s / 1e9, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": round(compulsory / att_s / 1e9 / PEAK_HBM_GBS, 4)},
         "hbm_gather_ceiling_gbs": ceil["hbm_resident_4GiB_table"],
-        "staged_gather_ceiling_gbs": ceil["l2_resident_2MiB_table_staged_through_lds"],
-        "frac_of_staged_gather_ceiling": round(att_gbs / ceil["l2_resident_2MiB_table_staged_through_lds"], 4),
-        "staged_gather_ceiling_source": "the same gather with every row written to and read back from LDS once (gsa_probe_gather_staged, "
-                                        "eight waves per CU): load return, LDS write and LDS read share a CU's data path",
+        "staged_gather_probe_gbs": ceil["l2_resident_2MiB_table_staged_through_lds"],
+        "ratio_to_staged_gather_probe": round(att_gbs / ceil["l2_resident_2MiB_table_staged_through_lds"], 4),
+        "staged_gather_probe_note": "the same gather with every row written to LDS and read back once, no arithmetic "
+                                    "(gsa_probe_gather_staged, eight waves per CU): what a plain kernel reaches when gathered rows have to "
+                                    "pass through LDS, as MFMA operands do; a reference point, not a bound (frac above is against the bound)",
         "traffic": None,
     }
     if isinstance(traffic, dict):
