@@ -324,21 +324,29 @@ def training_leg(G, S, wl, dev):
     dQ, dg1 = torch.empty(t["Q"].shape, **f32), torch.empty(t["Q"].shape, **f32)
     dK, dV, dg2 = (torch.empty(t["K"].shape, **f32) for _ in range(3))
     p_mean = torch.empty((wl.B, wl.Lq, k_cap), **f32)
-    bms = timed(lambda: G.gsa_sparse_gated_attn_bwd(sh, t["Q"], t["K"], t["V"], t["g2"], t["g1"], run.idx, run.n_sel, k_cap, 0.0, dout,
-                                                    dQ, dK, dV, dg1, dg2, p_mean), 2)
+    bwd = lambda ws: G.gsa_sparse_gated_attn_bwd(sh, t["Q"], t["K"], t["V"], t["g2"], t["g1"], run.idx, run.n_sel, k_cap, 0.0, dout,
+                                                 dQ, dK, dV, dg1, dg2, p_mean, workspace=ws)
+    ams = timed(lambda: bwd(None), 2)                      # one pass, dK / dV' by fp32 atomics
+    dK_atomic = dK.clone()
+    bws_bytes = G.gsa_attn_bwd_workspace_bytes(sh, k_cap)
+    bws = G.workspace(bws_bytes)
+    bms = timed(lambda: bwd(bws), 3)                       # with a workspace: key-centred second pass over inverted lists
+    dk_diff = float((dK - dK_atomic).abs().max().item() / max(float(dK_atomic.abs().max().item()), 1e-30))
     loss = torch.empty((wl.B, wl.Lq), **f32)
     dqI, dkI, dw = torch.empty(t["qI"].shape, **f32), torch.empty(t["kI"].shape, **f32), torch.empty(t["w"].shape, **f32)
     kms = timed(lambda: G.gsa_indexer_sparse_kl(sh, t["qI"], t["kI"], t["w"], None, run.idx, run.n_sel, k_cap, p_mean, loss, dqI, dkI, dw),
                 2)
     fms, _ = run.time(3, 1)
     pairs = int(run.n_sel.sum().item())
-    # fp32 atomic adds of the backward: one dK and one dV' row per (query, selected key, chunk of up to four query
-    # heads of a kv group)
+    # rows gathered by the backward per (query, selected key, kv head): K and V (and g2) rows in the query-centred pass (twice),
+    # the query and dO rows of the group's heads in the key-centred pass
+    elt = 2 if wl.dtype == "bf16" else 4
     G_ = wl.H // wl.H_kv
-    hc = 4 if G_ % 4 == 0 else (2 if G_ % 2 == 0 else 1)
-    atomic_bytes = pairs * (wl.H // hc) * wl.d_h * 4 * 2
-    return {"workload": wl.name, "forward_ms": round(fms, 3), "attn_backward_ms": round(bms, 3), "indexer_kl_ms": round(kms, 3),
-            "selected_pairs": pairs, "attn_backward_atomic_gbs": round(atomic_bytes / (bms * 1e-3) / 1e9, 1),
+    gathered = pairs * wl.H_kv * wl.d_h * (2 * 3 * elt + G_ * (elt + 4))
+    return {"workload": wl.name, "forward_ms": round(fms, 3), "attn_backward_ms": round(bms, 3),
+            "attn_backward_workspace_bytes": bws_bytes, "attn_backward_gathered_gbs": round(gathered / (bms * 1e-3) / 1e9, 1),
+            "attn_backward_atomics_ms": round(ams, 3), "dK_max_rel_diff_between_the_two": dk_diff,
+            "indexer_kl_ms": round(kms, 3), "selected_pairs": pairs,
             "mean_kl_per_row": round(float(loss.double().mean().item()), 5)}
 
 

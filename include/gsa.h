@@ -318,8 +318,13 @@ int32_t gsa_output_projection(const gsa_shape* shape, int32_t d_model, const voi
  *   ds_j = P_j (dO.V'_j - dO.O)     dq = scale * sum_j ds_j k_j     dk_j += scale * ds_j q     dV'_j += P_j dO
  *   dV = dV' * sigmoid(g2)          dg2 = dV' * V * sigmoid(g2) (1 - sigmoid(g2))
  * All gradients are fp32: dQ, dg1 [B, Lq, H, d_h]; dK, dV, dg2 [B, Lk, H_kv, d_h] (written entirely: rows no
- * query selected are zero; sums over the queries use fp32 atomics, so their last bits vary between runs).
- * g1_logits and dg1 are given together or both NULL, likewise g2_logits and dg2.
+ * query selected are zero).  g1_logits and dg1 are given together or both NULL, likewise g2_logits and dg2.
+ *   workspace  device, scratch, 256-byte aligned, gsa_attn_bwd_workspace_bytes(shape, k_cap) bytes, or NULL.
+ *           Given: dK and dV' are summed key by key in a second pass over inverted lists (for every key, the
+ *           queries that selected it, grouped by windows of queries), without atomics on the gradients; only
+ *           the order of a key's list, and with it the last bits of its sums, varies between runs.  Needs
+ *           B * Lq * k_cap < 2^31 (GSA_ERR_UNSUPPORTED otherwise); too small: GSA_ERR_WORKSPACE.
+ *           NULL: one pass, every (query, key) contribution added with fp32 atomics (several times slower).
  *   p_mean  device, out, fp32 [B, Lq, k_cap] or NULL: the attention weights of every row over its selected keys,
  *           averaged over the H heads -- the target p_{t,S_t} of the sparse-phase indexer loss.
  *
@@ -332,7 +337,8 @@ int32_t gsa_sparse_gated_attn_bwd(const gsa_shape* shape, const void* Q, const v
                                   const void* g2_logits, const void* g1_logits, const int32_t* idx,
                                   const int32_t* n_sel, int32_t k_cap, float softmax_scale, const void* dout,
                                   float* dQ, float* dK, float* dV, float* dg1, float* dg2, float* p_mean,
-                                  void* stream);
+                                  void* workspace, size_t workspace_bytes, void* stream);
+size_t gsa_attn_bwd_workspace_bytes(const gsa_shape* shape, int32_t k_cap); /* 0 for a bad shape */
 int32_t gsa_indexer_sparse_kl(const gsa_shape* shape, const void* qI, const void* kI, const float* w,
                               const float* bI, const int32_t* idx, const int32_t* n_sel, int32_t k_cap,
                               const float* p, float* loss_rows, float* dqI, float* dkI, float* dw, float* dbI,

@@ -27,6 +27,7 @@ ENTRY_POINTS = (
     "gsa_forward_workspace_bytes", "gsa_forward_noalloc", "gsa_dense_gated_attn", "gsa_dense_attn_workspace_bytes",
     "gsa_cache_append", "gsa_decode_step", "gsa_decode_workspace_bytes", "gsa_paged_cache_append", "gsa_paged_decode_step",
     "gsa_paged_decode_workspace_bytes", "gsa_input_projections", "gsa_output_projection", "gsa_sparse_gated_attn_bwd",
+    "gsa_attn_bwd_workspace_bytes",
     "gsa_indexer_sparse_kl",
     "gsa_probe_gather", "gsa_probe_gather_staged", "gsa_status_string", "gsa_last_error", "gsa_version",
 )
@@ -103,8 +104,10 @@ def load():
     lib.gsa_decode_step.restype = i32
     lib.gsa_decode_workspace_bytes.argtypes = [shp, i32, tun]
     lib.gsa_decode_workspace_bytes.restype = sz
-    lib.gsa_sparse_gated_attn_bwd.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, i32, f32] + [vp] * 8
+    lib.gsa_sparse_gated_attn_bwd.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, i32, f32] + [vp] * 8 + [sz, vp]
     lib.gsa_sparse_gated_attn_bwd.restype = i32
+    lib.gsa_attn_bwd_workspace_bytes.argtypes = [shp, i32]
+    lib.gsa_attn_bwd_workspace_bytes.restype = sz
     lib.gsa_indexer_sparse_kl.argtypes = [shp, vp, vp, vp, vp, vp, vp, i32] + [vp] * 7
     lib.gsa_indexer_sparse_kl.restype = i32
     lib.gsa_paged_cache_append.argtypes = [shp, i32, vp, i32] + [vp] * 10
@@ -346,11 +349,16 @@ def gsa_paged_decode_step(shape, ctl, page_size, block_table, pool_pages, Q, g1_
 
 
 def gsa_sparse_gated_attn_bwd(shape, Q, K, V, g2_logits, g1_logits, idx, n_sel, k_cap, softmax_scale, dout, dQ, dK, dV, dg1, dg2,
-                              p_mean=None, stream=None):
+                              p_mean=None, workspace=None, stream=None):
     rc = load().gsa_sparse_gated_attn_bwd(ctypes.byref(shape), _ptr(Q), _ptr(K), _ptr(V), _ptr(g2_logits), _ptr(g1_logits), _ptr(idx),
                                           _ptr(n_sel), k_cap, float(softmax_scale), _ptr(dout), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dg1),
-                                          _ptr(dg2), _ptr(p_mean), _stream(stream))
+                                          _ptr(dg2), _ptr(p_mean), _ptr(workspace),
+                                          0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream))
     _check(rc, "gsa_sparse_gated_attn_bwd")
+
+
+def gsa_attn_bwd_workspace_bytes(shape, k_cap):
+    return int(load().gsa_attn_bwd_workspace_bytes(ctypes.byref(shape), k_cap))
 
 
 def gsa_indexer_sparse_kl(shape, qI, kI, w, bI, idx, n_sel, k_cap, p, loss_rows, dqI, dkI, dw, dbI=None, stream=None):

@@ -39,7 +39,8 @@ hipError_t launch_projection(const void* x, int64_t tokens, int K, int nseg, con
                              const int32_t* width, const int32_t* kind, hipStream_t st);
 hipError_t launch_attention_bwd(const gsa_shape& sh, const void* Q, const void* K, const void* V, const void* g2, const void* g1,
                                 const int32_t* idx, const int32_t* n_sel, int k_cap, float scale, const void* dout, float* dQ,
-                                float* dK, float* dV, float* dg1, float* dg2, float* p_sum, hipStream_t st);
+                                float* dK, float* dV, float* dg1, float* dg2, float* p_sum, void* workspace, hipStream_t st);
+size_t attention_bwd_workspace_bytes(const gsa_shape& sh, int k_cap);
 hipError_t launch_indexer_kl(const gsa_shape& sh, const void* qI, const void* kI, const float* w, const float* bI, const int32_t* idx,
                              const int32_t* n_sel, int k_cap, const float* p, float* loss, float* dqI, float* dkI, float* dw,
                              float* dbI, hipStream_t st);
@@ -725,19 +726,34 @@ int32_t gsa_output_projection(const gsa_shape* shape, int32_t d_model, const voi
     return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_output_projection");
 }
 
+size_t gsa_attn_bwd_workspace_bytes(const gsa_shape* shape, int32_t k_cap) {
+    if (check_shape(shape) != GSA_OK || k_cap < 1 || k_cap > 8192) return 0;
+    return up256(attention_bwd_workspace_bytes(*shape, k_cap));
+}
+
 int32_t gsa_sparse_gated_attn_bwd(const gsa_shape* shape, const void* Q, const void* K, const void* V, const void* g2_logits,
                                   const void* g1_logits, const int32_t* idx, const int32_t* n_sel, int32_t k_cap,
                                   float softmax_scale, const void* dout, float* dQ, float* dK, float* dV, float* dg1, float* dg2,
-                                  float* p_mean, void* stream) {
+                                  float* p_mean, void* workspace, size_t workspace_bytes, void* stream) {
     int32_t rc = check_shape(shape);
     if (rc != GSA_OK) return rc;
     if (!Q || !K || !V || !idx || !n_sel || !dout || !dQ || !dK || !dV) return GSA_ERR_NULL;
     if ((g1_logits == nullptr) != (dg1 == nullptr) || (g2_logits == nullptr) != (dg2 == nullptr)) return GSA_ERR_NULL;
     if (k_cap < 1 || k_cap > 8192) return GSA_ERR_SHAPE;
     if (!(softmax_scale >= 0.0f) || !std::isfinite(softmax_scale)) return GSA_ERR_SHAPE;
+    if (workspace) {
+        if (!aligned(workspace, 256)) return GSA_ERR_SHAPE;
+        const size_t need = attention_bwd_workspace_bytes(*shape, k_cap);
+        if (workspace_bytes < need) {
+            g_last_error = "gsa_sparse_gated_attn_bwd: workspace of " + std::to_string(workspace_bytes) + " bytes, " + std::to_string(need) +
+                           " needed (gsa_attn_bwd_workspace_bytes)";
+            return GSA_ERR_WORKSPACE;
+        }
+        if ((int64_t)shape->B * shape->Lq * k_cap > 0x7fffffffLL) return GSA_ERR_UNSUPPORTED;  // list positions are 32-bit
+    }
     const float scale = softmax_scale > 0.0f ? softmax_scale : 1.0f / std::sqrt((float)shape->d_h);
     hipError_t e = launch_attention_bwd(*shape, Q, K, V, g2_logits, g1_logits, idx, n_sel, k_cap, scale, dout, dQ, dK, dV, dg1, dg2,
-                                        p_mean, static_cast<hipStream_t>(stream));
+                                        p_mean, workspace, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? GSA_OK : hip_fail(e, "gsa_sparse_gated_attn_bwd");
 }
 

@@ -46,6 +46,11 @@ struct AttnBwdArgs {
     float* p_sum;          // [B, Lq, k_cap] or null, zeroed before the launch: attention weights averaged over the heads
     int32_t B, Lq, Lk, H, H_kv, k_cap;
     float scale;
+    // Key-centred second pass (workspace given): the query-centred kernel leaves dK / dV' alone and stores what the
+    // key-centred kernel needs instead.
+    float* dO_ws;   // [B, Lq, H, d_h]: gradient of the ungated outputs, dout * sigmoid(g1)
+    float* lse_ws;  // [B, Lq, H]: log of the softmax denominator of the scaled logits (natural log)
+    float* D_ws;    // [B, Lq, H]: dO . O
 };
 
 // Eight consecutive elements of a row as floats (one or two 16-byte loads).
@@ -64,10 +69,34 @@ __device__ __forceinline__ void load8(const __bf16* p, float (&x)[8]) {
     }
 }
 
+// N = 4 or 8 consecutive elements of a row as floats.
+template <int N>
+__device__ __forceinline__ void loadn(const float* p, float (&x)[N]) {
+#pragma unroll
+    for (int i = 0; i < N; i += 4) {
+        const float4 a = *reinterpret_cast<const float4*>(p + i);
+        x[i] = a.x; x[i + 1] = a.y; x[i + 2] = a.z; x[i + 3] = a.w;
+    }
+}
+template <int N>
+__device__ __forceinline__ void loadn(const __bf16* p, float (&x)[N]) {
+    if constexpr (N == 8) {
+        load8(p, x);
+    } else {
+        const u32x2 v = *reinterpret_cast<const u32x2*>(p);
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            x[2 * e] = bf16_bits_to_f32(v[e] & 0xffffu);
+            x[2 * e + 1] = bf16_bits_to_f32(v[e] >> 16);
+        }
+    }
+}
+
 // One wave per (query, chunk of HC query heads of one kv group): dQ, dg1 of those heads and their contributions to
 // dK and dV' of the selected keys.  The heads of a chunk share every K / V / g2 row the wave reads, and their
 // contributions to a key are summed in registers before the one atomic add per feature.
-template <typename T, int DH, int HC>
+// SCATTER: dK and dV' by fp32 atomic adds from here; otherwise they are left to attn_bwd_keys_kernel.
+template <typename T, int DH, int HC, bool SCATTER>
 __global__ __launch_bounds__(256) void attn_bwd_kernel(AttnBwdArgs a) {
     constexpr int DPL = DH / 64;  // features per lane
     __shared__ __attribute__((aligned(16))) float lds[4][2 * HC * DH];
@@ -182,9 +211,16 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(AttnBwdArgs a) {
                 }
                 dO[hh][e] = dy * s1;
                 dos[hh * DH + lane + 64 * e] = dO[hh][e];
+                if constexpr (!SCATTER) a.dO_ws[i] = dO[hh][e];
                 dpart = fmaf(dO[hh][e], Oe, dpart);
             }
             D[hh] = wave_sum(dpart);
+            if constexpr (!SCATTER) {
+                if (lane == 0) {
+                    a.lse_ws[qrow * a.H + h0 + hh] = l[hh] > 0.f ? m[hh] + logf(l[hh]) : 0.f;
+                    a.D_ws[qrow * a.H + h0 + hh] = D[hh];
+                }
+            }
         }
         __builtin_amdgcn_s_waitcnt(0);
         __builtin_amdgcn_wave_barrier();
@@ -245,14 +281,18 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(AttnBwdArgs a) {
 #pragma unroll
                     for (int e = 0; e < DPL; ++e) {
                         dq[hh][e] = fmaf(dsu, kel[e], dq[hh][e]);
-                        dk[e] = fmaf(dsu, q[hh][e], dk[e]);
-                        dv[e] = fmaf(pu, dO[hh][e], dv[e]);
+                        if constexpr (SCATTER) {
+                            dk[e] = fmaf(dsu, q[hh][e], dk[e]);
+                            dv[e] = fmaf(pu, dO[hh][e], dv[e]);
+                        }
                     }
                 }
+                if constexpr (SCATTER) {
 #pragma unroll
-                for (int e = 0; e < DPL; ++e) {
-                    atomicAdd(&a.dK[krow + lane + 64 * e], dk[e]);
-                    atomicAdd(&a.dVp[krow + lane + 64 * e], dv[e]);
+                    for (int e = 0; e < DPL; ++e) {
+                        atomicAdd(&a.dK[krow + lane + 64 * e], dk[e]);
+                        atomicAdd(&a.dVp[krow + lane + 64 * e], dv[e]);
+                    }
                 }
             }
         }
@@ -261,6 +301,212 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(AttnBwdArgs a) {
 #pragma unroll
             for (int e = 0; e < DPL; ++e) a.dQ[qbase + hh * DH + lane + 64 * e] = dq[hh][e];
         __builtin_amdgcn_wave_barrier();  // the next chunk rewrites qs and dos
+    }
+}
+
+// ---- key-centred second pass: dK and dV' without atomics ------------------------------------------------------------
+// The selection is turned round first: for every key and every window of WQ consecutive queries, the list of the
+// queries of that window that selected the key ("inverted lists": a two-level histogram, its exclusive prefix sum,
+// and a fill through per-list cursors).  Then one wave per (key, kv head, query window) walks its list, recomputes
+// p and ds of every (query, head) pair from the saved softmax denominators, and sums q ds and dO p in registers;
+// the windows are separate launches in ascending order, so all waves of a launch gather query and dO rows of one
+// window (a few MiB per kv head: they stay in the L2s) and a key's sums pass from window to window through dK / dV'
+// themselves, read and written by the one wave that owns (key, kv head) in that launch.
+struct InvArgs {
+    const int32_t* idx;    // [B, Lq, k_cap]
+    const int32_t* n_sel;  // [B, Lq]
+    int32_t* off;          // [B * Lk * NW + 1]: counts, then (after the scan) list starts; list (key, window) = slot key * NW + window
+    int32_t* cursor;       // [B * Lk * NW], zeroed: entries of the list already filled
+    int32_t* inv;          // [B * Lq * k_cap]: the lists, query positions t
+    int32_t B, Lq, Lk, k_cap, wq_shift, NW;
+};
+
+template <bool FILL>
+__global__ __launch_bounds__(256) void inv_lists_kernel(InvArgs a) {  // one wave per query row
+    const int lane = threadIdx.x & 63;
+    const int64_t qrow = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (qrow >= (int64_t)a.B * a.Lq) return;
+    const int b = (int)(qrow / a.Lq), t = (int)(qrow % a.Lq);
+    const int nsel = max(0, min(a.n_sel[qrow], a.k_cap));
+    const int w = t >> a.wq_shift;
+    for (int j = lane; j < nsel; j += 64) {
+        const int tok = max(0, min(a.idx[qrow * a.k_cap + j], a.Lk - 1));
+        const int64_t slot = ((int64_t)b * a.Lk + tok) * a.NW + w;
+        if constexpr (FILL)
+            a.inv[a.off[slot] + atomicAdd(&a.cursor[slot], 1)] = t;
+        else
+            atomicAdd(&a.off[slot], 1);
+    }
+}
+
+// Exclusive prefix sum over n int32 values in place, in three steps: sums of blocks of 2048 values, the exclusive
+// sums of those (one workgroup, serial over chunks of 1024 block sums), then every block scans its values from
+// its offset.  block_sums holds ceil(n / 2048) values.
+constexpr int kScanBlock = 2048;
+__global__ __launch_bounds__(256) void scan_block_sums_kernel(const int32_t* v, int64_t n, int32_t* block_sums) {
+    __shared__ int32_t red[4];
+    const int64_t base = (int64_t)blockIdx.x * kScanBlock;
+    int32_t s = 0;
+    for (int i = threadIdx.x; i < kScanBlock; i += 256)
+        if (base + i < n) s += v[base + i];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) block_sums[blockIdx.x] = red[0] + red[1] + red[2] + red[3];
+}
+__global__ __launch_bounds__(1024) void scan_of_sums_kernel(int32_t* block_sums, int64_t nb) {  // one workgroup
+    __shared__ int32_t wsum[16];
+    __shared__ int32_t carry_s;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    for (int64_t c0 = 0; c0 < nb; c0 += 1024) {
+        const int64_t i = c0 + threadIdx.x;
+        const int32_t x = i < nb ? block_sums[i] : 0;
+        int32_t incl = x;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int32_t y = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += y;
+        }
+        if (lane == 63) wsum[wv] = incl;
+        __syncthreads();
+        int32_t before = carry_s;
+        for (int k = 0; k < wv; ++k) before += wsum[k];
+        if (i < nb) block_sums[i] = before + incl - x;
+        __syncthreads();
+        if (threadIdx.x == 1023) carry_s = before + incl;
+        __syncthreads();
+    }
+}
+__global__ __launch_bounds__(256) void scan_blocks_kernel(int32_t* v, int64_t n, const int32_t* block_sums) {
+    __shared__ int32_t wsum[4];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int64_t base = (int64_t)blockIdx.x * kScanBlock + threadIdx.x * 8;  // eight consecutive values per thread
+    int32_t x[8], tot = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        x[e] = base + e < n ? v[base + e] : 0;
+        tot += x[e];
+    }
+    int32_t incl = tot;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int32_t y = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += y;
+    }
+    if (lane == 63) wsum[wv] = incl;
+    __syncthreads();
+    int32_t run = block_sums[blockIdx.x] + incl - tot;
+    for (int k = 0; k < wv; ++k) run += wsum[k];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        if (base + e < n) v[base + e] = run;
+        run += x[e];
+    }
+}
+
+struct KeyBwdArgs {
+    const void* Q;
+    const void* K;
+    const void* V;
+    const void* g2;
+    const float* dO;   // [B, Lq, H, d_h]
+    const float* lse;  // [B, Lq, H]
+    const float* D;    // [B, Lq, H]
+    const int32_t* off;
+    const int32_t* inv;
+    float* dK;   // [B, Lk, H_kv, d_h]: sums of the windows before this one on entry
+    float* dVp;
+    int32_t B, Lq, Lk, H, H_kv, NW, win, keys;  // keys: the keys 0 .. keys-1 can have entries in this window
+    float scale;
+};
+
+// One wave per (key, kv head) of one query window.  Lane = (head slot hh = lane / 16, feature chunk c = lane % 16): a
+// lane holds DH / 16 consecutive features of the key's K and V' rows and, entry by entry, of one head's query and
+// dO rows; the two dot products of a pair are reduced over the sixteen lanes of its head slot.  Groups of more than
+// four query heads per kv head take several passes over the list.
+template <typename T, int DH>
+__global__ __launch_bounds__(256) void attn_bwd_keys_kernel(KeyBwdArgs a) {
+    constexpr int FPL = DH / 16;
+    const int lane = threadIdx.x & 63;
+    const int hh = lane >> 4, c = lane & 15;
+    const int key = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int g = blockIdx.y, b = blockIdx.z;
+    if (key >= a.keys) return;
+    const int64_t slot = ((int64_t)b * a.Lk + key) * a.NW + a.win;
+    const int e0 = a.off[slot], e1 = a.off[slot + 1];
+    if (e0 >= e1) return;
+    const int G = a.H / a.H_kv;
+    const T* Q = static_cast<const T*>(a.Q);
+    const int64_t krow = (((int64_t)b * a.Lk + key) * a.H_kv + g) * DH + c * FPL;
+    float kf[FPL], vf[FPL], dk[FPL], dv[FPL];
+    loadn<FPL>(static_cast<const T*>(a.K) + krow, kf);
+    loadn<FPL>(static_cast<const T*>(a.V) + krow, vf);
+    if (a.g2) {
+        float gf[FPL];
+        loadn<FPL>(static_cast<const T*>(a.g2) + krow, gf);
+#pragma unroll
+        for (int f = 0; f < FPL; ++f) vf[f] *= precise_sigmoid(gf[f]);
+    }
+#pragma unroll
+    for (int f = 0; f < FPL; ++f) dk[f] = dv[f] = 0.f;
+    for (int h0 = 0; h0 < G; h0 += 4) {
+        const int hq = h0 + hh;
+        const bool live = hq < G;
+        const int head = g * G + (live ? hq : 0);
+        for (int e = e0; e < e1; e += 2) {  // two entries per step: the loads of both go out before either is used
+            const bool two = e + 1 < e1;
+            const int64_t r0 = ((int64_t)b * a.Lq + a.inv[e]) * a.H + head;
+            const int64_t r1 = ((int64_t)b * a.Lq + a.inv[two ? e + 1 : e]) * a.H + head;
+            float q0[FPL], q1[FPL], o0[FPL], o1[FPL];
+            loadn<FPL>(Q + r0 * DH + c * FPL, q0);
+            loadn<FPL>(Q + r1 * DH + c * FPL, q1);
+            loadn<FPL>(a.dO + r0 * DH + c * FPL, o0);
+            loadn<FPL>(a.dO + r1 * DH + c * FPL, o1);
+            const float l0 = a.lse[r0], l1 = a.lse[r1], D0 = a.D[r0], D1 = a.D[r1];
+            float s0 = 0.f, s1 = 0.f, p0 = 0.f, p1 = 0.f;
+#pragma unroll
+            for (int f = 0; f < FPL; ++f) {
+                s0 = fmaf(q0[f], kf[f], s0);
+                s1 = fmaf(q1[f], kf[f], s1);
+                p0 = fmaf(o0[f], vf[f], p0);
+                p1 = fmaf(o1[f], vf[f], p1);
+            }
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) {
+                s0 += __shfl_xor(s0, o, 64);
+                s1 += __shfl_xor(s1, o, 64);
+                p0 += __shfl_xor(p0, o, 64);
+                p1 += __shfl_xor(p1, o, 64);
+            }
+            const float P0 = live ? expf(s0 * a.scale - l0) : 0.f;
+            const float P1 = live && two ? expf(s1 * a.scale - l1) : 0.f;
+            const float ds0 = P0 * (p0 - D0) * a.scale, ds1 = P1 * (p1 - D1) * a.scale;
+#pragma unroll
+            for (int f = 0; f < FPL; ++f) {
+                dk[f] = fmaf(ds0, q0[f], dk[f]);
+                dk[f] = fmaf(ds1, q1[f], dk[f]);
+                dv[f] = fmaf(P0, o0[f], dv[f]);
+                dv[f] = fmaf(P1, o1[f], dv[f]);
+            }
+        }
+    }
+    // sum over the four head slots; head slot 0 adds the result to what the earlier windows left
+#pragma unroll
+    for (int f = 0; f < FPL; ++f) {
+        dk[f] += __shfl_xor(dk[f], 16, 64);
+        dk[f] += __shfl_xor(dk[f], 32, 64);
+        dv[f] += __shfl_xor(dv[f], 16, 64);
+        dv[f] += __shfl_xor(dv[f], 32, 64);
+    }
+    if (hh == 0) {
+#pragma unroll
+        for (int f = 0; f < FPL; ++f) {
+            a.dK[krow + f] += dk[f];
+            a.dVp[krow + f] += dv[f];
+        }
     }
 }
 
@@ -287,9 +533,45 @@ static void zero_fill(float* p, int64_t n, hipStream_t st) {
     if (p && n > 0) hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st, p, n);
 }
 
+// Workspace of the key-centred second pass.  Query windows of WQ = 2^wq_shift rows: the query and dO rows of one
+// window and one kv head (G heads x d_h x (element + 4) bytes per row) stay near 3 MiB; at most 256 windows.
+struct BwdPlan {
+    int wq_shift, NW;
+    int64_t n_slots;  // B * Lk * NW lists
+    size_t o_dO, o_lse, o_D, o_off, o_cursor, o_sums, o_inv, total;
+};
+static BwdPlan plan_bwd(const gsa_shape& sh, int k_cap) {
+    BwdPlan p;
+    const int elt = sh.dtype == GSA_BF16 ? 2 : 4;
+    const int64_t row_bytes = (int64_t)(sh.H / sh.H_kv) * sh.d_h * (elt + 4);
+    int shift = 6;
+    while (shift < 20 && ((int64_t)2 << shift) * row_bytes <= (3 << 20)) ++shift;
+    while (cdiv(sh.Lq, (int64_t)1 << shift) > 256) ++shift;
+    p.wq_shift = shift;
+    p.NW = (int)cdiv(sh.Lq, (int64_t)1 << shift);
+    p.n_slots = (int64_t)sh.B * sh.Lk * p.NW;
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    size_t o = 0;
+    p.o_dO = o;      o += up((size_t)sh.B * sh.Lq * sh.H * sh.d_h * sizeof(float));
+    p.o_lse = o;     o += up((size_t)sh.B * sh.Lq * sh.H * sizeof(float));
+    p.o_D = o;       o += up((size_t)sh.B * sh.Lq * sh.H * sizeof(float));
+    p.o_off = o;     o += up((size_t)(p.n_slots + 1) * sizeof(int32_t));
+    p.o_cursor = o;  o += up((size_t)p.n_slots * sizeof(int32_t));
+    p.o_sums = o;    o += up((size_t)cdiv(p.n_slots + 1, kScanBlock) * sizeof(int32_t));
+    p.o_inv = o;     o += up((size_t)sh.B * sh.Lq * k_cap * sizeof(int32_t));
+    p.total = o;
+    return p;
+}
+size_t attention_bwd_workspace_bytes(const gsa_shape& sh, int k_cap) { return plan_bwd(sh, k_cap).total; }
+
+template <typename T, int DH, bool SCATTER>
+static void (*pick_bwd_kernel(int hc))(AttnBwdArgs) {
+    return hc == 4 ? attn_bwd_kernel<T, DH, 4, SCATTER> : (hc == 2 ? attn_bwd_kernel<T, DH, 2, SCATTER> : attn_bwd_kernel<T, DH, 1, SCATTER>);
+}
+
 hipError_t launch_attention_bwd(const gsa_shape& sh, const void* Q, const void* K, const void* V, const void* g2, const void* g1,
                                 const int32_t* idx, const int32_t* n_sel, int k_cap, float scale, const void* dout, float* dQ,
-                                float* dK, float* dV, float* dg1, float* dg2, float* p_sum, hipStream_t st) {
+                                float* dK, float* dV, float* dg1, float* dg2, float* p_sum, void* workspace, hipStream_t st) {
     AttnBwdArgs a;
     a.Q = Q;
     a.K = K;
@@ -311,6 +593,12 @@ hipError_t launch_attention_bwd(const gsa_shape& sh, const void* Q, const void* 
     a.H_kv = sh.H_kv;
     a.k_cap = k_cap;
     a.scale = scale;
+    const bool scatter = workspace == nullptr;
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    const BwdPlan p = plan_bwd(sh, k_cap);
+    a.dO_ws = scatter ? nullptr : reinterpret_cast<float*>(ws + p.o_dO);
+    a.lse_ws = scatter ? nullptr : reinterpret_cast<float*>(ws + p.o_lse);
+    a.D_ws = scatter ? nullptr : reinterpret_cast<float*>(ws + p.o_D);
     const int64_t kv_elems = (int64_t)sh.B * sh.Lk * sh.H_kv * sh.d_h;
     zero_fill(dK, kv_elems, st);
     zero_fill(dV, kv_elems, st);
@@ -321,16 +609,69 @@ hipError_t launch_attention_bwd(const gsa_shape& sh, const void* Q, const void* 
     void (*kern)(AttnBwdArgs) = nullptr;
     if (sh.dtype == GSA_BF16) {
         if (sh.d_h == 128)
-            kern = hc == 4 ? attn_bwd_kernel<__bf16, 128, 4> : (hc == 2 ? attn_bwd_kernel<__bf16, 128, 2> : attn_bwd_kernel<__bf16, 128, 1>);
+            kern = scatter ? pick_bwd_kernel<__bf16, 128, true>(hc) : pick_bwd_kernel<__bf16, 128, false>(hc);
         else
-            kern = hc == 4 ? attn_bwd_kernel<__bf16, 64, 4> : (hc == 2 ? attn_bwd_kernel<__bf16, 64, 2> : attn_bwd_kernel<__bf16, 64, 1>);
+            kern = scatter ? pick_bwd_kernel<__bf16, 64, true>(hc) : pick_bwd_kernel<__bf16, 64, false>(hc);
     } else {
         if (sh.d_h == 128)
-            kern = hc == 4 ? attn_bwd_kernel<float, 128, 4> : (hc == 2 ? attn_bwd_kernel<float, 128, 2> : attn_bwd_kernel<float, 128, 1>);
+            kern = scatter ? pick_bwd_kernel<float, 128, true>(hc) : pick_bwd_kernel<float, 128, false>(hc);
         else
-            kern = hc == 4 ? attn_bwd_kernel<float, 64, 4> : (hc == 2 ? attn_bwd_kernel<float, 64, 2> : attn_bwd_kernel<float, 64, 1>);
+            kern = scatter ? pick_bwd_kernel<float, 64, true>(hc) : pick_bwd_kernel<float, 64, false>(hc);
     }
     hipLaunchKernelGGL(kern, grid, dim3(256), 0, st, a);
+    if (!scatter) {
+        // inverted lists: counts -> exclusive prefix sum -> fill
+        InvArgs ia;
+        ia.idx = idx;
+        ia.n_sel = n_sel;
+        ia.off = reinterpret_cast<int32_t*>(ws + p.o_off);
+        ia.cursor = reinterpret_cast<int32_t*>(ws + p.o_cursor);
+        ia.inv = reinterpret_cast<int32_t*>(ws + p.o_inv);
+        ia.B = sh.B;
+        ia.Lq = sh.Lq;
+        ia.Lk = sh.Lk;
+        ia.k_cap = k_cap;
+        ia.wq_shift = p.wq_shift;
+        ia.NW = p.NW;
+        int32_t* sums = reinterpret_cast<int32_t*>(ws + p.o_sums);
+        const int64_t n = p.n_slots + 1;
+        const unsigned nblk = (unsigned)cdiv(n, kScanBlock);
+        // (int32 and fp32 zeros are the same bits; off and cursor are adjacent 256-byte multiples)
+        zero_fill(reinterpret_cast<float*>(ia.off), (int64_t)((p.o_sums - p.o_off) / sizeof(int32_t)), st);
+        const unsigned rgrid = (unsigned)cdiv((int64_t)sh.B * sh.Lq, 4);
+        hipLaunchKernelGGL(inv_lists_kernel<false>, dim3(rgrid), dim3(256), 0, st, ia);
+        hipLaunchKernelGGL(scan_block_sums_kernel, dim3(nblk), dim3(256), 0, st, ia.off, n, sums);
+        hipLaunchKernelGGL(scan_of_sums_kernel, dim3(1), dim3(1024), 0, st, sums, (int64_t)nblk);
+        hipLaunchKernelGGL(scan_blocks_kernel, dim3(nblk), dim3(256), 0, st, ia.off, n, sums);
+        hipLaunchKernelGGL(inv_lists_kernel<true>, dim3(rgrid), dim3(256), 0, st, ia);
+        KeyBwdArgs ka;
+        ka.Q = Q;
+        ka.K = K;
+        ka.V = V;
+        ka.g2 = g2;
+        ka.dO = a.dO_ws;
+        ka.lse = a.lse_ws;
+        ka.D = a.D_ws;
+        ka.off = ia.off;
+        ka.inv = ia.inv;
+        ka.dK = dK;
+        ka.dVp = dV;
+        ka.B = sh.B;
+        ka.Lq = sh.Lq;
+        ka.Lk = sh.Lk;
+        ka.H = sh.H;
+        ka.H_kv = sh.H_kv;
+        ka.NW = p.NW;
+        ka.scale = scale;
+        void (*kk)(KeyBwdArgs) = sh.dtype == GSA_BF16
+                                     ? (sh.d_h == 128 ? attn_bwd_keys_kernel<__bf16, 128> : attn_bwd_keys_kernel<__bf16, 64>)
+                                     : (sh.d_h == 128 ? attn_bwd_keys_kernel<float, 128> : attn_bwd_keys_kernel<float, 64>);
+        ka.keys = sh.Lk;  // (lists are taken as they are: a list may name any key, visible to its query or not)
+        for (int w = 0; w < p.NW; ++w) {
+            ka.win = w;
+            hipLaunchKernelGGL(kk, dim3((unsigned)cdiv(ka.keys, 4), (unsigned)sh.H_kv, (unsigned)sh.B), dim3(256), 0, st, ka);
+        }
+    }
     if (sh.dtype == GSA_BF16)
         hipLaunchKernelGGL(value_gate_bwd_kernel<__bf16>, dim3((unsigned)cdiv(kv_elems, 256)), dim3(256), 0, st,
                            static_cast<const __bf16*>(V), static_cast<const __bf16*>(g2), dV, dg2, kv_elems);

@@ -3,8 +3,10 @@ the sparse-phase indexer loss and the gradients it sends into the indexer (Sec. 
 the same inputs and the same selection.
 
 Tolerances: everything is fp32 arithmetic on bf16 or fp32 inputs, sums of up to k_cap * H products per entry,
-added with atomics in arbitrary order: |got - ref| <= 2e-4 * scale_of_that_tensor + 1e-6, where the scale is the
-largest |ref| entry (gradient entries of one tensor are sums of the same kind)."""
+added in an order that varies (atomics, or lists filled through atomic cursors): |got - ref| <= 2e-4 *
+scale_of_that_tensor + 1e-6, where the scale is the largest |ref| entry (gradient entries of one tensor are sums of
+the same kind).  Both forms of the attention backward run: with a workspace (dK, dV' summed key by key over inverted
+lists) and without (fp32 atomics)."""
 import numpy as np
 import pytest
 import torch
@@ -40,11 +42,13 @@ CASES = [
     ("f32", 1, 130, 4, 4, 64, 3, 64, 33, False, True),
     ("f32", 2, 90, 8, 2, 128, 8, 128, 90, True, False),     # budget covers every visible key of every row
     ("bf16", 1, 140, 16, 1, 64, 5, 32, 130, True, True),    # sixteen query heads on one kv head: four chunks of four heads
+    ("bf16", 1, 150, 12, 4, 64, 2, 32, 40, True, False),    # groups of three heads: a head slot of the key-centred pass stays idle
 ]
 
 
+@pytest.mark.parametrize("two_pass", [True, False], ids=["key-centred second pass", "atomics"])
 @pytest.mark.parametrize("dtype,B,L,H,Hkv,dh,HI,dI,k,gates,bias", CASES)
-def test_attention_backward_and_sparse_kl(dtype, B, L, H, Hkv, dh, HI, dI, k, gates, bias):
+def test_attention_backward_and_sparse_kl(dtype, B, L, H, Hkv, dh, HI, dI, k, gates, bias, two_pass):
     wl = S.Workload("train", B, L, L, 0, H, Hkv, dh, HI, dI, dtype, k, k, k, k_fixed=k, seed=400 + L)
     t_cpu = S.make_inputs(wl, "cpu", with_bias=bias)
     t = T.to_device(t_cpu)
@@ -59,8 +63,12 @@ def test_attention_backward_and_sparse_kl(dtype, B, L, H, Hkv, dh, HI, dI, k, ga
     dg1 = torch.full(t["Q"].shape, float("nan"), **f32) if gates else None
     dg2 = torch.full(t["K"].shape, float("nan"), **f32) if gates else None
     p_mean = torch.full((B, L, k), float("nan"), **f32)
+    ws = None
+    if two_pass:
+        ws = G.workspace(G.gsa_attn_bwd_workspace_bytes(sh, k))
+        ws.fill_(0x7F)      # nothing in the workspace has to be cleared by the caller
     G.gsa_sparse_gated_attn_bwd(sh, t["Q"], t["K"], t["V"], t["g2"] if gates else None, t["g1"] if gates else None, idx, n_sel, k, 0.0,
-                                dout, dQ, dK, dV, dg1, dg2, p_mean)
+                                dout, dQ, dK, dV, dg1, dg2, p_mean, workspace=ws)
     loss = torch.full((B, L), float("nan"), **f32)
     dqI = torch.full(t["qI"].shape, float("nan"), **f32)
     dkI = torch.full(t["kI"].shape, float("nan"), **f32)
@@ -121,6 +129,10 @@ def test_training_entry_points_reject_half_given_pairs():
         G.gsa_sparse_gated_attn_bwd(sh, t["Q"], t["K"], t["V"], None, t["g1"], idx, n_sel, 8, 0.0, t["Q"], f(t["Q"]), f(t["K"]), f(t["K"]),
                                     None, None)
     assert e.value.status == G.GSA_ERR_NULL
+    with pytest.raises(G.GsaError) as e:      # a workspace that is too small
+        G.gsa_sparse_gated_attn_bwd(sh, t["Q"], t["K"], t["V"], None, None, idx, n_sel, 8, 0.0, t["Q"], f(t["Q"]), f(t["K"]), f(t["K"]),
+                                    None, None, workspace=G.workspace(256))
+    assert e.value.status == G.GSA_ERR_WORKSPACE
     with pytest.raises(G.GsaError) as e:      # dbI without bI
         G.gsa_indexer_sparse_kl(sh, t["qI"], t["kI"], t["w"], None, idx, n_sel, 8, torch.zeros((1, 64, 8), device="cuda"),
                                 torch.empty((1, 64), device="cuda"), f(t["qI"]), f(t["kI"]), f(t["w"]), torch.empty(2, device="cuda"))
