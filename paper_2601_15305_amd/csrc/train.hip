@@ -304,6 +304,288 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(AttnBwdArgs a) {
     }
 }
 
+// ---- query-centred pass on the matrix cores (bf16 inputs, workspace given) ------------------------------------------
+// One wave per (query, kv head), the G = H / H_kv query heads of the kv head as the N dimension (padded to 16) of
+// v_mfma_f32_16x16x32_bf16, the gathered tokens as M or K: the dataflow of the forward kernel (attention.hip: whole
+// K and V' rows staged in wave-private LDS tiles of 32 tokens, V' gated on the way).  Two passes over the list:
+//   1. the forward: S^T = K Q^T, online softmax, O^T += V'^T P^T  ->  O, the softmax maximum and denominator;
+//      then dO = dout * sigmoid(g1), D = dO . O, dg1, and what the key-centred pass needs (dO, log-sum-exp, D);
+//   2. S^T again and dP^T = V' dO^T (V' rows read as an A operand, like K), P = exp(S - lse),
+//      dS = P (dP - D) scale, dQ^T += K^T dS^T (K read back transposed, like V' in the forward).
+// P, dO and dS enter the products rounded to bf16, as P does in the forward.
+struct QBwdArgs {
+    const void* Q;
+    const void* K;
+    const void* V;
+    const void* g2;
+    const void* g1;
+    const void* dout;
+    const int32_t* idx;
+    const int32_t* n_sel;
+    float* dQ;
+    float* dg1;
+    float* p_sum;
+    float* dO_ws;
+    float* lse_ws;
+    float* D_ws;
+    int32_t B, Lq, Lk, H, H_kv, k_cap;
+    float scale;
+};
+typedef __attribute__((address_space(3))) s16x4 train_lds_s16x4;
+__device__ __forceinline__ float train_quad_row_max(float x) {  // max over lanes {l, l^16, l^32, l^48}
+    auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float train_quad_row_sum(float x) {
+    auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+template <int DH, bool HAS_G2>
+__global__ __launch_bounds__(256, 2) void attn_bwd_q_mfma_kernel(QBwdArgs a) {
+    constexpr int KK = DH / 32, MB = DH / 16, ROWB = DH * 2, VROW = ROWB + 32, KROW = ROWB + 16;
+    constexpr int VCH = ROWB / 16, TPI = 64 / VCH, NVL = 32 / TPI;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int n = lane & 15, q = lane >> 4;
+    unsigned char* vlds = smem + wv * (32 * (VROW + KROW));
+    unsigned char* klds = vlds + 32 * VROW;
+    const int g = __builtin_amdgcn_readfirstlane(blockIdx.y * 4 + wv);
+    if (g >= a.H_kv) return;  // (the waves of a workgroup never synchronise with each other)
+    const int64_t qrow = blockIdx.x;
+    const int b = (int)(qrow / a.Lq);
+    const int G = a.H / a.H_kv;
+    const int head = g * G + n;
+    const bool head_ok = n < G;
+    const float sl2 = a.scale * kLog2e;
+    const uint32_t tokstride = (uint32_t)a.H_kv * ROWB;
+    const int nsel = max(0, min(a.n_sel[qrow], a.k_cap));
+    const int32_t* idxrow = a.idx + qrow * a.k_cap;
+    const int64_t row0 = (int64_t)b * a.Lk;
+    const unsigned char* Kb = static_cast<const unsigned char*>(a.K) + (row0 * a.H_kv + g) * ROWB;
+    const unsigned char* Vb = static_cast<const unsigned char*>(a.V) + (row0 * a.H_kv + g) * ROWB;
+    const unsigned char* Gb = HAS_G2 ? static_cast<const unsigned char*>(a.g2) + (row0 * a.H_kv + g) * ROWB : nullptr;
+    const int64_t hbase = (qrow * a.H + (head_ok ? head : 0)) * DH;  // this lane's head row in Q / dout / g1 / dQ
+
+    // B operands: lane (head n, chunk q) holds features (4 kk + q) * 8 .. + 8
+    bf16x8 qf[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+        const u32x4 v = head_ok ? reinterpret_cast<const u32x4*>(static_cast<const __bf16*>(a.Q) + hbase)[kk * 4 + q] : u32x4{0, 0, 0, 0};
+        qf[kk] = __builtin_bit_cast(bf16x8, v);
+    }
+    u32x4 kr[NVL], vf[NVL], gf[HAS_G2 ? NVL : 1];
+    const int slot0 = (lane / VCH) * NVL;
+    auto load_idx = [&](int j0, int (&tk)[NVL]) {
+#pragma unroll
+        for (int r = 0; r < NVL; ++r) tk[r] = idxrow[min(j0 + slot0 + r, nsel - 1)];
+    };
+    auto issue = [&](const int (&tokv)[NVL]) {
+#pragma unroll
+        for (int r = 0; r < NVL; ++r) {
+            const int tk = max(0, min(tokv[r], a.Lk - 1));
+            const uint32_t off = __umul24((uint32_t)tk, tokstride) + (uint32_t)(lane % VCH) * 16u;
+            kr[r] = *reinterpret_cast<const u32x4*>(Kb + off);
+            vf[r] = *reinterpret_cast<const u32x4*>(Vb + off);
+            if constexpr (HAS_G2) gf[r] = *reinterpret_cast<const u32x4*>(Gb + off);
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int r = 0; r < NVL; ++r) *reinterpret_cast<u32x4*>(klds + (slot0 + r) * KROW + (lane % VCH) * 16) = kr[r];
+#pragma unroll
+        for (int r = 0; r < NVL; ++r) {
+            u32x4 v = vf[r];
+            if constexpr (HAS_G2) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float v0 = bf16_bits_to_f32(v[e] & 0xffffu) * sigmoid_f32(bf16_bits_to_f32(gf[r][e] & 0xffffu));
+                    const float v1 = bf16_bits_to_f32(v[e] >> 16) * sigmoid_f32(bf16_bits_to_f32(gf[r][e] >> 16));
+                    v[e] = pack_bf16x2(v0, v1);
+                }
+            }
+            *reinterpret_cast<u32x4*>(vlds + (slot0 + r) * VROW + (lane % VCH) * 16) = v;
+        }
+    };
+    // S^T (or dP^T) of the tile in LDS: rows of `tile` (row stride ROWSTRIDE) against the B operand bf
+    auto rows_times = [&](const unsigned char* tile, int rowstride, const bf16x8 (&bf)[KK], f32x4& r0, f32x4& r1) {
+        r0 = f32x4{0.f, 0.f, 0.f, 0.f};
+        r1 = f32x4{0.f, 0.f, 0.f, 0.f};
+        const unsigned char* p0 = tile + n * rowstride + q * 16;
+        const unsigned char* p1 = p0 + 16 * rowstride;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            const u32x4 a0 = *reinterpret_cast<const u32x4*>(p0 + kk * 64);
+            const u32x4 a1 = *reinterpret_cast<const u32x4*>(p1 + kk * 64);
+            r0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a0), bf[kk], r0, 0, 0, 0);
+            r1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a1), bf[kk], r1, 0, 0, 0);
+        }
+    };
+    // acc^T[d, head] += tile^T[d, token] . w^T[token, head], the tile read back transposed
+    auto transposed_times = [&](const unsigned char* tile, int rowstride, const bf16x8 wfrag, f32x4 (&acc)[MB]) {
+        const int r4 = (lane & 15) >> 2, c4 = lane & 3;
+        const unsigned char* p0 = tile + (4 * q + r4) * rowstride + c4 * 8;
+        const unsigned char* p1 = p0 + 16 * rowstride;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            s16x4 a0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((train_lds_s16x4*)(p0 + mb * 32));
+            s16x4 a1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((train_lds_s16x4*)(p1 + mb * 32));
+            typedef __attribute__((ext_vector_type(8))) short s16x8;
+            s16x8 av = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+            acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av), wfrag, acc[mb], 0, 0, 0);
+        }
+    };
+    const int ntile = (nsel + 31) >> 5;
+    // walks the list tile by tile: the next tile's rows and the entries of the tile after it are in flight while
+    // `body(j0)` works on the tile in LDS
+    auto for_tiles = [&](auto&& body) {
+        int tok[NVL];
+        if (ntile > 0) {
+            load_idx(0, tok);
+            issue(tok);
+            if (ntile > 1) load_idx(32, tok);
+        }
+        for (int it = 0; it < ntile; ++it) {
+            stage();
+            if (it + 1 < ntile) {
+                issue(tok);
+                if (it + 2 < ntile) load_idx((it + 2) * 32, tok);
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this wave's LDS writes have landed
+            body(it * 32);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // reads done before the tile is overwritten
+        }
+    };
+
+    // ---- pass 1: the forward ---------------------------------------------------------------------------------------
+    f32x4 o[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) o[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float mrun = kTrainNegBig, lrun = 0.f;
+    for_tiles([&](int j0) {
+        f32x4 s0, s1;
+        rows_times(klds, KROW, qf, s0, s1);
+        float x[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            x[i] = j0 + 4 * q + i < nsel ? s0[i] * sl2 : kTrainNegBig;
+            x[4 + i] = j0 + 16 + 4 * q + i < nsel ? s1[i] * sl2 : kTrainNegBig;
+        }
+        float tmax = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+        tmax = train_quad_row_max(tmax);
+        const float mnew = fmaxf(mrun, tmax);
+        const float alpha = fast_exp2(mrun - mnew);
+        float psum = 0.f, p[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            p[i] = fast_exp2(x[i] - mnew);
+            psum += p[i];
+        }
+        lrun = lrun * alpha + psum;
+        mrun = mnew;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) o[mb] *= alpha;
+        const u32x4 pw = {pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]), pack_bf16x2(p[4], p[5]), pack_bf16x2(p[6], p[7])};
+        transposed_times(vlds, VROW, __builtin_bit_cast(bf16x8, pw), o);
+    });
+    const float ltot = train_quad_row_sum(lrun);
+    const float inv = ltot > 0.f ? 1.0f / ltot : 0.f;
+
+    // ---- dO = dout * sigmoid(g1), D = dO . O, dg1; lane (head n, q) holds features mb * 16 + 4 q + i of O ---------------
+    float dpart = 0.f;
+    if (head_ok) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            const int d0 = mb * 16 + 4 * q;
+            const u32x2 dw = *reinterpret_cast<const u32x2*>(static_cast<const __bf16*>(a.dout) + hbase + d0);
+            const float dy[4] = {bf16_bits_to_f32(dw[0] & 0xffffu), bf16_bits_to_f32(dw[0] >> 16), bf16_bits_to_f32(dw[1] & 0xffffu),
+                                 bf16_bits_to_f32(dw[1] >> 16)};
+            float s1v[4] = {1.f, 1.f, 1.f, 1.f};
+            if (a.g1) {
+                const u32x2 gw = *reinterpret_cast<const u32x2*>(static_cast<const __bf16*>(a.g1) + hbase + d0);
+                s1v[0] = precise_sigmoid(bf16_bits_to_f32(gw[0] & 0xffffu));
+                s1v[1] = precise_sigmoid(bf16_bits_to_f32(gw[0] >> 16));
+                s1v[2] = precise_sigmoid(bf16_bits_to_f32(gw[1] & 0xffffu));
+                s1v[3] = precise_sigmoid(bf16_bits_to_f32(gw[1] >> 16));
+            }
+            f32x4 dOv, dgv;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float Oe = o[mb][i] * inv;
+                dOv[i] = dy[i] * s1v[i];
+                dgv[i] = dy[i] * Oe * s1v[i] * (1.0f - s1v[i]);
+                dpart = fmaf(dOv[i], Oe, dpart);
+            }
+            *reinterpret_cast<f32x4*>(a.dO_ws + hbase + d0) = dOv;
+            if (a.dg1) *reinterpret_cast<f32x4*>(a.dg1 + hbase + d0) = dgv;
+        }
+    }
+    const float D = train_quad_row_sum(dpart);
+    if (head_ok && q == 0) {
+        a.lse_ws[qrow * a.H + head] = ltot > 0.f ? (mrun + log2f(ltot)) * 0.6931471805599453f : 0.f;
+        a.D_ws[qrow * a.H + head] = D;
+    }
+    // dO as a B operand: lane (head n, chunk q) holds features (4 kk + q) * 8 .. + 8
+    bf16x8 dof[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+        u32x4 w = {0, 0, 0, 0};
+        if (head_ok) {
+            const u32x4 dv = reinterpret_cast<const u32x4*>(static_cast<const __bf16*>(a.dout) + hbase)[kk * 4 + q];
+            u32x4 gv = {0, 0, 0, 0};
+            if (a.g1) gv = reinterpret_cast<const u32x4*>(static_cast<const __bf16*>(a.g1) + hbase)[kk * 4 + q];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float y0 = bf16_bits_to_f32(dv[e] & 0xffffu), y1 = bf16_bits_to_f32(dv[e] >> 16);
+                if (a.g1) {
+                    y0 *= precise_sigmoid(bf16_bits_to_f32(gv[e] & 0xffffu));
+                    y1 *= precise_sigmoid(bf16_bits_to_f32(gv[e] >> 16));
+                }
+                w[e] = pack_bf16x2(y0, y1);
+            }
+        }
+        dof[kk] = __builtin_bit_cast(bf16x8, w);
+    }
+
+    // ---- pass 2: P, dS, dQ ------------------------------------------------------------------------------------------
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) o[mb] = f32x4{0.f, 0.f, 0.f, 0.f};  // now dQ^T
+    const float inv_heads = 1.0f / (float)a.H;
+    for_tiles([&](int j0) {
+        f32x4 s0, s1, d0, d1;
+        rows_times(klds, KROW, qf, s0, s1);
+        rows_times(vlds, VROW, dof, d0, d1);
+        float p[8], ds[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            p[i] = j0 + 4 * q + i < nsel ? fast_exp2(s0[i] * sl2 - mrun) * inv : 0.f;
+            p[4 + i] = j0 + 16 + 4 * q + i < nsel ? fast_exp2(s1[i] * sl2 - mrun) * inv : 0.f;
+            ds[i] = p[i] * (d0[i] - D) * a.scale;
+            ds[4 + i] = p[4 + i] * (d1[i] - D) * a.scale;
+        }
+        if (a.p_sum) {  // attention weights averaged over the heads: sum over the sixteen lanes of a token group
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                float v = head_ok ? p[i] : 0.f;
+#pragma unroll
+                for (int ofs = 8; ofs > 0; ofs >>= 1) v += __shfl_xor(v, ofs, 64);
+                const int j = j0 + (i < 4 ? 4 * q + i : 16 + 4 * q + (i - 4));
+                if (n == 0 && j < nsel) atomicAdd(&a.p_sum[qrow * a.k_cap + j], v * inv_heads);
+            }
+        }
+        const u32x4 dw = {pack_bf16x2(ds[0], ds[1]), pack_bf16x2(ds[2], ds[3]), pack_bf16x2(ds[4], ds[5]), pack_bf16x2(ds[6], ds[7])};
+        transposed_times(klds, KROW, __builtin_bit_cast(bf16x8, dw), o);
+    });
+    if (head_ok) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) *reinterpret_cast<f32x4*>(a.dQ + hbase + mb * 16 + 4 * q) = o[mb];
+    }
+}
+
 // ---- key-centred second pass: dK and dV' without atomics ------------------------------------------------------------
 // The selection is turned round first: for every key and every window of WQ consecutive queries, the list of the
 // queries of that window that selected the key ("inverted lists": a two-level histogram, its exclusive prefix sum,
@@ -618,7 +900,41 @@ hipError_t launch_attention_bwd(const gsa_shape& sh, const void* Q, const void* 
         else
             kern = scatter ? pick_bwd_kernel<float, 64, true>(hc) : pick_bwd_kernel<float, 64, false>(hc);
     }
-    hipLaunchKernelGGL(kern, grid, dim3(256), 0, st, a);
+    const bool mfma = !scatter && sh.dtype == GSA_BF16 && G <= 16;  // query-centred pass on the matrix cores
+    if (mfma) {
+        QBwdArgs qa;
+        qa.Q = Q;
+        qa.K = K;
+        qa.V = V;
+        qa.g2 = g2;
+        qa.g1 = g1;
+        qa.dout = dout;
+        qa.idx = idx;
+        qa.n_sel = n_sel;
+        qa.dQ = dQ;
+        qa.dg1 = dg1;
+        qa.p_sum = p_sum;
+        qa.dO_ws = a.dO_ws;
+        qa.lse_ws = a.lse_ws;
+        qa.D_ws = a.D_ws;
+        qa.B = sh.B;
+        qa.Lq = sh.Lq;
+        qa.Lk = sh.Lk;
+        qa.H = sh.H;
+        qa.H_kv = sh.H_kv;
+        qa.k_cap = k_cap;
+        qa.scale = scale;
+        void (*qk)(QBwdArgs) = sh.d_h == 128 ? (g2 ? attn_bwd_q_mfma_kernel<128, true> : attn_bwd_q_mfma_kernel<128, false>)
+                                             : (g2 ? attn_bwd_q_mfma_kernel<64, true> : attn_bwd_q_mfma_kernel<64, false>);
+        const size_t smem = (size_t)4 * 32 * ((sh.d_h * 2 + 32) + (sh.d_h * 2 + 16));
+        if (smem > 48 * 1024) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(qk), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+            if (e != hipSuccess) return e;
+        }
+        hipLaunchKernelGGL(qk, dim3((unsigned)((int64_t)sh.B * sh.Lq), (unsigned)cdiv(sh.H_kv, 4)), dim3(256), smem, st, qa);
+    } else {
+        hipLaunchKernelGGL(kern, grid, dim3(256), 0, st, a);
+    }
     if (!scatter) {
         // inverted lists: counts -> exclusive prefix sum -> fill
         InvArgs ia;

@@ -6,7 +6,8 @@ Tolerances: everything is fp32 arithmetic on bf16 or fp32 inputs, sums of up to 
 added in an order that varies (atomics, or lists filled through atomic cursors): |got - ref| <= 2e-4 *
 scale_of_that_tensor + 1e-6, where the scale is the largest |ref| entry (gradient entries of one tensor are sums of
 the same kind).  Both forms of the attention backward run: with a workspace (dK, dV' summed key by key over inverted
-lists) and without (fp32 atomics)."""
+lists) and without (fp32 atomics).  With a workspace and bf16 inputs the query-centred pass is the matrix-core
+kernel, whose products take P, dO and dS rounded to bf16 like the forward's: 1e-2 of the scale there."""
 import numpy as np
 import pytest
 import torch
@@ -100,9 +101,13 @@ def test_attention_backward_and_sparse_kl(dtype, B, L, H, Hkv, dh, HI, dI, k, ga
             q_, k_, w_, b_ = O.indexer_scores_bwd_row(o["qI"][b, i], o["kI"][b][sel], o["w"][b, i], o["bI"] if bias else None, dI)
             r_dqI[b, i] = q_; r_dw[b, i] = w_; r_dbI += b_
             np.add.at(r_dkI[b], sel, k_)
-    _close(dQ, r_dQ, "dQ"); _close(dK, r_dK, "dK"); _close(dV, r_dV, "dV")
+    # bf16 inputs with a workspace: the query-centred pass runs on the matrix cores with P, dO and dS rounded to bf16
+    # (unit roundoff u = 2^-9 per operand).  An entry of dQ is a sum of signed products dS_j K_jd whose absolute values
+    # add up to a few times the largest entry, so the rounding of dS alone can move it by a few u of the scale: 5 u = 1e-2
+    rel = 1e-2 if (two_pass and dtype == "bf16") else 2e-4
+    _close(dQ, r_dQ, "dQ", rel); _close(dK, r_dK, "dK", rel); _close(dV, r_dV, "dV", rel)
     if gates:
-        _close(dg1, r_dg1, "dg1"); _close(dg2, r_dg2, "dg2")
+        _close(dg1, r_dg1, "dg1", rel); _close(dg2, r_dg2, "dg2", rel)
     valid = (np.arange(k)[None, None, :] < n_h[..., None])
     _close(torch.where(torch.from_numpy(valid).cuda(), p_mean, torch.zeros_like(p_mean)), r_p, "p_mean", rel=2e-5)
     assert np.allclose(np.where(valid, p_mean.cpu().numpy(), 0).sum(-1)[n_h > 0], 1.0, atol=1e-5)
