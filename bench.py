@@ -338,11 +338,11 @@ def training_leg(G, S, wl, dev):
                 2)
     fms, _ = run.time(3, 1)
     pairs = int(run.n_sel.sum().item())
-    # rows gathered by the backward per (query, selected key, kv head): K and V (and g2) rows in the query-centred pass (twice),
-    # the query and dO rows of the group's heads in the key-centred pass
+    # rows gathered by the backward per (query, selected key, kv head): K and gated-value rows in the query-centred pass
+    # (twice), the query and dO rows of the group's heads in the key-centred pass (bf16 inputs: all bf16)
     elt = 2 if wl.dtype == "bf16" else 4
     G_ = wl.H // wl.H_kv
-    gathered = pairs * wl.H_kv * wl.d_h * (2 * 3 * elt + G_ * (elt + 4))
+    gathered = pairs * wl.H_kv * wl.d_h * ((2 * 2 * elt + G_ * 2 * elt) if wl.dtype == "bf16" else (2 * 3 * elt + G_ * 2 * elt))
     return {"workload": wl.name, "forward_ms": round(fms, 3), "attn_backward_ms": round(bms, 3),
             "attn_backward_workspace_bytes": bws_bytes, "attn_backward_gathered_gbs": round(gathered / (bms * 1e-3) / 1e9, 1),
             "attn_backward_atomics_ms": round(ams, 3), "dK_max_rel_diff_between_the_two": dk_diff,

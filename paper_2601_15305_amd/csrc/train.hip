@@ -11,6 +11,8 @@
 
 namespace gsa {
 
+hipError_t launch_value_gate(const gsa_shape& sh, const void* V, const void* g2, void* Vg, hipStream_t st);
+
 constexpr float kTrainNegBig = -1.0e30f;
 
 template <typename T>
@@ -48,7 +50,7 @@ struct AttnBwdArgs {
     float scale;
     // Key-centred second pass (workspace given): the query-centred kernel leaves dK / dV' alone and stores what the
     // key-centred kernel needs instead.
-    float* dO_ws;   // [B, Lq, H, d_h]: gradient of the ungated outputs, dout * sigmoid(g1)
+    void* dO_ws;    // [B, Lq, H, d_h], element type of the inputs: gradient of the ungated outputs, dout * sigmoid(g1)
     float* lse_ws;  // [B, Lq, H]: log of the softmax denominator of the scaled logits (natural log)
     float* D_ws;    // [B, Lq, H]: dO . O
 };
@@ -211,7 +213,7 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(AttnBwdArgs a) {
                 }
                 dO[hh][e] = dy * s1;
                 dos[hh * DH + lane + 64 * e] = dO[hh][e];
-                if constexpr (!SCATTER) a.dO_ws[i] = dO[hh][e];
+                if constexpr (!SCATTER) static_cast<float*>(a.dO_ws)[i] = dO[hh][e];  // (this kernel: fp32 inputs only)
                 dpart = fmaf(dO[hh][e], Oe, dpart);
             }
             D[hh] = wave_sum(dpart);
@@ -325,7 +327,7 @@ struct QBwdArgs {
     float* dQ;
     float* dg1;
     float* p_sum;
-    float* dO_ws;
+    __bf16* dO_ws;
     float* lse_ws;
     float* D_ws;
     int32_t B, Lq, Lk, H, H_kv, k_cap;
@@ -520,7 +522,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_q_mfma_kernel(QBwdArgs a) {
                 dgv[i] = dy[i] * Oe * s1v[i] * (1.0f - s1v[i]);
                 dpart = fmaf(dOv[i], Oe, dpart);
             }
-            *reinterpret_cast<f32x4*>(a.dO_ws + hbase + d0) = dOv;
+            *reinterpret_cast<u32x2*>(a.dO_ws + hbase + d0) = u32x2{pack_bf16x2(dOv[0], dOv[1]), pack_bf16x2(dOv[2], dOv[3])};
             if (a.dg1) *reinterpret_cast<f32x4*>(a.dg1 + hbase + d0) = dgv;
         }
     }
@@ -689,12 +691,24 @@ __global__ __launch_bounds__(256) void scan_blocks_kernel(int32_t* v, int64_t n,
     }
 }
 
+// Sum over the sixteen lanes of a row (every lane gets it), without LDS: two quad permutes, then the mirrored halves.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+    return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float row16_sum(float x) {
+    x = dpp_add<0xB1>(x);   // quad_perm [1,0,3,2]
+    x = dpp_add<0x4E>(x);   // quad_perm [2,3,0,1]
+    x = dpp_add<0x141>(x);  // row_half_mirror
+    return dpp_add<0x140>(x);  // row_mirror
+}
+
 struct KeyBwdArgs {
     const void* Q;
     const void* K;
     const void* V;
     const void* g2;
-    const float* dO;   // [B, Lq, H, d_h]
+    const void* dO;    // [B, Lq, H, d_h], element type of the inputs
     const float* lse;  // [B, Lq, H]
     const float* D;    // [B, Lq, H]
     const int32_t* off;
@@ -738,40 +752,43 @@ __global__ __launch_bounds__(256) void attn_bwd_keys_kernel(KeyBwdArgs a) {
         const int hq = h0 + hh;
         const bool live = hq < G;
         const int head = g * G + (live ? hq : 0);
-        for (int e = e0; e < e1; e += 2) {  // two entries per step: the loads of both go out before either is used
-            const bool two = e + 1 < e1;
-            const int64_t r0 = ((int64_t)b * a.Lq + a.inv[e]) * a.H + head;
-            const int64_t r1 = ((int64_t)b * a.Lq + a.inv[two ? e + 1 : e]) * a.H + head;
-            float q0[FPL], q1[FPL], o0[FPL], o1[FPL];
-            loadn<FPL>(Q + r0 * DH + c * FPL, q0);
-            loadn<FPL>(Q + r1 * DH + c * FPL, q1);
-            loadn<FPL>(a.dO + r0 * DH + c * FPL, o0);
-            loadn<FPL>(a.dO + r1 * DH + c * FPL, o1);
-            const float l0 = a.lse[r0], l1 = a.lse[r1], D0 = a.D[r0], D1 = a.D[r1];
-            float s0 = 0.f, s1 = 0.f, p0 = 0.f, p1 = 0.f;
+        int tq[4];  // the queries of the next step's entries, requested a step ahead
 #pragma unroll
-            for (int f = 0; f < FPL; ++f) {
-                s0 = fmaf(q0[f], kf[f], s0);
-                s1 = fmaf(q1[f], kf[f], s1);
-                p0 = fmaf(o0[f], vf[f], p0);
-                p1 = fmaf(o1[f], vf[f], p1);
+        for (int u = 0; u < 4; ++u) tq[u] = a.inv[min(e0 + u, e1 - 1)];
+        for (int e = e0; e < e1; e += 4) {  // four entries per step: the loads of all go out before any is used
+            int64_t r[4];
+            float qv[4][FPL], ov[4][FPL], lse[4], Dv[4], sv[4], pv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) r[u] = ((int64_t)b * a.Lq + tq[u]) * a.H + head;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) tq[u] = a.inv[min(e + 4 + u, e1 - 1)];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                loadn<FPL>(Q + r[u] * DH + c * FPL, qv[u]);
+                loadn<FPL>(static_cast<const T*>(a.dO) + r[u] * DH + c * FPL, ov[u]);
+                lse[u] = a.lse[r[u]];
+                Dv[u] = a.D[r[u]];
             }
 #pragma unroll
-            for (int o = 8; o > 0; o >>= 1) {
-                s0 += __shfl_xor(s0, o, 64);
-                s1 += __shfl_xor(s1, o, 64);
-                p0 += __shfl_xor(p0, o, 64);
-                p1 += __shfl_xor(p1, o, 64);
-            }
-            const float P0 = live ? expf(s0 * a.scale - l0) : 0.f;
-            const float P1 = live && two ? expf(s1 * a.scale - l1) : 0.f;
-            const float ds0 = P0 * (p0 - D0) * a.scale, ds1 = P1 * (p1 - D1) * a.scale;
+            for (int u = 0; u < 4; ++u) {
+                sv[u] = pv[u] = 0.f;
 #pragma unroll
-            for (int f = 0; f < FPL; ++f) {
-                dk[f] = fmaf(ds0, q0[f], dk[f]);
-                dk[f] = fmaf(ds1, q1[f], dk[f]);
-                dv[f] = fmaf(P0, o0[f], dv[f]);
-                dv[f] = fmaf(P1, o1[f], dv[f]);
+                for (int f = 0; f < FPL; ++f) {
+                    sv[u] = fmaf(qv[u][f], kf[f], sv[u]);
+                    pv[u] = fmaf(ov[u][f], vf[f], pv[u]);
+                }
+                sv[u] = row16_sum(sv[u]);
+                pv[u] = row16_sum(pv[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float P = live && e + u < e1 ? expf(sv[u] * a.scale - lse[u]) : 0.f;
+                const float ds = P * (pv[u] - Dv[u]) * a.scale;
+#pragma unroll
+                for (int f = 0; f < FPL; ++f) {
+                    dk[f] = fmaf(ds, qv[u][f], dk[f]);
+                    dv[f] = fmaf(P, ov[u][f], dv[f]);
+                }
             }
         }
     }
@@ -820,7 +837,7 @@ static void zero_fill(float* p, int64_t n, hipStream_t st) {
 struct BwdPlan {
     int wq_shift, NW;
     int64_t n_slots;  // B * Lk * NW lists
-    size_t o_dO, o_lse, o_D, o_off, o_cursor, o_sums, o_inv, total;
+    size_t o_dO, o_lse, o_D, o_off, o_cursor, o_sums, o_inv, o_vg, total;
 };
 static BwdPlan plan_bwd(const gsa_shape& sh, int k_cap) {
     BwdPlan p;
@@ -834,13 +851,14 @@ static BwdPlan plan_bwd(const gsa_shape& sh, int k_cap) {
     p.n_slots = (int64_t)sh.B * sh.Lk * p.NW;
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     size_t o = 0;
-    p.o_dO = o;      o += up((size_t)sh.B * sh.Lq * sh.H * sh.d_h * sizeof(float));
+    p.o_dO = o;      o += up((size_t)sh.B * sh.Lq * sh.H * sh.d_h * elt);  // in the element type of the inputs
     p.o_lse = o;     o += up((size_t)sh.B * sh.Lq * sh.H * sizeof(float));
     p.o_D = o;       o += up((size_t)sh.B * sh.Lq * sh.H * sizeof(float));
     p.o_off = o;     o += up((size_t)(p.n_slots + 1) * sizeof(int32_t));
     p.o_cursor = o;  o += up((size_t)p.n_slots * sizeof(int32_t));
     p.o_sums = o;    o += up((size_t)cdiv(p.n_slots + 1, kScanBlock) * sizeof(int32_t));
     p.o_inv = o;     o += up((size_t)sh.B * sh.Lq * k_cap * sizeof(int32_t));
+    p.o_vg = o;      o += sh.dtype == GSA_BF16 ? up((size_t)sh.B * sh.Lk * sh.H_kv * sh.d_h * elt) : 0;  // gated values (bf16 path)
     p.total = o;
     return p;
 }
@@ -878,7 +896,7 @@ hipError_t launch_attention_bwd(const gsa_shape& sh, const void* Q, const void* 
     const bool scatter = workspace == nullptr;
     unsigned char* ws = static_cast<unsigned char*>(workspace);
     const BwdPlan p = plan_bwd(sh, k_cap);
-    a.dO_ws = scatter ? nullptr : reinterpret_cast<float*>(ws + p.o_dO);
+    a.dO_ws = scatter ? nullptr : static_cast<void*>(ws + p.o_dO);
     a.lse_ws = scatter ? nullptr : reinterpret_cast<float*>(ws + p.o_lse);
     a.D_ws = scatter ? nullptr : reinterpret_cast<float*>(ws + p.o_D);
     const int64_t kv_elems = (int64_t)sh.B * sh.Lk * sh.H_kv * sh.d_h;
@@ -901,12 +919,22 @@ hipError_t launch_attention_bwd(const gsa_shape& sh, const void* Q, const void* 
             kern = scatter ? pick_bwd_kernel<float, 64, true>(hc) : pick_bwd_kernel<float, 64, false>(hc);
     }
     const bool mfma = !scatter && sh.dtype == GSA_BF16 && G <= 16;  // query-centred pass on the matrix cores
+    // bf16 inputs with a workspace: the value gate runs once as a pre-pass (as in the forward of long prefills), both
+    // passes then gather gated values
+    const void* Vp = V;
+    const void* g2p = g2;
+    if (mfma && g2) {
+        hipError_t e = launch_value_gate(sh, V, g2, ws + p.o_vg, st);
+        if (e != hipSuccess) return e;
+        Vp = ws + p.o_vg;
+        g2p = nullptr;
+    }
     if (mfma) {
         QBwdArgs qa;
         qa.Q = Q;
         qa.K = K;
-        qa.V = V;
-        qa.g2 = g2;
+        qa.V = Vp;
+        qa.g2 = g2p;
         qa.g1 = g1;
         qa.dout = dout;
         qa.idx = idx;
@@ -914,7 +942,7 @@ hipError_t launch_attention_bwd(const gsa_shape& sh, const void* Q, const void* 
         qa.dQ = dQ;
         qa.dg1 = dg1;
         qa.p_sum = p_sum;
-        qa.dO_ws = a.dO_ws;
+        qa.dO_ws = static_cast<__bf16*>(a.dO_ws);
         qa.lse_ws = a.lse_ws;
         qa.D_ws = a.D_ws;
         qa.B = sh.B;
@@ -924,8 +952,7 @@ hipError_t launch_attention_bwd(const gsa_shape& sh, const void* Q, const void* 
         qa.H_kv = sh.H_kv;
         qa.k_cap = k_cap;
         qa.scale = scale;
-        void (*qk)(QBwdArgs) = sh.d_h == 128 ? (g2 ? attn_bwd_q_mfma_kernel<128, true> : attn_bwd_q_mfma_kernel<128, false>)
-                                             : (g2 ? attn_bwd_q_mfma_kernel<64, true> : attn_bwd_q_mfma_kernel<64, false>);
+        void (*qk)(QBwdArgs) = sh.d_h == 128 ? attn_bwd_q_mfma_kernel<128, false> : attn_bwd_q_mfma_kernel<64, false>;
         const size_t smem = (size_t)4 * 32 * ((sh.d_h * 2 + 32) + (sh.d_h * 2 + 16));
         if (smem > 48 * 1024) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(qk), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -963,8 +990,8 @@ hipError_t launch_attention_bwd(const gsa_shape& sh, const void* Q, const void* 
         KeyBwdArgs ka;
         ka.Q = Q;
         ka.K = K;
-        ka.V = V;
-        ka.g2 = g2;
+        ka.V = Vp;
+        ka.g2 = g2p;
         ka.dO = a.dO_ws;
         ka.lse = a.lse_ws;
         ka.D = a.D_ws;
