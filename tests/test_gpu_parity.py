@@ -294,6 +294,8 @@ ATTN_CASES = [
     ("bf16", 16, 1, 128, 1, 70, 70, 0, 70),
     ("bf16", 8, 2, 64, 1, 130, 130, 0, 96),
     ("bf16", 16, 4, 128, 3, 1, 400, 399, 333),
+    ("bf16", 12, 4, 128, 1, 80, 80, 0, 60),      # groups of three heads (the fourth head slot of a transfer is a copy)
+    ("bf16", 12, 2, 128, 1, 80, 80, 0, 60),      # groups of six heads: two query-head transfers per row
     ("f32", 4, 4, 64, 1, 200, 200, 0, 64),
     ("f32", 4, 1, 128, 2, 100, 100, 0, 100),
 ]
