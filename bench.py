@@ -53,6 +53,7 @@ def parse():
     ap.add_argument("--stage-steps", type=int, default=0, help="steps of the per-stage timing loop (0 = same as --steps)")
     ap.add_argument("--no-traffic", action="store_true", help="do not collect the HBM-side byte counters (two child runs under rocprofv3)")
     ap.add_argument("--no-extras", action="store_true", help="skip the one-slab, decode and 16-kv-head legs")
+    ap.add_argument("--training-only", action="store_true", help="run only the training leg (C2-8k) and print its figures as one JSON line")
     ap.add_argument("--traffic-child", action="store_true", help=argparse.SUPPRESS)
     return ap.parse_args()
 
@@ -432,6 +433,15 @@ def main():
         sys.exit(2)
     if args.traffic_child:
         traffic_child(args)
+        return
+    if args.training_only:
+        import torch
+        import paper_2601_15305_amd as G
+        from paper_2601_15305_amd import synthetic as S
+        assert torch.cuda.is_available(), "bench.py needs the GPU"
+        G.load()
+        torch.cuda.set_device(0)
+        print(json.dumps({"training_c2": training_leg(G, S, S.C2, torch.device("cuda:0"))}))
         return
     traffic = "not collected (--no-traffic)" if args.no_traffic else collect_traffic(args)
 
