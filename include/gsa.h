@@ -322,8 +322,11 @@ int32_t gsa_output_projection(const gsa_shape* shape, int32_t d_model, const voi
  *   workspace  device, scratch, 256-byte aligned, gsa_attn_bwd_workspace_bytes(shape, k_cap) bytes, or NULL.
  *           Given: dK and dV' are summed key by key in a second pass over inverted lists (for every key, the
  *           queries that selected it, grouped by windows of queries), without atomics on the gradients; only
- *           the order of a key's list, and with it the last bits of its sums, varies between runs.  Needs
- *           B * Lq * k_cap < 2^31 (GSA_ERR_UNSUPPORTED otherwise); too small: GSA_ERR_WORKSPACE.
+ *           the order of a key's list, and with it the last bits of its sums, varies between runs.  For
+ *           GSA_BF16 shapes the first pass runs on the matrix cores and, like the forward, rounds the
+ *           operands of its products (P, dO, dS) to bf16: gradients within about 1e-2 of their largest
+ *           entry; GSA_F32 shapes stay in fp32 arithmetic.  Needs B * Lq * k_cap < 2^31
+ *           (GSA_ERR_UNSUPPORTED otherwise); too small: GSA_ERR_WORKSPACE.
  *           NULL: one pass, every (query, key) contribution added with fp32 atomics (several times slower).
  *   p_mean  device, out, fp32 [B, Lq, k_cap] or NULL: the attention weights of every row over its selected keys,
  *           averaged over the H heads -- the target p_{t,S_t} of the sparse-phase indexer loss.

@@ -19,7 +19,11 @@
 // plain 16-byte reads (a lane owns 16 consecutive bytes of a token's row), V' comes back transposed with
 // the LDS transpose read of gfx950 (ds_read_b64_tr_b16), which turns 4 tokens x 16 features into the
 // "feature row, token contraction" A operand of the second.  Softmax is the usual online form in base 2;
-// G2 is applied to the V rows in registers on their way to LDS, G1 to the accumulators before the store.
+// G1 is applied to the accumulators before the store.
+// Two ways of getting the rows into the tiles.  Staged: rows -> registers -> LDS (padded tiles), G2 applied to the
+// V rows in registers on the way.  Direct (gated values given, 256-byte rows): global_load_lds_dwordx4 moves the
+// rows straight into unpadded, XOR-swizzled tiles, with the K rows of the next tile and its V' rows requested as
+// two separate streams and the waits for them placed by hand (see the DIRECT branch of the kernel).
 #include "common.hpp"
 
 namespace gsa {

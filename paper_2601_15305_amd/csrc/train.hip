@@ -2,11 +2,13 @@
 // fixed (top-k has no gradient), the sparse-phase loss of the indexer, KL(p_{t,S_t} || softmax(I_{t,S_t})), and
 // the gradients of the indexer scores of Sec. 3.3 that this loss sends back.
 //
-// All kernels use plain vector arithmetic in fp32 (inputs bf16 or fp32, gradients fp32).  One wave handles one
-// query and up to four query heads of one kv group: a lane computes the logits of one selected token from the whole
-// K row (chunks of 64 tokens), then every lane owns d_h / 64 features for the sums over tokens.  Contributions to
-// keys that several queries select are added with fp32 atomics (their order, and so the last bits of dK, dV, dg2,
-// dkI, dbI, varies from run to run).
+// The attention backward has two forms.  Without a workspace: one kernel in plain fp32 vector arithmetic, one wave
+// per query and up to four query heads of one kv group (a lane computes the logits of one selected token from the
+// whole K row, then every lane owns d_h / 64 features for the sums over tokens); contributions to keys that several
+// queries select are added with fp32 atomics.  With a workspace: a query-centred pass (on the matrix cores for bf16
+// inputs) for dQ and dg1, the selection turned into per-key lists, and a key-centred pass that sums dK and dV' key
+// by key without atomics.  The indexer loss kernel is vector arithmetic with atomics into dkI and dbI.  Wherever
+// sums are formed by atomics, or over lists filled through atomic cursors, their last bits vary from run to run.
 #include "common.hpp"
 
 namespace gsa {
