@@ -311,7 +311,7 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(AttnBwdArgs a) {
 // ---- query-centred pass on the matrix cores (bf16 inputs, workspace given) ------------------------------------------
 // One wave per (query, kv head), the G = H / H_kv query heads of the kv head as the N dimension (padded to 16) of
 // v_mfma_f32_16x16x32_bf16, the gathered tokens as M or K: the dataflow of the forward kernel (attention.hip: whole
-// K and V' rows staged in wave-private LDS tiles of 32 tokens, V' gated on the way).  Two passes over the list:
+// K and V' rows staged in wave-private LDS tiles of 32 tokens; V holds the gated values).  Two passes over the list:
 //   1. the forward: S^T = K Q^T, online softmax, O^T += V'^T P^T  ->  O, the softmax maximum and denominator;
 //      then dO = dout * sigmoid(g1), D = dO . O, dg1, and what the key-centred pass needs (dO, log-sum-exp, D);
 //   2. S^T again and dP^T = V' dO^T (V' rows read as an A operand, like K), P = exp(S - lse),
@@ -321,7 +321,6 @@ struct QBwdArgs {
     const void* Q;
     const void* K;
     const void* V;
-    const void* g2;
     const void* g1;
     const void* dout;
     const int32_t* idx;
@@ -349,7 +348,7 @@ __device__ __forceinline__ float train_quad_row_sum(float x) {
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-template <int DH, bool HAS_G2>
+template <int DH>
 __global__ __launch_bounds__(256, 2) void attn_bwd_q_mfma_kernel(QBwdArgs a) {
     constexpr int KK = DH / 32, MB = DH / 16, ROWB = DH * 2, VROW = ROWB + 32, KROW = ROWB + 16;
     constexpr int VCH = ROWB / 16, TPI = 64 / VCH, NVL = 32 / TPI;
@@ -372,7 +371,6 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_q_mfma_kernel(QBwdArgs a) {
     const int64_t row0 = (int64_t)b * a.Lk;
     const unsigned char* Kb = static_cast<const unsigned char*>(a.K) + (row0 * a.H_kv + g) * ROWB;
     const unsigned char* Vb = static_cast<const unsigned char*>(a.V) + (row0 * a.H_kv + g) * ROWB;
-    const unsigned char* Gb = HAS_G2 ? static_cast<const unsigned char*>(a.g2) + (row0 * a.H_kv + g) * ROWB : nullptr;
     const int64_t hbase = (qrow * a.H + (head_ok ? head : 0)) * DH;  // this lane's head row in Q / dout / g1 / dQ
 
     // B operands: lane (head n, chunk q) holds features (4 kk + q) * 8 .. + 8
@@ -382,7 +380,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_q_mfma_kernel(QBwdArgs a) {
         const u32x4 v = head_ok ? reinterpret_cast<const u32x4*>(static_cast<const __bf16*>(a.Q) + hbase)[kk * 4 + q] : u32x4{0, 0, 0, 0};
         qf[kk] = __builtin_bit_cast(bf16x8, v);
     }
-    u32x4 kr[NVL], vf[NVL], gf[HAS_G2 ? NVL : 1];
+    u32x4 kr[NVL], vf[NVL];
     const int slot0 = (lane / VCH) * NVL;
     auto load_idx = [&](int j0, int (&tk)[NVL]) {
 #pragma unroll
@@ -395,25 +393,13 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_q_mfma_kernel(QBwdArgs a) {
             const uint32_t off = __umul24((uint32_t)tk, tokstride) + (uint32_t)(lane % VCH) * 16u;
             kr[r] = *reinterpret_cast<const u32x4*>(Kb + off);
             vf[r] = *reinterpret_cast<const u32x4*>(Vb + off);
-            if constexpr (HAS_G2) gf[r] = *reinterpret_cast<const u32x4*>(Gb + off);
         }
     };
     auto stage = [&]() {
 #pragma unroll
         for (int r = 0; r < NVL; ++r) *reinterpret_cast<u32x4*>(klds + (slot0 + r) * KROW + (lane % VCH) * 16) = kr[r];
 #pragma unroll
-        for (int r = 0; r < NVL; ++r) {
-            u32x4 v = vf[r];
-            if constexpr (HAS_G2) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float v0 = bf16_bits_to_f32(v[e] & 0xffffu) * sigmoid_f32(bf16_bits_to_f32(gf[r][e] & 0xffffu));
-                    const float v1 = bf16_bits_to_f32(v[e] >> 16) * sigmoid_f32(bf16_bits_to_f32(gf[r][e] >> 16));
-                    v[e] = pack_bf16x2(v0, v1);
-                }
-            }
-            *reinterpret_cast<u32x4*>(vlds + (slot0 + r) * VROW + (lane % VCH) * 16) = v;
-        }
+        for (int r = 0; r < NVL; ++r) *reinterpret_cast<u32x4*>(vlds + (slot0 + r) * VROW + (lane % VCH) * 16) = vf[r];
     };
     // S^T (or dP^T) of the tile in LDS: rows of `tile` (row stride ROWSTRIDE) against the B operand bf
     auto rows_times = [&](const unsigned char* tile, int rowstride, const bf16x8 (&bf)[KK], f32x4& r0, f32x4& r1) {
@@ -937,8 +923,7 @@ hipError_t launch_attention_bwd(const gsa_shape& sh, const void* Q, const void* 
         QBwdArgs qa;
         qa.Q = Q;
         qa.K = K;
-        qa.V = Vp;
-        qa.g2 = g2p;
+        qa.V = Vp;  // gated values (the pre-pass above, or V itself when the layer has no value gate)
         qa.g1 = g1;
         qa.dout = dout;
         qa.idx = idx;
@@ -956,7 +941,7 @@ hipError_t launch_attention_bwd(const gsa_shape& sh, const void* Q, const void* 
         qa.H_kv = sh.H_kv;
         qa.k_cap = k_cap;
         qa.scale = scale;
-        void (*qk)(QBwdArgs) = sh.d_h == 128 ? attn_bwd_q_mfma_kernel<128, false> : attn_bwd_q_mfma_kernel<64, false>;
+        void (*qk)(QBwdArgs) = sh.d_h == 128 ? attn_bwd_q_mfma_kernel<128> : attn_bwd_q_mfma_kernel<64>;
         const size_t smem = (size_t)4 * 32 * ((sh.d_h * 2 + 32) + (sh.d_h * 2 + 16));
         if (smem > 48 * 1024) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(qk), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);

@@ -44,6 +44,8 @@ CASES = [
     ("f32", 2, 90, 8, 2, 128, 8, 128, 90, True, False),     # budget covers every visible key of every row
     ("bf16", 1, 140, 16, 1, 64, 5, 32, 130, True, True),    # sixteen query heads on one kv head: four chunks of four heads
     ("bf16", 1, 150, 12, 4, 64, 2, 32, 40, True, False),    # groups of three heads: a head slot of the key-centred pass stays idle
+    ("bf16", 1, 300, 16, 1, 128, 2, 32, 64, True, False),   # wide rows: the key-centred pass runs over three windows of 128 queries
+    ("f32", 2, 200, 16, 1, 128, 2, 32, 50, False, True),    # ... four windows of 64 queries, two batch elements, fp32 throughout
 ]
 
 
