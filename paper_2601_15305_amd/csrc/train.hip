@@ -1062,11 +1062,19 @@ __global__ __launch_bounds__(256) void indexer_kl_kernel(IndexerKlArgs a) {
         float z[8];
 #pragma unroll
         for (int h = 0; h < 8; ++h) z[h] = 0.f;
-        for (int c = 0; c < DI; ++c) {
-            const float kc = ldf(kr, c);
+        for (int c = 0; c < DI; c += 8) {  // (dI is a multiple of 32: whole 16-byte pieces of the key row)
+            float kv[8];
+            load8(kr + c, kv);
 #pragma unroll
             for (int h = 0; h < 8; ++h)
-                if (h < HI) z[h] = fmaf(qs[h * DI + c], kc, z[h]);
+                if (h < HI) {
+                    const float4 q0 = *reinterpret_cast<const float4*>(qs + h * DI + c);
+                    const float4 q1 = *reinterpret_cast<const float4*>(qs + h * DI + c + 4);
+                    z[h] = fmaf(q0.x, kv[0], z[h]); z[h] = fmaf(q0.y, kv[1], z[h]);
+                    z[h] = fmaf(q0.z, kv[2], z[h]); z[h] = fmaf(q0.w, kv[3], z[h]);
+                    z[h] = fmaf(q1.x, kv[4], z[h]); z[h] = fmaf(q1.y, kv[5], z[h]);
+                    z[h] = fmaf(q1.z, kv[6], z[h]); z[h] = fmaf(q1.w, kv[7], z[h]);
+                }
         }
         float sc = 0.f;
 #pragma unroll
