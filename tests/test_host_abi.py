@@ -128,6 +128,34 @@ def test_forward_workspace_grows_with_slab():
     assert G.gsa_forward_workspace_bytes(c4, 4096, True, 8192) < 4 * (1 << 30)
 
 
+def test_backward_workspace_size_and_host_side_checks():
+    """The workspace of the two-pass attention backward: what it has to hold (the inverted lists, B * Lq * k_cap entries;
+    dO in the element type; the gated values for bf16), and the argument checks that are decided before any launch."""
+    import ctypes
+    sh = G.make_shape(1, 8192, 8192, 0, 16, 4, 128, 4, 64, "bf16")
+    w1, w2 = G.gsa_attn_bwd_workspace_bytes(sh, 1024), G.gsa_attn_bwd_workspace_bytes(sh, 4096)
+    assert w1 % 256 == 0 and w2 % 256 == 0 and 0 < w1 < w2
+    assert w2 - w1 == 8192 * (4096 - 1024) * 4                        # the lists: one int32 per (query, list slot)
+    assert w1 >= 8192 * 1024 * 4 + 8192 * 16 * 128 * 2 + 8192 * 4 * 128 * 2
+    f32 = G.make_shape(1, 8192, 8192, 0, 16, 4, 128, 4, 64, "f32")
+    assert G.gsa_attn_bwd_workspace_bytes(f32, 1024) >= 8192 * 1024 * 4 + 8192 * 16 * 128 * 4
+    assert G.gsa_attn_bwd_workspace_bytes(_shape(d_h=96), 64) == 0     # a shape the library does not take
+    assert G.gsa_attn_bwd_workspace_bytes(sh, 0) == 0 and G.gsa_attn_bwd_workspace_bytes(sh, 9000) == 0
+    lib = G.load()
+    p = ctypes.c_void_p(FAKE)
+
+    def call(workspace, nbytes, k_cap=1024, dg1=None, g1=None, shape=sh):
+        return lib.gsa_sparse_gated_attn_bwd(ctypes.byref(shape), p, p, p, None, g1, p, p, k_cap, 0.0, p, p, p, p, dg1, None, None,
+                                             workspace, nbytes, None)
+
+    assert call(p, w1 - 256) == G.GSA_ERR_WORKSPACE and b"gsa_attn_bwd_workspace_bytes" in lib.gsa_last_error()
+    assert call(ctypes.c_void_p(FAKE + 8), w1) == G.GSA_ERR_SHAPE      # workspace not 256-byte aligned
+    assert call(p, w1, g1=p) == G.GSA_ERR_NULL                         # g1 without dg1
+    assert call(p, w1, k_cap=0) == G.GSA_ERR_SHAPE
+    huge = G.make_shape(64, 131072, 131072, 0, 16, 4, 128, 4, 64, "bf16")   # B * Lq * k_cap beyond 32-bit list positions
+    assert call(p, 1 << 62, k_cap=4096, shape=huge) == G.GSA_ERR_UNSUPPORTED
+
+
 def test_selection_rejects_contexts_beyond_the_on_chip_bitmaps():
     """The selection kernels keep bitmaps of a row in LDS; a context they cannot hold is refused on the host."""
     lib = G.load()
